@@ -1,0 +1,146 @@
+/*
+ * eqat.h  --  C ABI of the MI355X (gfx950) quantized-linear library for
+ * EfficientQAT (arXiv 2407.11062).
+ *
+ * The library implements the layer both training phases of the paper run on
+ * every step:
+ *   Block-AP (Sec. 3.2):  W_int = clamp(round(W/s) + z, 0, 2^N - 1)   Eq.(1)
+ *                         What  = (W_int - z) * s                     Eq.(2)
+ *                         Y = X * What^T, and the backward of App. B.
+ *   E2E-QP  (Sec. 3.3):   W_int frozen and packed at N bits; only Eq.(2) runs.
+ *
+ * Conventions (all entry points)
+ *   Layout     Row-major, contiguous.  X [T,I], W [O,I] (row = output channel),
+ *              s,z [O,G] with G = I/g, Y,dY [T,O], dX [T,I], dW [O,I],
+ *              ds,dz [O,G].  Group j of row o covers columns [j*g,(j+1)*g).
+ *   Memory     Every pointer is a DEVICE pointer owned by the caller, 16-byte
+ *              aligned.  The library never allocates, frees or keeps a pointer.
+ *              Each tensor must be smaller than 2 GiB.
+ *   Dtypes     X,Y,dY,dX have desc.act_dtype; W,dW have desc.w_dtype; s,z,ds,dz
+ *              are always fp32.  act bf16 selects the MFMA path (needs O % 8 == 0);
+ *              act fp32 selects the fp32 path.
+ *   Shapes     I % 32 == 0; g > 0, g % 32 == 0, g | I (group = -1 means g = I);
+ *              bits in {2,3,4}; T >= 0, O >= 1.
+ *   Stream     `stream` is a hipStream_t (NULL = default stream).  All work is
+ *              enqueued there; no call synchronises.  Outputs are overwritten.
+ *   Workspace  Caller-provided scratch of at least eqat_workspace_bytes(desc, op)
+ *              bytes, 256-byte aligned; contents undefined afterwards.
+ *   Errors     Arguments are checked on the host before anything is launched and
+ *              the first violation is returned; nothing is thrown or aborted.
+ *   Numerics   round() is round-half-to-even of the correctly rounded binary32
+ *              quotient w/s (bf16 weights are widened first), so integer codes
+ *              and packed bytes are identical on every implementation.
+ *              zbar = round(z) is used in place of z; it is clamped to [0,2^N-1]
+ *              only where it is packed.  Preconditions (not checked): s > 0 and
+ *              finite, |z| <= 2^20, all inputs finite.
+ *   Determinism  Same inputs give bitwise the same outputs.
+ */
+#ifndef EQAT_H_
+#define EQAT_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    EQAT_OK = 0,
+    EQAT_ERR_NULL = 1,      /* a required pointer is NULL                        */
+    EQAT_ERR_SHAPE = 2,     /* T < 0, I or O < 1, I % 32, O % 8 (bf16), >= 2 GiB */
+    EQAT_ERR_BITS = 3,      /* bits not in {2,3,4}                               */
+    EQAT_ERR_GROUP = 4,     /* group not -1 and (<= 0, % 32 != 0 or not | I)     */
+    EQAT_ERR_DTYPE = 5,     /* unknown dtype value                               */
+    EQAT_ERR_ALIGN = 6,     /* pointer not 16-byte (workspace: 256-byte) aligned */
+    EQAT_ERR_WORKSPACE = 7, /* workspace missing or too small                    */
+    EQAT_ERR_DEVICE = 8     /* the HIP runtime refused a launch                  */
+} eqat_status;
+
+typedef enum { EQAT_F32 = 0, EQAT_BF16 = 1 } eqat_dtype;
+
+typedef enum {
+    EQAT_OP_FQ_FWD = 0, EQAT_OP_FQ_BWD = 1, EQAT_OP_Q_FWD = 2, EQAT_OP_Q_BWD = 3
+} eqat_op;
+
+typedef struct eqat_desc {
+    int64_t tokens;        /* T                                                  */
+    int64_t in_features;   /* I                                                  */
+    int64_t out_features;  /* O                                                  */
+    int32_t bits;          /* N                                                  */
+    int32_t group;         /* g, or -1 for one group per row (per-channel)       */
+    int32_t act_dtype;     /* eqat_dtype of X, Y, dY, dX                         */
+    int32_t w_dtype;       /* eqat_dtype of W, dW                                */
+} eqat_desc;
+
+/* Host-only helpers.  Sizes are 0 for an invalid descriptor. */
+const char *eqat_status_string(int status);
+eqat_status eqat_validate_desc(const eqat_desc *d);
+size_t eqat_packed_w_bytes(const eqat_desc *d);   /* O * I*N/8                     */
+size_t eqat_packed_z_bytes(const eqat_desc *d);   /* O * 4*ceil(G*N/32)            */
+size_t eqat_workspace_bytes(const eqat_desc *d, int op);
+
+/*
+ * Per-group initialisation of step sizes and zero points.  The paper does not
+ * say how s and z start; this is the usual asymmetric min/max rule in binary32:
+ *   s = max((max - min) / (2^N - 1), 1e-10),  z = clamp(round(-min / s), 0, 2^N - 1).
+ * In: W [O,I].  Out: s, z [O,G].  d->tokens is ignored.
+ */
+eqat_status eqat_init_minmax(const eqat_desc *d, const void *W, float *s, float *z, void *stream);
+
+/*
+ * Block-AP forward (Sec. 3.2, Eqs.(1),(2)):  Y = X * What^T.
+ * What is rebuilt from W, s, z on the fly and never stored.
+ */
+eqat_status eqat_fq_linear_fwd(const eqat_desc *d, const void *X, const void *W, const float *s,
+                               const float *z, void *Y, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Block-AP backward (App. B, Eqs.(3)-(5), straight-through estimator):
+ *   dX = dY * What
+ *   dW = (dY^T X) where 0 <= round(w/s)+zbar <= 2^N-1, else 0            Eq.(5)
+ *   ds[o,j] = sum over group of (dY^T X) * { round(w/s) - w/s | -zbar | 2^N-1-zbar }   Eq.(3)
+ *   dz[o,j] = sum over group of (dY^T X) * { 0 in range | -s outside }                 Eq.(4)
+ * Eq.(4) is printed with -1; -s is the derivative of Eq.(2) for a zero point in
+ * integer units, and the printed form equals dz / s.  The appendix writes the
+ * upper bound as 2^(N-1); Eq.(1)'s 2^N - 1 is used.
+ * Any of dX, dW, ds, dz may be NULL and is then skipped.
+ */
+eqat_status eqat_fq_linear_bwd(const eqat_desc *d, const void *X, const void *W, const float *s,
+                               const float *z, const void *dY, void *dX, void *dW, float *ds, float *dz,
+                               void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Freeze after Block-AP (Sec. 3.2 last paragraph; App. E): W_q and z at N bits.
+ * Layout (the paper fixes none): each row is a little-endian bit stream, code i
+ * of the row in bits [i*N,(i+1)*N), stored as bytes, least significant first.
+ *   Wpacked [O, I*N/8] bytes, zpacked [O, 4*ceil(G*N/32)] bytes (tail bits 0).
+ * zbar is clamped to [0, 2^N-1] here.  d->tokens is ignored.
+ */
+eqat_status eqat_pack(const eqat_desc *d, const void *W, const float *s, const float *z,
+                      uint8_t *Wpacked, uint8_t *zpacked, void *stream);
+
+/* Test aid: expand the packed streams to int32 codes [O,I] and zero points [O,G]
+ * (either output may be NULL). */
+eqat_status eqat_unpack(const eqat_desc *d, const uint8_t *Wpacked, const uint8_t *zpacked,
+                        int32_t *codes, int32_t *zcodes, void *stream);
+
+/*
+ * E2E-QP forward (Sec. 3.3): What = (w_q - z) * s from the packed codes, Y = X * What^T.
+ */
+eqat_status eqat_qlinear_fwd(const eqat_desc *d, const void *X, const uint8_t *Wpacked, const float *s,
+                             const uint8_t *zpacked, void *Y, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * E2E-QP backward (Sec. 3.3): dX = dY * What and
+ *   ds[o,j] = sum over group of (dY^T X)[o,i] * (w_q[o,i] - z[o,j]).
+ * dX or ds may be NULL (skipped).  d->w_dtype is ignored.
+ */
+eqat_status eqat_qlinear_bwd(const eqat_desc *d, const void *X, const uint8_t *Wpacked, const float *s,
+                             const uint8_t *zpacked, const void *dY, void *dX, float *ds,
+                             void *ws, size_t ws_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EQAT_H_ */

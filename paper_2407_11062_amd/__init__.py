@@ -1,0 +1,194 @@
+"""Thin Python binding of the eqat C ABI (``include/eqat.h``).
+
+Argument marshalling only: every function here turns torch tensors into raw
+device pointers and sizes, allocates outputs / workspace with torch when the
+caller did not pass them, and calls the entry point of the same name in
+``libeqat.so`` on torch's current stream.  No arithmetic of the method runs in
+Python, and there is no fallback: without the built library every call raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libeqat.so")
+
+F32, BF16 = 0, 1
+OP_FQ_FWD, OP_FQ_BWD, OP_Q_FWD, OP_Q_BWD = 0, 1, 2, 3
+
+STATUS_NAMES = ["EQAT_OK", "EQAT_ERR_NULL", "EQAT_ERR_SHAPE", "EQAT_ERR_BITS", "EQAT_ERR_GROUP", "EQAT_ERR_DTYPE",
+                "EQAT_ERR_ALIGN", "EQAT_ERR_WORKSPACE", "EQAT_ERR_DEVICE"]
+
+EXPORTS = ["eqat_status_string", "eqat_validate_desc", "eqat_packed_w_bytes", "eqat_packed_z_bytes",
+           "eqat_workspace_bytes", "eqat_init_minmax", "eqat_fq_linear_fwd", "eqat_fq_linear_bwd", "eqat_pack",
+           "eqat_unpack", "eqat_qlinear_fwd", "eqat_qlinear_bwd"]
+
+
+class Desc(ctypes.Structure):
+    _fields_ = [("tokens", ctypes.c_int64), ("in_features", ctypes.c_int64), ("out_features", ctypes.c_int64),
+                ("bits", ctypes.c_int32), ("group", ctypes.c_int32), ("act_dtype", ctypes.c_int32),
+                ("w_dtype", ctypes.c_int32)]
+
+
+class EqatError(RuntimeError):
+    def __init__(self, fn, status):
+        self.status = status
+        name = STATUS_NAMES[status] if 0 <= status < len(STATUS_NAMES) else str(status)
+        super().__init__(f"{fn}: {name}: {lib().eqat_status_string(status).decode()}")
+
+
+_lib = None
+
+
+def lib():
+    """The loaded C library (raises if it has not been built)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2407_11062_amd.build` "
+                               "(there is no fallback path)")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, dp, sz = ctypes.c_void_p, ctypes.POINTER(Desc), ctypes.c_size_t
+        L.eqat_status_string.restype = ctypes.c_char_p
+        L.eqat_status_string.argtypes = [ctypes.c_int]
+        L.eqat_validate_desc.argtypes = [dp]
+        for f in (L.eqat_packed_w_bytes, L.eqat_packed_z_bytes):
+            f.restype, f.argtypes = sz, [dp]
+        L.eqat_workspace_bytes.restype, L.eqat_workspace_bytes.argtypes = sz, [dp, ctypes.c_int]
+        L.eqat_init_minmax.argtypes = [dp, vp, vp, vp, vp]
+        L.eqat_fq_linear_fwd.argtypes = [dp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.eqat_fq_linear_bwd.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.eqat_pack.argtypes = [dp, vp, vp, vp, vp, vp, vp]
+        L.eqat_unpack.argtypes = [dp, vp, vp, vp, vp, vp]
+        L.eqat_qlinear_fwd.argtypes = [dp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.eqat_qlinear_bwd.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        _lib = L
+    return _lib
+
+
+def _dt(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _tdt(code: int):
+    return torch.bfloat16 if code == BF16 else torch.float32
+
+
+def _p(t):
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("eqat tensors must be contiguous device tensors")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _check(fn, status):
+    if status != 0:
+        raise EqatError(fn, status)
+
+
+def make_desc(T, I, O, bits, group, act_dtype, w_dtype) -> Desc:
+    return Desc(int(T), int(I), int(O), int(bits), int(group), int(act_dtype), int(w_dtype))
+
+
+def workspace(desc: Desc, op: int, device) -> torch.Tensor | None:
+    n = lib().eqat_workspace_bytes(ctypes.byref(desc), op)
+    return torch.empty(max(n, 256), dtype=torch.uint8, device=device)
+
+
+def _groups(I, group):
+    return 1 if group == -1 else I // group
+
+
+def eqat_init_minmax(W, bits, group, s=None, z=None):
+    O, I = W.shape
+    d = make_desc(0, I, O, bits, group, BF16, _dt(W))
+    G = _groups(I, group)
+    s = torch.empty((O, G), dtype=torch.float32, device=W.device) if s is None else s
+    z = torch.empty((O, G), dtype=torch.float32, device=W.device) if z is None else z
+    _check("eqat_init_minmax", lib().eqat_init_minmax(ctypes.byref(d), _p(W), _p(s), _p(z), _stream()))
+    return s, z
+
+
+def eqat_fq_linear_fwd(X, W, s, z, bits, group, Y=None, ws=None):
+    T, I = X.shape
+    O = W.shape[0]
+    d = make_desc(T, I, O, bits, group, _dt(X), _dt(W))
+    Y = torch.empty((T, O), dtype=X.dtype, device=X.device) if Y is None else Y
+    ws = workspace(d, OP_FQ_FWD, X.device) if ws is None else ws
+    _check("eqat_fq_linear_fwd", lib().eqat_fq_linear_fwd(ctypes.byref(d), _p(X), _p(W), _p(s), _p(z), _p(Y), _p(ws),
+                                                          ws.numel(), _stream()))
+    return Y
+
+
+def eqat_fq_linear_bwd(X, W, s, z, dY, bits, group, want=("dX", "dW", "ds", "dz"), out=None, ws=None):
+    T, O = dY.shape
+    I = W.shape[1]
+    d = make_desc(T, I, O, bits, group, _dt(dY), _dt(W))
+    G = _groups(I, group)
+    out = {} if out is None else out
+    if "dX" in want and "dX" not in out: out["dX"] = torch.empty((T, I), dtype=dY.dtype, device=dY.device)
+    if "dW" in want and "dW" not in out: out["dW"] = torch.empty((O, I), dtype=W.dtype, device=dY.device)
+    if "ds" in want and "ds" not in out: out["ds"] = torch.empty((O, G), dtype=torch.float32, device=dY.device)
+    if "dz" in want and "dz" not in out: out["dz"] = torch.empty((O, G), dtype=torch.float32, device=dY.device)
+    ws = workspace(d, OP_FQ_BWD, dY.device) if ws is None else ws
+    _check("eqat_fq_linear_bwd", lib().eqat_fq_linear_bwd(
+        ctypes.byref(d), _p(X), _p(W), _p(s), _p(z), _p(dY), _p(out.get("dX")), _p(out.get("dW")), _p(out.get("ds")),
+        _p(out.get("dz")), _p(ws), ws.numel(), _stream()))
+    return out
+
+
+def eqat_pack(W, s, z, bits, group, Wpacked=None, zpacked=None):
+    O, I = W.shape
+    d = make_desc(0, I, O, bits, group, BF16, _dt(W))
+    nw, nz = lib().eqat_packed_w_bytes(ctypes.byref(d)), lib().eqat_packed_z_bytes(ctypes.byref(d))
+    if nw == 0:
+        _check("eqat_pack", lib().eqat_validate_desc(ctypes.byref(d)) or 2)
+    Wpacked = torch.empty((O, nw // O), dtype=torch.uint8, device=W.device) if Wpacked is None else Wpacked
+    zpacked = torch.empty((O, nz // O), dtype=torch.uint8, device=W.device) if zpacked is None else zpacked
+    _check("eqat_pack", lib().eqat_pack(ctypes.byref(d), _p(W), _p(s), _p(z), _p(Wpacked), _p(zpacked), _stream()))
+    return Wpacked, zpacked
+
+
+def eqat_unpack(Wpacked, zpacked, in_features, bits, group):
+    O, I = Wpacked.shape[0], int(in_features)
+    d = make_desc(0, I, O, bits, group, BF16, BF16)
+    codes = torch.empty((O, I), dtype=torch.int32, device=Wpacked.device)
+    zc = torch.empty((O, _groups(I, group)), dtype=torch.int32, device=Wpacked.device)
+    _check("eqat_unpack", lib().eqat_unpack(ctypes.byref(d), _p(Wpacked), _p(zpacked), _p(codes), _p(zc), _stream()))
+    return codes, zc
+
+
+def eqat_qlinear_fwd(X, Wpacked, s, zpacked, bits, group, Y=None, ws=None):
+    T, I = X.shape
+    O = Wpacked.shape[0]
+    d = make_desc(T, I, O, bits, group, _dt(X), BF16)
+    Y = torch.empty((T, O), dtype=X.dtype, device=X.device) if Y is None else Y
+    ws = workspace(d, OP_Q_FWD, X.device) if ws is None else ws
+    _check("eqat_qlinear_fwd", lib().eqat_qlinear_fwd(ctypes.byref(d), _p(X), _p(Wpacked), _p(s), _p(zpacked), _p(Y),
+                                                      _p(ws), ws.numel(), _stream()))
+    return Y
+
+
+def eqat_qlinear_bwd(X, Wpacked, s, zpacked, dY, in_features, bits, group, want=("dX", "ds"), out=None, ws=None):
+    T, O = dY.shape
+    I = int(in_features)
+    d = make_desc(T, I, O, bits, group, _dt(dY), BF16)
+    out = {} if out is None else out
+    if "dX" in want and "dX" not in out: out["dX"] = torch.empty((T, I), dtype=dY.dtype, device=dY.device)
+    if "ds" in want and "ds" not in out: out["ds"] = torch.empty((O, _groups(I, group)), dtype=torch.float32, device=dY.device)
+    ws = workspace(d, OP_Q_BWD, dY.device) if ws is None else ws
+    _check("eqat_qlinear_bwd", lib().eqat_qlinear_bwd(ctypes.byref(d), _p(X), _p(Wpacked), _p(s), _p(zpacked), _p(dY),
+                                                      _p(out.get("dX")), _p(out.get("ds")), _p(ws), ws.numel(), _stream()))
+    return out

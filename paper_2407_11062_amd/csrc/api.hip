@@ -1,0 +1,253 @@
+// C ABI of the eqat library: argument checking on the host, workspace carving, kernel dispatch.
+#include <hip/hip_runtime.h>
+
+#include "../../include/eqat.h"
+#include "kernels.h"
+
+using eqat::Problem;
+
+namespace {
+
+constexpr int64_t kMaxTensorBytes = (int64_t)1 << 31;   // buffer descriptors and 32-bit offsets
+
+inline size_t align256(size_t n) { return (n + 255) & ~(size_t)255; }
+inline bool aligned(const void *p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+inline int64_t dsize(int32_t dt) { return dt == EQAT_BF16 ? 2 : 4; }
+
+// Checks everything that does not involve a pointer and fills `p`.  `with_tokens` = the call uses T.
+eqat_status check_desc(const eqat_desc *d, bool with_tokens, Problem *p)
+{
+    if (d == nullptr) return EQAT_ERR_NULL;
+    if ((d->act_dtype != EQAT_F32 && d->act_dtype != EQAT_BF16) || (d->w_dtype != EQAT_F32 && d->w_dtype != EQAT_BF16))
+        return EQAT_ERR_DTYPE;
+    if (d->bits < 2 || d->bits > 4) return EQAT_ERR_BITS;
+    const int64_t T = with_tokens ? d->tokens : 0, I = d->in_features, O = d->out_features;
+    if (T < 0 || I < 1 || O < 1 || I % 32 != 0) return EQAT_ERR_SHAPE;
+    if (I >= kMaxTensorBytes || O >= kMaxTensorBytes || T >= kMaxTensorBytes) return EQAT_ERR_SHAPE;
+    if (O * I * dsize(d->w_dtype) >= kMaxTensorBytes) return EQAT_ERR_SHAPE;
+    if (with_tokens) {
+        if (d->act_dtype == EQAT_BF16 && O % 8 != 0) return EQAT_ERR_SHAPE;
+        if (T * I * dsize(d->act_dtype) >= kMaxTensorBytes || T * O * dsize(d->act_dtype) >= kMaxTensorBytes)
+            return EQAT_ERR_SHAPE;
+    }
+    int64_t g = d->group;
+    if (g == -1) g = I;
+    if (g <= 0 || g % 32 != 0 || I % g != 0) return EQAT_ERR_GROUP;
+    if (p != nullptr) {
+        p->T = T; p->I = I; p->O = O; p->g = g; p->G = I / g; p->bits = d->bits;
+        p->act_bf16 = d->act_dtype == EQAT_BF16; p->w_bf16 = d->w_dtype == EQAT_BF16;
+    }
+    return EQAT_OK;
+}
+
+struct WsLayout { size_t codes, clamp, sz, part, dwhat, total; };
+
+WsLayout ws_layout(const Problem &p, int op)
+{
+    WsLayout l{};
+    size_t off = 0;
+    auto take = [&](size_t bytes) { const size_t at = off; off += align256(bytes); return at; };
+    const size_t codes_b = (size_t)p.O * p.I * p.bits / 8, clamp_b = (size_t)p.O * p.I / 8, sz_b = (size_t)p.O * p.G * 8;
+    const size_t part_b = (size_t)p.O * (p.I / 32) * 4, dwhat_b = (size_t)p.O * p.I * 4;
+    const bool bwd = (op == EQAT_OP_FQ_BWD || op == EQAT_OP_Q_BWD), fq = (op == EQAT_OP_FQ_FWD || op == EQAT_OP_FQ_BWD);
+    if (p.act_bf16) {
+        if (fq) { l.codes = take(codes_b); if (bwd) l.clamp = take(clamp_b); }
+        l.sz = take(sz_b);
+        if (bwd && eqat::dw_needs_partials(p)) l.part = take(2 * part_b);
+    } else {
+        if (!fq) l.sz = take(sz_b);
+        if (bwd) l.dwhat = take(dwhat_b);
+    }
+    l.total = off;
+    return l;
+}
+
+eqat_status check_ws(const WsLayout &l, const void *ws, size_t ws_bytes)
+{
+    if (l.total == 0) return EQAT_OK;
+    if (ws == nullptr || ws_bytes < l.total) return EQAT_ERR_WORKSPACE;
+    if (!aligned(ws, 256)) return EQAT_ERR_ALIGN;
+    return EQAT_OK;
+}
+
+inline eqat_status launch_status() { return hipGetLastError() == hipSuccess ? EQAT_OK : EQAT_ERR_DEVICE; }
+
+#define EQAT_REQUIRE(ptr) do { if ((ptr) == nullptr) return EQAT_ERR_NULL; } while (0)
+#define EQAT_ALIGNED(ptr) do { if (!aligned((ptr), 16)) return EQAT_ERR_ALIGN; } while (0)
+
+}  // namespace
+
+extern "C" {
+
+const char *eqat_status_string(int status)
+{
+    switch (status) {
+    case EQAT_OK: return "ok";
+    case EQAT_ERR_NULL: return "a required pointer is NULL";
+    case EQAT_ERR_SHAPE: return "bad shape (T<0, I or O < 1, I % 32 != 0, O % 8 != 0 with bf16 activations, or a tensor of 2 GiB or more)";
+    case EQAT_ERR_BITS: return "bits must be 2, 3 or 4";
+    case EQAT_ERR_GROUP: return "group must be -1 or a positive multiple of 32 that divides in_features";
+    case EQAT_ERR_DTYPE: return "unknown dtype";
+    case EQAT_ERR_ALIGN: return "pointer not 16-byte aligned (workspace: 256-byte)";
+    case EQAT_ERR_WORKSPACE: return "workspace missing or too small";
+    case EQAT_ERR_DEVICE: return "HIP launch failed";
+    default: return "unknown status";
+    }
+}
+
+eqat_status eqat_validate_desc(const eqat_desc *d) { return check_desc(d, true, nullptr); }
+
+size_t eqat_packed_w_bytes(const eqat_desc *d)
+{
+    Problem p;
+    if (check_desc(d, false, &p) != EQAT_OK) return 0;
+    return (size_t)p.O * p.I * p.bits / 8;
+}
+
+size_t eqat_packed_z_bytes(const eqat_desc *d)
+{
+    Problem p;
+    if (check_desc(d, false, &p) != EQAT_OK) return 0;
+    return (size_t)p.O * 4 * ((p.G * p.bits + 31) / 32);
+}
+
+size_t eqat_workspace_bytes(const eqat_desc *d, int op)
+{
+    Problem p;
+    if (op < EQAT_OP_FQ_FWD || op > EQAT_OP_Q_BWD || check_desc(d, true, &p) != EQAT_OK) return 0;
+    return ws_layout(p, op).total;
+}
+
+eqat_status eqat_init_minmax(const eqat_desc *d, const void *W, float *s, float *z, void *stream)
+{
+    Problem p;
+    if (eqat_status e = check_desc(d, false, &p)) return e;
+    EQAT_REQUIRE(W); EQAT_REQUIRE(s); EQAT_REQUIRE(z);
+    EQAT_ALIGNED(W); EQAT_ALIGNED(s); EQAT_ALIGNED(z);
+    eqat::launch_init_minmax(p, W, s, z, (hipStream_t)stream);
+    return launch_status();
+}
+
+eqat_status eqat_pack(const eqat_desc *d, const void *W, const float *s, const float *z, uint8_t *Wpacked,
+                      uint8_t *zpacked, void *stream)
+{
+    Problem p;
+    if (eqat_status e = check_desc(d, false, &p)) return e;
+    EQAT_REQUIRE(W); EQAT_REQUIRE(s); EQAT_REQUIRE(z); EQAT_REQUIRE(Wpacked); EQAT_REQUIRE(zpacked);
+    EQAT_ALIGNED(W); EQAT_ALIGNED(s); EQAT_ALIGNED(z); EQAT_ALIGNED(Wpacked); EQAT_ALIGNED(zpacked);
+    hipStream_t st = (hipStream_t)stream;
+    eqat::launch_quantize(p, W, s, z, Wpacked, nullptr, nullptr, false, st);
+    eqat::launch_pack_z(p, z, zpacked, st);
+    return launch_status();
+}
+
+eqat_status eqat_unpack(const eqat_desc *d, const uint8_t *Wpacked, const uint8_t *zpacked, int32_t *codes,
+                        int32_t *zcodes, void *stream)
+{
+    Problem p;
+    if (eqat_status e = check_desc(d, false, &p)) return e;
+    if (codes != nullptr) { EQAT_REQUIRE(Wpacked); EQAT_ALIGNED(Wpacked); EQAT_ALIGNED(codes); }
+    if (zcodes != nullptr) { EQAT_REQUIRE(zpacked); EQAT_ALIGNED(zpacked); EQAT_ALIGNED(zcodes); }
+    eqat::launch_unpack(p, Wpacked, zpacked, codes, zcodes, (hipStream_t)stream);
+    return launch_status();
+}
+
+eqat_status eqat_fq_linear_fwd(const eqat_desc *d, const void *X, const void *W, const float *s, const float *z,
+                               void *Y, void *ws, size_t ws_bytes, void *stream)
+{
+    Problem p;
+    if (eqat_status e = check_desc(d, true, &p)) return e;
+    EQAT_REQUIRE(W); EQAT_REQUIRE(s); EQAT_REQUIRE(z);
+    if (p.T > 0) { EQAT_REQUIRE(X); EQAT_REQUIRE(Y); }
+    EQAT_ALIGNED(X); EQAT_ALIGNED(W); EQAT_ALIGNED(s); EQAT_ALIGNED(z); EQAT_ALIGNED(Y);
+    const WsLayout l = ws_layout(p, EQAT_OP_FQ_FWD);
+    if (eqat_status e = check_ws(l, ws, ws_bytes)) return e;
+    if (p.T == 0) return EQAT_OK;
+    hipStream_t st = (hipStream_t)stream;
+    char *w8 = (char *)ws;
+    if (p.act_bf16) {
+        eqat::launch_quantize(p, W, s, z, w8 + l.codes, nullptr, w8 + l.sz, false, st);
+        eqat::launch_mfma_fwd(p, X, w8 + l.codes, w8 + l.sz, Y, st);
+    } else {
+        eqat::launch_f32_fwd(p, false, X, W, s, z, Y, st);
+    }
+    return launch_status();
+}
+
+eqat_status eqat_fq_linear_bwd(const eqat_desc *d, const void *X, const void *W, const float *s, const float *z,
+                               const void *dY, void *dX, void *dW, float *ds, float *dz, void *ws, size_t ws_bytes,
+                               void *stream)
+{
+    Problem p;
+    if (eqat_status e = check_desc(d, true, &p)) return e;
+    EQAT_REQUIRE(W); EQAT_REQUIRE(s); EQAT_REQUIRE(z);
+    const bool want_w = (dW != nullptr || ds != nullptr || dz != nullptr);
+    if (p.T > 0) { EQAT_REQUIRE(dY); if (want_w) EQAT_REQUIRE(X); }
+    EQAT_ALIGNED(X); EQAT_ALIGNED(W); EQAT_ALIGNED(s); EQAT_ALIGNED(z); EQAT_ALIGNED(dY);
+    EQAT_ALIGNED(dX); EQAT_ALIGNED(dW); EQAT_ALIGNED(ds); EQAT_ALIGNED(dz);
+    const WsLayout l = ws_layout(p, EQAT_OP_FQ_BWD);
+    if (eqat_status e = check_ws(l, ws, ws_bytes)) return e;
+    if (dX == nullptr && !want_w) return EQAT_OK;
+    hipStream_t st = (hipStream_t)stream;
+    char *w8 = (char *)ws;
+    if (p.act_bf16) {
+        eqat::launch_quantize(p, W, s, z, w8 + l.codes, w8 + l.clamp, w8 + l.sz, false, st);
+        if (dX != nullptr) eqat::launch_mfma_dx(p, dY, w8 + l.codes, w8 + l.sz, dX, st);
+        if (want_w)
+            eqat::launch_mfma_dw(p, true, X, dY, W, w8 + l.codes, w8 + l.clamp, w8 + l.sz, s, dW, ds, dz,
+                                 (float *)(w8 + l.part), st);
+    } else {
+        if (dX != nullptr && p.T > 0) eqat::launch_f32_dx(p, false, dY, W, s, z, dX, st);
+        if (want_w) eqat::launch_f32_dw(p, true, X, dY, W, s, z, (float *)(w8 + l.dwhat), dW, ds, dz, st);
+    }
+    return launch_status();
+}
+
+eqat_status eqat_qlinear_fwd(const eqat_desc *d, const void *X, const uint8_t *Wpacked, const float *s,
+                             const uint8_t *zpacked, void *Y, void *ws, size_t ws_bytes, void *stream)
+{
+    Problem p;
+    if (eqat_status e = check_desc(d, true, &p)) return e;
+    EQAT_REQUIRE(Wpacked); EQAT_REQUIRE(s); EQAT_REQUIRE(zpacked);
+    if (p.T > 0) { EQAT_REQUIRE(X); EQAT_REQUIRE(Y); }
+    EQAT_ALIGNED(X); EQAT_ALIGNED(Wpacked); EQAT_ALIGNED(s); EQAT_ALIGNED(zpacked); EQAT_ALIGNED(Y);
+    const WsLayout l = ws_layout(p, EQAT_OP_Q_FWD);
+    if (eqat_status e = check_ws(l, ws, ws_bytes)) return e;
+    if (p.T == 0) return EQAT_OK;
+    hipStream_t st = (hipStream_t)stream;
+    char *w8 = (char *)ws;
+    eqat::launch_unpack_sz(p, s, zpacked, w8 + l.sz, st);
+    if (p.act_bf16) eqat::launch_mfma_fwd(p, X, Wpacked, w8 + l.sz, Y, st);
+    else eqat::launch_f32_fwd(p, true, X, Wpacked, s, w8 + l.sz, Y, st);
+    return launch_status();
+}
+
+eqat_status eqat_qlinear_bwd(const eqat_desc *d, const void *X, const uint8_t *Wpacked, const float *s,
+                             const uint8_t *zpacked, const void *dY, void *dX, float *ds, void *ws, size_t ws_bytes,
+                             void *stream)
+{
+    Problem p;
+    if (eqat_status e = check_desc(d, true, &p)) return e;
+    EQAT_REQUIRE(Wpacked); EQAT_REQUIRE(s); EQAT_REQUIRE(zpacked);
+    if (p.T > 0) { EQAT_REQUIRE(dY); if (ds != nullptr) EQAT_REQUIRE(X); }
+    EQAT_ALIGNED(X); EQAT_ALIGNED(Wpacked); EQAT_ALIGNED(s); EQAT_ALIGNED(zpacked); EQAT_ALIGNED(dY);
+    EQAT_ALIGNED(dX); EQAT_ALIGNED(ds);
+    const WsLayout l = ws_layout(p, EQAT_OP_Q_BWD);
+    if (eqat_status e = check_ws(l, ws, ws_bytes)) return e;
+    if (dX == nullptr && ds == nullptr) return EQAT_OK;
+    hipStream_t st = (hipStream_t)stream;
+    char *w8 = (char *)ws;
+    eqat::launch_unpack_sz(p, s, zpacked, w8 + l.sz, st);
+    if (p.act_bf16) {
+        if (dX != nullptr) eqat::launch_mfma_dx(p, dY, Wpacked, w8 + l.sz, dX, st);
+        if (ds != nullptr)
+            eqat::launch_mfma_dw(p, false, X, dY, nullptr, Wpacked, nullptr, w8 + l.sz, s, nullptr, ds, nullptr,
+                                 (float *)(w8 + l.part), st);
+    } else {
+        if (dX != nullptr && p.T > 0) eqat::launch_f32_dx(p, true, dY, Wpacked, s, w8 + l.sz, dX, st);
+        if (ds != nullptr) eqat::launch_f32_dw(p, false, X, dY, Wpacked, s, w8 + l.sz, (float *)(w8 + l.dwhat), nullptr, ds, nullptr, st);
+    }
+    return launch_status();
+}
+
+}  // extern "C"

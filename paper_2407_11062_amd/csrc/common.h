@@ -1,0 +1,92 @@
+// Shared device helpers of the eqat HIP library (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/eqat.h"
+
+namespace eqat {
+
+typedef __bf16 bf16_t;
+typedef bf16_t bf16x8 __attribute__((ext_vector_type(8)));
+typedef bf16_t bf16x4 __attribute__((ext_vector_type(4)));
+typedef bf16_t bf16x2 __attribute__((ext_vector_type(2)));
+typedef short short4v __attribute__((ext_vector_type(4)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef float floatx2 __attribute__((ext_vector_type(2)));
+typedef int intx4 __attribute__((ext_vector_type(4)));
+typedef int intx3 __attribute__((ext_vector_type(3)));
+typedef int intx2 __attribute__((ext_vector_type(2)));
+typedef unsigned int uintx4 __attribute__((ext_vector_type(4)));
+
+// Offset that is out of range for every buffer this library binds (tensors are < 2 GiB):
+// a buffer load from it returns zeros.
+constexpr uint32_t kOobOffset = 0x80000000u;
+
+// A raw buffer resource over [p, p + bytes): loads past the end return 0, stores are dropped.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *p, uint32_t bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p), 0, (int)bytes, 0x00020000);
+}
+
+__device__ __forceinline__ intx4 buf_load16(__amdgpu_buffer_rsrc_t r, uint32_t off)
+{
+    return __builtin_amdgcn_raw_buffer_load_b128(r, (int)off, 0, 0);
+}
+__device__ __forceinline__ intx3 buf_load12(__amdgpu_buffer_rsrc_t r, uint32_t off)
+{
+    return __builtin_amdgcn_raw_buffer_load_b96(r, (int)off, 0, 0);
+}
+__device__ __forceinline__ intx2 buf_load8(__amdgpu_buffer_rsrc_t r, uint32_t off)
+{
+    return __builtin_amdgcn_raw_buffer_load_b64(r, (int)off, 0, 0);
+}
+__device__ __forceinline__ int buf_load4(__amdgpu_buffer_rsrc_t r, uint32_t off)
+{
+    return __builtin_amdgcn_raw_buffer_load_b32(r, (int)off, 0, 0);
+}
+
+__device__ __forceinline__ float bf16_bits_to_float(uint32_t hi16_in_low)
+{
+    return __uint_as_float(hi16_in_low << 16);
+}
+
+// N words (N = BITS) hold 32 codes of BITS bits, little-endian bit stream.
+template <int BITS> struct CodeWords { uint32_t w[BITS]; };
+
+template <int BITS>
+__device__ __forceinline__ CodeWords<BITS> load_code_words(__amdgpu_buffer_rsrc_t r, uint32_t off)
+{
+    CodeWords<BITS> c;
+    if constexpr (BITS == 2) { intx2 v = buf_load8(r, off); c.w[0] = v[0]; c.w[1] = v[1]; }
+    else if constexpr (BITS == 3) { intx3 v = buf_load12(r, off); c.w[0] = v[0]; c.w[1] = v[1]; c.w[2] = v[2]; }
+    else { intx4 v = buf_load16(r, off); c.w[0] = v[0]; c.w[1] = v[1]; c.w[2] = v[2]; c.w[3] = v[3]; }
+    return c;
+}
+
+// Code number IDX (compile time) of a 32-code segment.
+template <int BITS, int IDX>
+__device__ __forceinline__ uint32_t code_at(const CodeWords<BITS> &c)
+{
+    constexpr int bit = IDX * BITS, wi = bit >> 5, sh = bit & 31;
+    constexpr uint32_t mask = (1u << BITS) - 1u;
+    if constexpr (sh + BITS <= 32) return (c.w[wi] >> sh) & mask;
+    else return ((c.w[wi] >> sh) | (c.w[wi + 1] << (32 - sh))) & mask;
+}
+
+// Runtime-indexed variant (slow paths only).
+template <int BITS>
+__device__ __forceinline__ uint32_t code_at_rt(const uint32_t *words, int idx)
+{
+    const int bit = idx * BITS, wi = bit >> 5, sh = bit & 31;
+    const uint32_t mask = (1u << BITS) - 1u;
+    uint64_t two = words[wi];
+    if (sh + BITS > 32) two |= (uint64_t)words[wi + 1] << 32;
+    return (uint32_t)(two >> sh) & mask;
+}
+
+__device__ __forceinline__ float to_float(float v) { return v; }
+__device__ __forceinline__ float to_float(bf16_t v) { return (float)v; }
+
+}  // namespace eqat

@@ -1,0 +1,540 @@
+// bf16 MFMA GEMMs of the quantized linear layer (gfx950, v_mfma_f32_32x32x16_bf16).
+//
+//   fwd :  Y [T,O]  = X [T,I]  * What[O,I]^T        (K = I)
+//   dX  :  dX[T,I]  = dY[T,O]  * What[O,I]          (K = O)
+//   dW  :  dWhat^T[I,O] = X[T,I]^T * dY[T,O]        (K = T), fused with the Eq.(3)-(5) epilogue
+//
+// What is never in HBM: the weight operand of fwd / dX is rebuilt per tile, in registers, from packed
+// N-bit codes and the (s, zbar) pair of each group, and written to LDS as bf16.
+//
+// Two LDS tile formats feed the MFMA operands:
+//   KC  "K contiguous"  [row][BK + 8]      fragment = one ds_read_b128 per lane
+//   KM  "K major"       [k][cols + 32]     fragment = two ds_read_b64_tr_b16 (LDS transpose reads)
+// The paddings make both read patterns bank-conflict free.
+#include "common.h"
+#include "kernels.h"
+
+namespace eqat {
+
+constexpr int kPadKC = 8;    // bf16 elements
+constexpr int kPadKM = 32;
+
+// ---- fragment reads ---------------------------------------------------------------------------------
+// KC tile: lane l supplies row (l % 32), k = kk*16 + (l / 32) * 8 .. + 8
+template <int LD>
+__device__ __forceinline__ bf16x8 frag_kc(const bf16_t *tile, int row0, int kk, int lane)
+{
+    return *reinterpret_cast<const bf16x8 *>(tile + (row0 + (lane & 31)) * LD + kk * 16 + (lane >> 5) * 8);
+}
+// KM tile: the transpose read hands lane i (of each 16-lane block) four k-consecutive values of column
+// i, gathered from the lanes that addressed rows k..k+3.  Block b = lane/16: columns 16*(b&1).., k half b>>1.
+template <int LD>
+__device__ __forceinline__ bf16x8 frag_km(const bf16_t *tile, int col0, int kk, int lane)
+{
+    const int i = lane & 15, b = lane >> 4;
+    const bf16_t *p = tile + (kk * 16 + (b >> 1) * 8 + (i >> 2)) * LD + col0 + (b & 1) * 16 + (i & 3) * 4;
+    typedef short4v __attribute__((address_space(3))) * lds_p;
+    const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_p)(p));
+    const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_p)(p + 4 * LD));
+    typedef short short8v __attribute__((ext_vector_type(8)));
+    short8v r = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, r);
+}
+
+// ---- 32 codes -> 32 bf16 of What ------------------------------------------------------------------------
+template <int BITS, int K0>
+__device__ __forceinline__ bf16x8 dequant8(const CodeWords<BITS> &c, float s, float b)
+{
+    bf16x8 o;
+#define EQAT_DQ(J) o[J] = (bf16_t)__builtin_fmaf((float)code_at<BITS, K0 + J>(c), s, b)
+    EQAT_DQ(0); EQAT_DQ(1); EQAT_DQ(2); EQAT_DQ(3); EQAT_DQ(4); EQAT_DQ(5); EQAT_DQ(6); EQAT_DQ(7);
+#undef EQAT_DQ
+    return o;
+}
+
+// ---- workgroup -> tile mapping ---------------------------------------------------------------------------
+// Consecutive workgroup ids go round-robin over the 8 XCDs, each with its own L2.  Give every XCD a
+// contiguous range of tile ids, then walk the tiles in bands of 8 tile-rows so that the tiles resident on
+// one XCD at a time share their operand panels.
+__device__ __forceinline__ void tile_of_block(int tiles_m, int tiles_n, int &tm, int &tn)
+{
+    const int nb = gridDim.x, bid = blockIdx.x;
+    const int xcd = bid & 7, loc = bid >> 3, per = nb >> 3, rem = nb & 7;
+    const int pid = (xcd < rem ? xcd * (per + 1) : rem * (per + 1) + (xcd - rem) * per) + loc;
+    constexpr int kBand = 8;
+    const int width = kBand * tiles_n, band = pid / width, first = band * kBand;
+    const int rows = min(tiles_m - first, kBand), in = pid - band * width;
+    tm = first + in % rows;
+    tn = in / rows;
+}
+
+// ======================================================================================================
+// fwd / dX:  C[M,N] = A[M,K] * B,  A plain bf16 (K contiguous), B = What rebuilt from codes.
+//   BT = false (fwd): B element (k, n) = What[n][k]   -> weight tile is KC  [BN][BK]
+//   BT = true  (dX) : B element (k, n) = What[k][n]   -> weight tile is KM  [BK][BN]
+// ======================================================================================================
+struct GemmQArgs {
+    const bf16_t *A; const uint32_t *codes; const floatx2 *sz; bf16_t *C;
+    int M, N, K;           // problem
+    int I, G, g;           // weight matrix geometry: row length, groups per row, group size
+    uint32_t a_bytes, codes_bytes, sz_bytes;
+    int tiles_m, tiles_n;
+};
+
+template <int BITS, bool BT, int BM, int BN, int BK, int WGM, int WGN>
+__global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_q(const GemmQArgs a)
+{
+    constexpr int NT = 64 * WGM * WGN, WTM = BM / WGM, WTN = BN / WGN, MI = WTM / 32, NI = WTN / 32;
+    constexpr int LDA = BK + kPadKC;
+    constexpr int LDB = BT ? BN + kPadKM : BK + kPadKC;
+    constexpr int A_ELEMS = BM * LDA, B_ELEMS = BT ? BK * LDB : BN * LDB;
+    constexpr int A_CHUNKS = BM * BK / 8 / NT;        // 16-byte chunks per thread
+    constexpr int B_SEGS = BN * BK / 32 / NT;         // 32-code segments per thread
+    static_assert(BM * BK / 8 % NT == 0 && BN * BK / 32 % NT == 0 && BK % 32 == 0, "tile / thread mismatch");
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    bf16_t *sA = reinterpret_cast<bf16_t *>(smem_raw);            // [2][A_ELEMS]
+    bf16_t *sB = sA + 2 * A_ELEMS;                                // [2][B_ELEMS]
+
+    int tm, tn;
+    tile_of_block(a.tiles_m, a.tiles_n, tm, tn);
+    const int m0 = tm * BM, n0 = tn * BN;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wm = wave / WGN, wn = wave % WGN;
+
+    const __amdgpu_buffer_rsrc_t rA = make_rsrc(a.A, a.a_bytes);
+    const __amdgpu_buffer_rsrc_t rC = make_rsrc(a.codes, a.codes_bytes);
+    const __amdgpu_buffer_rsrc_t rS = make_rsrc(a.sz, a.sz_bytes);
+    const uint32_t code_row_bytes = (uint32_t)a.I * BITS / 8;
+
+    intx4 stA[A_CHUNKS];
+    CodeWords<BITS> stC[B_SEGS];
+    floatx2 stS[B_SEGS];
+
+    auto load_global = [&](int k0) {
+#pragma unroll
+        for (int it = 0; it < A_CHUNKS; ++it) {
+            const int c = it * NT + tid, row = c / (BK / 8), kc = c % (BK / 8);
+            const int k = k0 + kc * 8;
+            const uint32_t off = (k < a.K) ? ((uint32_t)(m0 + row) * (uint32_t)a.K + (uint32_t)k) * 2u : kOobOffset;
+            stA[it] = buf_load16(rA, off);
+        }
+#pragma unroll
+        for (int it = 0; it < B_SEGS; ++it) {
+            const int sidx = it * NT + tid;
+            int wrow, wcol;   // position in the weight matrix [O][I]
+            if (!BT) { wrow = n0 + sidx / (BK / 32); wcol = k0 + (sidx % (BK / 32)) * 32; }
+            else     { wrow = k0 + sidx / (BN / 32); wcol = n0 + (sidx % (BN / 32)) * 32; }
+            const bool ok = wcol < a.I;
+            stC[it] = load_code_words<BITS>(rC, (uint32_t)wrow * code_row_bytes + (uint32_t)(wcol >> 5) * (4u * BITS));
+            const intx2 sv = buf_load8(rS, ok ? ((uint32_t)wrow * (uint32_t)a.G + (uint32_t)(wcol / a.g)) * 8u : kOobOffset);
+            stS[it][0] = __int_as_float(sv[0]);
+            stS[it][1] = __int_as_float(sv[1]);
+        }
+    };
+    auto store_lds = [&](int buf) {
+        bf16_t *dA = sA + buf * A_ELEMS, *dB = sB + buf * B_ELEMS;
+#pragma unroll
+        for (int it = 0; it < A_CHUNKS; ++it) {
+            const int c = it * NT + tid, row = c / (BK / 8), kc = c % (BK / 8);
+            *reinterpret_cast<intx4 *>(dA + row * LDA + kc * 8) = stA[it];
+        }
+#pragma unroll
+        for (int it = 0; it < B_SEGS; ++it) {
+            const int sidx = it * NT + tid;
+            int r, c;
+            if (!BT) { r = sidx / (BK / 32); c = (sidx % (BK / 32)) * 32; }
+            else     { r = sidx / (BN / 32); c = (sidx % (BN / 32)) * 32; }
+            const float s = stS[it][0], b = -stS[it][1] * s;     // What = code*s - zbar*s
+            bf16x8 *dst = reinterpret_cast<bf16x8 *>(dB + r * LDB + c);
+            dst[0] = dequant8<BITS, 0>(stC[it], s, b);
+            dst[1] = dequant8<BITS, 8>(stC[it], s, b);
+            dst[2] = dequant8<BITS, 16>(stC[it], s, b);
+            dst[3] = dequant8<BITS, 24>(stC[it], s, b);
+        }
+    };
+
+    floatx16 acc[MI][NI];
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NI; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+    const int nk = (a.K + BK - 1) / BK;
+    load_global(0);
+    store_lds(0);
+    __syncthreads();
+    for (int kt = 0; kt < nk; ++kt) {
+        const int buf = kt & 1;
+        if (kt + 1 < nk) load_global((kt + 1) * BK);
+        const bf16_t *cA = sA + buf * A_ELEMS, *cB = sB + buf * B_ELEMS;
+#pragma unroll
+        for (int kk = 0; kk < BK / 16; ++kk) {
+            bf16x8 fa[MI], fb[NI];
+#pragma unroll
+            for (int i = 0; i < MI; ++i) fa[i] = frag_kc<LDA>(cA, wm * WTM + i * 32, kk, lane);
+#pragma unroll
+            for (int j = 0; j < NI; ++j) {
+                if (!BT) fb[j] = frag_kc<LDB>(cB, wn * WTN + j * 32, kk, lane);
+                else     fb[j] = frag_km<LDB>(cB, wn * WTN + j * 32, kk, lane);
+            }
+#pragma unroll
+            for (int i = 0; i < MI; ++i)
+#pragma unroll
+                for (int j = 0; j < NI; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+        }
+        if (kt + 1 < nk) store_lds(buf ^ 1);
+        __syncthreads();
+    }
+
+    // C[m][n]: lane holds column n = l % 32 and rows 8*(r/4) + 4*(l/32) + r%4 of each 32x32 block
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NI; ++j) {
+            const int n = n0 + wn * WTN + j * 32 + (lane & 31);
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int m = m0 + wm * WTM + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                if (m < a.M && n < a.N) a.C[(size_t)m * a.N + n] = (bf16_t)acc[i][j][r];
+            }
+        }
+}
+
+// ======================================================================================================
+// dW:  D[i][o] = sum_t X[t][i] * dY[t][o]   (M <-> i, N <-> o, K = T; both operand tiles KM)
+// and, on the accumulators, for every weight (o, i):
+//   Block-AP:  clamped = bit of the clamp plane; q = code; r = q - zbar
+//              cs = clamped ? r : r - w/s ;  dW = clamped ? 0 : D ;  ds += D*cs ;  dz += clamped ? -s*D : 0
+//   E2E-QP  :  ds += D * (q - z)
+// M <-> i puts the 32 columns of a group segment into the registers of one lane pair, so the group sums
+// need one cross-lane exchange per 32x32 block.
+// ======================================================================================================
+struct GemmDwArgs {
+    const bf16_t *X, *dY; const void *W; const uint32_t *codes; const uint8_t *clampbits; const floatx2 *sz;
+    void *dW; float *ds, *dz, *part_ds, *part_dz;
+    int T, I, O, G, g;
+    uint32_t x_bytes, dy_bytes, w_bytes, codes_bytes, clamp_bytes, sz_bytes;
+    int tiles_m, tiles_n;
+    int direct;           // 1: every group lies inside one tile -> final ds/dz; 0: per-32-column partials
+};
+
+template <typename WT> struct WQuad;     // four consecutive weights of one row
+template <> struct WQuad<bf16_t> {
+    float v[4];
+    __device__ __forceinline__ void load(__amdgpu_buffer_rsrc_t r, uint32_t elem)
+    {
+        const intx2 u = buf_load8(r, elem * 2u);
+        v[0] = __uint_as_float((uint32_t)u[0] << 16); v[1] = __uint_as_float((uint32_t)u[0] & 0xFFFF0000u);
+        v[2] = __uint_as_float((uint32_t)u[1] << 16); v[3] = __uint_as_float((uint32_t)u[1] & 0xFFFF0000u);
+    }
+    static __device__ __forceinline__ void store(void *base, size_t elem, const float (&d)[4])
+    {
+        bf16x4 o; o[0] = (bf16_t)d[0]; o[1] = (bf16_t)d[1]; o[2] = (bf16_t)d[2]; o[3] = (bf16_t)d[3];
+        *reinterpret_cast<bf16x4 *>(reinterpret_cast<bf16_t *>(base) + elem) = o;
+    }
+};
+template <> struct WQuad<float> {
+    float v[4];
+    __device__ __forceinline__ void load(__amdgpu_buffer_rsrc_t r, uint32_t elem)
+    {
+        const intx4 u = buf_load16(r, elem * 4u);
+        v[0] = __int_as_float(u[0]); v[1] = __int_as_float(u[1]); v[2] = __int_as_float(u[2]); v[3] = __int_as_float(u[3]);
+    }
+    static __device__ __forceinline__ void store(void *base, size_t elem, const float (&d)[4])
+    {
+        floatx4 o; o[0] = d[0]; o[1] = d[1]; o[2] = d[2]; o[3] = d[3];
+        *reinterpret_cast<floatx4 *>(reinterpret_cast<float *>(base) + elem) = o;
+    }
+};
+
+template <int BITS, typename WT, bool BLOCK_AP, int BM, int BN, int BK, int WGM, int WGN>
+__global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_dw(const GemmDwArgs a)
+{
+    constexpr int NT = 64 * WGM * WGN, WTM = BM / WGM, WTN = BN / WGN, MI = WTM / 32, NI = WTN / 32;
+    constexpr int LDA = BM + kPadKM, LDB = BN + kPadKM;
+    constexpr int A_ELEMS = BK * LDA, B_ELEMS = BK * LDB;
+    constexpr int A_CHUNKS = BK * BM / 8 / NT, B_CHUNKS = BK * BN / 8 / NT;
+    static_assert(BK * BM / 8 % NT == 0 && BK * BN / 8 % NT == 0, "tile / thread mismatch");
+    static_assert(2 * (A_ELEMS + B_ELEMS) * 2 >= 2 * (BM / 32) * BN * 4, "partials must fit in the tile buffers");
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    bf16_t *sA = reinterpret_cast<bf16_t *>(smem_raw);
+    bf16_t *sB = sA + 2 * A_ELEMS;
+
+    int tm, tn;
+    tile_of_block(a.tiles_m, a.tiles_n, tm, tn);
+    const int m0 = tm * BM, n0 = tn * BN;      // m0: first in-feature i, n0: first out-feature o
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wm = wave / WGN, wn = wave % WGN;
+
+    const __amdgpu_buffer_rsrc_t rX = make_rsrc(a.X, a.x_bytes);
+    const __amdgpu_buffer_rsrc_t rY = make_rsrc(a.dY, a.dy_bytes);
+
+    intx4 stA[A_CHUNKS], stB[B_CHUNKS];
+    auto load_global = [&](int k0) {
+#pragma unroll
+        for (int it = 0; it < A_CHUNKS; ++it) {
+            const int c = it * NT + tid, row = c / (BM / 8), cc = c % (BM / 8);
+            const int col = m0 + cc * 8;
+            stA[it] = buf_load16(rX, col < a.I ? ((uint32_t)(k0 + row) * (uint32_t)a.I + (uint32_t)col) * 2u : kOobOffset);
+        }
+#pragma unroll
+        for (int it = 0; it < B_CHUNKS; ++it) {
+            const int c = it * NT + tid, row = c / (BN / 8), cc = c % (BN / 8);
+            const int col = n0 + cc * 8;
+            stB[it] = buf_load16(rY, col < a.O ? ((uint32_t)(k0 + row) * (uint32_t)a.O + (uint32_t)col) * 2u : kOobOffset);
+        }
+    };
+    auto store_lds = [&](int buf) {
+        bf16_t *dA = sA + buf * A_ELEMS, *dB = sB + buf * B_ELEMS;
+#pragma unroll
+        for (int it = 0; it < A_CHUNKS; ++it) {
+            const int c = it * NT + tid, row = c / (BM / 8), cc = c % (BM / 8);
+            *reinterpret_cast<intx4 *>(dA + row * LDA + cc * 8) = stA[it];
+        }
+#pragma unroll
+        for (int it = 0; it < B_CHUNKS; ++it) {
+            const int c = it * NT + tid, row = c / (BN / 8), cc = c % (BN / 8);
+            *reinterpret_cast<intx4 *>(dB + row * LDB + cc * 8) = stB[it];
+        }
+    };
+
+    floatx16 acc[MI][NI];
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NI; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+    const int nk = (a.T + BK - 1) / BK;
+    if (nk > 0) {
+        load_global(0);
+        store_lds(0);
+    }
+    __syncthreads();
+    for (int kt = 0; kt < nk; ++kt) {
+        const int buf = kt & 1;
+        if (kt + 1 < nk) load_global((kt + 1) * BK);
+        const bf16_t *cA = sA + buf * A_ELEMS, *cB = sB + buf * B_ELEMS;
+#pragma unroll
+        for (int kk = 0; kk < BK / 16; ++kk) {
+            bf16x8 fa[MI], fb[NI];
+#pragma unroll
+            for (int i = 0; i < MI; ++i) fa[i] = frag_km<LDA>(cA, wm * WTM + i * 32, kk, lane);
+#pragma unroll
+            for (int j = 0; j < NI; ++j) fb[j] = frag_km<LDB>(cB, wn * WTN + j * 32, kk, lane);
+#pragma unroll
+            for (int i = 0; i < MI; ++i)
+#pragma unroll
+                for (int j = 0; j < NI; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+        }
+        if (kt + 1 < nk) store_lds(buf ^ 1);
+        __syncthreads();
+    }
+
+    // ---- epilogue ----------------------------------------------------------------------------------
+    float *p_ds = reinterpret_cast<float *>(smem_raw);            // [BM/32][BN]
+    float *p_dz = p_ds + (BM / 32) * BN;
+    const __amdgpu_buffer_rsrc_t rC = make_rsrc(a.codes, a.codes_bytes);
+    const __amdgpu_buffer_rsrc_t rS = make_rsrc(a.sz, a.sz_bytes);
+    const __amdgpu_buffer_rsrc_t rW = make_rsrc(a.W, a.w_bytes);
+    const __amdgpu_buffer_rsrc_t rB = make_rsrc(a.clampbits, a.clamp_bytes);
+    const uint32_t code_row_bytes = (uint32_t)a.I * BITS / 8;
+    const int h = lane >> 5;
+
+#pragma unroll
+    for (int j = 0; j < NI; ++j) {
+        const int ol = wn * WTN + j * 32 + (lane & 31), o = n0 + ol;
+#pragma unroll
+        for (int i = 0; i < MI; ++i) {
+            const int ib = m0 + wm * WTM + i * 32;                 // first of 32 in-features; whole block valid or not
+            const bool valid = (o < a.O) && (ib < a.I);
+            CodeWords<BITS> cw = load_code_words<BITS>(rC, valid ? (uint32_t)o * code_row_bytes + (uint32_t)(ib >> 5) * (4u * BITS) : kOobOffset);
+            // this lane owns codes 8a + 4h + b (a, b in 0..3): shift the stream right by 4h codes
+            {
+                const uint32_t sh = (uint32_t)h * 4u * BITS;
+#pragma unroll
+                for (int k = 0; k < BITS; ++k) {
+                    const uint32_t hi = (k + 1 < BITS) ? cw.w[k + 1] : 0u;
+                    cw.w[k] = (uint32_t)(((uint64_t)hi << 32 | cw.w[k]) >> sh);
+                }
+            }
+            const intx2 sv = buf_load8(rS, valid ? ((uint32_t)o * (uint32_t)a.G + (uint32_t)(ib / a.g)) * 8u : kOobOffset);
+            const float s = __int_as_float(sv[0]), zb = __int_as_float(sv[1]);
+            float sum_s = 0.0f, sum_z = 0.0f;
+            if constexpr (BLOCK_AP) {
+                const uint32_t cl = (uint32_t)buf_load4(rB, valid ? (uint32_t)o * (uint32_t)(a.I >> 3) + (uint32_t)(ib >> 3) : kOobOffset) >> (4 * h);
+                const float rinv = valid ? 1.0f / s : 0.0f;
+                WQuad<WT> wq[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    wq[q].load(rW, valid ? (uint32_t)o * (uint32_t)a.I + (uint32_t)(ib + 8 * q + 4 * h) : (kOobOffset / (uint32_t)sizeof(WT)));
+#define EQAT_ELEM(Q, B)                                                                                   \
+    {                                                                                                     \
+        const float d = acc[i][j][(Q) * 4 + (B)];                                                         \
+        const float r = (float)code_at<BITS, (Q) * 8 + (B)>(cw) - zb;                                     \
+        const bool clamped = (cl >> ((Q) * 8 + (B))) & 1u;                                                \
+        const float cs = clamped ? r : r - wq[Q].v[B] * rinv;                                             \
+        sum_s = __builtin_fmaf(d, cs, sum_s);                                                             \
+        sum_z += clamped ? d : 0.0f;                                                                      \
+        dwv[B] = clamped ? 0.0f : d;                                                                      \
+    }
+#define EQAT_QUAD(Q)                                                                                      \
+    {                                                                                                     \
+        float dwv[4];                                                                                     \
+        EQAT_ELEM(Q, 0) EQAT_ELEM(Q, 1) EQAT_ELEM(Q, 2) EQAT_ELEM(Q, 3)                                   \
+        if (a.dW != nullptr && valid) WQuad<WT>::store(a.dW, (size_t)o * a.I + (ib + 8 * (Q) + 4 * h), dwv); \
+    }
+                EQAT_QUAD(0) EQAT_QUAD(1) EQAT_QUAD(2) EQAT_QUAD(3)
+#undef EQAT_QUAD
+#undef EQAT_ELEM
+            } else {
+#define EQAT_ELEM(Q, B) sum_s = __builtin_fmaf(acc[i][j][(Q) * 4 + (B)], (float)code_at<BITS, (Q) * 8 + (B)>(cw) - zb, sum_s);
+#define EQAT_QUAD(Q) EQAT_ELEM(Q, 0) EQAT_ELEM(Q, 1) EQAT_ELEM(Q, 2) EQAT_ELEM(Q, 3)
+                EQAT_QUAD(0) EQAT_QUAD(1) EQAT_QUAD(2) EQAT_QUAD(3)
+#undef EQAT_QUAD
+#undef EQAT_ELEM
+            }
+            sum_s += __shfl_xor(sum_s, 32);
+            if (BLOCK_AP) sum_z += __shfl_xor(sum_z, 32);
+            if (h == 0) {
+                p_ds[(wm * MI + i) * BN + ol] = sum_s;
+                if (BLOCK_AP) p_dz[(wm * MI + i) * BN + ol] = sum_z;
+            }
+        }
+    }
+    __syncthreads();
+    if (a.direct) {
+        // every group of this tile's rows is complete here: sum its g/32 block partials in order
+        const int bpg = a.g >> 5, gpt = BM / a.g;
+        for (int e = tid; e < gpt * BN; e += NT) {
+            const int ol = e % BN, gi = e / BN, o = n0 + ol, i0 = m0 + gi * a.g;
+            if (o >= a.O || i0 >= a.I) continue;
+            float vs = 0.0f, vz = 0.0f;
+            for (int k = 0; k < bpg; ++k) {
+                vs += p_ds[(gi * bpg + k) * BN + ol];
+                if (BLOCK_AP) vz += p_dz[(gi * bpg + k) * BN + ol];
+            }
+            const size_t gidx = (size_t)o * a.G + i0 / a.g;
+            if (a.ds != nullptr) a.ds[gidx] = vs;
+            if (BLOCK_AP && a.dz != nullptr) a.dz[gidx] = -a.sz[gidx][0] * vz;
+        }
+    } else {
+        const int nb32 = a.I >> 5;
+        for (int e = tid; e < (BM / 32) * BN; e += NT) {
+            const int ol = e % BN, blk = e / BN, o = n0 + ol, i0 = m0 + blk * 32;
+            if (o >= a.O || i0 >= a.I) continue;
+            a.part_ds[(size_t)o * nb32 + (i0 >> 5)] = p_ds[blk * BN + ol];
+            if (BLOCK_AP) a.part_dz[(size_t)o * nb32 + (i0 >> 5)] = p_dz[blk * BN + ol];
+        }
+    }
+}
+
+// ======================================================================================================
+// host side
+// ======================================================================================================
+namespace {
+
+struct TileShape { static constexpr int BM = 128, BN = 128, BK = 64, WGM = 2, WGN = 2; };
+
+template <int BITS, bool BT, typename TS>
+void launch_q(const GemmQArgs &args, hipStream_t st)
+{
+    constexpr int LDA = TS::BK + kPadKC, LDB = BT ? TS::BN + kPadKM : TS::BK + kPadKC;
+    constexpr size_t smem = 2 * (size_t)(TS::BM * LDA + (BT ? TS::BK * LDB : TS::BN * LDB)) * sizeof(bf16_t);
+    auto kern = k_gemm_q<BITS, BT, TS::BM, TS::BN, TS::BK, TS::WGM, TS::WGN>;
+    static bool attr_set = false;
+    if (!attr_set) { (void)hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem); attr_set = true; }
+    GemmQArgs a = args;
+    a.tiles_m = (a.M + TS::BM - 1) / TS::BM;
+    a.tiles_n = (a.N + TS::BN - 1) / TS::BN;
+    kern<<<dim3(a.tiles_m * a.tiles_n), dim3(64 * TS::WGM * TS::WGN), smem, st>>>(a);
+}
+
+template <bool BT>
+void launch_q_bits(int bits, const GemmQArgs &args, hipStream_t st)
+{
+    if (bits == 2) launch_q<2, BT, TileShape>(args, st);
+    else if (bits == 3) launch_q<3, BT, TileShape>(args, st);
+    else launch_q<4, BT, TileShape>(args, st);
+}
+
+template <int BITS, typename WT, bool AP, typename TS>
+void launch_dw_t(const GemmDwArgs &args, hipStream_t st)
+{
+    constexpr size_t smem = 2 * (size_t)TS::BK * ((TS::BM + kPadKM) + (TS::BN + kPadKM)) * sizeof(bf16_t);
+    auto kern = k_gemm_dw<BITS, WT, AP, TS::BM, TS::BN, TS::BK, TS::WGM, TS::WGN>;
+    static bool attr_set = false;
+    if (!attr_set) { (void)hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem); attr_set = true; }
+    GemmDwArgs a = args;
+    a.tiles_m = (a.I + TS::BM - 1) / TS::BM;
+    a.tiles_n = (a.O + TS::BN - 1) / TS::BN;
+    a.direct = (TS::BM % a.g == 0) ? 1 : 0;
+    kern<<<dim3(a.tiles_m * a.tiles_n), dim3(64 * TS::WGM * TS::WGN), smem, st>>>(a);
+}
+
+template <typename WT, bool AP>
+void launch_dw_bits(int bits, const GemmDwArgs &args, hipStream_t st)
+{
+    if (bits == 2) launch_dw_t<2, WT, AP, TileShape>(args, st);
+    else if (bits == 3) launch_dw_t<3, WT, AP, TileShape>(args, st);
+    else launch_dw_t<4, WT, AP, TileShape>(args, st);
+}
+
+}  // namespace
+
+bool dw_needs_partials(const Problem &p) { return TileShape::BM % p.g != 0; }
+
+void launch_mfma_fwd(const Problem &p, const void *X, const void *codes, const void *sz, void *Y, hipStream_t st)
+{
+    if (p.T == 0) return;
+    GemmQArgs a{};
+    a.A = (const bf16_t *)X; a.codes = (const uint32_t *)codes; a.sz = (const floatx2 *)sz; a.C = (bf16_t *)Y;
+    a.M = (int)p.T; a.N = (int)p.O; a.K = (int)p.I; a.I = (int)p.I; a.G = (int)p.G; a.g = (int)p.g;
+    a.a_bytes = (uint32_t)(p.T * p.I * 2); a.codes_bytes = (uint32_t)(p.O * p.I * p.bits / 8); a.sz_bytes = (uint32_t)(p.O * p.G * 8);
+    launch_q_bits<false>(p.bits, a, st);
+}
+
+void launch_mfma_dx(const Problem &p, const void *dY, const void *codes, const void *sz, void *dX, hipStream_t st)
+{
+    if (p.T == 0) return;
+    GemmQArgs a{};
+    a.A = (const bf16_t *)dY; a.codes = (const uint32_t *)codes; a.sz = (const floatx2 *)sz; a.C = (bf16_t *)dX;
+    a.M = (int)p.T; a.N = (int)p.I; a.K = (int)p.O; a.I = (int)p.I; a.G = (int)p.G; a.g = (int)p.g;
+    a.a_bytes = (uint32_t)(p.T * p.O * 2); a.codes_bytes = (uint32_t)(p.O * p.I * p.bits / 8); a.sz_bytes = (uint32_t)(p.O * p.G * 8);
+    launch_q_bits<true>(p.bits, a, st);
+}
+
+void launch_mfma_dw(const Problem &p, bool block_ap, const void *X, const void *dY, const void *W, const void *codes,
+                    const void *clampbits, const void *sz, const float *s, void *dW, float *ds, float *dz, float *part,
+                    hipStream_t st)
+{
+    GemmDwArgs a{};
+    a.X = (const bf16_t *)X; a.dY = (const bf16_t *)dY; a.W = W; a.codes = (const uint32_t *)codes;
+    a.clampbits = (const uint8_t *)clampbits; a.sz = (const floatx2 *)sz;
+    a.dW = dW; a.ds = ds; a.dz = dz;
+    a.T = (int)p.T; a.I = (int)p.I; a.O = (int)p.O; a.G = (int)p.G; a.g = (int)p.g;
+    a.x_bytes = (uint32_t)(p.T * p.I * 2); a.dy_bytes = (uint32_t)(p.T * p.O * 2);
+    a.w_bytes = (uint32_t)(p.O * p.I * (p.w_bf16 ? 2 : 4)); a.codes_bytes = (uint32_t)(p.O * p.I * p.bits / 8);
+    a.clamp_bytes = (uint32_t)(p.O * p.I / 8); a.sz_bytes = (uint32_t)(p.O * p.G * 8);
+    const bool partials = dw_needs_partials(p);
+    const size_t n32 = (size_t)p.O * (p.I / 32);
+    a.part_ds = part; a.part_dz = part ? part + n32 : nullptr;
+    if (block_ap) {
+        if (p.w_bf16) launch_dw_bits<bf16_t, true>(p.bits, a, st);
+        else launch_dw_bits<float, true>(p.bits, a, st);
+    } else {
+        launch_dw_bits<bf16_t, false>(p.bits, a, st);
+    }
+    if (partials) {
+        const uint32_t n_per = (uint32_t)(p.g / 32);
+        if (ds != nullptr) launch_reduce_partials(a.part_ds, ds, s, (size_t)p.O * p.G, n_per, false, st);
+        if (block_ap && dz != nullptr) launch_reduce_partials(a.part_dz, dz, s, (size_t)p.O * p.G, n_per, true, st);
+    }
+}
+
+}  // namespace eqat

@@ -1,0 +1,50 @@
+// Internal launcher interface between the C ABI (api.hip) and the kernel files.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace eqat {
+
+struct Problem {
+    int64_t T, I, O, g, G;
+    int bits;
+    bool act_bf16, w_bf16;
+};
+
+// ---- quant.hip -------------------------------------------------------------------------------
+// Eq.(1): W,s,z -> packed codes (+ optional clamp bit-plane [O,I/8] bytes, + optional (s,zbar) pairs [O,G]).
+void launch_quantize(const Problem &p, const void *W, const float *s, const float *z, void *codes, void *clampbits,
+                     void *sz, bool clamp_z, hipStream_t st);
+void launch_pack_z(const Problem &p, const float *z, void *zpacked, hipStream_t st);
+void launch_unpack_sz(const Problem &p, const float *s, const void *zpacked, void *sz, hipStream_t st);
+void launch_unpack(const Problem &p, const void *Wpacked, const void *zpacked, int32_t *codes, int32_t *zcodes, hipStream_t st);
+void launch_init_minmax(const Problem &p, const void *W, float *s, float *z, hipStream_t st);
+void launch_reduce_partials(const float *part, float *out, const float *s, size_t n_out, uint32_t n_per, bool scale_by_s,
+                            hipStream_t st);
+void launch_fill_zero(void *p, size_t bytes, hipStream_t st);
+
+// ---- gemm_mfma.hip (bf16 activations) -----------------------------------------------------------
+// Y[T,O] = X[T,I] * What[O,I]^T with What = (code - zbar) * s rebuilt per tile from packed codes.
+void launch_mfma_fwd(const Problem &p, const void *X, const void *codes, const void *sz, void *Y, hipStream_t st);
+// dX[T,I] = dY[T,O] * What[O,I]
+void launch_mfma_dx(const Problem &p, const void *dY, const void *codes, const void *sz, void *dX, hipStream_t st);
+// dWhat = dY^T X fused with the per-element / per-group epilogue.
+//   block_ap: needs W, clampbits; writes dW (W's dtype, may be NULL), ds, dz (may be NULL).
+//   e2e_qp  : W = clampbits = dW = dz = NULL; writes ds.
+// `part` is scratch for [2][O, I/32] floats, used only when a group is wider than one tile (see dw_needs_partials).
+void launch_mfma_dw(const Problem &p, bool block_ap, const void *X, const void *dY, const void *W, const void *codes,
+                    const void *clampbits, const void *sz, const float *s, void *dW, float *ds, float *dz, float *part,
+                    hipStream_t st);
+bool dw_needs_partials(const Problem &p);
+
+// ---- gemm_f32.hip (fp32 activations; simple tiled FMA kernels, exact division everywhere) --------
+void launch_f32_fwd(const Problem &p, bool packed, const void *X, const void *W_or_codes, const float *s, const void *z_or_sz,
+                    void *Y, hipStream_t st);
+void launch_f32_dx(const Problem &p, bool packed, const void *dY, const void *W_or_codes, const float *s, const void *z_or_sz,
+                   void *dX, hipStream_t st);
+// dWhat[O,I] fp32 = dY^T X into `dwhat` (scratch O*I floats), then the per-group epilogue.
+void launch_f32_dw(const Problem &p, bool block_ap, const void *X, const void *dY, const void *W_or_codes, const float *s,
+                   const void *z_or_sz, float *dwhat, void *dW, float *ds, float *dz, hipStream_t st);
+
+}  // namespace eqat

@@ -1,0 +1,371 @@
+// HBM-bound passes: min/max initialisation, the quantize pass (Eq.(1) -> packed N-bit codes),
+// zero-point packing / unpacking, code unpacking, and the small reductions the GEMM epilogues need.
+#include "common.h"
+#include "kernels.h"
+
+namespace eqat {
+
+// ---------------------------------------------------------------------------------------------
+// Eq.(1) for one weight.  The code must equal clamp(round_half_even(fl32(w/s)) + zbar, 0, Qmax)
+// exactly.  fl32(w/s) costs a dozen instructions, so the common case uses w * (1/s), which is within
+// 2^-23 relative of the true quotient; only when that product lies within 2^-20 (relative) of a
+// rounding tie - where the cheap and the exact quotient could round differently - is the exact
+// division evaluated.  Far from a tie both quotients round to the same integer, so the code is exact.
+// Returns round(w/s); `tie` is set when the caller must redo the element with quant_exact().
+__device__ __forceinline__ float quant_fast(float w, float rinv, bool &tie)
+{
+    const float t = w * rinv;
+    const float r = __builtin_rintf(t);
+    const float thr = __builtin_fmaf(__builtin_fabsf(t), -0x1p-20f, 0.5f - 0x1p-20f);
+    tie = __builtin_fabsf(t - r) >= thr;
+    return r;
+}
+__device__ __forceinline__ float quant_exact(float w, float s) { return __builtin_rintf(w / s); }
+
+template <typename WT> struct Chunk8;   // 8 consecutive weights of one lane
+template <> struct Chunk8<bf16_t> {
+    static constexpr int kBytes = 16;
+    uintx4 v;
+    __device__ __forceinline__ void load(const bf16_t *p) { v = *reinterpret_cast<const uintx4 *>(p); }
+    __device__ __forceinline__ float get(int k) const
+    {
+        const uint32_t u = v[k >> 1];
+        return __uint_as_float((k & 1) ? (u & 0xFFFF0000u) : (u << 16));
+    }
+};
+template <> struct Chunk8<float> {
+    static constexpr int kBytes = 32;
+    floatx4 a, b;
+    __device__ __forceinline__ void load(const float *p)
+    {
+        a = *reinterpret_cast<const floatx4 *>(p);
+        b = *reinterpret_cast<const floatx4 *>(p + 4);
+    }
+    __device__ __forceinline__ float get(int k) const { return k < 4 ? a[k] : b[k - 4]; }
+};
+
+__device__ __forceinline__ uint32_t quad_bcast(uint32_t v, int k)
+{
+    // value of lane (lane & ~3) + k, through a DPP quad permute
+    switch (k) {
+    case 0: return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x00, 0xF, 0xF, false);
+    case 1: return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x55, 0xF, 0xF, false);
+    case 2: return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xAA, 0xF, 0xF, false);
+    default: return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xFF, 0xF, 0xF, false);
+    }
+}
+
+// The quantize pass.  One lane owns 8 consecutive weights (a 16- or 32-byte load); the four lanes of a
+// quad own one 32-code segment, i.e. BITS output words, assembled with quad permutes.
+//   codes     [O, I*BITS/32] words      packed stream (same layout as eqat_pack's Wpacked)
+//   clampbits [O, I/8] bytes or NULL    bit k of byte e/8: weight e was clamped by Eq.(1)
+//   sz        [O, G] float2 or NULL     (s, zbar) per group, zbar = round(z) (clamped iff CLAMP_Z)
+template <typename WT, int BITS, bool CLAMP_Z>
+__global__ __launch_bounds__(256) void k_quantize(const WT *__restrict__ W, const float *__restrict__ s,
+                                                  const float *__restrict__ z, uint32_t *__restrict__ codes,
+                                                  uint8_t *__restrict__ clampbits, floatx2 *__restrict__ sz,
+                                                  uint32_t n_chunks, uint32_t I, uint32_t g, uint32_t G)
+{
+    const uint32_t c = blockIdx.x * 256u + threadIdx.x;   // chunk index; n_chunks % 4 == 0 so quads stay whole
+    if (c >= n_chunks) return;
+    const uint32_t e = c * 8u;
+    const uint32_t row = e / I, col = e - row * I;
+    const uint32_t j = col / g;
+    const float sv = s[row * G + j];
+    float zb = __builtin_rintf(z[row * G + j]);
+    constexpr float qmax = (float)((1 << BITS) - 1);
+    if (CLAMP_Z) zb = __builtin_fminf(__builtin_fmaxf(zb, 0.0f), qmax);
+    if (sz != nullptr && col == j * g) { floatx2 o; o[0] = sv; o[1] = zb; sz[row * G + j] = o; }
+
+    Chunk8<WT> ch;
+    ch.load(W + e);
+    const float rinv = 1.0f / sv;
+    float r[8];
+    bool any_tie = false;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        bool tie;
+        r[k] = quant_fast(ch.get(k), rinv, tie);
+        any_tie |= tie;
+    }
+    if (any_tie) {
+#pragma unroll
+        for (int k = 0; k < 8; ++k) r[k] = quant_exact(ch.get(k), sv);
+    }
+    uint32_t p = 0, cb = 0;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        const float qpre = r[k] + zb;
+        const float q = __builtin_fminf(__builtin_fmaxf(qpre, 0.0f), qmax);
+        p |= (uint32_t)q << (k * BITS);
+        cb |= (qpre != q ? 1u : 0u) << k;
+    }
+    if (clampbits != nullptr) clampbits[c] = (uint8_t)cb;
+
+    const uint32_t p0 = quad_bcast(p, 0), p1 = quad_bcast(p, 1), p2 = quad_bcast(p, 2), p3 = quad_bcast(p, 3);
+    const uint32_t q4 = threadIdx.x & 3u;
+    uint32_t word;
+    if constexpr (BITS == 2) {
+        word = (q4 == 0) ? (p0 | (p1 << 16)) : (p2 | (p3 << 16));
+    } else if constexpr (BITS == 3) {
+        word = (q4 == 0) ? (p0 | (p1 << 24)) : (q4 == 1) ? ((p1 >> 8) | (p2 << 16)) : ((p2 >> 16) | (p3 << 8));
+    } else {
+        word = (q4 == 0) ? p0 : (q4 == 1) ? p1 : (q4 == 2) ? p2 : p3;
+    }
+    if (q4 < (uint32_t)BITS) codes[(c >> 2) * BITS + q4] = word;
+}
+
+// Zero points at N bits: one thread per 32 zero points of a row (BITS words, tail padded with zeros).
+template <int BITS>
+__global__ __launch_bounds__(256) void k_pack_z(const float *__restrict__ z, uint32_t *__restrict__ zpacked,
+                                                uint32_t O, uint32_t G, uint32_t row_words)
+{
+    const uint32_t segs = (G + 31u) / 32u;
+    const uint32_t t = blockIdx.x * 256u + threadIdx.x;
+    if (t >= O * segs) return;
+    const uint32_t row = t / segs, seg = t - row * segs;
+    constexpr float qmax = (float)((1 << BITS) - 1);
+    uint64_t acc = 0;
+    int nbits = 0;
+    uint32_t wi = seg * BITS;
+    for (uint32_t k = 0; k < 32u; ++k) {
+        const uint32_t j = seg * 32u + k;
+        uint32_t code = 0;
+        if (j < G) code = (uint32_t)__builtin_fminf(__builtin_fmaxf(__builtin_rintf(z[row * G + j]), 0.0f), qmax);
+        acc |= (uint64_t)code << nbits;
+        nbits += BITS;
+        if (nbits >= 32) {
+            if (wi < row_words) zpacked[row * row_words + wi] = (uint32_t)acc;
+            acc >>= 32; nbits -= 32; ++wi;
+        }
+    }
+}
+
+// (s, z) pairs for the E2E-QP kernels: sz[o,j] = (s[o,j], float(zpacked code j of row o)).
+template <int BITS>
+__global__ __launch_bounds__(256) void k_unpack_sz(const float *__restrict__ s, const uint32_t *__restrict__ zpacked,
+                                                   floatx2 *__restrict__ sz, uint32_t O, uint32_t G, uint32_t row_words)
+{
+    const uint32_t t = blockIdx.x * 256u + threadIdx.x;
+    if (t >= O * G) return;
+    const uint32_t row = t / G, j = t - row * G;
+    const uint32_t bit = j * BITS, wi = bit >> 5, sh = bit & 31u;
+    uint64_t two = zpacked[row * row_words + wi];
+    if (sh + BITS > 32u) two |= (uint64_t)zpacked[row * row_words + wi + 1] << 32;
+    floatx2 o; o[0] = s[t]; o[1] = (float)((uint32_t)(two >> sh) & ((1u << BITS) - 1u));
+    sz[t] = o;
+}
+
+// Test aid: codes [O,I] int32 from the packed stream (one thread per 32-code segment), zero points [O,G].
+template <int BITS>
+__global__ __launch_bounds__(256) void k_unpack_codes(const uint32_t *__restrict__ packed, int32_t *__restrict__ out,
+                                                      uint32_t n_segs)
+{
+    const uint32_t t = blockIdx.x * 256u + threadIdx.x;
+    if (t >= n_segs) return;
+    uint32_t w[BITS];
+#pragma unroll
+    for (int k = 0; k < BITS; ++k) w[k] = packed[(size_t)t * BITS + k];
+    for (int k = 0; k < 32; ++k) out[(size_t)t * 32 + k] = (int32_t)code_at_rt<BITS>(w, k);
+}
+template <int BITS>
+__global__ __launch_bounds__(256) void k_unpack_z(const uint32_t *__restrict__ zpacked, int32_t *__restrict__ out,
+                                                  uint32_t O, uint32_t G, uint32_t row_words)
+{
+    const uint32_t t = blockIdx.x * 256u + threadIdx.x;
+    if (t >= O * G) return;
+    const uint32_t row = t / G, j = t - row * G;
+    const uint32_t bit = j * BITS, wi = bit >> 5, sh = bit & 31u;
+    uint64_t two = zpacked[row * row_words + wi];
+    if (sh + BITS > 32u) two |= (uint64_t)zpacked[row * row_words + wi + 1] << 32;
+    out[t] = (int32_t)((uint32_t)(two >> sh) & ((1u << BITS) - 1u));
+}
+
+// ---------------------------------------------------------------------------------------------
+// min/max initialisation.  LPG = lanes per group (g/8), a power of two <= 64: one lane reduces its 8
+// weights, an xor butterfly reduces the group.
+template <typename WT, int LPG>
+__global__ __launch_bounds__(256) void k_init_minmax_small(const WT *__restrict__ W, float *__restrict__ s,
+                                                           float *__restrict__ z, uint32_t n_chunks, float qmax)
+{
+    const uint32_t c = blockIdx.x * 256u + threadIdx.x;
+    if (c >= n_chunks) return;   // n_chunks % LPG == 0 and 256 % LPG == 0: groups never straddle the guard
+    Chunk8<WT> ch;
+    ch.load(W + (size_t)c * 8);
+    float lo = ch.get(0), hi = lo;
+#pragma unroll
+    for (int k = 1; k < 8; ++k) { lo = __builtin_fminf(lo, ch.get(k)); hi = __builtin_fmaxf(hi, ch.get(k)); }
+#pragma unroll
+    for (int m = 1; m < LPG; m <<= 1) {
+        lo = __builtin_fminf(lo, __shfl_xor(lo, m));
+        hi = __builtin_fmaxf(hi, __shfl_xor(hi, m));
+    }
+    if ((c & (LPG - 1)) == 0) {
+        float step = (hi - lo) / qmax;
+        if (!(step >= 1e-10f)) step = 1e-10f;
+        float zf = __builtin_rintf((-lo) / step);
+        zf = __builtin_fminf(__builtin_fmaxf(zf, 0.0f), qmax);
+        s[c / LPG] = step;
+        z[c / LPG] = zf;
+    }
+}
+// Any other group size: one wavefront per group.
+template <typename WT>
+__global__ __launch_bounds__(256) void k_init_minmax_wave(const WT *__restrict__ W, float *__restrict__ s,
+                                                          float *__restrict__ z, uint32_t n_groups, uint32_t g, float qmax)
+{
+    const uint32_t grp = blockIdx.x * 4u + (threadIdx.x >> 6);
+    if (grp >= n_groups) return;
+    const uint32_t lane = threadIdx.x & 63u;
+    const WT *base = W + (size_t)grp * g;
+    float lo = __builtin_inff(), hi = -__builtin_inff();
+    for (uint32_t c = lane; c < g / 8u; c += 64u) {
+        Chunk8<WT> ch;
+        ch.load(base + c * 8u);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) { lo = __builtin_fminf(lo, ch.get(k)); hi = __builtin_fmaxf(hi, ch.get(k)); }
+    }
+#pragma unroll
+    for (int m = 1; m < 64; m <<= 1) {
+        lo = __builtin_fminf(lo, __shfl_xor(lo, m));
+        hi = __builtin_fmaxf(hi, __shfl_xor(hi, m));
+    }
+    if (lane == 0) {
+        float step = (hi - lo) / qmax;
+        if (!(step >= 1e-10f)) step = 1e-10f;
+        float zf = __builtin_rintf((-lo) / step);
+        zf = __builtin_fminf(__builtin_fmaxf(zf, 0.0f), qmax);
+        s[grp] = step;
+        z[grp] = zf;
+    }
+}
+
+// out[o,j] = sum of the n_per consecutive per-32-column partials of group j, in index order;
+// `scale_by_s` multiplies by -s[o,j] (turns a sum of clamped dWhat into dz).
+__global__ __launch_bounds__(256) void k_reduce_partials(const float *__restrict__ part, float *__restrict__ out,
+                                                         const float *__restrict__ s, uint32_t n_out, uint32_t n_per,
+                                                         int scale_by_s)
+{
+    const uint32_t t = blockIdx.x * 256u + threadIdx.x;
+    if (t >= n_out) return;
+    float acc = 0.0f;
+    for (uint32_t k = 0; k < n_per; ++k) acc += part[(size_t)t * n_per + k];
+    out[t] = scale_by_s ? -s[t] * acc : acc;
+}
+
+__global__ __launch_bounds__(256) void k_fill_zero(uint32_t *__restrict__ p, size_t n_words)
+{
+    size_t i = (size_t)blockIdx.x * 256u + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * 256u;
+    for (; i < n_words; i += stride) p[i] = 0u;
+}
+
+// ---------------------------------------------------------------------------------------------
+// host-side launchers
+
+static inline unsigned blocks_for(size_t n, unsigned per = 256) { return (unsigned)((n + per - 1) / per); }
+
+template <typename WT, int BITS>
+static void quantize_t(const Problem &p, const void *W, const float *s, const float *z, void *codes, void *clampbits,
+                       void *sz, bool clamp_z, hipStream_t st)
+{
+    const uint32_t n_chunks = (uint32_t)((size_t)p.O * p.I / 8);
+    const dim3 grid(blocks_for(n_chunks)), block(256);
+    if (clamp_z)
+        k_quantize<WT, BITS, true><<<grid, block, 0, st>>>((const WT *)W, s, z, (uint32_t *)codes, (uint8_t *)clampbits,
+                                                           (floatx2 *)sz, n_chunks, (uint32_t)p.I, (uint32_t)p.g, (uint32_t)p.G);
+    else
+        k_quantize<WT, BITS, false><<<grid, block, 0, st>>>((const WT *)W, s, z, (uint32_t *)codes, (uint8_t *)clampbits,
+                                                            (floatx2 *)sz, n_chunks, (uint32_t)p.I, (uint32_t)p.g, (uint32_t)p.G);
+}
+
+void launch_quantize(const Problem &p, const void *W, const float *s, const float *z, void *codes, void *clampbits,
+                     void *sz, bool clamp_z, hipStream_t st)
+{
+#define EQAT_Q(WT, B) quantize_t<WT, B>(p, W, s, z, codes, clampbits, sz, clamp_z, st)
+    if (p.w_bf16) { if (p.bits == 2) EQAT_Q(bf16_t, 2); else if (p.bits == 3) EQAT_Q(bf16_t, 3); else EQAT_Q(bf16_t, 4); }
+    else          { if (p.bits == 2) EQAT_Q(float, 2);  else if (p.bits == 3) EQAT_Q(float, 3);  else EQAT_Q(float, 4); }
+#undef EQAT_Q
+}
+
+void launch_pack_z(const Problem &p, const float *z, void *zpacked, hipStream_t st)
+{
+    const uint32_t row_words = (uint32_t)((p.G * p.bits + 31) / 32);
+    const size_t n = (size_t)p.O * ((p.G + 31) / 32);
+    const dim3 grid(blocks_for(n)), block(256);
+    if (p.bits == 2) k_pack_z<2><<<grid, block, 0, st>>>(z, (uint32_t *)zpacked, (uint32_t)p.O, (uint32_t)p.G, row_words);
+    else if (p.bits == 3) k_pack_z<3><<<grid, block, 0, st>>>(z, (uint32_t *)zpacked, (uint32_t)p.O, (uint32_t)p.G, row_words);
+    else k_pack_z<4><<<grid, block, 0, st>>>(z, (uint32_t *)zpacked, (uint32_t)p.O, (uint32_t)p.G, row_words);
+}
+
+void launch_unpack_sz(const Problem &p, const float *s, const void *zpacked, void *sz, hipStream_t st)
+{
+    const uint32_t row_words = (uint32_t)((p.G * p.bits + 31) / 32);
+    const size_t n = (size_t)p.O * p.G;
+    const dim3 grid(blocks_for(n)), block(256);
+    if (p.bits == 2) k_unpack_sz<2><<<grid, block, 0, st>>>(s, (const uint32_t *)zpacked, (floatx2 *)sz, (uint32_t)p.O, (uint32_t)p.G, row_words);
+    else if (p.bits == 3) k_unpack_sz<3><<<grid, block, 0, st>>>(s, (const uint32_t *)zpacked, (floatx2 *)sz, (uint32_t)p.O, (uint32_t)p.G, row_words);
+    else k_unpack_sz<4><<<grid, block, 0, st>>>(s, (const uint32_t *)zpacked, (floatx2 *)sz, (uint32_t)p.O, (uint32_t)p.G, row_words);
+}
+
+void launch_unpack(const Problem &p, const void *Wpacked, const void *zpacked, int32_t *codes, int32_t *zcodes, hipStream_t st)
+{
+    const uint32_t row_words = (uint32_t)((p.G * p.bits + 31) / 32);
+    if (codes != nullptr) {
+        const uint32_t n_segs = (uint32_t)((size_t)p.O * p.I / 32);
+        const dim3 grid(blocks_for(n_segs)), block(256);
+        if (p.bits == 2) k_unpack_codes<2><<<grid, block, 0, st>>>((const uint32_t *)Wpacked, codes, n_segs);
+        else if (p.bits == 3) k_unpack_codes<3><<<grid, block, 0, st>>>((const uint32_t *)Wpacked, codes, n_segs);
+        else k_unpack_codes<4><<<grid, block, 0, st>>>((const uint32_t *)Wpacked, codes, n_segs);
+    }
+    if (zcodes != nullptr) {
+        const size_t n = (size_t)p.O * p.G;
+        const dim3 grid(blocks_for(n)), block(256);
+        if (p.bits == 2) k_unpack_z<2><<<grid, block, 0, st>>>((const uint32_t *)zpacked, zcodes, (uint32_t)p.O, (uint32_t)p.G, row_words);
+        else if (p.bits == 3) k_unpack_z<3><<<grid, block, 0, st>>>((const uint32_t *)zpacked, zcodes, (uint32_t)p.O, (uint32_t)p.G, row_words);
+        else k_unpack_z<4><<<grid, block, 0, st>>>((const uint32_t *)zpacked, zcodes, (uint32_t)p.O, (uint32_t)p.G, row_words);
+    }
+}
+
+template <typename WT>
+static void init_minmax_t(const Problem &p, const void *W, float *s, float *z, hipStream_t st)
+{
+    const float qmax = (float)((1 << p.bits) - 1);
+    const uint32_t n_chunks = (uint32_t)((size_t)p.O * p.I / 8);
+    const dim3 grid(blocks_for(n_chunks)), block(256);
+    const WT *w = (const WT *)W;
+    switch (p.g) {
+    case 32:  k_init_minmax_small<WT, 4><<<grid, block, 0, st>>>(w, s, z, n_chunks, qmax); break;
+    case 64:  k_init_minmax_small<WT, 8><<<grid, block, 0, st>>>(w, s, z, n_chunks, qmax); break;
+    case 128: k_init_minmax_small<WT, 16><<<grid, block, 0, st>>>(w, s, z, n_chunks, qmax); break;
+    case 256: k_init_minmax_small<WT, 32><<<grid, block, 0, st>>>(w, s, z, n_chunks, qmax); break;
+    case 512: k_init_minmax_small<WT, 64><<<grid, block, 0, st>>>(w, s, z, n_chunks, qmax); break;
+    default: {
+        const uint32_t n_groups = (uint32_t)((size_t)p.O * p.G);
+        k_init_minmax_wave<WT><<<dim3(blocks_for(n_groups, 4)), block, 0, st>>>(w, s, z, n_groups, (uint32_t)p.g, qmax);
+    }
+    }
+}
+
+void launch_init_minmax(const Problem &p, const void *W, float *s, float *z, hipStream_t st)
+{
+    if (p.w_bf16) init_minmax_t<bf16_t>(p, W, s, z, st);
+    else init_minmax_t<float>(p, W, s, z, st);
+}
+
+void launch_reduce_partials(const float *part, float *out, const float *s, size_t n_out, uint32_t n_per, bool scale_by_s,
+                            hipStream_t st)
+{
+    k_reduce_partials<<<dim3(blocks_for(n_out)), dim3(256), 0, st>>>(part, out, s, (uint32_t)n_out, n_per, scale_by_s ? 1 : 0);
+}
+
+void launch_fill_zero(void *p, size_t bytes, hipStream_t st)
+{
+    if (bytes == 0) return;
+    const size_t n_words = bytes / 4;
+    unsigned blocks = blocks_for(n_words);
+    if (blocks > 4096) blocks = 4096;
+    k_fill_zero<<<dim3(blocks), dim3(256), 0, st>>>((uint32_t *)p, n_words);
+}
+
+}  // namespace eqat

@@ -1,0 +1,213 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle, element by element.
+
+Sizes are chosen so that the fp64 oracle finishes in seconds while the GPU kernels still run several
+tiles with ragged edges in every dimension.  Bars: integer codes / packed bytes / s, z of the min-max
+initialisation bit-exact; floating-point outputs max|gpu - ref| / max|ref| <= 2e-2 on the bf16 MFMA
+path and <= 1e-5 on the fp32 path.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2407_11062_amd as eq
+from paper_2407_11062_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+TOL = {torch.bfloat16: 2e-2, torch.float32: 1e-5}
+
+
+def dev(t):
+    return t.cuda().contiguous()
+
+
+def npf(t):
+    return t.detach().float().cpu().numpy()
+
+
+def relerr(got, ref):
+    got = npf(got).astype(np.float64)
+    denom = np.abs(ref).max()
+    if denom == 0:
+        return float(np.abs(got).max())
+    return float(np.abs(got - ref).max() / denom)
+
+
+def make_case(tag, T, I, O, bits, g, act, wdt, trained=True, w_std=0.02):
+    G = 1 if g == -1 else I // g
+    W = synth.normal((O, I), w_std, synth.seed_of(tag, "W"), wdt)
+    X = synth.normal((T, I), 1.0, synth.seed_of(tag, "X"), act)
+    dY = synth.normal((T, O), 1.0, synth.seed_of(tag, "dY"), act)
+    s, z = oracle.init_minmax(npf(W), bits, g)
+    if trained:
+        u, d = synth.trained_state_noise((O, G), synth.seed_of(tag, "sz"))
+        s = (s * u.numpy()).astype(np.float32)
+        z = (z + d.numpy()).astype(np.float32)
+    return X, W, torch.from_numpy(s), torch.from_numpy(z), dY
+
+
+BF16_CASES = [
+    # tag, T, I, O, bits, g, w dtype
+    ("b2g64", 300, 384, 264, 2, 64, torch.bfloat16),
+    ("b3g128", 257, 512, 136, 3, 128, torch.bfloat16),
+    ("b4g32", 130, 160, 72, 4, 32, torch.bfloat16),
+    ("b2g64w32", 200, 256, 128, 2, 64, torch.float32),
+    ("b2perchan", 150, 384, 40, 2, -1, torch.bfloat16),
+    ("b3g96", 96, 192, 64, 3, 96, torch.bfloat16),
+    ("b4g256", 64, 512, 8, 4, 256, torch.float32),
+    ("t1", 1, 128, 16, 2, 64, torch.bfloat16),
+]
+
+
+# --------------------------------------------------------------------------- elementwise passes
+
+@pytest.mark.parametrize("bits,g,wdt", [(2, 64, torch.bfloat16), (3, 128, torch.float32), (4, 32, torch.bfloat16),
+                                        (2, 512, torch.bfloat16), (4, 96, torch.float32), (3, -1, torch.bfloat16)])
+def test_init_minmax_bit_exact(bits, g, wdt):
+    O, I = 67, 1536
+    W = synth.normal((O, I), 0.02, synth.seed_of("init", bits, g), wdt)
+    W[3, :64] = 0.125                                  # a constant group: the 1e-10 floor
+    s_ref, z_ref = oracle.init_minmax(npf(W), bits, g)
+    s, z = eq.eqat_init_minmax(dev(W), bits, g)
+    assert np.array_equal(npf(s), s_ref)
+    assert np.array_equal(npf(z), z_ref)
+
+
+@pytest.mark.parametrize("bits,g,wdt", [(2, 64, torch.bfloat16), (3, 128, torch.bfloat16), (4, 32, torch.float32),
+                                        (3, 32, torch.float32), (2, -1, torch.bfloat16), (4, 128, torch.bfloat16)])
+def test_pack_bytes_bit_exact_and_unpack(bits, g, wdt):
+    O, I = 93, 1024
+    X, W, s, z, dY = make_case(("pack", bits, g), 1, I, O, bits, g, torch.float32, wdt)
+    z[0, 0] = -2.0                                      # zero points outside the code range are clamped when packed
+    z[1, 0] = 2 ** bits + 1.0
+    Wp_ref, zp_ref = oracle.pack(npf(W), s.numpy(), z.numpy(), bits, g)
+    Wp, zp = eq.eqat_pack(dev(W), dev(s), dev(z), bits, g)
+    assert Wp.shape == Wp_ref.shape and zp.shape == zp_ref.shape
+    assert np.array_equal(Wp.cpu().numpy(), Wp_ref)
+    assert np.array_equal(zp.cpu().numpy(), zp_ref)
+    codes, zc = eq.eqat_unpack(Wp, zp, I, bits, g)
+    c_ref, z_refc = oracle.unpack(Wp_ref, zp_ref, I, bits, g)
+    assert np.array_equal(codes.cpu().numpy(), c_ref) and np.array_equal(zc.cpu().numpy(), z_refc)
+    c_direct, _ = oracle.quantize(npf(W), s.numpy(), z.numpy(), bits, g)
+    assert np.array_equal(codes.cpu().numpy(), c_direct)
+
+
+def test_codes_exact_near_rounding_ties():
+    # weights placed within a few ulp of every rounding tie of their group: the cheap reciprocal path must
+    # hand these to the exact division
+    bits, g, O, I = 4, 32, 64, 1024
+    rng = np.random.default_rng(5)
+    s = rng.uniform(0.001, 0.01, (O, I // g)).astype(np.float32)
+    z = np.full((O, I // g), 8.0, np.float32)
+    k = rng.integers(-8, 8, (O, I)) + 0.5
+    W = (k * np.repeat(s, g, 1)).astype(np.float32)
+    bump = rng.integers(-2, 3, (O, I)).astype(np.int32)
+    W = (W.view(np.int32) + bump).view(np.float32)
+    c_ref, _ = oracle.quantize(W, s, z, bits, g)
+    Wp, zp = eq.eqat_pack(dev(torch.from_numpy(W)), dev(torch.from_numpy(s)), dev(torch.from_numpy(z)), bits, g)
+    codes, _ = eq.eqat_unpack(Wp, zp, I, bits, g)
+    assert np.array_equal(codes.cpu().numpy(), c_ref)
+
+
+# --------------------------------------------------------------------------- Block-AP
+
+def check_block_ap(X, W, s, z, dY, bits, g, tol):
+    Xn, Wn, sn, zn, dYn = npf(X), npf(W), s.numpy(), z.numpy(), npf(dY)
+    Y_ref = oracle.fq_linear_fwd(Xn, Wn, sn, zn, bits, g)
+    ref = oracle.fq_linear_bwd(Xn, Wn, sn, zn, dYn, bits, g)
+    Xd, Wd, sd, zd, dYd = dev(X), dev(W), dev(s), dev(z), dev(dY)
+    Y = eq.eqat_fq_linear_fwd(Xd, Wd, sd, zd, bits, g)
+    out = eq.eqat_fq_linear_bwd(Xd, Wd, sd, zd, dYd, bits, g)
+    torch.cuda.synchronize()
+    errs = {"Y": relerr(Y, Y_ref)}
+    for k in ("dX", "dW", "ds", "dz"):
+        errs[k] = relerr(out[k], ref[k])
+    assert all(e <= tol for e in errs.values()), errs
+    # the STE mask itself is an integer decision: dW must be exactly zero where, and only where, Eq.(1) clamped
+    _, side = oracle.quantize(Wn, sn, zn, bits, g)
+    dWn = npf(out["dW"])
+    assert not dWn[side != 0].any()
+    nz_ref = (ref["dW"] != 0) & (np.abs(ref["dW"]) > 1e-3 * np.abs(ref["dW"]).max())
+    assert np.all(dWn[nz_ref] != 0)
+    return errs
+
+
+@pytest.mark.parametrize("trained", [False, True])
+def test_block_ap_fp32_single_linear(trained):
+    w = synth.WORKLOADS["single_fp32_w4g128"]
+    lin = w.layers[0]
+    X, W, s, z, dY = make_case(("cfg1", trained), w.tokens, lin.in_features, lin.out_features, w.bits, w.group,
+                               torch.float32, torch.float32, trained)
+    check_block_ap(X, W, s, z, dY, w.bits, w.group, TOL[torch.float32])
+
+
+def test_block_ap_fp32_ragged():
+    X, W, s, z, dY = make_case("f32ragged", 77, 96, 50, 3, 32, torch.float32, torch.float32)
+    check_block_ap(X, W, s, z, dY, 3, 32, TOL[torch.float32])
+
+
+@pytest.mark.parametrize("tag,T,I,O,bits,g,wdt", BF16_CASES)
+def test_block_ap_bf16(tag, T, I, O, bits, g, wdt):
+    X, W, s, z, dY = make_case(tag, T, I, O, bits, g, torch.bfloat16, wdt)
+    check_block_ap(X, W, s, z, dY, bits, g, TOL[torch.bfloat16])
+
+
+def test_block_ap_outputs_are_optional_and_deterministic():
+    X, W, s, z, dY = make_case("opt", 140, 256, 136, 2, 64, torch.bfloat16, torch.bfloat16)
+    Xd, Wd, sd, zd, dYd = dev(X), dev(W), dev(s), dev(z), dev(dY)
+    full = eq.eqat_fq_linear_bwd(Xd, Wd, sd, zd, dYd, 2, 64)
+    again = eq.eqat_fq_linear_bwd(Xd, Wd, sd, zd, dYd, 2, 64)
+    for k in full:
+        assert torch.equal(full[k], again[k]), k
+    only_ds = eq.eqat_fq_linear_bwd(Xd, Wd, sd, zd, dYd, 2, 64, want=("ds",))
+    assert set(only_ds) == {"ds"} and torch.equal(only_ds["ds"], full["ds"])
+    only_dx = eq.eqat_fq_linear_bwd(None, Wd, sd, zd, dYd, 2, 64, want=("dX",))
+    assert torch.equal(only_dx["dX"], full["dX"])
+
+
+def test_empty_token_batch():
+    X, W, s, z, dY = make_case("empty", 4, 128, 16, 2, 64, torch.bfloat16, torch.bfloat16)
+    Wd, sd, zd = dev(W), dev(s), dev(z)
+    Xe = torch.empty((0, 128), dtype=torch.bfloat16, device="cuda")
+    dYe = torch.empty((0, 16), dtype=torch.bfloat16, device="cuda")
+    assert eq.eqat_fq_linear_fwd(Xe, Wd, sd, zd, 2, 64).shape == (0, 16)
+    out = eq.eqat_fq_linear_bwd(Xe, Wd, sd, zd, dYe, 2, 64)
+    torch.cuda.synchronize()
+    assert out["dX"].shape == (0, 128)
+    for k in ("dW", "ds", "dz"):
+        assert not out[k].float().abs().sum().item(), k
+
+
+# --------------------------------------------------------------------------- E2E-QP
+
+def check_e2e(X, W, s, z, dY, bits, g, tol):
+    I = W.shape[1]
+    qmax = 2 ** bits - 1
+    z = z.clamp(0, qmax)
+    Xn, Wn, sn, zn, dYn = npf(X), npf(W), s.numpy(), z.numpy(), npf(dY)
+    Wp_ref, zp_ref = oracle.pack(Wn, sn, zn, bits, g)
+    Y_ref = oracle.qlinear_fwd(Xn, Wp_ref, sn, zp_ref, bits, g)
+    ref = oracle.qlinear_bwd(Xn, Wp_ref, sn, zp_ref, dYn, I, bits, g)
+    Xd, sd, dYd = dev(X), dev(s), dev(dY)
+    Wp, zp = eq.eqat_pack(dev(W), sd, dev(z), bits, g)
+    assert np.array_equal(Wp.cpu().numpy(), Wp_ref) and np.array_equal(zp.cpu().numpy(), zp_ref)
+    Y = eq.eqat_qlinear_fwd(Xd, Wp, sd, zp, bits, g)
+    out = eq.eqat_qlinear_bwd(Xd, Wp, sd, zp, dYd, I, bits, g)
+    torch.cuda.synchronize()
+    errs = {"Y": relerr(Y, Y_ref), "dX": relerr(out["dX"], ref["dX"]), "ds": relerr(out["ds"], ref["ds"])}
+    assert all(e <= tol for e in errs.values()), errs
+    only_ds = eq.eqat_qlinear_bwd(Xd, Wp, sd, zp, dYd, I, bits, g, want=("ds",))
+    assert torch.equal(only_ds["ds"], out["ds"])
+
+
+@pytest.mark.parametrize("tag,T,I,O,bits,g,wdt", BF16_CASES)
+def test_e2e_qp_bf16(tag, T, I, O, bits, g, wdt):
+    X, W, s, z, dY = make_case(tag, T, I, O, bits, g, torch.bfloat16, wdt)
+    check_e2e(X, W, s, z, dY, bits, g, TOL[torch.bfloat16])
+
+
+@pytest.mark.parametrize("bits,g", [(4, 128), (3, 32), (2, -1)])
+def test_e2e_qp_fp32(bits, g):
+    X, W, s, z, dY = make_case(("e2e32", bits, g), 70, 256, 44, bits, g, torch.float32, torch.float32)
+    check_e2e(X, W, s, z, dY, bits, g, TOL[torch.float32])

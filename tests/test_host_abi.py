@@ -1,0 +1,129 @@
+"""CPU-only checks of the C ABI: the library loads, exports every symbol the header declares, sizes its
+buffers as documented, and turns every bad argument into its status code on the host (nothing is launched:
+each call below fails validation by construction)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2407_11062_amd as eq
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+OK, NULL, SHAPE, BITS, GROUP, DTYPE, ALIGN, WORKSPACE, DEVICE = range(9)
+P = 0x10000   # a fake, non-NULL, 256-byte aligned "device pointer"; never dereferenced on these paths
+
+
+def d(T=16, I=128, O=64, bits=2, group=64, act=eq.BF16, w=eq.BF16):
+    return eq.make_desc(T, I, O, bits, group, act, w)
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "eqat.h")).read()
+    declared = set(re.findall(r"\b(eqat_[a-z0-9_]+)\s*\(", header))
+    assert declared == set(eq.EXPORTS)
+    L = eq.lib()
+    for name in declared:
+        assert hasattr(L, name), name
+
+
+def test_status_strings():
+    L = eq.lib()
+    seen = {L.eqat_status_string(i) for i in range(9)}
+    assert len(seen) == 9 and all(s for s in seen)
+    assert L.eqat_status_string(99) == b"unknown status"
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(bits=1), BITS), (dict(bits=5), BITS), (dict(bits=8), BITS),
+    (dict(I=100), SHAPE), (dict(I=0), SHAPE), (dict(O=0), SHAPE), (dict(T=-1), SHAPE),
+    (dict(O=12), SHAPE),                                  # bf16 activations need O % 8 == 0
+    (dict(group=0), GROUP), (dict(group=48), GROUP), (dict(group=96), GROUP), (dict(group=-2), GROUP), (dict(group=16), GROUP),
+    (dict(act=2), DTYPE), (dict(w=7), DTYPE),
+    (dict(T=40000, I=28672), SHAPE),                      # X would be 2 GiB or more
+    (dict(O=32768, I=32768, w=eq.F32), SHAPE),            # W would be 4 GiB
+    (dict(), OK), (dict(group=-1), OK), (dict(O=12, act=eq.F32), OK), (dict(T=0), OK), (dict(I=96, group=96, bits=3), OK),
+])
+def test_descriptor_validation(kw, code):
+    desc = d(**kw)
+    assert eq.lib().eqat_validate_desc(ctypes.byref(desc)) == code
+    assert eq.lib().eqat_validate_desc(None) == NULL
+
+
+def test_packed_sizes():
+    L = eq.lib()
+    for bits, I, g, O in [(2, 4096, 64, 4096), (3, 5120, 128, 13824), (4, 128, 32, 8), (3, 96, 96, 5), (2, 8192, 64, 28672)]:
+        desc = d(I=I, O=O, bits=bits, group=g)
+        G = I // g
+        assert L.eqat_packed_w_bytes(ctypes.byref(desc)) == O * I * bits // 8
+        assert L.eqat_packed_z_bytes(ctypes.byref(desc)) == O * 4 * ((G * bits + 31) // 32)
+    bad = d(bits=7)
+    assert L.eqat_packed_w_bytes(ctypes.byref(bad)) == 0 and L.eqat_packed_z_bytes(ctypes.byref(bad)) == 0
+
+
+def test_workspace_sizes_are_modest_and_monotone():
+    L = eq.lib()
+    desc = d(T=4096, I=4096, O=4096)
+    w = [L.eqat_workspace_bytes(ctypes.byref(desc), op) for op in range(4)]
+    wbytes = 4096 * 4096 * 2
+    assert 0 < w[eq.OP_FQ_FWD] < wbytes // 4          # 2-bit codes + (s, z) pairs, a fraction of W itself
+    assert w[eq.OP_FQ_FWD] < w[eq.OP_FQ_BWD] < wbytes // 2
+    assert 0 < w[eq.OP_Q_FWD] <= w[eq.OP_Q_BWD] < wbytes // 8
+    assert L.eqat_workspace_bytes(ctypes.byref(desc), 9) == 0
+    f32 = d(T=256, I=512, O=512, bits=4, group=128, act=eq.F32, w=eq.F32)
+    assert L.eqat_workspace_bytes(ctypes.byref(f32), eq.OP_FQ_FWD) == 0
+    assert L.eqat_workspace_bytes(ctypes.byref(f32), eq.OP_FQ_BWD) >= 512 * 512 * 4
+
+
+def test_null_alignment_and_workspace_errors_come_back_before_any_launch():
+    L = eq.lib()
+    desc = d()
+    r = ctypes.byref(desc)
+    ws_need = L.eqat_workspace_bytes(r, eq.OP_FQ_BWD)
+    # NULL
+    assert L.eqat_init_minmax(r, None, P, P, None) == NULL
+    assert L.eqat_init_minmax(r, P, None, P, None) == NULL
+    assert L.eqat_pack(r, P, P, P, None, P, None) == NULL
+    assert L.eqat_fq_linear_fwd(r, None, P, P, P, P, P, 1 << 30, None) == NULL
+    assert L.eqat_fq_linear_fwd(r, P, P, P, P, None, P, 1 << 30, None) == NULL
+    assert L.eqat_fq_linear_bwd(r, P, P, P, P, None, P, P, P, P, P, 1 << 30, None) == NULL
+    assert L.eqat_fq_linear_bwd(r, None, P, P, P, P, P, P, P, P, P, 1 << 30, None) == NULL   # dW wanted, X missing
+    assert L.eqat_qlinear_fwd(r, P, None, P, P, P, P, 1 << 30, None) == NULL
+    assert L.eqat_qlinear_bwd(r, None, P, P, P, P, None, P, P, 1 << 30, None) == NULL        # ds wanted, X missing
+    assert L.eqat_unpack(r, None, P, P, None, None) == NULL
+    # alignment
+    assert L.eqat_init_minmax(r, P + 2, P, P, None) == ALIGN
+    assert L.eqat_pack(r, P, P, P, P + 8, P, None) == ALIGN
+    assert L.eqat_fq_linear_fwd(r, P, P, P, P, P + 4, P, 1 << 30, None) == ALIGN
+    assert L.eqat_fq_linear_fwd(r, P, P, P, P, P, P + 16, 1 << 30, None) == ALIGN            # workspace: 256 bytes
+    assert L.eqat_qlinear_bwd(r, P, P, P, P, P, P, P + 1, P, 1 << 30, None) == ALIGN
+    # workspace
+    assert ws_need > 0
+    assert L.eqat_fq_linear_bwd(r, P, P, P, P, P, P, P, P, P, P, ws_need - 1, None) == WORKSPACE
+    assert L.eqat_fq_linear_bwd(r, P, P, P, P, P, P, P, P, P, None, ws_need, None) == WORKSPACE
+    assert L.eqat_fq_linear_fwd(r, P, P, P, P, P, P, 0, None) == WORKSPACE
+    assert L.eqat_qlinear_fwd(r, P, P, P, P, P, None, 0, None) == WORKSPACE
+    assert L.eqat_qlinear_bwd(r, P, P, P, P, P, P, P, P, 16, None) == WORKSPACE
+    # descriptor errors win over everything else
+    bad = d(bits=9)
+    assert L.eqat_fq_linear_fwd(ctypes.byref(bad), None, None, None, None, None, None, 0, None) == BITS
+    assert L.eqat_pack(ctypes.byref(d(group=50)), P, P, P, P, P, None) == GROUP
+
+
+def test_nothing_to_do_returns_ok_without_a_device():
+    L = eq.lib()
+    desc = d(T=0)
+    r = ctypes.byref(desc)
+    big = 1 << 30
+    assert L.eqat_fq_linear_fwd(r, None, P, P, P, None, P, big, None) == OK          # T = 0: nothing to compute
+    assert L.eqat_qlinear_fwd(r, None, P, P, P, None, P, big, None) == OK
+    full = d()
+    assert L.eqat_fq_linear_bwd(ctypes.byref(full), P, P, P, P, P, None, None, None, None, P, big, None) == OK   # no output wanted
+    assert L.eqat_qlinear_bwd(ctypes.byref(full), P, P, P, P, P, None, None, P, big, None) == OK
+
+
+def test_binding_fails_loudly_without_the_library(monkeypatch, tmp_path):
+    monkeypatch.setattr(eq, "_lib", None)
+    monkeypatch.setattr(eq, "LIB_PATH", str(tmp_path / "libeqat.so"))
+    with pytest.raises(RuntimeError, match="no fallback"):
+        eq.lib()
