@@ -1,0 +1,234 @@
+#!/usr/bin/env python3
+"""Benchmark of the EfficientQAT quantized-linear hot path on one MI355X.
+
+One "step" = one Block-AP pass (eqat_fq_linear_fwd + eqat_fq_linear_bwd with dX, dW, ds, dz) over the
+seven linears of a Llama-2-7B-shaped decoder block, 8192 tokens, 2-bit codes, group 64, bf16 operands
+(the configuration the headline metric is quoted on).  Inputs are synthetic, seeded, generated on the
+device before the timed region; outputs and workspaces are pre-allocated.
+
+Prints ONE JSON line.  Besides the contract fields it carries
+  roofline      the dominant kernel of the step against the bf16 MFMA peak (HIP events inside the library),
+  cpu_baseline  the fp64 CPU oracle timed on a bounded sample of the same workload,
+  rows          the remaining rows of the hot path measured in the same run: E2E-QP fwd+bwd (4096 tokens),
+                eqat_pack and eqat_init_minmax (GB/s against the HBM peak).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="llama2_7b_block_ap_w2g64")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-rows", action="store_true", help="skip the E2E-QP / pack / init measurements")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        return 2
+    import torch
+    import paper_2407_11062_amd as eq
+    from paper_2407_11062_amd import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    eq.lib()   # fail loudly if the HIP library was not built
+    dev = torch.device("cuda:0")
+    wl = synth.WORKLOADS[args.workload]
+    T, bits, g = wl.tokens, wl.bits, wl.group
+    adt = synth.torch_dtype(wl.act_dtype)
+    gen = torch.Generator(device=dev)
+
+    def randn(shape, std, seed, dtype):
+        gen.manual_seed(seed)
+        t = torch.empty(shape, dtype=torch.float32, device=dev).normal_(0.0, 1.0, generator=gen)
+        return (t * std).to(dtype) if std != 1.0 else t.to(dtype)
+
+    layers = []
+    for lin in wl.layers:
+        O, I = lin.out_features, lin.in_features
+        L = {"name": lin.name, "O": O, "I": I}
+        L["W"] = randn((O, I), wl.w_std, synth.seed_of(wl.name, lin.name, "W"), adt)
+        L["X"] = randn((T, I), 1.0, synth.seed_of(wl.name, lin.name, "X"), adt)
+        L["dY"] = randn((T, O), 1.0, synth.seed_of(wl.name, lin.name, "dY"), adt)
+        s, z = eq.eqat_init_minmax(L["W"], bits, g)
+        # move the fresh min/max state into a "trained" one so that the clamped branches run
+        gen.manual_seed(synth.seed_of(wl.name, lin.name, "sz"))
+        u = torch.empty_like(s).uniform_(0.7, 1.1, generator=gen)
+        d = torch.randint(-1, 2, s.shape, generator=gen, device=dev).float()
+        L["s"], L["z"] = (s * u).contiguous(), (z + d).clamp_(0, 2 ** bits - 1).contiguous()
+        G = I // g
+        L["Y"] = torch.empty((T, O), dtype=adt, device=dev)
+        L["out"] = {"dX": torch.empty((T, I), dtype=adt, device=dev), "dW": torch.empty((O, I), dtype=adt, device=dev),
+                    "ds": torch.empty((O, G), dtype=torch.float32, device=dev),
+                    "dz": torch.empty((O, G), dtype=torch.float32, device=dev)}
+        dsc = eq.make_desc(T, I, O, bits, g, eq._dt(L["X"]), eq._dt(L["W"]))
+        L["ws_f"] = eq.workspace(dsc, eq.OP_FQ_FWD, dev)
+        L["ws_b"] = eq.workspace(dsc, eq.OP_FQ_BWD, dev)
+        layers.append(L)
+    sum_io = sum(L["O"] * L["I"] for L in layers)
+    flops_step = 6.0 * T * sum_io
+
+    def block_ap_step():
+        for L in layers:
+            eq.eqat_fq_linear_fwd(L["X"], L["W"], L["s"], L["z"], bits, g, Y=L["Y"], ws=L["ws_f"])
+            eq.eqat_fq_linear_bwd(L["X"], L["W"], L["s"], L["z"], L["dY"], bits, g, out=L["out"], ws=L["ws_b"])
+
+    for _ in range(args.warmup):
+        block_ap_step()
+    torch.cuda.synchronize()
+    eq.eqat_profile_start()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        block_ap_step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    prof = eq.eqat_profile_stop()
+    ms_step = 1e3 * elapsed / args.steps
+    tflops = flops_step / (elapsed / args.steps) / 1e12
+
+    # dominant kernel of the step: all three GEMM kernels do 2*T*I*O flop per launch
+    gemms = {k: v for k, v in prof.items() if k.startswith("gemm_")}
+    dom = max(gemms, key=lambda k: gemms[k][0])
+    dom_ms, dom_n = gemms[dom]
+    flop_per_launch = 2.0 * T * sum_io / len(layers)          # mean over the seven shapes
+    dom_tflops = flop_per_launch / (dom_ms / dom_n * 1e-3) / 1e12
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(tpath):
+        traffic = json.load(open(tpath)).get(args.workload, {}).get(dom)
+    roofline = {"bound": "mfma", "kernel": dom, "achieved": round(dom_tflops, 2), "peak": PEAK_BF16_TFLOPS,
+                "unit": "TFLOP/s", "frac": round(dom_tflops / PEAK_BF16_TFLOPS, 4), "traffic": traffic,
+                "avg_launch_ms": round(dom_ms / dom_n, 4), "launches": dom_n,
+                "flop_per_launch": flop_per_launch}
+    kernels = {k: {"total_ms": round(v[0], 3), "launches": v[1], "avg_ms": round(v[0] / v[1], 4)} for k, v in prof.items()}
+    for k in gemms:
+        kernels[k]["tflops"] = round(flop_per_launch / (gemms[k][0] / gemms[k][1] * 1e-3) / 1e12, 2)
+    if "quantize" in prof:
+        qb = sum(L["O"] * L["I"] for L in layers) / len(layers) * (2 + bits / 8 + 8.0 / g)   # fwd pass: W in, codes + (s,z) out
+        kernels["quantize"]["approx_gbs"] = round(qb / (prof["quantize"][0] / prof["quantize"][1] * 1e-3) / 1e9, 1)
+
+    result = {
+        "metric": "quantized-linear fwd+bwd TFLOP/s (% bf16 MFMA peak) and tokens/s per layer",
+        "value": round(tflops, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": wl.name, "phase": "block_ap", "tokens": T, "bits": bits, "group": g,
+                   "layers": [[L["name"], L["O"], L["I"]] for L in layers], "flop_per_step": flops_step},
+        "pct_of_bf16_mfma_peak": round(100.0 * tflops / PEAK_BF16_TFLOPS, 2),
+        "tokens_per_s_per_layer": round(T / (elapsed / args.steps), 1),
+        "roofline": roofline, "kernels": kernels,
+    }
+
+    if not args.no_rows:
+        result["rows"] = measure_other_rows(torch, eq, layers, bits, g, adt, dev, args)
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(wl)
+    print(json.dumps(result))
+    return 0
+
+
+def measure_other_rows(torch, eq, layers, bits, g, adt, dev, args):
+    """E2E-QP fwd+bwd at 4096 tokens, eqat_pack and eqat_init_minmax on the same seven weight matrices."""
+    T2 = 4096
+    rows = {}
+    packed = []
+    for L in layers:
+        Wp, zp = eq.eqat_pack(L["W"], L["s"], L["z"], bits, g)
+        dsc = eq.make_desc(T2, L["I"], L["O"], bits, g, eq.BF16, eq.BF16)
+        packed.append({"Wp": Wp, "zp": zp, "X": L["X"][:T2], "dY": L["dY"][:T2], "Y": L["Y"][:T2],
+                       "out": {"dX": L["out"]["dX"][:T2], "ds": L["out"]["ds"]},
+                       "ws_f": eq.workspace(dsc, eq.OP_Q_FWD, dev), "ws_b": eq.workspace(dsc, eq.OP_Q_BWD, dev)})
+
+    def e2e_step():
+        for L, P in zip(layers, packed):
+            eq.eqat_qlinear_fwd(P["X"], P["Wp"], L["s"], P["zp"], bits, g, Y=P["Y"], ws=P["ws_f"])
+            eq.eqat_qlinear_bwd(P["X"], P["Wp"], L["s"], P["zp"], P["dY"], L["I"], bits, g, out=P["out"], ws=P["ws_b"])
+
+    def timed(fn, n):
+        for _ in range(2):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / n
+
+    sum_io = sum(L["O"] * L["I"] for L in layers)
+    dt = timed(e2e_step, args.steps)
+    fl = 6.0 * T2 * sum_io
+    rows["e2e_qp_fwd_bwd"] = {"tokens": T2, "ms_per_step": round(dt * 1e3, 4), "tflops": round(fl / dt / 1e12, 2),
+                              "pct_of_bf16_mfma_peak": round(100 * fl / dt / 1e12 / PEAK_BF16_TFLOPS, 2),
+                              "tokens_per_s_per_layer": round(T2 / dt, 1)}
+    wbytes = 2 if adt == torch.bfloat16 else 4
+
+    def pack_all():
+        for L, P in zip(layers, packed):
+            eq.eqat_pack(L["W"], L["s"], L["z"], bits, g, Wpacked=P["Wp"], zpacked=P["zp"])
+
+    dt = timed(pack_all, args.steps)
+    b = sum_io * (wbytes + 8.0 / g + bits / 8.0 + bits / (8.0 * g))
+    rows["eqat_pack"] = {"ms": round(dt * 1e3, 4), "gbs": round(b / dt / 1e9, 1), "frac_of_hbm_peak": round(b / dt / 1e9 / PEAK_HBM_GBS, 4),
+                         "bytes": b}
+    sz = [(torch.empty_like(L["s"]), torch.empty_like(L["z"])) for L in layers]
+
+    def init_all():
+        for L, (s, z) in zip(layers, sz):
+            eq.eqat_init_minmax(L["W"], bits, g, s=s, z=z)
+
+    dt = timed(init_all, args.steps)
+    b = sum_io * (wbytes + 8.0 / g)
+    rows["eqat_init_minmax"] = {"ms": round(dt * 1e3, 4), "gbs": round(b / dt / 1e9, 1), "frac_of_hbm_peak": round(b / dt / 1e9 / PEAK_HBM_GBS, 4),
+                                "bytes": b}
+    return rows
+
+
+def cpu_baseline(wl):
+    """The fp64 oracle on a bounded sample of the same workload: the q projection, a slab of token rows for
+    Y and dX (against the full weight matrix) and a slab of output rows for dW/ds/dz (full token contraction)."""
+    import torch
+    import oracle
+    from paper_2407_11062_amd import synth
+    lin = wl.layers[0]
+    O, I, T = lin.out_features, lin.in_features, wl.tokens
+    n_tok, n_rows = T, O          # the whole projection: about 10 s on 16 host cores
+    adt = synth.torch_dtype(wl.act_dtype)
+    W = synth.normal((O, I), wl.w_std, 11, adt).float().numpy()
+    Xs = synth.normal((n_tok, I), 1.0, 12, adt).float().numpy()
+    dYs = synth.normal((n_tok, O), 1.0, 13, adt).float().numpy()
+    Xf = synth.normal((T, I), 1.0, 14, adt).float().numpy()
+    dYr = synth.normal((T, n_rows), 1.0, 15, adt).float().numpy()
+    s, z = oracle.init_minmax(W, wl.bits, wl.group)
+    t0 = time.perf_counter()
+    oracle.fq_linear_fwd(Xs, W, s, z, wl.bits, wl.group)
+    oracle.fq_linear_bwd(None, W, s, z, dYs, wl.bits, wl.group, want=("dX",))
+    oracle.fq_linear_bwd(Xf, W[:n_rows], s[:n_rows], z[:n_rows], dYr, wl.bits, wl.group, want=("dW", "ds", "dz"))
+    dt = time.perf_counter() - t0
+    flops = 2.0 * n_tok * O * I * 2 + 2.0 * T * n_rows * I
+    return {"value": round(flops / dt / 1e12, 6), "unit": "TFLOP/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "seconds": round(dt, 3),
+            "sample": f"q projection {O}x{I}, w{wl.bits}g{wl.group}: Y and dX for {n_tok} token rows against the full "
+                      f"weight matrix, dW/ds/dz for {n_rows} output rows over all {T} tokens ({flops:.3e} flop, fp64)"}
+
+
+if __name__ == "__main__":
+    sys.exit(main())

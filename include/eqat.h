@@ -140,6 +140,20 @@ eqat_status eqat_qlinear_bwd(const eqat_desc *d, const void *X, const uint8_t *W
                              const uint8_t *zpacked, const void *dY, void *dX, float *ds,
                              void *ws, size_t ws_bytes, void *stream);
 
+/*
+ * Optional per-kernel timing (measurement aid, not part of the paper's method).
+ * Between eqat_profile_start() and eqat_profile_stop() every kernel launch of the
+ * library is bracketed by a pair of HIP events recorded on the caller's stream.
+ * eqat_profile_stop() waits for those events and writes, per kernel class k in
+ * [0, eqat_profile_kernels()), the summed elapsed milliseconds and the number of
+ * launches into host arrays of length n; it then switches timing off.  Event
+ * objects are created on first use and kept.  Not thread-safe.
+ */
+int eqat_profile_kernels(void);
+const char *eqat_profile_kernel_name(int k);
+eqat_status eqat_profile_start(void);
+eqat_status eqat_profile_stop(double *total_ms, int64_t *launches, int n);
+
 #ifdef __cplusplus
 }
 #endif

@@ -24,7 +24,8 @@ STATUS_NAMES = ["EQAT_OK", "EQAT_ERR_NULL", "EQAT_ERR_SHAPE", "EQAT_ERR_BITS", "
 
 EXPORTS = ["eqat_status_string", "eqat_validate_desc", "eqat_packed_w_bytes", "eqat_packed_z_bytes",
            "eqat_workspace_bytes", "eqat_init_minmax", "eqat_fq_linear_fwd", "eqat_fq_linear_bwd", "eqat_pack",
-           "eqat_unpack", "eqat_qlinear_fwd", "eqat_qlinear_bwd"]
+           "eqat_unpack", "eqat_qlinear_fwd", "eqat_qlinear_bwd", "eqat_profile_kernels", "eqat_profile_kernel_name",
+           "eqat_profile_start", "eqat_profile_stop"]
 
 
 class Desc(ctypes.Structure):
@@ -65,6 +66,9 @@ def lib():
         L.eqat_unpack.argtypes = [dp, vp, vp, vp, vp, vp]
         L.eqat_qlinear_fwd.argtypes = [dp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.eqat_qlinear_bwd.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.eqat_profile_kernel_name.restype = ctypes.c_char_p
+        L.eqat_profile_kernel_name.argtypes = [ctypes.c_int]
+        L.eqat_profile_stop.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64), ctypes.c_int]
         _lib = L
     return _lib
 
@@ -192,3 +196,16 @@ def eqat_qlinear_bwd(X, Wpacked, s, zpacked, dY, in_features, bits, group, want=
     _check("eqat_qlinear_bwd", lib().eqat_qlinear_bwd(ctypes.byref(d), _p(X), _p(Wpacked), _p(s), _p(zpacked), _p(dY),
                                                       _p(out.get("dX")), _p(out.get("ds")), _p(ws), ws.numel(), _stream()))
     return out
+
+
+def eqat_profile_start():
+    _check("eqat_profile_start", lib().eqat_profile_start())
+
+
+def eqat_profile_stop():
+    """{kernel class: (total ms, launches)} for every class that ran since eqat_profile_start()."""
+    n = lib().eqat_profile_kernels()
+    ms = (ctypes.c_double * n)()
+    cnt = (ctypes.c_int64 * n)()
+    _check("eqat_profile_stop", lib().eqat_profile_stop(ms, cnt, n))
+    return {lib().eqat_profile_kernel_name(k).decode(): (ms[k], cnt[k]) for k in range(n) if cnt[k]}

@@ -3,8 +3,36 @@
 
 #include "../../include/eqat.h"
 #include "kernels.h"
+#include "prof.h"
+
+#include <vector>
 
 using eqat::Problem;
+using eqat::ProfScope;
+
+namespace eqat {
+bool g_prof_on = false;
+namespace {
+struct ProfRec { hipEvent_t a, b; int kernel; };
+std::vector<ProfRec> g_recs;     // event pairs, reused between profiling sessions
+size_t g_used = 0;
+}  // namespace
+void prof_mark(int kernel, hipStream_t st, bool begin)
+{
+    if (begin) {
+        if (g_used == g_recs.size()) {
+            ProfRec r{};
+            if (hipEventCreate(&r.a) != hipSuccess || hipEventCreate(&r.b) != hipSuccess) { g_prof_on = false; return; }
+            g_recs.push_back(r);
+        }
+        g_recs[g_used].kernel = kernel;
+        (void)hipEventRecord(g_recs[g_used].a, st);
+    } else if (g_used < g_recs.size()) {
+        (void)hipEventRecord(g_recs[g_used].b, st);
+        ++g_used;
+    }
+}
+}  // namespace eqat
 
 namespace {
 
@@ -97,6 +125,38 @@ const char *eqat_status_string(int status)
 
 eqat_status eqat_validate_desc(const eqat_desc *d) { return check_desc(d, true, nullptr); }
 
+int eqat_profile_kernels(void) { return eqat::PK_COUNT; }
+
+const char *eqat_profile_kernel_name(int k)
+{
+    static const char *names[eqat::PK_COUNT] = {"init_minmax", "quantize", "pack_z", "unpack_sz", "gemm_fwd", "gemm_dx",
+                                                "gemm_dw", "reduce_partials", "f32_path"};
+    return (k >= 0 && k < eqat::PK_COUNT) ? names[k] : "?";
+}
+
+eqat_status eqat_profile_start(void)
+{
+    eqat::g_used = 0;
+    eqat::g_prof_on = true;
+    return EQAT_OK;
+}
+
+eqat_status eqat_profile_stop(double *total_ms, int64_t *launches, int n)
+{
+    eqat::g_prof_on = false;
+    if (total_ms == nullptr || launches == nullptr) return EQAT_ERR_NULL;
+    for (int k = 0; k < n; ++k) { total_ms[k] = 0.0; launches[k] = 0; }
+    eqat_status rc = EQAT_OK;
+    for (size_t i = 0; i < eqat::g_used; ++i) {
+        const eqat::ProfRec &r = eqat::g_recs[i];
+        float ms = 0.0f;
+        if (hipEventSynchronize(r.b) != hipSuccess || hipEventElapsedTime(&ms, r.a, r.b) != hipSuccess) { rc = EQAT_ERR_DEVICE; continue; }
+        if (r.kernel < n) { total_ms[r.kernel] += ms; launches[r.kernel] += 1; }
+    }
+    eqat::g_used = 0;
+    return rc;
+}
+
 size_t eqat_packed_w_bytes(const eqat_desc *d)
 {
     Problem p;
@@ -124,7 +184,7 @@ eqat_status eqat_init_minmax(const eqat_desc *d, const void *W, float *s, float 
     if (eqat_status e = check_desc(d, false, &p)) return e;
     EQAT_REQUIRE(W); EQAT_REQUIRE(s); EQAT_REQUIRE(z);
     EQAT_ALIGNED(W); EQAT_ALIGNED(s); EQAT_ALIGNED(z);
-    eqat::launch_init_minmax(p, W, s, z, (hipStream_t)stream);
+    { ProfScope ps(eqat::PK_INIT_MINMAX, (hipStream_t)stream); eqat::launch_init_minmax(p, W, s, z, (hipStream_t)stream); }
     return launch_status();
 }
 
@@ -136,8 +196,8 @@ eqat_status eqat_pack(const eqat_desc *d, const void *W, const float *s, const f
     EQAT_REQUIRE(W); EQAT_REQUIRE(s); EQAT_REQUIRE(z); EQAT_REQUIRE(Wpacked); EQAT_REQUIRE(zpacked);
     EQAT_ALIGNED(W); EQAT_ALIGNED(s); EQAT_ALIGNED(z); EQAT_ALIGNED(Wpacked); EQAT_ALIGNED(zpacked);
     hipStream_t st = (hipStream_t)stream;
-    eqat::launch_quantize(p, W, s, z, Wpacked, nullptr, nullptr, false, st);
-    eqat::launch_pack_z(p, z, zpacked, st);
+    { ProfScope ps(eqat::PK_QUANTIZE, st); eqat::launch_quantize(p, W, s, z, Wpacked, nullptr, nullptr, false, st); }
+    { ProfScope ps(eqat::PK_PACK_Z, st); eqat::launch_pack_z(p, z, zpacked, st); }
     return launch_status();
 }
 
@@ -166,10 +226,10 @@ eqat_status eqat_fq_linear_fwd(const eqat_desc *d, const void *X, const void *W,
     hipStream_t st = (hipStream_t)stream;
     char *w8 = (char *)ws;
     if (p.act_bf16) {
-        eqat::launch_quantize(p, W, s, z, w8 + l.codes, nullptr, w8 + l.sz, false, st);
-        eqat::launch_mfma_fwd(p, X, w8 + l.codes, w8 + l.sz, Y, st);
+        { ProfScope ps(eqat::PK_QUANTIZE, st); eqat::launch_quantize(p, W, s, z, w8 + l.codes, nullptr, w8 + l.sz, false, st); }
+        { ProfScope ps(eqat::PK_GEMM_FWD, st); eqat::launch_mfma_fwd(p, X, w8 + l.codes, w8 + l.sz, Y, st); }
     } else {
-        eqat::launch_f32_fwd(p, false, X, W, s, z, Y, st);
+        { ProfScope ps(eqat::PK_F32, st); eqat::launch_f32_fwd(p, false, X, W, s, z, Y, st); }
     }
     return launch_status();
 }
@@ -191,12 +251,13 @@ eqat_status eqat_fq_linear_bwd(const eqat_desc *d, const void *X, const void *W,
     hipStream_t st = (hipStream_t)stream;
     char *w8 = (char *)ws;
     if (p.act_bf16) {
-        eqat::launch_quantize(p, W, s, z, w8 + l.codes, w8 + l.clamp, w8 + l.sz, false, st);
-        if (dX != nullptr) eqat::launch_mfma_dx(p, dY, w8 + l.codes, w8 + l.sz, dX, st);
+        { ProfScope ps(eqat::PK_QUANTIZE, st); eqat::launch_quantize(p, W, s, z, w8 + l.codes, w8 + l.clamp, w8 + l.sz, false, st); }
+        if (dX != nullptr) { ProfScope ps(eqat::PK_GEMM_DX, st); eqat::launch_mfma_dx(p, dY, w8 + l.codes, w8 + l.sz, dX, st); }
         if (want_w)
             eqat::launch_mfma_dw(p, true, X, dY, W, w8 + l.codes, w8 + l.clamp, w8 + l.sz, s, dW, ds, dz,
                                  (float *)(w8 + l.part), st);
     } else {
+        ProfScope ps(eqat::PK_F32, st);
         if (dX != nullptr && p.T > 0) eqat::launch_f32_dx(p, false, dY, W, s, z, dX, st);
         if (want_w) eqat::launch_f32_dw(p, true, X, dY, W, s, z, (float *)(w8 + l.dwhat), dW, ds, dz, st);
     }
@@ -216,9 +277,9 @@ eqat_status eqat_qlinear_fwd(const eqat_desc *d, const void *X, const uint8_t *W
     if (p.T == 0) return EQAT_OK;
     hipStream_t st = (hipStream_t)stream;
     char *w8 = (char *)ws;
-    eqat::launch_unpack_sz(p, s, zpacked, w8 + l.sz, st);
-    if (p.act_bf16) eqat::launch_mfma_fwd(p, X, Wpacked, w8 + l.sz, Y, st);
-    else eqat::launch_f32_fwd(p, true, X, Wpacked, s, w8 + l.sz, Y, st);
+    { ProfScope ps(eqat::PK_UNPACK_SZ, st); eqat::launch_unpack_sz(p, s, zpacked, w8 + l.sz, st); }
+    if (p.act_bf16) { ProfScope ps(eqat::PK_GEMM_FWD, st); eqat::launch_mfma_fwd(p, X, Wpacked, w8 + l.sz, Y, st); }
+    else { ProfScope ps(eqat::PK_F32, st); eqat::launch_f32_fwd(p, true, X, Wpacked, s, w8 + l.sz, Y, st); }
     return launch_status();
 }
 
@@ -237,13 +298,14 @@ eqat_status eqat_qlinear_bwd(const eqat_desc *d, const void *X, const uint8_t *W
     if (dX == nullptr && ds == nullptr) return EQAT_OK;
     hipStream_t st = (hipStream_t)stream;
     char *w8 = (char *)ws;
-    eqat::launch_unpack_sz(p, s, zpacked, w8 + l.sz, st);
+    { ProfScope ps(eqat::PK_UNPACK_SZ, st); eqat::launch_unpack_sz(p, s, zpacked, w8 + l.sz, st); }
     if (p.act_bf16) {
-        if (dX != nullptr) eqat::launch_mfma_dx(p, dY, Wpacked, w8 + l.sz, dX, st);
+        if (dX != nullptr) { ProfScope ps(eqat::PK_GEMM_DX, st); eqat::launch_mfma_dx(p, dY, Wpacked, w8 + l.sz, dX, st); }
         if (ds != nullptr)
             eqat::launch_mfma_dw(p, false, X, dY, nullptr, Wpacked, nullptr, w8 + l.sz, s, nullptr, ds, nullptr,
                                  (float *)(w8 + l.part), st);
     } else {
+        ProfScope ps(eqat::PK_F32, st);
         if (dX != nullptr && p.T > 0) eqat::launch_f32_dx(p, true, dY, Wpacked, s, w8 + l.sz, dX, st);
         if (ds != nullptr) eqat::launch_f32_dw(p, false, X, dY, Wpacked, s, w8 + l.sz, (float *)(w8 + l.dwhat), nullptr, ds, nullptr, st);
     }

@@ -13,6 +13,7 @@
 // The paddings make both read patterns bank-conflict free.
 #include "common.h"
 #include "kernels.h"
+#include "prof.h"
 
 namespace eqat {
 
@@ -524,13 +525,17 @@ void launch_mfma_dw(const Problem &p, bool block_ap, const void *X, const void *
     const bool partials = dw_needs_partials(p);
     const size_t n32 = (size_t)p.O * (p.I / 32);
     a.part_ds = part; a.part_dz = part ? part + n32 : nullptr;
-    if (block_ap) {
-        if (p.w_bf16) launch_dw_bits<bf16_t, true>(p.bits, a, st);
-        else launch_dw_bits<float, true>(p.bits, a, st);
-    } else {
-        launch_dw_bits<bf16_t, false>(p.bits, a, st);
+    {
+        ProfScope ps(PK_GEMM_DW, st);
+        if (block_ap) {
+            if (p.w_bf16) launch_dw_bits<bf16_t, true>(p.bits, a, st);
+            else launch_dw_bits<float, true>(p.bits, a, st);
+        } else {
+            launch_dw_bits<bf16_t, false>(p.bits, a, st);
+        }
     }
     if (partials) {
+        ProfScope ps(PK_REDUCE, st);
         const uint32_t n_per = (uint32_t)(p.g / 32);
         if (ds != nullptr) launch_reduce_partials(a.part_ds, ds, s, (size_t)p.O * p.G, n_per, false, st);
         if (block_ap && dz != nullptr) launch_reduce_partials(a.part_dz, dz, s, (size_t)p.O * p.G, n_per, true, st);
