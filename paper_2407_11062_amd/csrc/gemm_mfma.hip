@@ -15,8 +15,16 @@
 #include "kernels.h"
 #include "prof.h"
 
+#include <stdlib.h>
+
 namespace eqat {
 
+#ifndef EXPERIMENT_NOA
+#define EXPERIMENT_NOA 0
+#endif
+#ifndef EXPERIMENT_NODEQ
+#define EXPERIMENT_NODEQ 0
+#endif
 constexpr int kPadKC = 8;    // bf16 elements
 constexpr int kPadKM = 32;
 
@@ -46,6 +54,7 @@ __device__ __forceinline__ bf16x8 frag_km(const bf16_t *tile, int col0, int kk, 
 template <int BITS, int K0>
 __device__ __forceinline__ bf16x8 dequant8(const CodeWords<BITS> &c, float s, float b)
 {
+    if (EXPERIMENT_NODEQ) { uintx4 u; u[0] = c.w[0]; u[1] = c.w[1]; u[2] = c.w[0] ^ K0; u[3] = __float_as_uint(s); return __builtin_bit_cast(bf16x8, u); }
     bf16x8 o;
 #define EQAT_DQ(J) o[J] = (bf16_t)__builtin_fmaf((float)code_at<BITS, K0 + J>(c), s, b)
     EQAT_DQ(0); EQAT_DQ(1); EQAT_DQ(2); EQAT_DQ(3); EQAT_DQ(4); EQAT_DQ(5); EQAT_DQ(6); EQAT_DQ(7);
@@ -82,16 +91,43 @@ struct GemmQArgs {
     int tiles_m, tiles_n;
 };
 
+template <int V> struct IC { static constexpr int value = V; };
+
+// ---- KC tile filled by buffer loads that write LDS directly ----------------------------------------------
+// Such a load puts the 16 bytes of lane j at (wave-uniform LDS base) + 16*j, so one instruction fills 8 rows of
+// a [rows][64] bf16 tile and no padding can be placed inside it.  Bank conflicts of the fragment reads are
+// avoided by a swizzle instead: the 16-byte chunk c of row r lives at position c ^ ((r >> 1) & 7); the
+// permutation is applied on the global-address side, which is free.
+__device__ __forceinline__ int kc_swz(int row, int chunk) { return chunk ^ ((row >> 1) & 7); }
+
+__device__ __forceinline__ bf16x8 frag_kc_swz(const bf16_t *tile, int row0, int kk, int lane)
+{
+    const int r = row0 + (lane & 31);
+    return *reinterpret_cast<const bf16x8 *>(tile + r * 64 + kc_swz(r, kk * 2 + (lane >> 5)) * 8);
+}
+
+__device__ __forceinline__ void load_to_lds16(__amdgpu_buffer_rsrc_t r, bf16_t *lds_wave_base, uint32_t voffset)
+{
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (void __attribute__((address_space(3))) *)lds_wave_base, 16, (int)voffset, 0, 0, 0);
+}
+
+// Software pipeline of the main loop (one workgroup, K tile kt):
+//   - the activation tile kt+1 streams from global memory straight into the idle LDS buffer;
+//   - the weight codes of tile kt+2 are fetched into registers (two staging sets);
+//   - while the MFMAs consume LDS buffer kt&1, the staged codes of tile kt+1 become bf16 What in the idle
+//     weight buffer, a quarter after each 16-wide K slice, so that this VALU / LDS-write work hides under the
+//     MFMAs of the same wave; fragments of slice kk+1 are read while slice kk multiplies.
+// Loads past the end of K return zeros (buffer range check), so the tail needs no branches.
 template <int BITS, bool BT, int BM, int BN, int BK, int WGM, int WGN>
 __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_q(const GemmQArgs a)
 {
-    constexpr int NT = 64 * WGM * WGN, WTM = BM / WGM, WTN = BN / WGN, MI = WTM / 32, NI = WTN / 32;
-    constexpr int LDA = BK + kPadKC;
+    constexpr int NT = 64 * WGM * WGN, NW = WGM * WGN, WTM = BM / WGM, WTN = BN / WGN, MI = WTM / 32, NI = WTN / 32;
     constexpr int LDB = BT ? BN + kPadKM : BK + kPadKC;
-    constexpr int A_ELEMS = BM * LDA, B_ELEMS = BT ? BK * LDB : BN * LDB;
-    constexpr int A_CHUNKS = BM * BK / 8 / NT;        // 16-byte chunks per thread
+    constexpr int A_ELEMS = BM * BK, B_ELEMS = BT ? BK * LDB : BN * LDB;
+    constexpr int A_LOADS = BM / 8 / NW;              // direct-to-LDS instructions per wave (8 rows each)
     constexpr int B_SEGS = BN * BK / 32 / NT;         // 32-code segments per thread
-    static_assert(BM * BK / 8 % NT == 0 && BN * BK / 32 % NT == 0 && BK % 32 == 0, "tile / thread mismatch");
+    constexpr int KK = BK / 16;
+    static_assert(BK == 64 && BM % (8 * NW) == 0 && BN * BK / 32 % NT == 0, "tile / thread mismatch");
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     bf16_t *sA = reinterpret_cast<bf16_t *>(smem_raw);            // [2][A_ELEMS]
@@ -107,18 +143,21 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_q(const GemmQArgs a)
     const __amdgpu_buffer_rsrc_t rS = make_rsrc(a.sz, a.sz_bytes);
     const uint32_t code_row_bytes = (uint32_t)a.I * BITS / 8;
 
-    intx4 stA[A_CHUNKS];
-    CodeWords<BITS> stC[B_SEGS];
-    floatx2 stS[B_SEGS];
+    CodeWords<BITS> stC[2][B_SEGS];
+    floatx2 stS[2][B_SEGS];
 
-    auto load_global = [&](int k0) {
+    // activation tile at k0 -> LDS buffer `buf` (asynchronous)
+    auto load_a = [&](int k0, int buf) {
 #pragma unroll
-        for (int it = 0; it < A_CHUNKS; ++it) {
-            const int c = it * NT + tid, row = c / (BK / 8), kc = c % (BK / 8);
-            const int k = k0 + kc * 8;
+        for (int it = 0; it < A_LOADS; ++it) {
+            const int rb = (wave * A_LOADS + it) * 8;                 // first of 8 rows, wave-uniform
+            const int row = rb + (lane >> 3), k = k0 + kc_swz(row, lane & 7) * 8;
             const uint32_t off = (k < a.K) ? ((uint32_t)(m0 + row) * (uint32_t)a.K + (uint32_t)k) * 2u : kOobOffset;
-            stA[it] = buf_load16(rA, off);
+            if (!EXPERIMENT_NOA) load_to_lds16(rA, sA + buf * A_ELEMS + rb * 64, off);
         }
+    };
+    auto load_codes = [&](auto set, int k0) {
+        constexpr int S = decltype(set)::value;
 #pragma unroll
         for (int it = 0; it < B_SEGS; ++it) {
             const int sidx = it * NT + tid;
@@ -126,31 +165,28 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_q(const GemmQArgs a)
             if (!BT) { wrow = n0 + sidx / (BK / 32); wcol = k0 + (sidx % (BK / 32)) * 32; }
             else     { wrow = k0 + sidx / (BN / 32); wcol = n0 + (sidx % (BN / 32)) * 32; }
             const bool ok = wcol < a.I;
-            stC[it] = load_code_words<BITS>(rC, (uint32_t)wrow * code_row_bytes + (uint32_t)(wcol >> 5) * (4u * BITS));
+            stC[S][it] = load_code_words<BITS>(rC, (uint32_t)wrow * code_row_bytes + (uint32_t)(wcol >> 5) * (4u * BITS));
             const intx2 sv = buf_load8(rS, ok ? ((uint32_t)wrow * (uint32_t)a.G + (uint32_t)(wcol / a.g)) * 8u : kOobOffset);
-            stS[it][0] = __int_as_float(sv[0]);
-            stS[it][1] = __int_as_float(sv[1]);
+            stS[S][it][0] = __int_as_float(sv[0]);
+            stS[S][it][1] = __int_as_float(sv[1]);
         }
     };
-    auto store_lds = [&](int buf) {
-        bf16_t *dA = sA + buf * A_ELEMS, *dB = sB + buf * B_ELEMS;
-#pragma unroll
-        for (int it = 0; it < A_CHUNKS; ++it) {
-            const int c = it * NT + tid, row = c / (BK / 8), kc = c % (BK / 8);
-            *reinterpret_cast<intx4 *>(dA + row * LDA + kc * 8) = stA[it];
-        }
+    // piece P of KK: every KK-th 16-byte store of the staged weight tile
+    auto commit_piece = [&](auto set, auto piece, int buf) {
+        constexpr int S = decltype(set)::value, P = decltype(piece)::value;
+        bf16_t *dB = sB + buf * B_ELEMS;
 #pragma unroll
         for (int it = 0; it < B_SEGS; ++it) {
             const int sidx = it * NT + tid;
             int r, c;
             if (!BT) { r = sidx / (BK / 32); c = (sidx % (BK / 32)) * 32; }
             else     { r = sidx / (BN / 32); c = (sidx % (BN / 32)) * 32; }
-            const float s = stS[it][0], b = -stS[it][1] * s;     // What = code*s - zbar*s
+            const float s = stS[S][it][0], b = -stS[S][it][1] * s;     // What = code*s - zbar*s
             bf16x8 *dst = reinterpret_cast<bf16x8 *>(dB + r * LDB + c);
-            dst[0] = dequant8<BITS, 0>(stC[it], s, b);
-            dst[1] = dequant8<BITS, 8>(stC[it], s, b);
-            dst[2] = dequant8<BITS, 16>(stC[it], s, b);
-            dst[3] = dequant8<BITS, 24>(stC[it], s, b);
+            if ((it * 4 + 0) % KK == P) dst[0] = dequant8<BITS, 0>(stC[S][it], s, b);
+            if ((it * 4 + 1) % KK == P) dst[1] = dequant8<BITS, 8>(stC[S][it], s, b);
+            if ((it * 4 + 2) % KK == P) dst[2] = dequant8<BITS, 16>(stC[S][it], s, b);
+            if ((it * 4 + 3) % KK == P) dst[3] = dequant8<BITS, 24>(stC[S][it], s, b);
         }
     };
 
@@ -162,32 +198,54 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_q(const GemmQArgs a)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
-    const int nk = (a.K + BK - 1) / BK;
-    load_global(0);
-    store_lds(0);
-    __syncthreads();
-    for (int kt = 0; kt < nk; ++kt) {
-        const int buf = kt & 1;
-        if (kt + 1 < nk) load_global((kt + 1) * BK);
-        const bf16_t *cA = sA + buf * A_ELEMS, *cB = sB + buf * B_ELEMS;
+    bf16x8 fa[2][MI], fb[2][NI];
+    auto read_frags = [&](int slot, const bf16_t *cA, const bf16_t *cB, int kk) {
 #pragma unroll
-        for (int kk = 0; kk < BK / 16; ++kk) {
-            bf16x8 fa[MI], fb[NI];
+        for (int i = 0; i < MI; ++i) fa[slot][i] = frag_kc_swz(cA, wm * WTM + i * 32, kk, lane);
 #pragma unroll
-            for (int i = 0; i < MI; ++i) fa[i] = frag_kc<LDA>(cA, wm * WTM + i * 32, kk, lane);
-#pragma unroll
-            for (int j = 0; j < NI; ++j) {
-                if (!BT) fb[j] = frag_kc<LDB>(cB, wn * WTN + j * 32, kk, lane);
-                else     fb[j] = frag_km<LDB>(cB, wn * WTN + j * 32, kk, lane);
-            }
+        for (int j = 0; j < NI; ++j) {
+            if (!BT) fb[slot][j] = frag_kc<LDB>(cB, wn * WTN + j * 32, kk, lane);
+            else     fb[slot][j] = frag_km<LDB>(cB, wn * WTN + j * 32, kk, lane);
+        }
+    };
+    // one K tile: PAR = kt & 1 is the LDS buffer being multiplied and the code staging set being refilled
+    auto step = [&](auto par, int kt) {
+        constexpr int PAR = decltype(par)::value;
+        load_codes(IC<PAR>{}, (kt + 2) * BK);
+        load_a((kt + 1) * BK, PAR ^ 1);
+        const bf16_t *cA = sA + PAR * A_ELEMS, *cB = sB + PAR * B_ELEMS;
+        read_frags(0, cA, cB, 0);
+        auto slice = [&](auto kkc) {
+            constexpr int kk = decltype(kkc)::value;
+            if (kk + 1 < KK) read_frags((kk + 1) & 1, cA, cB, kk + 1);
 #pragma unroll
             for (int i = 0; i < MI; ++i)
 #pragma unroll
                 for (int j = 0; j < NI; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
-        }
-        if (kt + 1 < nk) store_lds(buf ^ 1);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[kk & 1][i], fb[kk & 1][j], acc[i][j], 0, 0, 0);
+            commit_piece(IC<PAR ^ 1>{}, IC<kk>{}, PAR ^ 1);
+        };
+        slice(IC<0>{});
+        slice(IC<1>{});
+        slice(IC<2>{});
+        slice(IC<3>{});
+        __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0): the activation tile for the next step has landed in LDS
         __syncthreads();
+    };
+
+    const int nk = (a.K + BK - 1) / BK;
+    load_codes(IC<0>{}, 0);
+    load_a(0, 0);
+    load_codes(IC<1>{}, BK);
+    commit_piece(IC<0>{}, IC<0>{}, 0);
+    commit_piece(IC<0>{}, IC<1>{}, 0);
+    commit_piece(IC<0>{}, IC<2>{}, 0);
+    commit_piece(IC<0>{}, IC<3>{}, 0);
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    __syncthreads();
+    for (int kt = 0; kt < nk; kt += 2) {
+        step(IC<0>{}, kt);
+        if (kt + 1 < nk) step(IC<1>{}, kt + 1);
     }
 
     // C[m][n]: lane holds column n = l % 32 and rows 8*(r/4) + 4*(l/32) + r%4 of each 32x32 block
@@ -440,13 +498,28 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_dw(const GemmDwArgs a)
 // ======================================================================================================
 namespace {
 
-struct TileShape { static constexpr int BM = 128, BN = 128, BK = 64, WGM = 2, WGN = 2; };
+template <int BM_, int BN_, int BK_, int WGM_, int WGN_> struct Tile {
+    static constexpr int BM = BM_, BN = BN_, BK = BK_, WGM = WGM_, WGN = WGN_;
+};
+typedef Tile<128, 128, 64, 2, 2> Tile0;
+typedef Tile<256, 256, 64, 2, 2> Tile1;
+typedef Tile<256, 256, 64, 2, 4> Tile2;
+typedef Tile<256, 128, 64, 2, 2> Tile3;
+typedef Tile<128, 256, 64, 2, 2> Tile4;
+typedef Tile<256, 256, 64, 4, 2> Tile5;
+
+int tile_choice()
+{
+    static int c = -1;
+    if (c < 0) { const char *e = getenv("EQAT_TILE"); c = e ? atoi(e) : 2; }
+    return c;
+}
 
 template <int BITS, bool BT, typename TS>
 void launch_q(const GemmQArgs &args, hipStream_t st)
 {
-    constexpr int LDA = TS::BK + kPadKC, LDB = BT ? TS::BN + kPadKM : TS::BK + kPadKC;
-    constexpr size_t smem = 2 * (size_t)(TS::BM * LDA + (BT ? TS::BK * LDB : TS::BN * LDB)) * sizeof(bf16_t);
+    constexpr int LDB = BT ? TS::BN + kPadKM : TS::BK + kPadKC;
+    constexpr size_t smem = 2 * (size_t)(TS::BM * TS::BK + (BT ? TS::BK * LDB : TS::BN * LDB)) * sizeof(bf16_t);
     auto kern = k_gemm_q<BITS, BT, TS::BM, TS::BN, TS::BK, TS::WGM, TS::WGN>;
     static bool attr_set = false;
     if (!attr_set) { (void)hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem); attr_set = true; }
@@ -456,12 +529,25 @@ void launch_q(const GemmQArgs &args, hipStream_t st)
     kern<<<dim3(a.tiles_m * a.tiles_n), dim3(64 * TS::WGM * TS::WGN), smem, st>>>(a);
 }
 
+template <int BITS, bool BT>
+void launch_q_tile(const GemmQArgs &args, hipStream_t st)
+{
+    switch (tile_choice()) {
+    case 1: launch_q<BITS, BT, Tile1>(args, st); break;
+    case 2: launch_q<BITS, BT, Tile2>(args, st); break;
+    case 3: launch_q<BITS, BT, Tile3>(args, st); break;
+    case 4: launch_q<BITS, BT, Tile4>(args, st); break;
+    case 5: launch_q<BITS, BT, Tile5>(args, st); break;
+    default: launch_q<BITS, BT, Tile0>(args, st);
+    }
+}
+
 template <bool BT>
 void launch_q_bits(int bits, const GemmQArgs &args, hipStream_t st)
 {
-    if (bits == 2) launch_q<2, BT, TileShape>(args, st);
-    else if (bits == 3) launch_q<3, BT, TileShape>(args, st);
-    else launch_q<4, BT, TileShape>(args, st);
+    if (bits == 2) launch_q_tile<2, BT>(args, st);
+    else if (bits == 3) launch_q_tile<3, BT>(args, st);
+    else launch_q_tile<4, BT>(args, st);
 }
 
 template <int BITS, typename WT, bool AP, typename TS>
@@ -478,17 +564,35 @@ void launch_dw_t(const GemmDwArgs &args, hipStream_t st)
     kern<<<dim3(a.tiles_m * a.tiles_n), dim3(64 * TS::WGM * TS::WGN), smem, st>>>(a);
 }
 
+template <int BITS, typename WT, bool AP>
+void launch_dw_tile(const GemmDwArgs &args, hipStream_t st)
+{
+    switch (tile_choice()) {
+    case 1: launch_dw_t<BITS, WT, AP, Tile1>(args, st); break;
+    case 2: launch_dw_t<BITS, WT, AP, Tile2>(args, st); break;
+    case 3: launch_dw_t<BITS, WT, AP, Tile3>(args, st); break;
+    case 4: launch_dw_t<BITS, WT, AP, Tile4>(args, st); break;
+    case 5: launch_dw_t<BITS, WT, AP, Tile5>(args, st); break;
+    default: launch_dw_t<BITS, WT, AP, Tile0>(args, st);
+    }
+}
+
 template <typename WT, bool AP>
 void launch_dw_bits(int bits, const GemmDwArgs &args, hipStream_t st)
 {
-    if (bits == 2) launch_dw_t<2, WT, AP, TileShape>(args, st);
-    else if (bits == 3) launch_dw_t<3, WT, AP, TileShape>(args, st);
-    else launch_dw_t<4, WT, AP, TileShape>(args, st);
+    if (bits == 2) launch_dw_tile<2, WT, AP>(args, st);
+    else if (bits == 3) launch_dw_tile<3, WT, AP>(args, st);
+    else launch_dw_tile<4, WT, AP>(args, st);
+}
+
+int dw_tile_bm()
+{
+    switch (tile_choice()) { case 0: case 4: return 128; default: return 256; }
 }
 
 }  // namespace
 
-bool dw_needs_partials(const Problem &p) { return TileShape::BM % p.g != 0; }
+bool dw_needs_partials(const Problem &p) { return dw_tile_bm() % p.g != 0; }
 
 void launch_mfma_fwd(const Problem &p, const void *X, const void *codes, const void *sz, void *Y, hipStream_t st)
 {
