@@ -14,7 +14,7 @@ import os
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libeqat.so")
+LIB_PATH = os.environ.get("EQAT_LIB", os.path.join(_HERE, "libeqat.so"))   # EQAT_LIB: a build under test
 
 F32, BF16 = 0, 1
 OP_FQ_FWD, OP_FQ_BWD, OP_Q_FWD, OP_Q_BWD = 0, 1, 2, 3

@@ -19,6 +19,18 @@
 
 namespace eqat {
 
+#ifndef EXPERIMENT_NOCOMMIT
+#define EXPERIMENT_NOCOMMIT 0
+#endif
+#ifndef EXPERIMENT_NOFRAG
+#define EXPERIMENT_NOFRAG 0
+#endif
+#ifndef EXPERIMENT_NOWAITA
+#define EXPERIMENT_NOWAITA 0
+#endif
+#ifndef EXPERIMENT_ASMALL
+#define EXPERIMENT_ASMALL 0
+#endif
 #ifndef EXPERIMENT_NOA
 #define EXPERIMENT_NOA 0
 #endif
@@ -152,12 +164,14 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_q(const GemmQArgs a)
         for (int it = 0; it < A_LOADS; ++it) {
             const int rb = (wave * A_LOADS + it) * 8;                 // first of 8 rows, wave-uniform
             const int row = rb + (lane >> 3), k = k0 + kc_swz(row, lane & 7) * 8;
-            const uint32_t off = (k < a.K) ? ((uint32_t)(m0 + row) * (uint32_t)a.K + (uint32_t)k) * 2u : kOobOffset;
+            uint32_t off = (k < a.K) ? ((uint32_t)(m0 + row) * (uint32_t)a.K + (uint32_t)k) * 2u : kOobOffset;
+            if (EXPERIMENT_ASMALL) off = ((uint32_t)row * (uint32_t)a.K + (uint32_t)(k & 63)) * 2u;
             if (!EXPERIMENT_NOA) load_to_lds16(rA, sA + buf * A_ELEMS + rb * 64, off);
         }
     };
     auto load_codes = [&](auto set, int k0) {
         constexpr int S = decltype(set)::value;
+        if (EXPERIMENT_NOCOMMIT) return;
 #pragma unroll
         for (int it = 0; it < B_SEGS; ++it) {
             const int sidx = it * NT + tid;
@@ -174,6 +188,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_q(const GemmQArgs a)
     // piece P of KK: every KK-th 16-byte store of the staged weight tile
     auto commit_piece = [&](auto set, auto piece, int buf) {
         constexpr int S = decltype(set)::value, P = decltype(piece)::value;
+        if (EXPERIMENT_NOCOMMIT) return;
         bf16_t *dB = sB + buf * B_ELEMS;
 #pragma unroll
         for (int it = 0; it < B_SEGS; ++it) {
@@ -200,6 +215,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_q(const GemmQArgs a)
 
     bf16x8 fa[2][MI], fb[2][NI];
     auto read_frags = [&](int slot, const bf16_t *cA, const bf16_t *cB, int kk) {
+        if (EXPERIMENT_NOFRAG && kk >= 0) return;
 #pragma unroll
         for (int i = 0; i < MI; ++i) fa[slot][i] = frag_kc_swz(cA, wm * WTM + i * 32, kk, lane);
 #pragma unroll
@@ -208,29 +224,58 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_q(const GemmQArgs a)
             else     fb[slot][j] = frag_km<LDB>(cB, wn * WTN + j * 32, kk, lane);
         }
     };
-    // one K tile: PAR = kt & 1 is the LDS buffer being multiplied and the code staging set being refilled
+    // One K tile.  PAR = kt & 1 is the LDS buffer being multiplied.  On entry the fragments of slice 0 are already
+    // in registers.  The barrier sits BEFORE the MFMAs of the last slice: by then every wave has issued all its LDS
+    // reads of this tile and finished writing the next one, so after the barrier the next tile's first fragments and
+    // the global loads for later tiles are started and their latency hides under the last slice's MFMAs.
+    auto mfma_slice = [&](int slot) {
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int j = 0; j < NI; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[slot][i], fb[slot][j], acc[i][j], 0, 0, 0);
+    };
     auto step = [&](auto par, int kt) {
         constexpr int PAR = decltype(par)::value;
-        load_codes(IC<PAR>{}, (kt + 2) * BK);
-        load_a((kt + 1) * BK, PAR ^ 1);
         const bf16_t *cA = sA + PAR * A_ELEMS, *cB = sB + PAR * B_ELEMS;
-        read_frags(0, cA, cB, 0);
-        auto slice = [&](auto kkc) {
-            constexpr int kk = decltype(kkc)::value;
-            if (kk + 1 < KK) read_frags((kk + 1) & 1, cA, cB, kk + 1);
+        // stage kk: start the reads of slice kk+1, multiply slice kk, convert a quarter of the next weight tile
+        auto interleave = [&]() {
+            // pipeline hint for the scheduler: one MFMA, then a few VALU ops of the conversion, repeated
 #pragma unroll
-            for (int i = 0; i < MI; ++i)
-#pragma unroll
-                for (int j = 0; j < NI; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[kk & 1][i], fb[kk & 1][j], acc[i][j], 0, 0, 0);
-            commit_piece(IC<PAR ^ 1>{}, IC<kk>{}, PAR ^ 1);
+            for (int q = 0; q < MI * NI; ++q) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, 6, 0);
+            }
         };
-        slice(IC<0>{});
-        slice(IC<1>{});
-        slice(IC<2>{});
-        slice(IC<3>{});
-        __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0): the activation tile for the next step has landed in LDS
-        __syncthreads();
+        read_frags(1, cA, cB, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_slice(0);
+        commit_piece(IC<PAR ^ 1>{}, IC<1>{}, PAR ^ 1);
+        interleave();
+        __builtin_amdgcn_sched_barrier(0);
+        read_frags(0, cA, cB, 2);
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_slice(1);
+        commit_piece(IC<PAR ^ 1>{}, IC<2>{}, PAR ^ 1);
+        interleave();
+        __builtin_amdgcn_sched_barrier(0);
+        read_frags(1, cA, cB, 3);
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_slice(0);
+        commit_piece(IC<PAR ^ 1>{}, IC<3>{}, PAR ^ 1);
+        interleave();
+        __builtin_amdgcn_sched_barrier(0);
+        if (EXPERIMENT_NOWAITA) asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        else asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");   // next activation tile landed, my LDS traffic done
+        // last slice of this tile, overlapped with the start of the next two tiles
+        load_a((kt + 2) * BK, PAR);
+        read_frags(0, sA + (PAR ^ 1) * A_ELEMS, sB + (PAR ^ 1) * B_ELEMS, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_slice(1);
+        commit_piece(IC<PAR>{}, IC<0>{}, PAR);
+        interleave();
+        load_codes(IC<PAR ^ 1>{}, (kt + 3) * BK);
+        __builtin_amdgcn_sched_barrier(0);
     };
 
     const int nk = (a.K + BK - 1) / BK;
@@ -241,8 +286,11 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_q(const GemmQArgs a)
     commit_piece(IC<0>{}, IC<1>{}, 0);
     commit_piece(IC<0>{}, IC<2>{}, 0);
     commit_piece(IC<0>{}, IC<3>{}, 0);
-    __builtin_amdgcn_s_waitcnt(0x0F70);
-    __syncthreads();
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    load_a(BK, 1);
+    load_codes(IC<0>{}, 2 * BK);
+    commit_piece(IC<1>{}, IC<0>{}, 1);
+    read_frags(0, sA, sB, 0);
     for (int kt = 0; kt < nk; kt += 2) {
         step(IC<0>{}, kt);
         if (kt + 1 < nk) step(IC<1>{}, kt + 1);
@@ -309,14 +357,48 @@ template <> struct WQuad<float> {
     }
 };
 
+// ---- KM tile filled by direct-to-LDS loads ------------------------------------------------------------------
+// Tile [BK][COLS] bf16, rows unpadded.  A transpose read touches four consecutive k rows, 64 bytes of each, so
+// the 64-byte units of a row are XOR-swizzled with (k & 3) to spread those rows over the banks.
+template <int COLS>
+__device__ __forceinline__ int km_swz_col(int k, int col) { return (((col >> 5) ^ (k & 3)) << 5) | (col & 31); }
+
+template <int COLS>
+__device__ __forceinline__ bf16x8 frag_km_swz(const bf16_t *tile, int col0, int kk, int lane)
+{
+    const int i = lane & 15, b = lane >> 4;
+    const int k = kk * 16 + (b >> 1) * 8 + (i >> 2), col = col0 + (b & 1) * 16 + (i & 3) * 4;
+    const bf16_t *p = tile + k * COLS + km_swz_col<COLS>(k, col);
+    typedef short4v __attribute__((address_space(3))) * lds_p;
+    const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_p)(p));
+    const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_p)(p + 4 * COLS));     // (k + 4) & 3 == k & 3
+    typedef short short8v __attribute__((ext_vector_type(8)));
+    short8v r = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, r);
+}
+
+// rows [k0, k0 + BK) x columns [col0, col0 + COLS) of a row-major [rows][ld] bf16 matrix -> LDS tile (asynchronous)
+template <int BK, int COLS, int NW>
+__device__ __forceinline__ void load_km_tile(__amdgpu_buffer_rsrc_t r, int ld, int col0, int k0, bf16_t *tile, int wave, int lane)
+{
+    constexpr int CPR = COLS / 8, RPI = 64 / CPR, LOADS = BK / RPI / NW;   // chunks per row, rows per instruction
+    static_assert(BK % (RPI * NW) == 0 && CPR <= 64, "tile / wave mismatch");
+#pragma unroll
+    for (int it = 0; it < LOADS; ++it) {
+        const int rb = (wave * LOADS + it) * RPI;                 // wave-uniform first row
+        const int k = rb + lane / CPR, p = lane % CPR;
+        const int col = col0 + (((p >> 2) ^ (k & 3)) << 5) + (p & 3) * 8;
+        const uint32_t off = (col < ld) ? ((uint32_t)(k0 + k) * (uint32_t)ld + (uint32_t)col) * 2u : kOobOffset;
+        load_to_lds16(r, tile + rb * COLS, off);
+    }
+}
+
 template <int BITS, typename WT, bool BLOCK_AP, int BM, int BN, int BK, int WGM, int WGN>
 __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_dw(const GemmDwArgs a)
 {
-    constexpr int NT = 64 * WGM * WGN, WTM = BM / WGM, WTN = BN / WGN, MI = WTM / 32, NI = WTN / 32;
-    constexpr int LDA = BM + kPadKM, LDB = BN + kPadKM;
-    constexpr int A_ELEMS = BK * LDA, B_ELEMS = BK * LDB;
-    constexpr int A_CHUNKS = BK * BM / 8 / NT, B_CHUNKS = BK * BN / 8 / NT;
-    static_assert(BK * BM / 8 % NT == 0 && BK * BN / 8 % NT == 0, "tile / thread mismatch");
+    constexpr int NT = 64 * WGM * WGN, NW = WGM * WGN, WTM = BM / WGM, WTN = BN / WGN, MI = WTM / 32, NI = WTN / 32;
+    constexpr int A_ELEMS = BK * BM, B_ELEMS = BK * BN;
+    static_assert(BK == 64, "four 16-wide slices per tile");
     static_assert(2 * (A_ELEMS + B_ELEMS) * 2 >= 2 * (BM / 32) * BN * 4, "partials must fit in the tile buffers");
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
@@ -331,33 +413,9 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_dw(const GemmDwArgs a)
     const __amdgpu_buffer_rsrc_t rX = make_rsrc(a.X, a.x_bytes);
     const __amdgpu_buffer_rsrc_t rY = make_rsrc(a.dY, a.dy_bytes);
 
-    intx4 stA[A_CHUNKS], stB[B_CHUNKS];
-    auto load_global = [&](int k0) {
-#pragma unroll
-        for (int it = 0; it < A_CHUNKS; ++it) {
-            const int c = it * NT + tid, row = c / (BM / 8), cc = c % (BM / 8);
-            const int col = m0 + cc * 8;
-            stA[it] = buf_load16(rX, col < a.I ? ((uint32_t)(k0 + row) * (uint32_t)a.I + (uint32_t)col) * 2u : kOobOffset);
-        }
-#pragma unroll
-        for (int it = 0; it < B_CHUNKS; ++it) {
-            const int c = it * NT + tid, row = c / (BN / 8), cc = c % (BN / 8);
-            const int col = n0 + cc * 8;
-            stB[it] = buf_load16(rY, col < a.O ? ((uint32_t)(k0 + row) * (uint32_t)a.O + (uint32_t)col) * 2u : kOobOffset);
-        }
-    };
-    auto store_lds = [&](int buf) {
-        bf16_t *dA = sA + buf * A_ELEMS, *dB = sB + buf * B_ELEMS;
-#pragma unroll
-        for (int it = 0; it < A_CHUNKS; ++it) {
-            const int c = it * NT + tid, row = c / (BM / 8), cc = c % (BM / 8);
-            *reinterpret_cast<intx4 *>(dA + row * LDA + cc * 8) = stA[it];
-        }
-#pragma unroll
-        for (int it = 0; it < B_CHUNKS; ++it) {
-            const int c = it * NT + tid, row = c / (BN / 8), cc = c % (BN / 8);
-            *reinterpret_cast<intx4 *>(dB + row * LDB + cc * 8) = stB[it];
-        }
+    auto load_tiles = [&](int k0, int buf) {
+        load_km_tile<BK, BM, NW>(rX, a.I, m0, k0, sA + buf * A_ELEMS, wave, lane);
+        load_km_tile<BK, BN, NW>(rY, a.O, n0, k0, sB + buf * B_ELEMS, wave, lane);
     };
 
     floatx16 acc[MI][NI];
@@ -368,32 +426,55 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_dw(const GemmDwArgs a)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
+    bf16x8 fa[2][MI], fb[2][NI];
+    auto read_frags = [&](int slot, int buf, int kk) {
+#pragma unroll
+        for (int i = 0; i < MI; ++i) fa[slot][i] = frag_km_swz<BM>(sA + buf * A_ELEMS, wm * WTM + i * 32, kk, lane);
+#pragma unroll
+        for (int j = 0; j < NI; ++j) fb[slot][j] = frag_km_swz<BN>(sB + buf * B_ELEMS, wn * WTN + j * 32, kk, lane);
+    };
+    auto mfma_slice = [&](int slot) {
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int j = 0; j < NI; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[slot][i], fb[slot][j], acc[i][j], 0, 0, 0);
+    };
+    // Same pipeline as the forward kernel: the barrier sits before the last slice, whose MFMAs then cover the first
+    // fragment reads of the next tile and the issue of the loads for the tile after it.
+    auto step = [&](int buf, int kt) {
+        read_frags(1, buf, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_slice(0);
+        __builtin_amdgcn_sched_barrier(0);
+        read_frags(0, buf, 2);
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_slice(1);
+        __builtin_amdgcn_sched_barrier(0);
+        read_frags(1, buf, 3);
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_slice(0);
+        __builtin_amdgcn_sched_barrier(0);
+        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        load_tiles((kt + 2) * BK, buf);
+        read_frags(0, buf ^ 1, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_slice(1);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+
     const int nk = (a.T + BK - 1) / BK;
     if (nk > 0) {
-        load_global(0);
-        store_lds(0);
-    }
-    __syncthreads();
-    for (int kt = 0; kt < nk; ++kt) {
-        const int buf = kt & 1;
-        if (kt + 1 < nk) load_global((kt + 1) * BK);
-        const bf16_t *cA = sA + buf * A_ELEMS, *cB = sB + buf * B_ELEMS;
-#pragma unroll
-        for (int kk = 0; kk < BK / 16; ++kk) {
-            bf16x8 fa[MI], fb[NI];
-#pragma unroll
-            for (int i = 0; i < MI; ++i) fa[i] = frag_km<LDA>(cA, wm * WTM + i * 32, kk, lane);
-#pragma unroll
-            for (int j = 0; j < NI; ++j) fb[j] = frag_km<LDB>(cB, wn * WTN + j * 32, kk, lane);
-#pragma unroll
-            for (int i = 0; i < MI; ++i)
-#pragma unroll
-                for (int j = 0; j < NI; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+        load_tiles(0, 0);
+        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        load_tiles(BK, 1);
+        read_frags(0, 0, 0);
+        for (int kt = 0; kt < nk; kt += 2) {
+            step(0, kt);
+            if (kt + 1 < nk) step(1, kt + 1);
         }
-        if (kt + 1 < nk) store_lds(buf ^ 1);
-        __syncthreads();
     }
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");   // tile buffers become the partial-sum arrays
 
     // ---- epilogue ----------------------------------------------------------------------------------
     float *p_ds = reinterpret_cast<float *>(smem_raw);            // [BM/32][BN]
@@ -553,7 +634,7 @@ void launch_q_bits(int bits, const GemmQArgs &args, hipStream_t st)
 template <int BITS, typename WT, bool AP, typename TS>
 void launch_dw_t(const GemmDwArgs &args, hipStream_t st)
 {
-    constexpr size_t smem = 2 * (size_t)TS::BK * ((TS::BM + kPadKM) + (TS::BN + kPadKM)) * sizeof(bf16_t);
+    constexpr size_t smem = 2 * (size_t)TS::BK * (TS::BM + TS::BN) * sizeof(bf16_t);
     auto kern = k_gemm_dw<BITS, WT, AP, TS::BM, TS::BN, TS::BK, TS::WGM, TS::WGN>;
     static bool attr_set = false;
     if (!attr_set) { (void)hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem); attr_set = true; }
