@@ -185,20 +185,35 @@ def measure_other_rows(torch, eq, layers, bits, g, adt, dev, args):
         for L, P in zip(layers, packed):
             eq.eqat_pack(L["W"], L["s"], L["z"], bits, g, Wpacked=P["Wp"], zpacked=P["zp"])
 
-    dt = timed(pack_all, args.steps)
+    def timed_kernels(fn, n):
+        """Wall time per call of fn and the summed GPU time of the library's kernels inside it (HIP events)."""
+        for _ in range(2):
+            fn()
+        torch.cuda.synchronize()
+        eq.eqat_profile_start()
+        t0 = time.perf_counter()
+        for _ in range(n):
+            fn()
+        torch.cuda.synchronize()
+        wall = (time.perf_counter() - t0) / n
+        prof = eq.eqat_profile_stop()
+        return wall, sum(v[0] for v in prof.values()) * 1e-3 / n, {k: round(v[0] / n, 4) for k, v in prof.items()}
+
+    def hbm_row(fn, nbytes):
+        wall, gpu, per_kernel = timed_kernels(fn, args.steps)
+        return {"kernel_ms": round(gpu * 1e3, 4), "wall_ms": round(wall * 1e3, 4), "gbs": round(nbytes / gpu / 1e9, 1),
+                "frac_of_hbm_peak": round(nbytes / gpu / 1e9 / PEAK_HBM_GBS, 4), "bytes": nbytes, "kernels_ms": per_kernel}
+
     b = sum_io * (wbytes + 8.0 / g + bits / 8.0 + bits / (8.0 * g))
-    rows["eqat_pack"] = {"ms": round(dt * 1e3, 4), "gbs": round(b / dt / 1e9, 1), "frac_of_hbm_peak": round(b / dt / 1e9 / PEAK_HBM_GBS, 4),
-                         "bytes": b}
+    rows["eqat_pack"] = hbm_row(pack_all, b)
     sz = [(torch.empty_like(L["s"]), torch.empty_like(L["z"])) for L in layers]
 
     def init_all():
         for L, (s, z) in zip(layers, sz):
             eq.eqat_init_minmax(L["W"], bits, g, s=s, z=z)
 
-    dt = timed(init_all, args.steps)
     b = sum_io * (wbytes + 8.0 / g)
-    rows["eqat_init_minmax"] = {"ms": round(dt * 1e3, 4), "gbs": round(b / dt / 1e9, 1), "frac_of_hbm_peak": round(b / dt / 1e9 / PEAK_HBM_GBS, 4),
-                                "bytes": b}
+    rows["eqat_init_minmax"] = hbm_row(init_all, b)
     return rows
 
 

@@ -105,6 +105,13 @@ struct GemmQArgs {
 
 template <int V> struct IC { static constexpr int value = V; };
 
+// With more than 128 accumulator registers per lane the accumulators must live in AGPRs (the MFMA "acd" form);
+// the compiler only picks that form when it believes the kernel needs AGPRs, which this empty statement asserts.
+template <int ACC_REGS> __device__ __forceinline__ void want_agpr_accumulators()
+{
+    if constexpr (ACC_REGS > 128) { float zero = 0.0f; asm volatile("" ::"a"(zero)); }
+}
+
 // ---- KC tile filled by buffer loads that write LDS directly ----------------------------------------------
 // Such a load puts the 16 bytes of lane j at (wave-uniform LDS base) + 16*j, so one instruction fills 8 rows of
 // a [rows][64] bf16 tile and no padding can be placed inside it.  Bank conflicts of the fragment reads are
@@ -141,6 +148,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_q(const GemmQArgs a)
     constexpr int KK = BK / 16;
     static_assert(BK == 64 && BM % (8 * NW) == 0 && BN * BK / 32 % NT == 0, "tile / thread mismatch");
 
+    want_agpr_accumulators<MI * NI * 16>();
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     bf16_t *sA = reinterpret_cast<bf16_t *>(smem_raw);            // [2][A_ELEMS]
     bf16_t *sB = sA + 2 * A_ELEMS;                                // [2][B_ELEMS]
@@ -307,6 +315,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_q(const GemmQArgs a)
                 const int m = m0 + wm * WTM + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
                 if (m < a.M && n < a.N) a.C[(size_t)m * a.N + n] = (bf16_t)acc[i][j][r];
             }
+            __builtin_amdgcn_sched_barrier(0);     // one 32x32 block at a time: keeps the accumulator copies few
         }
 }
 
@@ -401,6 +410,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_dw(const GemmDwArgs a)
     static_assert(BK == 64, "four 16-wide slices per tile");
     static_assert(2 * (A_ELEMS + B_ELEMS) * 2 >= 2 * (BM / 32) * BN * 4, "partials must fit in the tile buffers");
 
+    want_agpr_accumulators<MI * NI * 16>();
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     bf16_t *sA = reinterpret_cast<bf16_t *>(smem_raw);
     bf16_t *sB = sA + 2 * A_ELEMS;
@@ -545,6 +555,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_dw(const GemmDwArgs a)
                 p_ds[(wm * MI + i) * BN + ol] = sum_s;
                 if (BLOCK_AP) p_dz[(wm * MI + i) * BN + ol] = sum_z;
             }
+            __builtin_amdgcn_sched_barrier(0);     // one 32x32 block at a time
         }
     }
     __syncthreads();

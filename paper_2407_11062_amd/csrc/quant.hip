@@ -58,51 +58,60 @@ __device__ __forceinline__ uint32_t quad_bcast(uint32_t v, int k)
 // The quantize pass.  One lane owns 8 consecutive weights (a 16- or 32-byte load); the four lanes of a
 // quad own one 32-code segment, i.e. BITS output words, assembled with quad permutes.
 //   codes     [O, I*BITS/32] words      packed stream (same layout as eqat_pack's Wpacked)
-//   clampbits [O, I/8] bytes or NULL    bit k of byte e/8: weight e was clamped by Eq.(1)
+//   clampbits [O, I/8] bytes (CLAMPBITS) bit k of byte e/8: weight e was clamped by Eq.(1)
 //   sz        [O, G] float2 or NULL     (s, zbar) per group, zbar = round(z) (clamped iff CLAMP_Z)
-template <typename WT, int BITS, bool CLAMP_Z>
+// Rows are contiguous and g divides I, so weight e belongs to group e / g of the flattened [O*G] arrays.
+// Per weight the common path costs: widen, multiply, round, two ops of tie test, clamp, convert, shift-add.
+// The clamp is applied to round(w/s) against [-zbar, Qmax - zbar] and zbar is added once, as an integer, to
+// all eight packed fields (the per-field sums stay inside [0, Qmax], so no carry crosses a field).
+template <typename WT, int BITS, bool CLAMP_Z, bool CLAMPBITS>
 __global__ __launch_bounds__(256) void k_quantize(const WT *__restrict__ W, const float *__restrict__ s,
                                                   const float *__restrict__ z, uint32_t *__restrict__ codes,
                                                   uint8_t *__restrict__ clampbits, floatx2 *__restrict__ sz,
-                                                  uint32_t n_chunks, uint32_t I, uint32_t g, uint32_t G)
+                                                  uint32_t n_chunks, uint32_t g, int g_shift)
 {
     const uint32_t c = blockIdx.x * 256u + threadIdx.x;   // chunk index; n_chunks % 4 == 0 so quads stay whole
     if (c >= n_chunks) return;
     const uint32_t e = c * 8u;
-    const uint32_t row = e / I, col = e - row * I;
-    const uint32_t j = col / g;
-    const float sv = s[row * G + j];
-    float zb = __builtin_rintf(z[row * G + j]);
+    const uint32_t gi = g_shift >= 0 ? (e >> g_shift) : (e / g);
+    const float sv = s[gi];
+    float zb = __builtin_rintf(z[gi]);
     constexpr float qmax = (float)((1 << BITS) - 1);
     if (CLAMP_Z) zb = __builtin_fminf(__builtin_fmaxf(zb, 0.0f), qmax);
-    if (sz != nullptr && col == j * g) { floatx2 o; o[0] = sv; o[1] = zb; sz[row * G + j] = o; }
+    if (sz != nullptr && e == gi * g) { floatx2 o; o[0] = sv; o[1] = zb; sz[gi] = o; }
 
     Chunk8<WT> ch;
     ch.load(W + e);
-    const float rinv = 1.0f / sv;
+    const float rinv = __builtin_amdgcn_rcpf(sv);          // 1 ulp; s is a normal number
+    const float lo = -zb, hi = qmax - zb;
+    // Far from a rounding tie the cheap quotient w * rcp(s) (within 2^-22 relative of w/s) rounds like the exact one.
+    // Only weights whose code is not clamped matter, and for those |w/s| <= |zbar| + Qmax + 1.
+    const float thr = 0.5f - 0x1p-20f * (__builtin_fabsf(zb) + qmax + 2.0f);
     float r[8];
-    bool any_tie = false;
+    float worst = 0.0f;
 #pragma unroll
     for (int k = 0; k < 8; ++k) {
-        bool tie;
-        r[k] = quant_fast(ch.get(k), rinv, tie);
-        any_tie |= tie;
+        const float t = ch.get(k) * rinv;
+        r[k] = __builtin_rintf(t);
+        worst = __builtin_fmaxf(worst, __builtin_fabsf(t - r[k]));
     }
-    if (any_tie) {
+    if (worst >= thr) {
 #pragma unroll
         for (int k = 0; k < 8; ++k) r[k] = quant_exact(ch.get(k), sv);
     }
     uint32_t p = 0, cb = 0;
 #pragma unroll
     for (int k = 0; k < 8; ++k) {
-        const float qpre = r[k] + zb;
-        const float q = __builtin_fminf(__builtin_fmaxf(qpre, 0.0f), qmax);
-        p |= (uint32_t)q << (k * BITS);
-        cb |= (qpre != q ? 1u : 0u) << k;
+        const float qc = __builtin_amdgcn_fmed3f(r[k], lo, hi);      // lo <= hi: the median is the clamp
+        p += (uint32_t)(int)qc << (k * BITS);              // two's complement: fields may be negative until zbar is added
+        if (CLAMPBITS) cb |= (qc != r[k] ? 1u : 0u) << k;
     }
-    if (clampbits != nullptr) clampbits[c] = (uint8_t)cb;
+    constexpr uint32_t ones = BITS == 2 ? 0x5555u : BITS == 3 ? 0x249249u : 0x11111111u;   // a one in every field
+    p += (uint32_t)(int)zb * ones;
+    if (CLAMPBITS) clampbits[c] = (uint8_t)cb;
 
-    const uint32_t p0 = quad_bcast(p, 0), p1 = quad_bcast(p, 1), p2 = quad_bcast(p, 2), p3 = quad_bcast(p, 3);
+    const uint32_t pu = p & (BITS == 4 ? 0xFFFFFFFFu : ((1u << (8 * BITS)) - 1u));
+    const uint32_t p0 = quad_bcast(pu, 0), p1 = quad_bcast(pu, 1), p2 = quad_bcast(pu, 2), p3 = quad_bcast(pu, 3);
     const uint32_t q4 = threadIdx.x & 3u;
     uint32_t word;
     if constexpr (BITS == 2) {
@@ -115,30 +124,24 @@ __global__ __launch_bounds__(256) void k_quantize(const WT *__restrict__ W, cons
     if (q4 < (uint32_t)BITS) codes[(c >> 2) * BITS + q4] = word;
 }
 
-// Zero points at N bits: one thread per 32 zero points of a row (BITS words, tail padded with zeros).
+// Zero points at N bits: one thread per output word (tail bits of a row are zero).
 template <int BITS>
 __global__ __launch_bounds__(256) void k_pack_z(const float *__restrict__ z, uint32_t *__restrict__ zpacked,
                                                 uint32_t O, uint32_t G, uint32_t row_words)
 {
-    const uint32_t segs = (G + 31u) / 32u;
     const uint32_t t = blockIdx.x * 256u + threadIdx.x;
-    if (t >= O * segs) return;
-    const uint32_t row = t / segs, seg = t - row * segs;
+    if (t >= O * row_words) return;
+    const uint32_t row = t / row_words, w = t - row * row_words;
     constexpr float qmax = (float)((1 << BITS) - 1);
+    const uint32_t bit0 = w * 32u;
+    uint32_t j = bit0 / BITS;                   // first code with bits in this word
     uint64_t acc = 0;
-    int nbits = 0;
-    uint32_t wi = seg * BITS;
-    for (uint32_t k = 0; k < 32u; ++k) {
-        const uint32_t j = seg * 32u + k;
-        uint32_t code = 0;
-        if (j < G) code = (uint32_t)__builtin_fminf(__builtin_fmaxf(__builtin_rintf(z[row * G + j]), 0.0f), qmax);
-        acc |= (uint64_t)code << nbits;
-        nbits += BITS;
-        if (nbits >= 32) {
-            if (wi < row_words) zpacked[row * row_words + wi] = (uint32_t)acc;
-            acc >>= 32; nbits -= 32; ++wi;
-        }
+    for (; j < G && j * BITS < bit0 + 32u; ++j) {
+        const uint32_t code = (uint32_t)__builtin_amdgcn_fmed3f(__builtin_rintf(z[row * G + j]), 0.0f, qmax);
+        const int sh = (int)(j * BITS) - (int)bit0;         // may be negative for a code straddling in from the left
+        acc |= sh >= 0 ? ((uint64_t)code << sh) : ((uint64_t)code >> (-sh));
     }
+    zpacked[t] = (uint32_t)acc;
 }
 
 // (s, z) pairs for the E2E-QP kernels: sz[o,j] = (s[o,j], float(zpacked code j of row o)).
@@ -265,18 +268,25 @@ __global__ __launch_bounds__(256) void k_fill_zero(uint32_t *__restrict__ p, siz
 
 static inline unsigned blocks_for(size_t n, unsigned per = 256) { return (unsigned)((n + per - 1) / per); }
 
+static inline int pow2_shift(int64_t v)
+{
+    for (int k = 0; k < 31; ++k) if (((int64_t)1 << k) == v) return k;
+    return -1;
+}
+
 template <typename WT, int BITS>
 static void quantize_t(const Problem &p, const void *W, const float *s, const float *z, void *codes, void *clampbits,
                        void *sz, bool clamp_z, hipStream_t st)
 {
     const uint32_t n_chunks = (uint32_t)((size_t)p.O * p.I / 8);
     const dim3 grid(blocks_for(n_chunks)), block(256);
-    if (clamp_z)
-        k_quantize<WT, BITS, true><<<grid, block, 0, st>>>((const WT *)W, s, z, (uint32_t *)codes, (uint8_t *)clampbits,
-                                                           (floatx2 *)sz, n_chunks, (uint32_t)p.I, (uint32_t)p.g, (uint32_t)p.G);
-    else
-        k_quantize<WT, BITS, false><<<grid, block, 0, st>>>((const WT *)W, s, z, (uint32_t *)codes, (uint8_t *)clampbits,
-                                                            (floatx2 *)sz, n_chunks, (uint32_t)p.I, (uint32_t)p.g, (uint32_t)p.G);
+    const int gs = pow2_shift(p.g);
+#define EQAT_LAUNCH(CZ, CB)                                                                                             \
+    k_quantize<WT, BITS, CZ, CB><<<grid, block, 0, st>>>((const WT *)W, s, z, (uint32_t *)codes, (uint8_t *)clampbits,   \
+                                                         (floatx2 *)sz, n_chunks, (uint32_t)p.g, gs)
+    if (clampbits != nullptr) { if (clamp_z) EQAT_LAUNCH(true, true); else EQAT_LAUNCH(false, true); }
+    else                      { if (clamp_z) EQAT_LAUNCH(true, false); else EQAT_LAUNCH(false, false); }
+#undef EQAT_LAUNCH
 }
 
 void launch_quantize(const Problem &p, const void *W, const float *s, const float *z, void *codes, void *clampbits,
@@ -291,7 +301,7 @@ void launch_quantize(const Problem &p, const void *W, const float *s, const floa
 void launch_pack_z(const Problem &p, const float *z, void *zpacked, hipStream_t st)
 {
     const uint32_t row_words = (uint32_t)((p.G * p.bits + 31) / 32);
-    const size_t n = (size_t)p.O * ((p.G + 31) / 32);
+    const size_t n = (size_t)p.O * row_words;
     const dim3 grid(blocks_for(n)), block(256);
     if (p.bits == 2) k_pack_z<2><<<grid, block, 0, st>>>(z, (uint32_t *)zpacked, (uint32_t)p.O, (uint32_t)p.G, row_words);
     else if (p.bits == 3) k_pack_z<3><<<grid, block, 0, st>>>(z, (uint32_t *)zpacked, (uint32_t)p.O, (uint32_t)p.G, row_words);
