@@ -78,12 +78,11 @@ __device__ __forceinline__ bf16x8 dequant8(const CodeWords<BITS> &c, float s, fl
 // Consecutive workgroup ids go round-robin over the 8 XCDs, each with its own L2.  Give every XCD a
 // contiguous range of tile ids, then walk the tiles in bands of 8 tile-rows so that the tiles resident on
 // one XCD at a time share their operand panels.
-__device__ __forceinline__ void tile_of_block(int tiles_m, int tiles_n, int &tm, int &tn)
+__device__ __forceinline__ void tile_of_block(int tiles_m, int tiles_n, int &tm, int &tn, int kBand = 8)
 {
     const int nb = gridDim.x, bid = blockIdx.x;
     const int xcd = bid & 7, loc = bid >> 3, per = nb >> 3, rem = nb & 7;
     const int pid = (xcd < rem ? xcd * (per + 1) : rem * (per + 1) + (xcd - rem) * per) + loc;
-    constexpr int kBand = 8;
     const int width = kBand * tiles_n, band = pid / width, first = band * kBand;
     const int rows = min(tiles_m - first, kBand), in = pid - band * width;
     tm = first + in % rows;
@@ -101,6 +100,7 @@ struct GemmQArgs {
     int I, G, g;           // weight matrix geometry: row length, groups per row, group size
     uint32_t a_bytes, codes_bytes, sz_bytes;
     int tiles_m, tiles_n;
+    int band;              // tile rows walked together by one XCD (see tile_of_block)
 };
 
 template <int V> struct IC { static constexpr int value = V; };
@@ -154,7 +154,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_q(const GemmQArgs a)
     bf16_t *sB = sA + 2 * A_ELEMS;                                // [2][B_ELEMS]
 
     int tm, tn;
-    tile_of_block(a.tiles_m, a.tiles_n, tm, tn);
+    tile_of_block(a.tiles_m, a.tiles_n, tm, tn, a.band);
     const int m0 = tm * BM, n0 = tn * BN;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wm = wave / WGN, wn = wave % WGN;
 
@@ -618,6 +618,7 @@ void launch_q(const GemmQArgs &args, hipStream_t st)
     GemmQArgs a = args;
     a.tiles_m = (a.M + TS::BM - 1) / TS::BM;
     a.tiles_n = (a.N + TS::BN - 1) / TS::BN;
+    { const char *e = getenv("EQAT_BAND"); a.band = e ? atoi(e) : 8; }
     kern<<<dim3(a.tiles_m * a.tiles_n), dim3(64 * TS::WGM * TS::WGN), smem, st>>>(a);
 }
 
