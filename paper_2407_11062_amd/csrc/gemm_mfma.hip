@@ -299,9 +299,12 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_q(const GemmQArgs a)
     load_codes(IC<0>{}, 2 * BK);
     commit_piece(IC<1>{}, IC<0>{}, 1);
     read_frags(0, sA, sB, 0);
+    // Two tiles per trip, unconditionally (the register staging sets alternate at compile time, and a branch
+    // between the two halves makes the accumulators flow through a merge that costs hundreds of copies).  With an
+    // odd tile count the extra tile lies past K and multiplies zeros.
     for (int kt = 0; kt < nk; kt += 2) {
         step(IC<0>{}, kt);
-        if (kt + 1 < nk) step(IC<1>{}, kt + 1);
+        step(IC<1>{}, kt + 1);
     }
 
     // C[m][n]: lane holds column n = l % 32 and rows 8*(r/4) + 4*(l/32) + r%4 of each 32x32 block
@@ -479,10 +482,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_dw(const GemmDwArgs a)
         asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
         load_tiles(BK, 1);
         read_frags(0, 0, 0);
-        for (int kt = 0; kt < nk; kt += 2) {
-            step(0, kt);
-            if (kt + 1 < nk) step(1, kt + 1);
-        }
+        for (int kt = 0; kt < nk; ++kt) step(kt & 1, kt);
     }
     asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");   // tile buffers become the partial-sum arrays
 
