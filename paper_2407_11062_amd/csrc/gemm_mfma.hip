@@ -19,24 +19,6 @@
 
 namespace eqat {
 
-#ifndef EXPERIMENT_NOCOMMIT
-#define EXPERIMENT_NOCOMMIT 0
-#endif
-#ifndef EXPERIMENT_NOFRAG
-#define EXPERIMENT_NOFRAG 0
-#endif
-#ifndef EXPERIMENT_NOWAITA
-#define EXPERIMENT_NOWAITA 0
-#endif
-#ifndef EXPERIMENT_ASMALL
-#define EXPERIMENT_ASMALL 0
-#endif
-#ifndef EXPERIMENT_NOA
-#define EXPERIMENT_NOA 0
-#endif
-#ifndef EXPERIMENT_NODEQ
-#define EXPERIMENT_NODEQ 0
-#endif
 constexpr int kPadKC = 8;    // bf16 elements
 constexpr int kPadKM = 32;
 
@@ -66,7 +48,6 @@ __device__ __forceinline__ bf16x8 frag_km(const bf16_t *tile, int col0, int kk, 
 template <int BITS, int K0>
 __device__ __forceinline__ bf16x8 dequant8(const CodeWords<BITS> &c, float s, float b)
 {
-    if (EXPERIMENT_NODEQ) { uintx4 u; u[0] = c.w[0]; u[1] = c.w[1]; u[2] = c.w[0] ^ K0; u[3] = __float_as_uint(s); return __builtin_bit_cast(bf16x8, u); }
     bf16x8 o;
 #define EQAT_DQ(J) o[J] = (bf16_t)__builtin_fmaf((float)code_at<BITS, K0 + J>(c), s, b)
     EQAT_DQ(0); EQAT_DQ(1); EQAT_DQ(2); EQAT_DQ(3); EQAT_DQ(4); EQAT_DQ(5); EQAT_DQ(6); EQAT_DQ(7);
@@ -173,13 +154,11 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_q(const GemmQArgs a)
             const int rb = (wave * A_LOADS + it) * 8;                 // first of 8 rows, wave-uniform
             const int row = rb + (lane >> 3), k = k0 + kc_swz(row, lane & 7) * 8;
             uint32_t off = (k < a.K) ? ((uint32_t)(m0 + row) * (uint32_t)a.K + (uint32_t)k) * 2u : kOobOffset;
-            if (EXPERIMENT_ASMALL) off = ((uint32_t)row * (uint32_t)a.K + (uint32_t)(k & 63)) * 2u;
-            if (!EXPERIMENT_NOA) load_to_lds16(rA, sA + buf * A_ELEMS + rb * 64, off);
+            load_to_lds16(rA, sA + buf * A_ELEMS + rb * 64, off);
         }
     };
     auto load_codes = [&](auto set, int k0) {
         constexpr int S = decltype(set)::value;
-        if (EXPERIMENT_NOCOMMIT) return;
 #pragma unroll
         for (int it = 0; it < B_SEGS; ++it) {
             const int sidx = it * NT + tid;
@@ -196,7 +175,6 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_q(const GemmQArgs a)
     // piece P of KK: every KK-th 16-byte store of the staged weight tile
     auto commit_piece = [&](auto set, auto piece, int buf) {
         constexpr int S = decltype(set)::value, P = decltype(piece)::value;
-        if (EXPERIMENT_NOCOMMIT) return;
         bf16_t *dB = sB + buf * B_ELEMS;
 #pragma unroll
         for (int it = 0; it < B_SEGS; ++it) {
@@ -223,7 +201,6 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_q(const GemmQArgs a)
 
     bf16x8 fa[2][MI], fb[2][NI];
     auto read_frags = [&](int slot, const bf16_t *cA, const bf16_t *cB, int kk) {
-        if (EXPERIMENT_NOFRAG && kk >= 0) return;
 #pragma unroll
         for (int i = 0; i < MI; ++i) fa[slot][i] = frag_kc_swz(cA, wm * WTM + i * 32, kk, lane);
 #pragma unroll
@@ -273,8 +250,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_q(const GemmQArgs a)
         commit_piece(IC<PAR ^ 1>{}, IC<3>{}, PAR ^ 1);
         interleave();
         __builtin_amdgcn_sched_barrier(0);
-        if (EXPERIMENT_NOWAITA) asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-        else asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");   // next activation tile landed, my LDS traffic done
+        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");   // next activation tile landed, my LDS traffic done
         // last slice of this tile, overlapped with the start of the next two tiles
         load_a((kt + 2) * BK, PAR);
         read_frags(0, sA + (PAR ^ 1) * A_ELEMS, sB + (PAR ^ 1) * B_ELEMS, 0);
@@ -593,18 +569,21 @@ namespace {
 template <int BM_, int BN_, int BK_, int WGM_, int WGN_> struct Tile {
     static constexpr int BM = BM_, BN = BN_, BK = BK_, WGM = WGM_, WGN = WGN_;
 };
-typedef Tile<128, 128, 64, 2, 2> Tile0;
-typedef Tile<256, 256, 64, 2, 2> Tile1;
-typedef Tile<256, 256, 64, 2, 4> Tile2;
-typedef Tile<256, 128, 64, 2, 2> Tile3;
-typedef Tile<128, 256, 64, 2, 2> Tile4;
-typedef Tile<256, 256, 64, 4, 2> Tile5;
+typedef Tile<128, 128, 64, 2, 2> TileSmall;   // 4 waves, 64x64 per wave: problems with few big tiles
+typedef Tile<256, 256, 64, 2, 4> TileBig;     // 8 waves, 128x64 per wave
 
-int tile_choice()
+// EQAT_TILE=0/1 forces the small / big tile (tuning aid)
+int tile_override()
 {
-    static int c = -1;
-    if (c < 0) { const char *e = getenv("EQAT_TILE"); c = e ? atoi(e) : 2; }
+    static int c = -2;
+    if (c == -2) { const char *e = getenv("EQAT_TILE"); c = e ? atoi(e) : -1; }
     return c;
+}
+// the big tile unless it would leave a large part of the 256 CUs without a workgroup
+bool use_small_tile(int64_t m, int64_t n)
+{
+    if (tile_override() >= 0) return tile_override() == 0;
+    return ((m + 255) / 256) * ((n + 255) / 256) < 160;
 }
 
 template <int BITS, bool BT, typename TS>
@@ -618,29 +597,17 @@ void launch_q(const GemmQArgs &args, hipStream_t st)
     GemmQArgs a = args;
     a.tiles_m = (a.M + TS::BM - 1) / TS::BM;
     a.tiles_n = (a.N + TS::BN - 1) / TS::BN;
-    { const char *e = getenv("EQAT_BAND"); a.band = e ? atoi(e) : 8; }
+    a.band = 8;
     kern<<<dim3(a.tiles_m * a.tiles_n), dim3(64 * TS::WGM * TS::WGN), smem, st>>>(a);
 }
 
-template <int BITS, bool BT>
-void launch_q_tile(const GemmQArgs &args, hipStream_t st)
-{
-    switch (tile_choice()) {
-    case 1: launch_q<BITS, BT, Tile1>(args, st); break;
-    case 2: launch_q<BITS, BT, Tile2>(args, st); break;
-    case 3: launch_q<BITS, BT, Tile3>(args, st); break;
-    case 4: launch_q<BITS, BT, Tile4>(args, st); break;
-    case 5: launch_q<BITS, BT, Tile5>(args, st); break;
-    default: launch_q<BITS, BT, Tile0>(args, st);
-    }
-}
-
 template <bool BT>
-void launch_q_bits(int bits, const GemmQArgs &args, hipStream_t st)
+void launch_q_bits(int bits, const GemmQArgs &a, hipStream_t st)
 {
-    if (bits == 2) launch_q_tile<2, BT>(args, st);
-    else if (bits == 3) launch_q_tile<3, BT>(args, st);
-    else launch_q_tile<4, BT>(args, st);
+    const bool small = use_small_tile(a.M, a.N);
+#define EQAT_GO(B) do { if (small) launch_q<B, BT, TileSmall>(a, st); else launch_q<B, BT, TileBig>(a, st); } while (0)
+    if (bits == 2) EQAT_GO(2); else if (bits == 3) EQAT_GO(3); else EQAT_GO(4);
+#undef EQAT_GO
 }
 
 template <int BITS, typename WT, bool AP, typename TS>
@@ -657,35 +624,20 @@ void launch_dw_t(const GemmDwArgs &args, hipStream_t st)
     kern<<<dim3(a.tiles_m * a.tiles_n), dim3(64 * TS::WGM * TS::WGN), smem, st>>>(a);
 }
 
-template <int BITS, typename WT, bool AP>
-void launch_dw_tile(const GemmDwArgs &args, hipStream_t st)
-{
-    switch (tile_choice()) {
-    case 1: launch_dw_t<BITS, WT, AP, Tile1>(args, st); break;
-    case 2: launch_dw_t<BITS, WT, AP, Tile2>(args, st); break;
-    case 3: launch_dw_t<BITS, WT, AP, Tile3>(args, st); break;
-    case 4: launch_dw_t<BITS, WT, AP, Tile4>(args, st); break;
-    case 5: launch_dw_t<BITS, WT, AP, Tile5>(args, st); break;
-    default: launch_dw_t<BITS, WT, AP, Tile0>(args, st);
-    }
-}
-
 template <typename WT, bool AP>
-void launch_dw_bits(int bits, const GemmDwArgs &args, hipStream_t st)
+bool launch_dw_bits(int bits, const GemmDwArgs &a, hipStream_t st)      // returns whether per-segment partials were written
 {
-    if (bits == 2) launch_dw_tile<2, WT, AP>(args, st);
-    else if (bits == 3) launch_dw_tile<3, WT, AP>(args, st);
-    else launch_dw_tile<4, WT, AP>(args, st);
-}
-
-int dw_tile_bm()
-{
-    switch (tile_choice()) { case 0: case 4: return 128; default: return 256; }
+    const bool small = use_small_tile(a.I, a.O);
+#define EQAT_GO(B) do { if (small) launch_dw_t<B, WT, AP, TileSmall>(a, st); else launch_dw_t<B, WT, AP, TileBig>(a, st); } while (0)
+    if (bits == 2) EQAT_GO(2); else if (bits == 3) EQAT_GO(3); else EQAT_GO(4);
+#undef EQAT_GO
+    return ((small ? TileSmall::BM : TileBig::BM) % a.g) != 0;
 }
 
 }  // namespace
 
-bool dw_needs_partials(const Problem &p) { return dw_tile_bm() % p.g != 0; }
+// workspace reservation: either tile shape may be picked at launch
+bool dw_needs_partials(const Problem &p) { return (TileSmall::BM % p.g) != 0; }
 
 void launch_mfma_fwd(const Problem &p, const void *X, const void *codes, const void *sz, void *Y, hipStream_t st)
 {
@@ -719,16 +671,16 @@ void launch_mfma_dw(const Problem &p, bool block_ap, const void *X, const void *
     a.x_bytes = (uint32_t)(p.T * p.I * 2); a.dy_bytes = (uint32_t)(p.T * p.O * 2);
     a.w_bytes = (uint32_t)(p.O * p.I * (p.w_bf16 ? 2 : 4)); a.codes_bytes = (uint32_t)(p.O * p.I * p.bits / 8);
     a.clamp_bytes = (uint32_t)(p.O * p.I / 8); a.sz_bytes = (uint32_t)(p.O * p.G * 8);
-    const bool partials = dw_needs_partials(p);
+    bool partials;
     const size_t n32 = (size_t)p.O * (p.I / 32);
     a.part_ds = part; a.part_dz = part ? part + n32 : nullptr;
     {
         ProfScope ps(PK_GEMM_DW, st);
         if (block_ap) {
-            if (p.w_bf16) launch_dw_bits<bf16_t, true>(p.bits, a, st);
-            else launch_dw_bits<float, true>(p.bits, a, st);
+            if (p.w_bf16) partials = launch_dw_bits<bf16_t, true>(p.bits, a, st);
+            else partials = launch_dw_bits<float, true>(p.bits, a, st);
         } else {
-            launch_dw_bits<bf16_t, false>(p.bits, a, st);
+            partials = launch_dw_bits<bf16_t, false>(p.bits, a, st);
         }
     }
     if (partials) {
