@@ -75,11 +75,12 @@ WsLayout ws_layout(const Problem &p, int op)
     WsLayout l{};
     size_t off = 0;
     auto take = [&](size_t bytes) { const size_t at = off; off += align256(bytes); return at; };
-    const size_t codes_b = (size_t)p.O * p.I * p.bits / 8, clamp_b = (size_t)p.O * p.I / 8, sz_b = (size_t)p.O * p.G * 8;
+    const size_t codes_b = eqat::work_code_bytes(p), clamp_b = (size_t)p.O * p.I / 8, sz_b = (size_t)p.O * p.G * 8;
     const size_t part_b = (size_t)p.O * (p.I / 32) * 4, dwhat_b = (size_t)p.O * p.I * 4;
     const bool bwd = (op == EQAT_OP_FQ_BWD || op == EQAT_OP_Q_BWD), fq = (op == EQAT_OP_FQ_FWD || op == EQAT_OP_FQ_BWD);
     if (p.act_bf16) {
-        if (fq) { l.codes = take(codes_b); if (bwd) l.clamp = take(clamp_b); }
+        l.codes = take(codes_b);          // codes in the working layout (from W, or repacked from the dense stream)
+        if (fq && bwd) l.clamp = take(clamp_b);
         l.sz = take(sz_b);
         if (bwd && eqat::dw_needs_partials(p)) l.part = take(2 * part_b);
     } else {
@@ -130,7 +131,7 @@ int eqat_profile_kernels(void) { return eqat::PK_COUNT; }
 const char *eqat_profile_kernel_name(int k)
 {
     static const char *names[eqat::PK_COUNT] = {"init_minmax", "quantize", "pack_z", "unpack_sz", "gemm_fwd", "gemm_dx",
-                                                "gemm_dw", "reduce_partials", "f32_path"};
+                                                "gemm_dw", "reduce_partials", "f32_path", "repack"};
     return (k >= 0 && k < eqat::PK_COUNT) ? names[k] : "?";
 }
 
@@ -196,7 +197,7 @@ eqat_status eqat_pack(const eqat_desc *d, const void *W, const float *s, const f
     EQAT_REQUIRE(W); EQAT_REQUIRE(s); EQAT_REQUIRE(z); EQAT_REQUIRE(Wpacked); EQAT_REQUIRE(zpacked);
     EQAT_ALIGNED(W); EQAT_ALIGNED(s); EQAT_ALIGNED(z); EQAT_ALIGNED(Wpacked); EQAT_ALIGNED(zpacked);
     hipStream_t st = (hipStream_t)stream;
-    { ProfScope ps(eqat::PK_QUANTIZE, st); eqat::launch_quantize(p, W, s, z, Wpacked, nullptr, nullptr, false, st); }
+    { ProfScope ps(eqat::PK_QUANTIZE, st); eqat::launch_quantize(p, W, s, z, Wpacked, nullptr, nullptr, true, st); }
     { ProfScope ps(eqat::PK_PACK_Z, st); eqat::launch_pack_z(p, z, zpacked, st); }
     return launch_status();
 }
@@ -278,7 +279,8 @@ eqat_status eqat_qlinear_fwd(const eqat_desc *d, const void *X, const uint8_t *W
     hipStream_t st = (hipStream_t)stream;
     char *w8 = (char *)ws;
     { ProfScope ps(eqat::PK_UNPACK_SZ, st); eqat::launch_unpack_sz(p, s, zpacked, w8 + l.sz, st); }
-    if (p.act_bf16) { ProfScope ps(eqat::PK_GEMM_FWD, st); eqat::launch_mfma_fwd(p, X, Wpacked, w8 + l.sz, Y, st); }
+    if (p.act_bf16) { ProfScope ps(eqat::PK_REPACK, st); eqat::launch_repack(p, Wpacked, w8 + l.codes, st); }
+    if (p.act_bf16) { ProfScope ps(eqat::PK_GEMM_FWD, st); eqat::launch_mfma_fwd(p, X, w8 + l.codes, w8 + l.sz, Y, st); }
     else { ProfScope ps(eqat::PK_F32, st); eqat::launch_f32_fwd(p, true, X, Wpacked, s, w8 + l.sz, Y, st); }
     return launch_status();
 }
@@ -300,9 +302,10 @@ eqat_status eqat_qlinear_bwd(const eqat_desc *d, const void *X, const uint8_t *W
     char *w8 = (char *)ws;
     { ProfScope ps(eqat::PK_UNPACK_SZ, st); eqat::launch_unpack_sz(p, s, zpacked, w8 + l.sz, st); }
     if (p.act_bf16) {
-        if (dX != nullptr) { ProfScope ps(eqat::PK_GEMM_DX, st); eqat::launch_mfma_dx(p, dY, Wpacked, w8 + l.sz, dX, st); }
+        { ProfScope ps(eqat::PK_REPACK, st); eqat::launch_repack(p, Wpacked, w8 + l.codes, st); }
+        if (dX != nullptr) { ProfScope ps(eqat::PK_GEMM_DX, st); eqat::launch_mfma_dx(p, dY, w8 + l.codes, w8 + l.sz, dX, st); }
         if (ds != nullptr)
-            eqat::launch_mfma_dw(p, false, X, dY, nullptr, Wpacked, nullptr, w8 + l.sz, s, nullptr, ds, nullptr,
+            eqat::launch_mfma_dw(p, false, X, dY, nullptr, w8 + l.codes, nullptr, w8 + l.sz, s, nullptr, ds, nullptr,
                                  (float *)(w8 + l.part), st);
     } else {
         ProfScope ps(eqat::PK_F32, st);

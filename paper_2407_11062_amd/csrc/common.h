@@ -86,6 +86,42 @@ __device__ __forceinline__ uint32_t code_at_rt(const uint32_t *words, int idx)
     return (uint32_t)(two >> sh) & mask;
 }
 
+// ---- working layout of the codes inside the library's workspace ------------------------------------------
+// The packed stream the C ABI exposes (CodeWords above) is dense, which makes 3-bit codes straddle words and every
+// code cost a shift, a mask and a convert to reach.  Kernels that consume codes in bulk read this layout instead:
+//   2 bit : 16 codes per word, code e of the word in bits [8*(e % 4) + 2*(e / 4), +2)
+//   3, 4 bit : 8 codes per word, code e of the word in bits [8*(e % 4) + 4*(e / 4), +4)   (3-bit codes zero-extended)
+// so that (word >> shift) & 0x0F0F0F0F-style masks leave FOUR CONSECUTIVE codes in the four bytes of a register.
+template <int BITS> struct WorkCodes {
+    static constexpr int kWords = BITS == 2 ? 2 : 4;              // words per 32-code segment
+    static constexpr int kField = BITS == 2 ? 2 : 4;              // bits per field
+    static constexpr int kPerWord = 32 / kWords;                  // codes per word
+    static constexpr uint32_t kByteMask = BITS == 2 ? 0x03030303u : BITS == 3 ? 0x07070707u : 0x0F0F0F0Fu;
+    uint32_t w[kWords];
+    // bit position of code e (0..31) of a segment inside its word
+    static constexpr int bit_of(int e) { return 8 * ((e % kPerWord) % 4) + kField * ((e % kPerWord) / 4); }
+    static constexpr int word_of(int e) { return e / kPerWord; }
+    // bytes of the result = codes e0 .. e0+3 (e0 a multiple of 4) after an extra right shift by `pre` bits
+    __device__ __forceinline__ uint32_t four(int e0, uint32_t pre = 0) const
+    {
+        return (w[word_of(e0)] >> (bit_of(e0) + pre)) & kByteMask;
+    }
+};
+
+template <int BITS>
+__device__ __forceinline__ WorkCodes<BITS> load_work_codes(__amdgpu_buffer_rsrc_t r, uint32_t off)
+{
+    WorkCodes<BITS> c;
+    if constexpr (BITS == 2) { intx2 v = buf_load8(r, off); c.w[0] = v[0]; c.w[1] = v[1]; }
+    else { intx4 v = buf_load16(r, off); c.w[0] = v[0]; c.w[1] = v[1]; c.w[2] = v[2]; c.w[3] = v[3]; }
+    return c;
+}
+
+__device__ __forceinline__ float byte_to_float(uint32_t v, int b)      // b compile-time after unrolling
+{
+    return (float)((v >> (8 * b)) & 0xFFu);                            // selected as v_cvt_f32_ubyte<b>
+}
+
 __device__ __forceinline__ float to_float(float v) { return v; }
 __device__ __forceinline__ float to_float(bf16_t v) { return (float)v; }
 

@@ -4,8 +4,8 @@
 //   dX  :  dX[T,I]  = dY[T,O]  * What[O,I]          (K = O)
 //   dW  :  dWhat^T[I,O] = X[T,I]^T * dY[T,O]        (K = T), fused with the Eq.(3)-(5) epilogue
 //
-// What is never in HBM: the weight operand of fwd / dX is rebuilt per tile, in registers, from packed
-// N-bit codes and the (s, zbar) pair of each group, and written to LDS as bf16.
+// What is never in HBM: the weight operand of fwd / dX is rebuilt per tile, in registers, from N-bit codes
+// (working layout, see WorkCodes) and the (s, zbar) pair of each group, and written to LDS as bf16.
 //
 // Two LDS tile formats feed the MFMA operands:
 //   KC  "K contiguous"  [row][BK + 8]      fragment = one ds_read_b128 per lane
@@ -44,16 +44,54 @@ __device__ __forceinline__ bf16x8 frag_km(const bf16_t *tile, int col0, int kk, 
     return __builtin_bit_cast(bf16x8, r);
 }
 
-// ---- 32 codes -> 32 bf16 of What ------------------------------------------------------------------------
-template <int BITS, int K0>
-__device__ __forceinline__ bf16x8 dequant8(const CodeWords<BITS> &c, float s, float b)
-{
-    bf16x8 o;
-#define EQAT_DQ(J) o[J] = (bf16_t)__builtin_fmaf((float)code_at<BITS, K0 + J>(c), s, b)
-    EQAT_DQ(0); EQAT_DQ(1); EQAT_DQ(2); EQAT_DQ(3); EQAT_DQ(4); EQAT_DQ(5); EQAT_DQ(6); EQAT_DQ(7);
-#undef EQAT_DQ
-    return o;
-}
+// ---- codes -> bf16 What ----------------------------------------------------------------------------------
+// A group has only 2^N distinct What values, (q - zbar) * s.  For 2 and 3 bits they are computed once per 32-code
+// segment and kept as two byte tables (low and high bytes of the bf16 values); four codes sitting in the four bytes
+// of a register then become four bf16 with four byte permutes, instead of four converts, four FMAs and two packs.
+// 4 bits (16 values) exceed what one permute can index and keep the arithmetic form.
+template <int BITS> struct WhatTable {
+    uint32_t lo[2], hi[2];      // byte q of lo / hi = low / high byte of bf16(What(q)); [1] only for 3 bits
+    float s, b;                 // What(q) = q * s + b
+    __device__ __forceinline__ void build(float s_, float zbar)
+    {
+        s = s_; b = -zbar * s_;
+        if constexpr (BITS <= 3) {
+#pragma unroll
+            for (int half = 0; half < (BITS == 3 ? 2 : 1); ++half) {
+                bf16x2 p01, p23;
+                p01[0] = (bf16_t)__builtin_fmaf((float)(4 * half + 0), s, b); p01[1] = (bf16_t)__builtin_fmaf((float)(4 * half + 1), s, b);
+                p23[0] = (bf16_t)__builtin_fmaf((float)(4 * half + 2), s, b); p23[1] = (bf16_t)__builtin_fmaf((float)(4 * half + 3), s, b);
+                const uint32_t v0 = __builtin_bit_cast(uint32_t, p01), v1 = __builtin_bit_cast(uint32_t, p23);
+                lo[half] = __builtin_amdgcn_perm(v1, v0, 0x06040200u);      // bytes 0 and 2 of v0, then of v1
+                hi[half] = __builtin_amdgcn_perm(v1, v0, 0x07050301u);      // bytes 1 and 3
+            }
+            if constexpr (BITS == 2) { lo[1] = lo[0]; hi[1] = hi[0]; }
+        }
+    }
+    // t: four codes in the four bytes -> two registers holding four bf16
+    __device__ __forceinline__ void four(uint32_t t, uint32_t &d0, uint32_t &d1) const
+    {
+        if constexpr (BITS <= 3) {
+            const uint32_t x = __builtin_amdgcn_perm(lo[1], lo[0], t), y = __builtin_amdgcn_perm(hi[1], hi[0], t);
+            d0 = __builtin_amdgcn_perm(y, x, 0x05010400u);     // x0 y0 x1 y1
+            d1 = __builtin_amdgcn_perm(y, x, 0x07030602u);     // x2 y2 x3 y3
+        } else {
+            bf16x2 p01, p23;
+            p01[0] = (bf16_t)__builtin_fmaf(byte_to_float(t, 0), s, b); p01[1] = (bf16_t)__builtin_fmaf(byte_to_float(t, 1), s, b);
+            p23[0] = (bf16_t)__builtin_fmaf(byte_to_float(t, 2), s, b); p23[1] = (bf16_t)__builtin_fmaf(byte_to_float(t, 3), s, b);
+            d0 = __builtin_bit_cast(uint32_t, p01); d1 = __builtin_bit_cast(uint32_t, p23);
+        }
+    }
+    // codes [8*q8, 8*q8 + 8) of a segment -> eight bf16
+    template <int Q8> __device__ __forceinline__ bf16x8 eight(const WorkCodes<BITS> &c) const
+    {
+        uintx4 u;
+        uint32_t d0, d1;
+        four(c.four(8 * Q8), d0, d1); u[0] = d0; u[1] = d1;
+        four(c.four(8 * Q8 + 4), d0, d1); u[2] = d0; u[3] = d1;
+        return __builtin_bit_cast(bf16x8, u);
+    }
+};
 
 // ---- workgroup -> tile mapping ---------------------------------------------------------------------------
 // Consecutive workgroup ids go round-robin over the 8 XCDs, each with its own L2.  Give every XCD a
@@ -142,10 +180,11 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_q(const GemmQArgs a)
     const __amdgpu_buffer_rsrc_t rA = make_rsrc(a.A, a.a_bytes);
     const __amdgpu_buffer_rsrc_t rC = make_rsrc(a.codes, a.codes_bytes);
     const __amdgpu_buffer_rsrc_t rS = make_rsrc(a.sz, a.sz_bytes);
-    const uint32_t code_row_bytes = (uint32_t)a.I * BITS / 8;
+    const uint32_t code_row_bytes = (uint32_t)a.I / 32u * (4u * WorkCodes<BITS>::kWords);
 
-    CodeWords<BITS> stC[2][B_SEGS];
+    WorkCodes<BITS> stC[2][B_SEGS];
     floatx2 stS[2][B_SEGS];
+    WhatTable<BITS> tabs[2][B_SEGS];
 
     // activation tile at k0 -> LDS buffer `buf` (asynchronous)
     auto load_a = [&](int k0, int buf) {
@@ -166,7 +205,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_q(const GemmQArgs a)
             if (!BT) { wrow = n0 + sidx / (BK / 32); wcol = k0 + (sidx % (BK / 32)) * 32; }
             else     { wrow = k0 + sidx / (BN / 32); wcol = n0 + (sidx % (BN / 32)) * 32; }
             const bool ok = wcol < a.I;
-            stC[S][it] = load_code_words<BITS>(rC, (uint32_t)wrow * code_row_bytes + (uint32_t)(wcol >> 5) * (4u * BITS));
+            stC[S][it] = load_work_codes<BITS>(rC, (uint32_t)wrow * code_row_bytes + (uint32_t)(wcol >> 5) * (4u * WorkCodes<BITS>::kWords));
             const intx2 sv = buf_load8(rS, ok ? ((uint32_t)wrow * (uint32_t)a.G + (uint32_t)(wcol / a.g)) * 8u : kOobOffset);
             stS[S][it][0] = __int_as_float(sv[0]);
             stS[S][it][1] = __int_as_float(sv[1]);
@@ -182,12 +221,13 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_q(const GemmQArgs a)
             int r, c;
             if (!BT) { r = sidx / (BK / 32); c = (sidx % (BK / 32)) * 32; }
             else     { r = sidx / (BN / 32); c = (sidx % (BN / 32)) * 32; }
-            const float s = stS[S][it][0], b = -stS[S][it][1] * s;     // What = code*s - zbar*s
+            WhatTable<BITS> &tab = tabs[S][it];
+            if constexpr (P == 0) tab.build(stS[S][it][0], stS[S][it][1]);     // piece 0 of a tile always runs first
             bf16x8 *dst = reinterpret_cast<bf16x8 *>(dB + r * LDB + c);
-            if ((it * 4 + 0) % KK == P) dst[0] = dequant8<BITS, 0>(stC[S][it], s, b);
-            if ((it * 4 + 1) % KK == P) dst[1] = dequant8<BITS, 8>(stC[S][it], s, b);
-            if ((it * 4 + 2) % KK == P) dst[2] = dequant8<BITS, 16>(stC[S][it], s, b);
-            if ((it * 4 + 3) % KK == P) dst[3] = dequant8<BITS, 24>(stC[S][it], s, b);
+            if ((it * 4 + 0) % KK == P) dst[0] = tab.template eight<0>(stC[S][it]);
+            if ((it * 4 + 1) % KK == P) dst[1] = tab.template eight<1>(stC[S][it]);
+            if ((it * 4 + 2) % KK == P) dst[2] = tab.template eight<2>(stC[S][it]);
+            if ((it * 4 + 3) % KK == P) dst[3] = tab.template eight<3>(stC[S][it]);
         }
     };
 
@@ -469,7 +509,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_dw(const GemmDwArgs a)
     const __amdgpu_buffer_rsrc_t rS = make_rsrc(a.sz, a.sz_bytes);
     const __amdgpu_buffer_rsrc_t rW = make_rsrc(a.W, a.w_bytes);
     const __amdgpu_buffer_rsrc_t rB = make_rsrc(a.clampbits, a.clamp_bytes);
-    const uint32_t code_row_bytes = (uint32_t)a.I * BITS / 8;
+    const uint32_t code_row_bytes = (uint32_t)a.I / 32u * (4u * WorkCodes<BITS>::kWords);
     const int h = lane >> 5;
 
 #pragma unroll
@@ -479,16 +519,10 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_dw(const GemmDwArgs a)
         for (int i = 0; i < MI; ++i) {
             const int ib = m0 + wm * WTM + i * 32;                 // first of 32 in-features; whole block valid or not
             const bool valid = (o < a.O) && (ib < a.I);
-            CodeWords<BITS> cw = load_code_words<BITS>(rC, valid ? (uint32_t)o * code_row_bytes + (uint32_t)(ib >> 5) * (4u * BITS) : kOobOffset);
-            // this lane owns codes 8a + 4h + b (a, b in 0..3): shift the stream right by 4h codes
-            {
-                const uint32_t sh = (uint32_t)h * 4u * BITS;
-#pragma unroll
-                for (int k = 0; k < BITS; ++k) {
-                    const uint32_t hi = (k + 1 < BITS) ? cw.w[k + 1] : 0u;
-                    cw.w[k] = (uint32_t)(((uint64_t)hi << 32 | cw.w[k]) >> sh);
-                }
-            }
+            const WorkCodes<BITS> cw = load_work_codes<BITS>(rC, valid ? (uint32_t)o * code_row_bytes + (uint32_t)(ib >> 5) * (4u * WorkCodes<BITS>::kWords) : kOobOffset);
+            // this lane owns codes 8a + 4h + b (a, b in 0..3): four consecutive codes per a, h fields further along
+            const uint32_t pre = (uint32_t)h * WorkCodes<BITS>::kField;
+            const uint32_t cq[4] = {cw.four(0, pre), cw.four(8, pre), cw.four(16, pre), cw.four(24, pre)};
             const intx2 sv = buf_load8(rS, valid ? ((uint32_t)o * (uint32_t)a.G + (uint32_t)(ib / a.g)) * 8u : kOobOffset);
             const float s = __int_as_float(sv[0]), zb = __int_as_float(sv[1]);
             float sum_s = 0.0f, sum_z = 0.0f;
@@ -502,7 +536,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_dw(const GemmDwArgs a)
 #define EQAT_ELEM(Q, B)                                                                                   \
     {                                                                                                     \
         const float d = acc[i][j][(Q) * 4 + (B)];                                                         \
-        const float r = (float)code_at<BITS, (Q) * 8 + (B)>(cw) - zb;                                     \
+        const float r = byte_to_float(cq[Q], B) - zb;                                                     \
         const bool clamped = (cl >> ((Q) * 8 + (B))) & 1u;                                                \
         const float cs = clamped ? r : r - wq[Q].v[B] * rinv;                                             \
         sum_s = __builtin_fmaf(d, cs, sum_s);                                                             \
@@ -519,7 +553,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_dw(const GemmDwArgs a)
 #undef EQAT_QUAD
 #undef EQAT_ELEM
             } else {
-#define EQAT_ELEM(Q, B) sum_s = __builtin_fmaf(acc[i][j][(Q) * 4 + (B)], (float)code_at<BITS, (Q) * 8 + (B)>(cw) - zb, sum_s);
+#define EQAT_ELEM(Q, B) sum_s = __builtin_fmaf(acc[i][j][(Q) * 4 + (B)], byte_to_float(cq[Q], B) - zb, sum_s);
 #define EQAT_QUAD(Q) EQAT_ELEM(Q, 0) EQAT_ELEM(Q, 1) EQAT_ELEM(Q, 2) EQAT_ELEM(Q, 3)
                 EQAT_QUAD(0) EQAT_QUAD(1) EQAT_QUAD(2) EQAT_QUAD(3)
 #undef EQAT_QUAD
@@ -645,7 +679,7 @@ void launch_mfma_fwd(const Problem &p, const void *X, const void *codes, const v
     GemmQArgs a{};
     a.A = (const bf16_t *)X; a.codes = (const uint32_t *)codes; a.sz = (const floatx2 *)sz; a.C = (bf16_t *)Y;
     a.M = (int)p.T; a.N = (int)p.O; a.K = (int)p.I; a.I = (int)p.I; a.G = (int)p.G; a.g = (int)p.g;
-    a.a_bytes = (uint32_t)(p.T * p.I * 2); a.codes_bytes = (uint32_t)(p.O * p.I * p.bits / 8); a.sz_bytes = (uint32_t)(p.O * p.G * 8);
+    a.a_bytes = (uint32_t)(p.T * p.I * 2); a.codes_bytes = (uint32_t)work_code_bytes(p); a.sz_bytes = (uint32_t)(p.O * p.G * 8);
     launch_q_bits<false>(p.bits, a, st);
 }
 
@@ -655,7 +689,7 @@ void launch_mfma_dx(const Problem &p, const void *dY, const void *codes, const v
     GemmQArgs a{};
     a.A = (const bf16_t *)dY; a.codes = (const uint32_t *)codes; a.sz = (const floatx2 *)sz; a.C = (bf16_t *)dX;
     a.M = (int)p.T; a.N = (int)p.I; a.K = (int)p.O; a.I = (int)p.I; a.G = (int)p.G; a.g = (int)p.g;
-    a.a_bytes = (uint32_t)(p.T * p.O * 2); a.codes_bytes = (uint32_t)(p.O * p.I * p.bits / 8); a.sz_bytes = (uint32_t)(p.O * p.G * 8);
+    a.a_bytes = (uint32_t)(p.T * p.O * 2); a.codes_bytes = (uint32_t)work_code_bytes(p); a.sz_bytes = (uint32_t)(p.O * p.G * 8);
     launch_q_bits<true>(p.bits, a, st);
 }
 
@@ -669,7 +703,7 @@ void launch_mfma_dw(const Problem &p, bool block_ap, const void *X, const void *
     a.dW = dW; a.ds = ds; a.dz = dz;
     a.T = (int)p.T; a.I = (int)p.I; a.O = (int)p.O; a.G = (int)p.G; a.g = (int)p.g;
     a.x_bytes = (uint32_t)(p.T * p.I * 2); a.dy_bytes = (uint32_t)(p.T * p.O * 2);
-    a.w_bytes = (uint32_t)(p.O * p.I * (p.w_bf16 ? 2 : 4)); a.codes_bytes = (uint32_t)(p.O * p.I * p.bits / 8);
+    a.w_bytes = (uint32_t)(p.O * p.I * (p.w_bf16 ? 2 : 4)); a.codes_bytes = (uint32_t)work_code_bytes(p);
     a.clamp_bytes = (uint32_t)(p.O * p.I / 8); a.sz_bytes = (uint32_t)(p.O * p.G * 8);
     bool partials;
     const size_t n32 = (size_t)p.O * (p.I / 32);

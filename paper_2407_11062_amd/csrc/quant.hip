@@ -64,7 +64,8 @@ __device__ __forceinline__ uint32_t quad_bcast(uint32_t v, int k)
 // Per weight the common path costs: widen, multiply, round, two ops of tie test, clamp, convert, shift-add.
 // The clamp is applied to round(w/s) against [-zbar, Qmax - zbar] and zbar is added once, as an integer, to
 // all eight packed fields (the per-field sums stay inside [0, Qmax], so no carry crosses a field).
-template <typename WT, int BITS, bool CLAMP_Z, bool CLAMPBITS>
+// WORK = false: the dense stream of the C ABI (eqat_pack).  WORK = true: the library's working layout (WorkCodes).
+template <typename WT, int BITS, bool CLAMP_Z, bool CLAMPBITS, bool WORK>
 __global__ __launch_bounds__(256) void k_quantize(const WT *__restrict__ W, const float *__restrict__ s,
                                                   const float *__restrict__ z, uint32_t *__restrict__ codes,
                                                   uint8_t *__restrict__ clampbits, floatx2 *__restrict__ sz,
@@ -100,28 +101,66 @@ __global__ __launch_bounds__(256) void k_quantize(const WT *__restrict__ W, cons
         for (int k = 0; k < 8; ++k) r[k] = quant_exact(ch.get(k), sv);
     }
     uint32_t p = 0, cb = 0;
-#pragma unroll
-    for (int k = 0; k < 8; ++k) {
-        const float qc = __builtin_amdgcn_fmed3f(r[k], lo, hi);      // lo <= hi: the median is the clamp
-        p += (uint32_t)(int)qc << (k * BITS);              // two's complement: fields may be negative until zbar is added
-        if (CLAMPBITS) cb |= (qc != r[k] ? 1u : 0u) << k;
-    }
-    constexpr uint32_t ones = BITS == 2 ? 0x5555u : BITS == 3 ? 0x249249u : 0x11111111u;   // a one in every field
-    p += (uint32_t)(int)zb * ones;
-    if (CLAMPBITS) clampbits[c] = (uint8_t)cb;
-
-    const uint32_t pu = p & (BITS == 4 ? 0xFFFFFFFFu : ((1u << (8 * BITS)) - 1u));
-    const uint32_t p0 = quad_bcast(pu, 0), p1 = quad_bcast(pu, 1), p2 = quad_bcast(pu, 2), p3 = quad_bcast(pu, 3);
     const uint32_t q4 = threadIdx.x & 3u;
-    uint32_t word;
-    if constexpr (BITS == 2) {
-        word = (q4 == 0) ? (p0 | (p1 << 16)) : (p2 | (p3 << 16));
-    } else if constexpr (BITS == 3) {
-        word = (q4 == 0) ? (p0 | (p1 << 24)) : (q4 == 1) ? ((p1 >> 8) | (p2 << 16)) : ((p2 >> 16) | (p3 << 8));
+    if constexpr (!WORK) {
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const float qc = __builtin_amdgcn_fmed3f(r[k], lo, hi);      // lo <= hi: the median is the clamp
+            p += (uint32_t)(int)qc << (k * BITS);              // two's complement: fields may be negative until zbar is added
+            if (CLAMPBITS) cb |= (qc != r[k] ? 1u : 0u) << k;
+        }
+        constexpr uint32_t ones = BITS == 2 ? 0x5555u : BITS == 3 ? 0x249249u : 0x11111111u;   // a one in every field
+        p += (uint32_t)(int)zb * ones;
+        if (CLAMPBITS) clampbits[c] = (uint8_t)cb;
+
+        const uint32_t pu = p & (BITS == 4 ? 0xFFFFFFFFu : ((1u << (8 * BITS)) - 1u));
+        const uint32_t p0 = quad_bcast(pu, 0), p1 = quad_bcast(pu, 1), p2 = quad_bcast(pu, 2), p3 = quad_bcast(pu, 3);
+        uint32_t word;
+        if constexpr (BITS == 2) {
+            word = (q4 == 0) ? (p0 | (p1 << 16)) : (p2 | (p3 << 16));
+        } else if constexpr (BITS == 3) {
+            word = (q4 == 0) ? (p0 | (p1 << 24)) : (q4 == 1) ? ((p1 >> 8) | (p2 << 16)) : ((p2 >> 16) | (p3 << 8));
+        } else {
+            word = (q4 == 0) ? p0 : (q4 == 1) ? p1 : (q4 == 2) ? p2 : p3;
+        }
+        if (q4 < (uint32_t)BITS) codes[(c >> 2) * BITS + q4] = word;
     } else {
-        word = (q4 == 0) ? p0 : (q4 == 1) ? p1 : (q4 == 2) ? p2 : p3;
+        // working layout: this lane's code k goes to byte k % 4, field k / 4 (+ 2 fields for the odd lane of a 2-bit pair)
+        constexpr int F = WorkCodes<BITS>::kField;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const float qc = __builtin_amdgcn_fmed3f(r[k], lo, hi);
+            p += (uint32_t)(int)qc << (8 * (k % 4) + F * (k / 4));
+            if (CLAMPBITS) cb |= (qc != r[k] ? 1u : 0u) << k;
+        }
+        constexpr uint32_t ones = BITS == 2 ? 0x05050505u : 0x11111111u;
+        p += (uint32_t)(int)zb * ones;
+        if (CLAMPBITS) clampbits[c] = (uint8_t)cb;
+        if constexpr (BITS == 2) {
+            const uint32_t mine = p & 0x0F0F0F0Fu;
+            const uint32_t other = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mine, 0xB1, 0xF, 0xF, false);   // quad_perm [1,0,3,2]
+            if ((q4 & 1u) == 0) codes[(c >> 2) * 2 + (q4 >> 1)] = mine | (other << 4);
+        } else {
+            codes[c] = p & WorkCodes<BITS>::kByteMask * 0x11u;
+        }
     }
-    if (q4 < (uint32_t)BITS) codes[(c >> 2) * BITS + q4] = word;
+}
+
+// The dense stream of the C ABI -> the working layout (one thread per 32-code segment).
+template <int BITS>
+__global__ __launch_bounds__(256) void k_repack(const uint32_t *__restrict__ packed, uint32_t *__restrict__ work, uint32_t n_segs)
+{
+    const uint32_t t = blockIdx.x * 256u + threadIdx.x;
+    if (t >= n_segs) return;
+    uint32_t in[BITS];
+#pragma unroll
+    for (int k = 0; k < BITS; ++k) in[k] = packed[(size_t)t * BITS + k];
+    uint32_t out[WorkCodes<BITS>::kWords] = {};
+#pragma unroll
+    for (int e = 0; e < 32; ++e)
+        out[WorkCodes<BITS>::word_of(e)] |= code_at_rt<BITS>(in, e) << WorkCodes<BITS>::bit_of(e);
+#pragma unroll
+    for (int k = 0; k < WorkCodes<BITS>::kWords; ++k) work[(size_t)t * WorkCodes<BITS>::kWords + k] = out[k];
 }
 
 // Zero points at N bits: one thread per output word (tail bits of a row are zero).
@@ -276,26 +315,38 @@ static inline int pow2_shift(int64_t v)
 
 template <typename WT, int BITS>
 static void quantize_t(const Problem &p, const void *W, const float *s, const float *z, void *codes, void *clampbits,
-                       void *sz, bool clamp_z, hipStream_t st)
+                       void *sz, bool for_pack, hipStream_t st)
 {
     const uint32_t n_chunks = (uint32_t)((size_t)p.O * p.I / 8);
     const dim3 grid(blocks_for(n_chunks)), block(256);
     const int gs = pow2_shift(p.g);
-#define EQAT_LAUNCH(CZ, CB)                                                                                             \
-    k_quantize<WT, BITS, CZ, CB><<<grid, block, 0, st>>>((const WT *)W, s, z, (uint32_t *)codes, (uint8_t *)clampbits,   \
-                                                         (floatx2 *)sz, n_chunks, (uint32_t)p.g, gs)
-    if (clampbits != nullptr) { if (clamp_z) EQAT_LAUNCH(true, true); else EQAT_LAUNCH(false, true); }
-    else                      { if (clamp_z) EQAT_LAUNCH(true, false); else EQAT_LAUNCH(false, false); }
+#define EQAT_LAUNCH(CB, WORK)                                                                                             \
+    k_quantize<WT, BITS, false, CB, WORK><<<grid, block, 0, st>>>((const WT *)W, s, z, (uint32_t *)codes,                 \
+                                                                 (uint8_t *)clampbits, (floatx2 *)sz, n_chunks, (uint32_t)p.g, gs)
+    // eqat_pack: dense stream, no clamp plane (zbar does not enter the codes, it is clamped where it is packed);
+    // the quantize pass of the Block-AP calls: working layout, clamp plane for the backward
+    if (for_pack) EQAT_LAUNCH(false, false);
+    else if (clampbits != nullptr) EQAT_LAUNCH(true, true);
+    else EQAT_LAUNCH(false, true);
 #undef EQAT_LAUNCH
 }
 
 void launch_quantize(const Problem &p, const void *W, const float *s, const float *z, void *codes, void *clampbits,
-                     void *sz, bool clamp_z, hipStream_t st)
+                     void *sz, bool for_pack, hipStream_t st)
 {
-#define EQAT_Q(WT, B) quantize_t<WT, B>(p, W, s, z, codes, clampbits, sz, clamp_z, st)
+#define EQAT_Q(WT, B) quantize_t<WT, B>(p, W, s, z, codes, clampbits, sz, for_pack, st)
     if (p.w_bf16) { if (p.bits == 2) EQAT_Q(bf16_t, 2); else if (p.bits == 3) EQAT_Q(bf16_t, 3); else EQAT_Q(bf16_t, 4); }
     else          { if (p.bits == 2) EQAT_Q(float, 2);  else if (p.bits == 3) EQAT_Q(float, 3);  else EQAT_Q(float, 4); }
 #undef EQAT_Q
+}
+
+void launch_repack(const Problem &p, const void *packed, void *work, hipStream_t st)
+{
+    const uint32_t n_segs = (uint32_t)((size_t)p.O * p.I / 32);
+    const dim3 grid(blocks_for(n_segs)), block(256);
+    if (p.bits == 2) k_repack<2><<<grid, block, 0, st>>>((const uint32_t *)packed, (uint32_t *)work, n_segs);
+    else if (p.bits == 3) k_repack<3><<<grid, block, 0, st>>>((const uint32_t *)packed, (uint32_t *)work, n_segs);
+    else k_repack<4><<<grid, block, 0, st>>>((const uint32_t *)packed, (uint32_t *)work, n_segs);
 }
 
 void launch_pack_z(const Problem &p, const float *z, void *zpacked, hipStream_t st)
