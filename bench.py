@@ -25,6 +25,7 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
+COPY_CALIBRATION_BYTES = 1 << 30
 
 
 def parse():
@@ -35,6 +36,8 @@ def parse():
     ap.add_argument("--workload", default="llama2_7b_block_ap_w2g64")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-rows", action="store_true", help="skip the E2E-QP / pack / init measurements")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run a few 1 GiB device copies: the reference reading for the FETCH_SIZE / WRITE_SIZE counters")
     return ap.parse_args()
 
 
@@ -52,6 +55,14 @@ def main():
         return 2
     eq.lib()   # fail loudly if the HIP library was not built
     dev = torch.device("cuda:0")
+    if args.copy_calibration:
+        src = torch.empty(COPY_CALIBRATION_BYTES, dtype=torch.uint8, device=dev).random_(0, 256)
+        dst = torch.empty_like(src)
+        for _ in range(4):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes": COPY_CALIBRATION_BYTES, "copies": 4}))
+        return 0
     wl = synth.WORKLOADS[args.workload]
     T, bits, g = wl.tokens, wl.bits, wl.group
     adt = synth.torch_dtype(wl.act_dtype)
