@@ -225,6 +225,29 @@ def measure_other_rows(torch, eq, layers, bits, g, adt, dev, args):
 
     b = sum_io * (wbytes + 8.0 / g)
     rows["eqat_init_minmax"] = hbm_row(init_all, b)
+
+    # The 7B matrices are 34-90 MB: each launch lasts 10-25 us, a good part of it ramp-up and the timing events
+    # themselves.  The same two passes on the largest matrix of the 70B block (gate/up, 28672 x 8192 = 470 MB, two
+    # buffers alternating so that nothing is served from the 256 MB last-level cache) show the kernels' streaming rate.
+    O2, I2 = 28672, 8192
+    big = []
+    for k in range(2):
+        W = torch.empty((O2, I2), dtype=adt, device=dev).normal_(0.0, 0.015)
+        s2, z2 = eq.eqat_init_minmax(W, bits, g)
+        Wp, zp = eq.eqat_pack(W, s2, z2, bits, g)
+        big.append((W, s2, z2, Wp, zp))
+
+    def pack_big():
+        for W, s2, z2, Wp, zp in big:
+            eq.eqat_pack(W, s2, z2, bits, g, Wpacked=Wp, zpacked=zp)
+
+    def init_big():
+        for W, s2, z2, Wp, zp in big:
+            eq.eqat_init_minmax(W, bits, g, s=s2, z=z2)
+
+    n2 = 2.0 * O2 * I2
+    rows["eqat_pack_28672x8192"] = hbm_row(pack_big, n2 * (wbytes + 8.0 / g + bits / 8.0 + bits / (8.0 * g)))
+    rows["eqat_init_minmax_28672x8192"] = hbm_row(init_big, n2 * (wbytes + 8.0 / g))
     return rows
 
 

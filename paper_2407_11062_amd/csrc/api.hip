@@ -130,7 +130,7 @@ int eqat_profile_kernels(void) { return eqat::PK_COUNT; }
 
 const char *eqat_profile_kernel_name(int k)
 {
-    static const char *names[eqat::PK_COUNT] = {"init_minmax", "quantize", "pack_z", "unpack_sz", "gemm_fwd", "gemm_dx",
+    static const char *names[eqat::PK_COUNT] = {"init_minmax", "quantize", "unpack_sz", "gemm_fwd", "gemm_dx",
                                                 "gemm_dw", "reduce_partials", "f32_path", "repack"};
     return (k >= 0 && k < eqat::PK_COUNT) ? names[k] : "?";
 }
@@ -197,8 +197,7 @@ eqat_status eqat_pack(const eqat_desc *d, const void *W, const float *s, const f
     EQAT_REQUIRE(W); EQAT_REQUIRE(s); EQAT_REQUIRE(z); EQAT_REQUIRE(Wpacked); EQAT_REQUIRE(zpacked);
     EQAT_ALIGNED(W); EQAT_ALIGNED(s); EQAT_ALIGNED(z); EQAT_ALIGNED(Wpacked); EQAT_ALIGNED(zpacked);
     hipStream_t st = (hipStream_t)stream;
-    { ProfScope ps(eqat::PK_QUANTIZE, st); eqat::launch_quantize(p, W, s, z, Wpacked, nullptr, nullptr, true, st); }
-    { ProfScope ps(eqat::PK_PACK_Z, st); eqat::launch_pack_z(p, z, zpacked, st); }
+    { ProfScope ps(eqat::PK_QUANTIZE, st); eqat::launch_quantize(p, W, s, z, Wpacked, nullptr, nullptr, zpacked, true, st); }
     return launch_status();
 }
 
@@ -227,7 +226,7 @@ eqat_status eqat_fq_linear_fwd(const eqat_desc *d, const void *X, const void *W,
     hipStream_t st = (hipStream_t)stream;
     char *w8 = (char *)ws;
     if (p.act_bf16) {
-        { ProfScope ps(eqat::PK_QUANTIZE, st); eqat::launch_quantize(p, W, s, z, w8 + l.codes, nullptr, w8 + l.sz, false, st); }
+        { ProfScope ps(eqat::PK_QUANTIZE, st); eqat::launch_quantize(p, W, s, z, w8 + l.codes, nullptr, w8 + l.sz, nullptr, false, st); }
         { ProfScope ps(eqat::PK_GEMM_FWD, st); eqat::launch_mfma_fwd(p, X, w8 + l.codes, w8 + l.sz, Y, st); }
     } else {
         { ProfScope ps(eqat::PK_F32, st); eqat::launch_f32_fwd(p, false, X, W, s, z, Y, st); }
@@ -252,7 +251,7 @@ eqat_status eqat_fq_linear_bwd(const eqat_desc *d, const void *X, const void *W,
     hipStream_t st = (hipStream_t)stream;
     char *w8 = (char *)ws;
     if (p.act_bf16) {
-        { ProfScope ps(eqat::PK_QUANTIZE, st); eqat::launch_quantize(p, W, s, z, w8 + l.codes, w8 + l.clamp, w8 + l.sz, false, st); }
+        { ProfScope ps(eqat::PK_QUANTIZE, st); eqat::launch_quantize(p, W, s, z, w8 + l.codes, w8 + l.clamp, w8 + l.sz, nullptr, false, st); }
         if (dX != nullptr) { ProfScope ps(eqat::PK_GEMM_DX, st); eqat::launch_mfma_dx(p, dY, w8 + l.codes, w8 + l.sz, dX, st); }
         if (want_w)
             eqat::launch_mfma_dw(p, true, X, dY, W, w8 + l.codes, w8 + l.clamp, w8 + l.sz, s, dW, ds, dz,

@@ -15,12 +15,12 @@ struct Problem {
 // ---- quant.hip -------------------------------------------------------------------------------
 // Eq.(1): W,s,z -> codes (+ optional clamp bit-plane [O,I/8] bytes, + optional (s,zbar) pairs [O,G]).
 // for_pack: the dense stream of the C ABI; otherwise the working layout the GEMM kernels read (work_code_bytes()).
+// zpacked (may be NULL): the zero points at N bits are packed by extra workgroups of the same launch.
 void launch_quantize(const Problem &p, const void *W, const float *s, const float *z, void *codes, void *clampbits,
-                     void *sz, bool for_pack, hipStream_t st);
+                     void *sz, void *zpacked, bool for_pack, hipStream_t st);
 // dense stream -> working layout
 void launch_repack(const Problem &p, const void *packed, void *work, hipStream_t st);
 inline size_t work_code_bytes(const Problem &p) { return (size_t)p.O * p.I / (p.bits == 2 ? 4 : 2); }
-void launch_pack_z(const Problem &p, const float *z, void *zpacked, hipStream_t st);
 void launch_unpack_sz(const Problem &p, const float *s, const void *zpacked, void *sz, hipStream_t st);
 void launch_unpack(const Problem &p, const void *Wpacked, const void *zpacked, int32_t *codes, int32_t *zcodes, hipStream_t st);
 void launch_init_minmax(const Problem &p, const void *W, float *s, float *z, hipStream_t st);

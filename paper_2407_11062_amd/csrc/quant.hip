@@ -65,83 +65,128 @@ __device__ __forceinline__ uint32_t quad_bcast(uint32_t v, int k)
 // The clamp is applied to round(w/s) against [-zbar, Qmax - zbar] and zbar is added once, as an integer, to
 // all eight packed fields (the per-field sums stay inside [0, Qmax], so no carry crosses a field).
 // WORK = false: the dense stream of the C ABI (eqat_pack).  WORK = true: the library's working layout (WorkCodes).
-template <typename WT, int BITS, bool CLAMP_Z, bool CLAMPBITS, bool WORK>
-__global__ __launch_bounds__(256) void k_quantize(const WT *__restrict__ W, const float *__restrict__ s,
-                                                  const float *__restrict__ z, uint32_t *__restrict__ codes,
-                                                  uint8_t *__restrict__ clampbits, floatx2 *__restrict__ sz,
-                                                  uint32_t n_chunks, uint32_t g, int g_shift)
+// Zero points at N bits: one thread per output word (tail bits of a row are zero).
+template <int BITS>
+__device__ __forceinline__ void pack_z_word(const float *__restrict__ z, uint32_t *__restrict__ zpacked, uint32_t t,
+                                            uint32_t G, uint32_t row_words)
 {
-    const uint32_t c = blockIdx.x * 256u + threadIdx.x;   // chunk index; n_chunks % 4 == 0 so quads stay whole
-    if (c >= n_chunks) return;
-    const uint32_t e = c * 8u;
-    const uint32_t gi = g_shift >= 0 ? (e >> g_shift) : (e / g);
-    const float sv = s[gi];
-    float zb = __builtin_rintf(z[gi]);
+    const uint32_t row = t / row_words, w = t - row * row_words;
     constexpr float qmax = (float)((1 << BITS) - 1);
-    if (CLAMP_Z) zb = __builtin_fminf(__builtin_fmaxf(zb, 0.0f), qmax);
-    if (sz != nullptr && e == gi * g) { floatx2 o; o[0] = sv; o[1] = zb; sz[gi] = o; }
+    const uint32_t bit0 = w * 32u;
+    uint32_t j = bit0 / BITS;                   // first code with bits in this word
+    uint64_t acc = 0;
+    for (; j < G && j * BITS < bit0 + 32u; ++j) {
+        const uint32_t code = (uint32_t)__builtin_amdgcn_fmed3f(__builtin_rintf(z[row * G + j]), 0.0f, qmax);
+        const int sh = (int)(j * BITS) - (int)bit0;         // may be negative for a code straddling in from the left
+        acc |= sh >= 0 ? ((uint64_t)code << sh) : ((uint64_t)code >> (-sh));
+    }
+    zpacked[t] = (uint32_t)acc;
+}
 
-    Chunk8<WT> ch;
-    ch.load(W + e);
-    const float rinv = __builtin_amdgcn_rcpf(sv);          // 1 ulp; s is a normal number
-    const float lo = -zb, hi = qmax - zb;
-    // Far from a rounding tie the cheap quotient w * rcp(s) (within 2^-22 relative of w/s) rounds like the exact one.
-    // Only weights whose code is not clamped matter, and for those |w/s| <= |zbar| + Qmax + 1.
-    const float thr = 0.5f - 0x1p-20f * (__builtin_fabsf(zb) + qmax + 2.0f);
-    float r[8];
-    float worst = 0.0f;
-#pragma unroll
-    for (int k = 0; k < 8; ++k) {
-        const float t = ch.get(k) * rinv;
-        r[k] = __builtin_rintf(t);
-        worst = __builtin_fmaxf(worst, __builtin_fabsf(t - r[k]));
+struct QuantizeArgs {
+    const void *W; const float *s, *z;
+    uint32_t *codes; uint8_t *clampbits; floatx2 *sz;
+    uint32_t n_chunks, g; int g_shift;
+    // eqat_pack only: the blocks past n_quant_blocks pack the zero points (one thread per word)
+    uint32_t *zpacked; uint32_t n_quant_blocks, n_zwords, G, row_words;
+};
+
+constexpr int kQuantUnroll = 4;     // chunks per thread: 64 B (bf16) / 128 B (fp32) of W in flight per lane
+
+template <typename WT, int BITS, bool CLAMP_Z, bool CLAMPBITS, bool WORK>
+__global__ __launch_bounds__(256) void k_quantize(const QuantizeArgs a)
+{
+    constexpr int U = kQuantUnroll;
+    if (blockIdx.x >= a.n_quant_blocks) {
+        const uint32_t t = (blockIdx.x - a.n_quant_blocks) * 256u + threadIdx.x;
+        if (t < a.n_zwords) pack_z_word<BITS>(a.z, a.zpacked, t, a.G, a.row_words);
+        return;
     }
-    if (worst >= thr) {
+    const WT *__restrict__ W = reinterpret_cast<const WT *>(a.W);
+    constexpr float qmax = (float)((1 << BITS) - 1);
+    const uint32_t c0 = blockIdx.x * (256u * U) + threadIdx.x;   // chunk index; n_chunks % 4 == 0 so quads stay whole
+    // all loads of the thread's U chunks first: the pass lives on bytes in flight
+    Chunk8<WT> ch[U];
+    uint32_t gi[U];
+    float sv[U], zb[U];
 #pragma unroll
-        for (int k = 0; k < 8; ++k) r[k] = quant_exact(ch.get(k), sv);
+    for (int u = 0; u < U; ++u) {
+        const uint32_t c = c0 + u * 256u;
+        const uint32_t cc = c < a.n_chunks ? c : 0u;             // past the end: recompute chunk 0, store nothing
+        const uint32_t e = cc * 8u;
+        gi[u] = a.g_shift >= 0 ? (e >> a.g_shift) : (e / a.g);
+        ch[u].load(W + e);
+        sv[u] = a.s[gi[u]];
+        zb[u] = a.z[gi[u]];
     }
-    uint32_t p = 0, cb = 0;
     const uint32_t q4 = threadIdx.x & 3u;
-    if constexpr (!WORK) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const uint32_t c = c0 + u * 256u;
+        if (c >= a.n_chunks) break;
+        const uint32_t e = c * 8u;
+        float zbar = __builtin_rintf(zb[u]);
+        if (CLAMP_Z) zbar = __builtin_amdgcn_fmed3f(zbar, 0.0f, qmax);
+        if (a.sz != nullptr && e == gi[u] * a.g) { floatx2 o; o[0] = sv[u]; o[1] = zbar; a.sz[gi[u]] = o; }
+        const float rinv = __builtin_amdgcn_rcpf(sv[u]);          // 1 ulp; s is a normal number
+        const float lo = -zbar, hi = qmax - zbar;
+        // Far from a rounding tie the cheap quotient w * rcp(s) (within 2^-22 relative of w/s) rounds like the exact one.
+        // Only weights whose code is not clamped matter, and for those |w/s| <= |zbar| + Qmax + 1.
+        const float thr = 0.5f - 0x1p-20f * (__builtin_fabsf(zbar) + qmax + 2.0f);
+        float r[8];
+        float worst = 0.0f;
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
-            const float qc = __builtin_amdgcn_fmed3f(r[k], lo, hi);      // lo <= hi: the median is the clamp
-            p += (uint32_t)(int)qc << (k * BITS);              // two's complement: fields may be negative until zbar is added
-            if (CLAMPBITS) cb |= (qc != r[k] ? 1u : 0u) << k;
+            const float t = ch[u].get(k) * rinv;
+            r[k] = __builtin_rintf(t);
+            worst = __builtin_fmaxf(worst, __builtin_fabsf(t - r[k]));
         }
-        constexpr uint32_t ones = BITS == 2 ? 0x5555u : BITS == 3 ? 0x249249u : 0x11111111u;   // a one in every field
-        p += (uint32_t)(int)zb * ones;
-        if (CLAMPBITS) clampbits[c] = (uint8_t)cb;
+        if (worst >= thr) {
+#pragma unroll
+            for (int k = 0; k < 8; ++k) r[k] = quant_exact(ch[u].get(k), sv[u]);
+        }
+        uint32_t p = 0, cb = 0;
+        if constexpr (!WORK) {
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const float qc = __builtin_amdgcn_fmed3f(r[k], lo, hi);      // lo <= hi: the median is the clamp
+                p += (uint32_t)(int)qc << (k * BITS);          // two's complement: fields may be negative until zbar is added
+                if (CLAMPBITS) cb |= (qc != r[k] ? 1u : 0u) << k;
+            }
+            constexpr uint32_t ones = BITS == 2 ? 0x5555u : BITS == 3 ? 0x249249u : 0x11111111u;   // a one in every field
+            p += (uint32_t)(int)zbar * ones;
+            if (CLAMPBITS) a.clampbits[c] = (uint8_t)cb;
 
-        const uint32_t pu = p & (BITS == 4 ? 0xFFFFFFFFu : ((1u << (8 * BITS)) - 1u));
-        const uint32_t p0 = quad_bcast(pu, 0), p1 = quad_bcast(pu, 1), p2 = quad_bcast(pu, 2), p3 = quad_bcast(pu, 3);
-        uint32_t word;
-        if constexpr (BITS == 2) {
-            word = (q4 == 0) ? (p0 | (p1 << 16)) : (p2 | (p3 << 16));
-        } else if constexpr (BITS == 3) {
-            word = (q4 == 0) ? (p0 | (p1 << 24)) : (q4 == 1) ? ((p1 >> 8) | (p2 << 16)) : ((p2 >> 16) | (p3 << 8));
+            const uint32_t pu = p & (BITS == 4 ? 0xFFFFFFFFu : ((1u << (8 * BITS)) - 1u));
+            const uint32_t p0 = quad_bcast(pu, 0), p1 = quad_bcast(pu, 1), p2 = quad_bcast(pu, 2), p3 = quad_bcast(pu, 3);
+            uint32_t word;
+            if constexpr (BITS == 2) {
+                word = (q4 == 0) ? (p0 | (p1 << 16)) : (p2 | (p3 << 16));
+            } else if constexpr (BITS == 3) {
+                word = (q4 == 0) ? (p0 | (p1 << 24)) : (q4 == 1) ? ((p1 >> 8) | (p2 << 16)) : ((p2 >> 16) | (p3 << 8));
+            } else {
+                word = (q4 == 0) ? p0 : (q4 == 1) ? p1 : (q4 == 2) ? p2 : p3;
+            }
+            if (q4 < (uint32_t)BITS) a.codes[(c >> 2) * BITS + q4] = word;
         } else {
-            word = (q4 == 0) ? p0 : (q4 == 1) ? p1 : (q4 == 2) ? p2 : p3;
-        }
-        if (q4 < (uint32_t)BITS) codes[(c >> 2) * BITS + q4] = word;
-    } else {
-        // working layout: this lane's code k goes to byte k % 4, field k / 4 (+ 2 fields for the odd lane of a 2-bit pair)
-        constexpr int F = WorkCodes<BITS>::kField;
+            // working layout: this lane's code k goes to byte k % 4, field k / 4 (+ 2 fields for the odd lane of a 2-bit pair)
+            constexpr int F = WorkCodes<BITS>::kField;
 #pragma unroll
-        for (int k = 0; k < 8; ++k) {
-            const float qc = __builtin_amdgcn_fmed3f(r[k], lo, hi);
-            p += (uint32_t)(int)qc << (8 * (k % 4) + F * (k / 4));
-            if (CLAMPBITS) cb |= (qc != r[k] ? 1u : 0u) << k;
-        }
-        constexpr uint32_t ones = BITS == 2 ? 0x05050505u : 0x11111111u;
-        p += (uint32_t)(int)zb * ones;
-        if (CLAMPBITS) clampbits[c] = (uint8_t)cb;
-        if constexpr (BITS == 2) {
-            const uint32_t mine = p & 0x0F0F0F0Fu;
-            const uint32_t other = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mine, 0xB1, 0xF, 0xF, false);   // quad_perm [1,0,3,2]
-            if ((q4 & 1u) == 0) codes[(c >> 2) * 2 + (q4 >> 1)] = mine | (other << 4);
-        } else {
-            codes[c] = p & WorkCodes<BITS>::kByteMask * 0x11u;
+            for (int k = 0; k < 8; ++k) {
+                const float qc = __builtin_amdgcn_fmed3f(r[k], lo, hi);
+                p += (uint32_t)(int)qc << (8 * (k % 4) + F * (k / 4));
+                if (CLAMPBITS) cb |= (qc != r[k] ? 1u : 0u) << k;
+            }
+            constexpr uint32_t ones = BITS == 2 ? 0x05050505u : 0x11111111u;
+            p += (uint32_t)(int)zbar * ones;
+            if (CLAMPBITS) a.clampbits[c] = (uint8_t)cb;
+            if constexpr (BITS == 2) {
+                const uint32_t mine = p & 0x0F0F0F0Fu;
+                const uint32_t other = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mine, 0xB1, 0xF, 0xF, false);   // quad_perm [1,0,3,2]
+                if ((q4 & 1u) == 0) a.codes[(c >> 2) * 2 + (q4 >> 1)] = mine | (other << 4);
+            } else {
+                a.codes[c] = p & WorkCodes<BITS>::kByteMask * 0x11u;
+            }
         }
     }
 }
@@ -161,26 +206,6 @@ __global__ __launch_bounds__(256) void k_repack(const uint32_t *__restrict__ pac
         out[WorkCodes<BITS>::word_of(e)] |= code_at_rt<BITS>(in, e) << WorkCodes<BITS>::bit_of(e);
 #pragma unroll
     for (int k = 0; k < WorkCodes<BITS>::kWords; ++k) work[(size_t)t * WorkCodes<BITS>::kWords + k] = out[k];
-}
-
-// Zero points at N bits: one thread per output word (tail bits of a row are zero).
-template <int BITS>
-__global__ __launch_bounds__(256) void k_pack_z(const float *__restrict__ z, uint32_t *__restrict__ zpacked,
-                                                uint32_t O, uint32_t G, uint32_t row_words)
-{
-    const uint32_t t = blockIdx.x * 256u + threadIdx.x;
-    if (t >= O * row_words) return;
-    const uint32_t row = t / row_words, w = t - row * row_words;
-    constexpr float qmax = (float)((1 << BITS) - 1);
-    const uint32_t bit0 = w * 32u;
-    uint32_t j = bit0 / BITS;                   // first code with bits in this word
-    uint64_t acc = 0;
-    for (; j < G && j * BITS < bit0 + 32u; ++j) {
-        const uint32_t code = (uint32_t)__builtin_amdgcn_fmed3f(__builtin_rintf(z[row * G + j]), 0.0f, qmax);
-        const int sh = (int)(j * BITS) - (int)bit0;         // may be negative for a code straddling in from the left
-        acc |= sh >= 0 ? ((uint64_t)code << sh) : ((uint64_t)code >> (-sh));
-    }
-    zpacked[t] = (uint32_t)acc;
 }
 
 // (s, z) pairs for the E2E-QP kernels: sz[o,j] = (s[o,j], float(zpacked code j of row o)).
@@ -230,25 +255,35 @@ template <typename WT, int LPG>
 __global__ __launch_bounds__(256) void k_init_minmax_small(const WT *__restrict__ W, float *__restrict__ s,
                                                            float *__restrict__ z, uint32_t n_chunks, float qmax)
 {
-    const uint32_t c = blockIdx.x * 256u + threadIdx.x;
-    if (c >= n_chunks) return;   // n_chunks % LPG == 0 and 256 % LPG == 0: groups never straddle the guard
-    Chunk8<WT> ch;
-    ch.load(W + (size_t)c * 8);
-    float lo = ch.get(0), hi = lo;
+    constexpr int U = kQuantUnroll;
+    const uint32_t c0 = blockIdx.x * (256u * U) + threadIdx.x;
+    // n_chunks % LPG == 0 and 256 % LPG == 0: a group never straddles the end of the array or of a 256-chunk slice
+    Chunk8<WT> ch[U];
 #pragma unroll
-    for (int k = 1; k < 8; ++k) { lo = __builtin_fminf(lo, ch.get(k)); hi = __builtin_fmaxf(hi, ch.get(k)); }
-#pragma unroll
-    for (int m = 1; m < LPG; m <<= 1) {
-        lo = __builtin_fminf(lo, __shfl_xor(lo, m));
-        hi = __builtin_fmaxf(hi, __shfl_xor(hi, m));
+    for (int u = 0; u < U; ++u) {
+        const uint32_t c = c0 + u * 256u;
+        ch[u].load(W + (size_t)(c < n_chunks ? c : 0u) * 8);
     }
-    if ((c & (LPG - 1)) == 0) {
-        float step = (hi - lo) / qmax;
-        if (!(step >= 1e-10f)) step = 1e-10f;
-        float zf = __builtin_rintf((-lo) / step);
-        zf = __builtin_fminf(__builtin_fmaxf(zf, 0.0f), qmax);
-        s[c / LPG] = step;
-        z[c / LPG] = zf;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const uint32_t c = c0 + u * 256u;
+        if (c >= n_chunks) break;
+        float lo = ch[u].get(0), hi = lo;
+#pragma unroll
+        for (int k = 1; k < 8; ++k) { lo = __builtin_fminf(lo, ch[u].get(k)); hi = __builtin_fmaxf(hi, ch[u].get(k)); }
+#pragma unroll
+        for (int m = 1; m < LPG; m <<= 1) {
+            lo = __builtin_fminf(lo, __shfl_xor(lo, m));
+            hi = __builtin_fmaxf(hi, __shfl_xor(hi, m));
+        }
+        if ((c & (LPG - 1)) == 0) {
+            float step = (hi - lo) / qmax;
+            if (!(step >= 1e-10f)) step = 1e-10f;
+            float zf = __builtin_rintf((-lo) / step);
+            zf = __builtin_fminf(__builtin_fmaxf(zf, 0.0f), qmax);
+            s[c / LPG] = step;
+            z[c / LPG] = zf;
+        }
     }
 }
 // Any other group size: one wavefront per group.
@@ -315,26 +350,26 @@ static inline int pow2_shift(int64_t v)
 
 template <typename WT, int BITS>
 static void quantize_t(const Problem &p, const void *W, const float *s, const float *z, void *codes, void *clampbits,
-                       void *sz, bool for_pack, hipStream_t st)
+                       void *sz, void *zpacked, bool for_pack, hipStream_t st)
 {
-    const uint32_t n_chunks = (uint32_t)((size_t)p.O * p.I / 8);
-    const dim3 grid(blocks_for(n_chunks)), block(256);
-    const int gs = pow2_shift(p.g);
-#define EQAT_LAUNCH(CB, WORK)                                                                                             \
-    k_quantize<WT, BITS, false, CB, WORK><<<grid, block, 0, st>>>((const WT *)W, s, z, (uint32_t *)codes,                 \
-                                                                 (uint8_t *)clampbits, (floatx2 *)sz, n_chunks, (uint32_t)p.g, gs)
+    QuantizeArgs a{};
+    a.W = W; a.s = s; a.z = z; a.codes = (uint32_t *)codes; a.clampbits = (uint8_t *)clampbits; a.sz = (floatx2 *)sz;
+    a.n_chunks = (uint32_t)((size_t)p.O * p.I / 8); a.g = (uint32_t)p.g; a.g_shift = pow2_shift(p.g);
+    a.n_quant_blocks = blocks_for(a.n_chunks, 256 * kQuantUnroll);
+    a.zpacked = (uint32_t *)zpacked; a.G = (uint32_t)p.G; a.row_words = (uint32_t)((p.G * p.bits + 31) / 32);
+    a.n_zwords = zpacked != nullptr ? (uint32_t)p.O * a.row_words : 0u;
+    const dim3 grid(a.n_quant_blocks + blocks_for(a.n_zwords)), block(256);
     // eqat_pack: dense stream, no clamp plane (zbar does not enter the codes, it is clamped where it is packed);
     // the quantize pass of the Block-AP calls: working layout, clamp plane for the backward
-    if (for_pack) EQAT_LAUNCH(false, false);
-    else if (clampbits != nullptr) EQAT_LAUNCH(true, true);
-    else EQAT_LAUNCH(false, true);
-#undef EQAT_LAUNCH
+    if (for_pack) k_quantize<WT, BITS, false, false, false><<<grid, block, 0, st>>>(a);
+    else if (clampbits != nullptr) k_quantize<WT, BITS, false, true, true><<<grid, block, 0, st>>>(a);
+    else k_quantize<WT, BITS, false, false, true><<<grid, block, 0, st>>>(a);
 }
 
 void launch_quantize(const Problem &p, const void *W, const float *s, const float *z, void *codes, void *clampbits,
-                     void *sz, bool for_pack, hipStream_t st)
+                     void *sz, void *zpacked, bool for_pack, hipStream_t st)
 {
-#define EQAT_Q(WT, B) quantize_t<WT, B>(p, W, s, z, codes, clampbits, sz, for_pack, st)
+#define EQAT_Q(WT, B) quantize_t<WT, B>(p, W, s, z, codes, clampbits, sz, zpacked, for_pack, st)
     if (p.w_bf16) { if (p.bits == 2) EQAT_Q(bf16_t, 2); else if (p.bits == 3) EQAT_Q(bf16_t, 3); else EQAT_Q(bf16_t, 4); }
     else          { if (p.bits == 2) EQAT_Q(float, 2);  else if (p.bits == 3) EQAT_Q(float, 3);  else EQAT_Q(float, 4); }
 #undef EQAT_Q
@@ -347,16 +382,6 @@ void launch_repack(const Problem &p, const void *packed, void *work, hipStream_t
     if (p.bits == 2) k_repack<2><<<grid, block, 0, st>>>((const uint32_t *)packed, (uint32_t *)work, n_segs);
     else if (p.bits == 3) k_repack<3><<<grid, block, 0, st>>>((const uint32_t *)packed, (uint32_t *)work, n_segs);
     else k_repack<4><<<grid, block, 0, st>>>((const uint32_t *)packed, (uint32_t *)work, n_segs);
-}
-
-void launch_pack_z(const Problem &p, const float *z, void *zpacked, hipStream_t st)
-{
-    const uint32_t row_words = (uint32_t)((p.G * p.bits + 31) / 32);
-    const size_t n = (size_t)p.O * row_words;
-    const dim3 grid(blocks_for(n)), block(256);
-    if (p.bits == 2) k_pack_z<2><<<grid, block, 0, st>>>(z, (uint32_t *)zpacked, (uint32_t)p.O, (uint32_t)p.G, row_words);
-    else if (p.bits == 3) k_pack_z<3><<<grid, block, 0, st>>>(z, (uint32_t *)zpacked, (uint32_t)p.O, (uint32_t)p.G, row_words);
-    else k_pack_z<4><<<grid, block, 0, st>>>(z, (uint32_t *)zpacked, (uint32_t)p.O, (uint32_t)p.G, row_words);
 }
 
 void launch_unpack_sz(const Problem &p, const float *s, const void *zpacked, void *sz, hipStream_t st)
@@ -393,7 +418,7 @@ static void init_minmax_t(const Problem &p, const void *W, float *s, float *z, h
 {
     const float qmax = (float)((1 << p.bits) - 1);
     const uint32_t n_chunks = (uint32_t)((size_t)p.O * p.I / 8);
-    const dim3 grid(blocks_for(n_chunks)), block(256);
+    const dim3 grid(blocks_for(n_chunks, 256 * kQuantUnroll)), block(256);
     const WT *w = (const WT *)W;
     switch (p.g) {
     case 32:  k_init_minmax_small<WT, 4><<<grid, block, 0, st>>>(w, s, z, n_chunks, qmax); break;
