@@ -144,9 +144,36 @@ __device__ __forceinline__ bf16x8 frag_kc_swz(const bf16_t *tile, int row0, int 
     return *reinterpret_cast<const bf16x8 *>(tile + r * 64 + kc_swz(r, kk * 2 + (lane >> 5)) * 8);
 }
 
-__device__ __forceinline__ void load_to_lds16(__amdgpu_buffer_rsrc_t r, bf16_t *lds_wave_base, uint32_t voffset)
+// 16 bytes per lane from a buffer straight into LDS: lane j's bytes land at lds_wave_base + 16 j; a voffset beyond the
+// buffer writes zeros.  Issued as inline assembly on purpose: the compiler models the builtin form as a store to LDS and,
+// not being able to tell it apart from the transpose reads of the other buffer, waits for vmcnt(0) before the next LDS
+// read, which puts the whole fetch latency on the critical path of every K tile.  Nothing tracks these loads, so every
+// consumer sits behind an explicit "s_waitcnt vmcnt(0)" + barrier (the one in the main loop, and the one after it).
+struct RawRsrc { intx4 w; };
+__device__ __forceinline__ RawRsrc make_raw_rsrc(const void *p, uint32_t bytes)
 {
-    __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (void __attribute__((address_space(3))) *)lds_wave_base, 16, (int)voffset, 0, 0, 0);
+    const uint64_t a = (uint64_t)p;
+    RawRsrc r;
+    r.w[0] = (int)(uint32_t)a; r.w[1] = (int)(uint32_t)((a >> 32) & 0xFFFFu); r.w[2] = (int)bytes; r.w[3] = 0x00020000;
+    return r;
+}
+__device__ __forceinline__ void load_to_lds16(const RawRsrc &r, bf16_t *lds_wave_base, uint32_t voffset)
+{
+    const uint32_t lds_addr = (uint32_t)(uintptr_t)lds_wave_base;      // LDS pointers are 32-bit offsets; wave-uniform
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                 :: "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(voffset), "s"(r.w) : "memory", "m0");
+}
+
+// Workgroup barrier behind "everything I issued has completed".  The wait is the builtin, not assembly text, so that the
+// compiler's own wait-count bookkeeping knows that its register loads are complete here and inserts no further vmcnt
+// wait while the (untracked) direct-to-LDS loads of the next tile are in flight: such a wait counts ALL outstanding
+// loads and would stall on the tile fetch.  The empty asm statements keep the compiler from moving LDS accesses across.
+__device__ __forceinline__ void wait_all_and_barrier()
+{
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_waitcnt(0x0070);       // vmcnt(0) lgkmcnt(0); expcnt field at its maximum = no wait
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
 }
 
 // Software pipeline of the main loop (one workgroup, K tile kt):
@@ -177,7 +204,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_q(const GemmQArgs a)
     const int m0 = tm * BM, n0 = tn * BN;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wm = wave / WGN, wn = wave % WGN;
 
-    const __amdgpu_buffer_rsrc_t rA = make_rsrc(a.A, a.a_bytes);
+    const RawRsrc rA = make_raw_rsrc(a.A, a.a_bytes);
     const __amdgpu_buffer_rsrc_t rC = make_rsrc(a.codes, a.codes_bytes);
     const __amdgpu_buffer_rsrc_t rS = make_rsrc(a.sz, a.sz_bytes);
     const uint32_t code_row_bytes = (uint32_t)a.I / 32u * (4u * WorkCodes<BITS>::kWords);
@@ -290,8 +317,9 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_q(const GemmQArgs a)
         commit_piece(IC<PAR ^ 1>{}, IC<3>{}, PAR ^ 1);
         interleave();
         __builtin_amdgcn_sched_barrier(0);
-        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");   // next activation tile landed, my LDS traffic done
-        // last slice of this tile, overlapped with the start of the next two tiles
+        wait_all_and_barrier();   // next activation tile landed, my LDS traffic done
+        // last slice of this tile, overlapped with the start of the next two tiles.  (The codes fetched here are first
+        // used behind the next barrier, so the compiler never needs a vmcnt wait while the activation loads fly.)
         load_a((kt + 2) * BK, PAR);
         read_frags(0, sA + (PAR ^ 1) * A_ELEMS, sB + (PAR ^ 1) * B_ELEMS, 0);
         __builtin_amdgcn_sched_barrier(0);
@@ -310,9 +338,9 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_q(const GemmQArgs a)
     commit_piece(IC<0>{}, IC<1>{}, 0);
     commit_piece(IC<0>{}, IC<2>{}, 0);
     commit_piece(IC<0>{}, IC<3>{}, 0);
-    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
-    load_a(BK, 1);
+    wait_all_and_barrier();
     load_codes(IC<0>{}, 2 * BK);
+    load_a(BK, 1);
     commit_piece(IC<1>{}, IC<0>{}, 1);
     read_frags(0, sA, sB, 0);
     // Two tiles per trip, unconditionally (the register staging sets alternate at compile time, and a branch
@@ -322,6 +350,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_q(const GemmQArgs a)
         step(IC<0>{}, kt);
         step(IC<1>{}, kt + 1);
     }
+    __builtin_amdgcn_s_waitcnt(0x0070);       // the loads issued for tiles past K (all zeros) have landed too
 
     // C[m][n]: lane holds column n = l % 32 and rows 8*(r/4) + 4*(l/32) + r%4 of each 32x32 block
 #pragma unroll
@@ -407,7 +436,7 @@ __device__ __forceinline__ bf16x8 frag_km_swz(const bf16_t *tile, int col0, int 
 
 // rows [k0, k0 + BK) x columns [col0, col0 + COLS) of a row-major [rows][ld] bf16 matrix -> LDS tile (asynchronous)
 template <int BK, int COLS, int NW>
-__device__ __forceinline__ void load_km_tile(__amdgpu_buffer_rsrc_t r, int ld, int col0, int k0, bf16_t *tile, int wave, int lane)
+__device__ __forceinline__ void load_km_tile(const RawRsrc &r, int ld, int col0, int k0, bf16_t *tile, int wave, int lane)
 {
     constexpr int CPR = COLS / 8, RPI = 64 / CPR, LOADS = BK / RPI / NW;   // chunks per row, rows per instruction
     static_assert(BK % (RPI * NW) == 0 && CPR <= 64, "tile / wave mismatch");
@@ -439,8 +468,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_dw(const GemmDwArgs a)
     const int m0 = tm * BM, n0 = tn * BN;      // m0: first in-feature i, n0: first out-feature o
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wm = wave / WGN, wn = wave % WGN;
 
-    const __amdgpu_buffer_rsrc_t rX = make_rsrc(a.X, a.x_bytes);
-    const __amdgpu_buffer_rsrc_t rY = make_rsrc(a.dY, a.dy_bytes);
+    const RawRsrc rX = make_raw_rsrc(a.X, a.x_bytes);
+    const RawRsrc rY = make_raw_rsrc(a.dY, a.dy_bytes);
 
     auto load_tiles = [&](int k0, int buf) {
         load_km_tile<BK, BM, NW>(rX, a.I, m0, k0, sA + buf * A_ELEMS, wave, lane);
@@ -484,7 +513,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_dw(const GemmDwArgs a)
         __builtin_amdgcn_sched_barrier(0);
         mfma_slice(0);
         __builtin_amdgcn_sched_barrier(0);
-        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        wait_all_and_barrier();
         load_tiles((kt + 2) * BK, buf);
         read_frags(0, buf ^ 1, 0);
         __builtin_amdgcn_sched_barrier(0);
@@ -495,12 +524,12 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_dw(const GemmDwArgs a)
     const int nk = (a.T + BK - 1) / BK;
     if (nk > 0) {
         load_tiles(0, 0);
-        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        wait_all_and_barrier();
         load_tiles(BK, 1);
         read_frags(0, 0, 0);
         for (int kt = 0; kt < nk; ++kt) step(kt & 1, kt);
     }
-    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");   // tile buffers become the partial-sum arrays
+    wait_all_and_barrier();   // tile buffers become the partial-sum arrays
 
     // ---- epilogue ----------------------------------------------------------------------------------
     float *p_ds = reinterpret_cast<float *>(smem_raw);            // [BM/32][BN]
