@@ -292,27 +292,26 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_q(const GemmQArgs a)
         const bf16_t *cA = sA + PAR * A_ELEMS, *cB = sB + PAR * B_ELEMS;
         // stage kk: start the reads of slice kk+1, multiply slice kk, convert a quarter of the next weight tile
         auto interleave = [&]() {
-            // pipeline hint for the scheduler: one MFMA, then a few VALU ops of the conversion, repeated
+            // pipeline hint for the scheduler: one MFMA, one fragment read of the next slice, a few VALU ops of the
+            // conversion, repeated (LDS reads spread over the slice measure 2-5 % faster than a burst in front of it)
 #pragma unroll
             for (int q = 0; q < MI * NI; ++q) {
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
                 __builtin_amdgcn_sched_group_barrier(0x002, 6, 0);
             }
         };
         read_frags(1, cA, cB, 1);
-        __builtin_amdgcn_sched_barrier(0);
         mfma_slice(0);
         commit_piece(IC<PAR ^ 1>{}, IC<1>{}, PAR ^ 1);
         interleave();
         __builtin_amdgcn_sched_barrier(0);
         read_frags(0, cA, cB, 2);
-        __builtin_amdgcn_sched_barrier(0);
         mfma_slice(1);
         commit_piece(IC<PAR ^ 1>{}, IC<2>{}, PAR ^ 1);
         interleave();
         __builtin_amdgcn_sched_barrier(0);
         read_frags(1, cA, cB, 3);
-        __builtin_amdgcn_sched_barrier(0);
         mfma_slice(0);
         commit_piece(IC<PAR ^ 1>{}, IC<3>{}, PAR ^ 1);
         interleave();
@@ -322,7 +321,6 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_q(const GemmQArgs a)
         // used behind the next barrier, so the compiler never needs a vmcnt wait while the activation loads fly.)
         load_a((kt + 2) * BK, PAR);
         read_frags(0, sA + (PAR ^ 1) * A_ELEMS, sB + (PAR ^ 1) * B_ELEMS, 0);
-        __builtin_amdgcn_sched_barrier(0);
         mfma_slice(1);
         commit_piece(IC<PAR>{}, IC<0>{}, PAR);
         interleave();
@@ -501,23 +499,32 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_dw(const GemmDwArgs a)
     // Same pipeline as the forward kernel: the barrier sits before the last slice, whose MFMAs then cover the first
     // fragment reads of the next tile and the issue of the loads for the tile after it.
     auto step = [&](int buf, int kt) {
+        // fragment reads of the next slice spread between the MFMAs of this one (see the forward kernel)
+        auto weave = [&]() {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);
+            }
+        };
         read_frags(1, buf, 1);
-        __builtin_amdgcn_sched_barrier(0);
         mfma_slice(0);
+        weave();
         __builtin_amdgcn_sched_barrier(0);
         read_frags(0, buf, 2);
-        __builtin_amdgcn_sched_barrier(0);
         mfma_slice(1);
+        weave();
         __builtin_amdgcn_sched_barrier(0);
         read_frags(1, buf, 3);
-        __builtin_amdgcn_sched_barrier(0);
         mfma_slice(0);
+        weave();
         __builtin_amdgcn_sched_barrier(0);
         wait_all_and_barrier();
         load_tiles((kt + 2) * BK, buf);
-        read_frags(0, buf ^ 1, 0);
         __builtin_amdgcn_sched_barrier(0);
+        read_frags(0, buf ^ 1, 0);
         mfma_slice(1);
+        weave();
         __builtin_amdgcn_sched_barrier(0);
     };
 
