@@ -267,14 +267,17 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_q(const GemmQArgs a)
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
     bf16x8 fa[2][MI], fb[2][NI];
+    // B fragments first: the MFMAs run i-major, so both B fragments and A0 are needed by the first two MFMAs of a
+    // slice and A3 only by the seventh; issued in that order, one read per MFMA of the previous slice, every read gets
+    // about a slice of latency budget.
     auto read_frags = [&](int slot, const bf16_t *cA, const bf16_t *cB, int kk) {
-#pragma unroll
-        for (int i = 0; i < MI; ++i) fa[slot][i] = frag_kc_swz(cA, wm * WTM + i * 32, kk, lane);
 #pragma unroll
         for (int j = 0; j < NI; ++j) {
             if (!BT) fb[slot][j] = frag_kc<LDB>(cB, wn * WTN + j * 32, kk, lane);
             else     fb[slot][j] = frag_km<LDB>(cB, wn * WTN + j * 32, kk, lane);
         }
+#pragma unroll
+        for (int i = 0; i < MI; ++i) fa[slot][i] = frag_kc_swz(cA, wm * WTM + i * 32, kk, lane);
     };
     // One K tile.  PAR = kt & 1 is the LDS buffer being multiplied.  On entry the fragments of slice 0 are already
     // in registers.  The barrier sits BEFORE the MFMAs of the last slice: by then every wave has issued all its LDS
@@ -483,11 +486,11 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_dw(const GemmDwArgs a)
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
     bf16x8 fa[2][MI], fb[2][NI];
-    auto read_frags = [&](int slot, int buf, int kk) {
-#pragma unroll
-        for (int i = 0; i < MI; ++i) fa[slot][i] = frag_km_swz<BM>(sA + buf * A_ELEMS, wm * WTM + i * 32, kk, lane);
+    auto read_frags = [&](int slot, int buf, int kk) {      // B first: see the forward kernel
 #pragma unroll
         for (int j = 0; j < NI; ++j) fb[slot][j] = frag_km_swz<BN>(sB + buf * B_ELEMS, wn * WTN + j * 32, kk, lane);
+#pragma unroll
+        for (int i = 0; i < MI; ++i) fa[slot][i] = frag_km_swz<BM>(sA + buf * A_ELEMS, wm * WTM + i * 32, kk, lane);
     };
     auto mfma_slice = [&](int slot) {
 #pragma unroll
