@@ -177,3 +177,34 @@ def qlinear_bwd(X, Wp, s, zp, dY, I, bits, g, want=("dX", "ds")):
     _check(_load().eqo_qlinear_bwd(pX, _ptr(Wp), ps, _ptr(zp), pdY, _ll(T), _ll(I), _ll(O), int(bits), _ll(g),
                                    _ptr(out.get("dX")), _ptr(out.get("ds"))), "qlinear_bwd")
     return out
+
+
+def qlinear_fwd_z(X, Wp, s, z, bits, g):
+    """E2E-QP forward with floating-point (trainable) zero points: What = (w_q - z) * s, z not rounded (Sec. 3.3)."""
+    X, pX = _f32(X); s, ps = _f32(s); z, pz = _f32(z)
+    Wp = np.ascontiguousarray(Wp, np.uint8)
+    T, I = X.shape
+    O = Wp.shape[0]
+    g = _group(I, g)
+    Y = np.empty((T, O), np.float64)
+    _check(_load().eqo_qlinear_fwd_z(pX, _ptr(Wp), ps, pz, _ll(T), _ll(I), _ll(O), int(bits), _ll(g), _ptr(Y)), "qlinear_fwd_z")
+    return Y
+
+
+def qlinear_bwd_z(X, Wp, s, z, dY, I, bits, g, want=("dX", "ds", "dz")):
+    """E2E-QP backward with trainable s and z: dX, ds = group-sum dWhat * (w_q - z), dz = -s * group-sum dWhat."""
+    s, ps = _f32(s); z, pz = _f32(z); dY, pdY = _f32(dY)
+    Wp = np.ascontiguousarray(Wp, np.uint8)
+    O = Wp.shape[0]
+    T = dY.shape[0]
+    g = _group(I, g)
+    pX = None
+    if X is not None:
+        X, pX = _f32(X)
+    out = {}
+    if "dX" in want: out["dX"] = np.empty((T, I), np.float64)
+    if "ds" in want: out["ds"] = np.empty((O, I // g), np.float64)
+    if "dz" in want: out["dz"] = np.empty((O, I // g), np.float64)
+    _check(_load().eqo_qlinear_bwd_z(pX, _ptr(Wp), ps, pz, pdY, _ll(T), _ll(I), _ll(O), int(bits), _ll(g),
+                                     _ptr(out.get("dX")), _ptr(out.get("ds")), _ptr(out.get("dz"))), "qlinear_bwd_z")
+    return out

@@ -448,3 +448,100 @@ int eqo_qlinear_bwd(const float *X, const uint8_t *Wpacked, const float *s, cons
     }
     return fail ? -2 : 0;
 }
+
+/* ---- E2E-QP with trainable zero points (Sec. 3.3; ablation "trainable parameters of E2E-QP") -----------------
+ * When z is trained end to end it leaves its N-bit storage and becomes a floating-point tensor (the ablation's
+ * average bit count rises from N + 16/g (+N/g) to N + 32/g for that reason).  There is no Eq.(1) in this phase,
+ * so z enters Eq.(2) as it is, without rounding:
+ *   What[o,i] = (w_q[o,i] - z[o,j]) * s[o,j],            Y = X * What^T,     dX = dY * What,
+ *   ds[o,j] = sum_{i in j} dWhat[o,i] * (w_q[o,i] - z[o,j]),
+ *   dz[o,j] = sum_{i in j} dWhat[o,i] * (-s[o,j])         (derivative of Eq.(2) with respect to z),
+ * with dWhat = dY^T X. */
+static void dequant_packed_row_fz(const uint8_t *wr, const float *zrow, const float *srow, i64 I, i64 g,
+                                  int bits, double *out)
+{
+    for (i64 i = 0; i < I; ++i) {
+        const i64 j = i / g;
+        out[i] = ((double)get_bits(wr, i, bits) - (double)zrow[j]) * (double)srow[j];
+    }
+}
+
+int eqo_qlinear_fwd_z(const float *X, const uint8_t *Wpacked, const float *s, const float *z,
+                      i64 T, i64 I, i64 O, int bits, i64 g, double *Y)
+{
+    if (!Wpacked || !s || !z || bad_shape(I, O, bits, g) || I % 32 != 0 || T < 0) return -1;
+    if (T == 0) return 0;
+    if (!X || !Y) return -1;
+    const i64 G = I / g;
+    const i64 wrb = eqo_packed_w_row_bytes(I, bits);
+    int fail = 0;
+#pragma omp parallel
+    {
+        double *wh = (double *)malloc((size_t)I * sizeof(double));
+        if (!wh) {
+#pragma omp atomic write
+            fail = 1;
+        }
+#pragma omp for schedule(static)
+        for (i64 o = 0; o < O; ++o) {
+            if (!wh) continue;
+            dequant_packed_row_fz(Wpacked + o * wrb, z + o * G, s + o * G, I, g, bits, wh);
+            for (i64 t = 0; t < T; ++t) {
+                const float *x = X + t * I;
+                double acc = 0.0;
+                for (i64 i = 0; i < I; ++i) acc += (double)x[i] * wh[i];
+                Y[t * O + o] = acc;
+            }
+        }
+        free(wh);
+    }
+    return fail ? -2 : 0;
+}
+
+int eqo_qlinear_bwd_z(const float *X, const uint8_t *Wpacked, const float *s, const float *z,
+                      const float *dY, i64 T, i64 I, i64 O, int bits, i64 g, double *dX, double *ds, double *dz)
+{
+    if (!Wpacked || !s || !z || bad_shape(I, O, bits, g) || I % 32 != 0 || T < 0) return -1;
+    if (T > 0 && !dY) return -1;
+    if ((ds || dz) && T > 0 && !X) return -1;
+    const i64 G = I / g;
+    const i64 wrb = eqo_packed_w_row_bytes(I, bits);
+
+    if (dX && T > 0) {
+        double *What = (double *)malloc((size_t)O * (size_t)I * sizeof(double));
+        if (!What) return -2;
+#pragma omp parallel for schedule(static)
+        for (i64 o = 0; o < O; ++o)
+            dequant_packed_row_fz(Wpacked + o * wrb, z + o * G, s + o * G, I, g, bits, What + o * I);
+        dx_from_what(dY, What, T, I, O, dX);
+        free(What);
+    }
+    if (!ds && !dz) return 0;
+
+    int fail = 0;
+#pragma omp parallel
+    {
+        double *acc = (double *)malloc((size_t)I * sizeof(double));
+        if (!acc) {
+#pragma omp atomic write
+            fail = 1;
+        }
+#pragma omp for schedule(static)
+        for (i64 o = 0; o < O; ++o) {
+            if (!acc) continue;
+            dwhat_row(X, dY, T, I, O, o, acc);
+            for (i64 j = 0; j < G; ++j) {
+                const double zf = (double)z[o * G + j], sf = (double)s[o * G + j];
+                double gs = 0.0, gz = 0.0;
+                for (i64 i = j * g; i < (j + 1) * g; ++i) {
+                    gs += acc[i] * ((double)get_bits(Wpacked + o * wrb, i, bits) - zf);
+                    gz += acc[i] * (-sf);
+                }
+                if (ds) ds[o * G + j] = gs;
+                if (dz) dz[o * G + j] = gz;
+            }
+        }
+        free(acc);
+    }
+    return fail ? -2 : 0;
+}

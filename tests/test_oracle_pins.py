@@ -396,6 +396,75 @@ def test_qlinear_ds_is_the_derivative_of_a_map_linear_in_s():
     np.testing.assert_allclose(out["dX"], oracle.fq_linear_bwd(None, W, s, z, dY, 3, 32, want=("dX",))["dX"], rtol=1e-13, atol=1e-15)
 
 
+# ---------------------------------------------------------------- E2E-QP with trainable zero points (Sec. 3.3)
+
+def test_trainable_z_with_integral_z_equals_the_packed_z_path():
+    X, W, s, z, dY, Wp, zp = _packed_case(63, bits=3)
+    codes, zc = oracle.unpack(Wp, zp, 64, 3, 32)
+    zf = zc.astype(np.float32)
+    np.testing.assert_allclose(oracle.qlinear_fwd_z(X, Wp, s, zf, 3, 32), oracle.qlinear_fwd(X, Wp, s, zp, 3, 32), rtol=1e-14, atol=0)
+    a, b = oracle.qlinear_bwd_z(X, Wp, s, zf, dY, 64, 3, 32), oracle.qlinear_bwd(X, Wp, s, zp, dY, 64, 3, 32)
+    np.testing.assert_allclose(a["dX"], b["dX"], rtol=1e-14, atol=0)
+    np.testing.assert_allclose(a["ds"], b["ds"], rtol=1e-14, atol=0)
+
+
+def test_trainable_z_is_not_rounded_and_matches_the_textbook_form():
+    X, W, s, z, dY, Wp, zp = _packed_case(64, bits=2)
+    codes, _ = oracle.unpack(Wp, zp, 64, 2, 32)
+    zf = (z + rng(5).uniform(-0.45, 0.45, z.shape)).astype(np.float32)          # deliberately fractional
+    What = (codes - np.repeat(zf.astype(np.float64), 32, 1)) * np.repeat(s.astype(np.float64), 32, 1)
+    np.testing.assert_allclose(oracle.qlinear_fwd_z(X, Wp, s, zf, 2, 32), X.astype(np.float64) @ What.T, rtol=1e-12, atol=1e-14)
+    out = oracle.qlinear_bwd_z(X, Wp, s, zf, dY, 64, 2, 32)
+    np.testing.assert_allclose(out["dX"], dY.astype(np.float64) @ What, rtol=1e-12, atol=1e-14)
+    dWhat = dY.astype(np.float64).T @ X.astype(np.float64)
+    G = 64 // 32
+    ds = (dWhat * (codes - np.repeat(zf.astype(np.float64), 32, 1))).reshape(-1, G, 32).sum(-1)
+    dz = (dWhat * -np.repeat(s.astype(np.float64), 32, 1)).reshape(-1, G, 32).sum(-1)
+    np.testing.assert_allclose(out["ds"], ds, rtol=1e-11, atol=1e-12)
+    np.testing.assert_allclose(out["dz"], dz, rtol=1e-11, atol=1e-12)
+
+
+def test_trainable_z_gradients_are_true_derivatives():
+    # Y is linear in z and in s separately, so central differences of L = sum(dY * Y) are exact up to rounding
+    X, W, s, z, dY, Wp, zp = _packed_case(65, bits=3)
+    zf = (z + rng(6).uniform(-0.3, 0.3, z.shape)).astype(np.float32)
+    out = oracle.qlinear_bwd_z(X, Wp, s, zf, dY, 64, 3, 32)
+    L = lambda sv, zv: float(np.sum(dY.astype(np.float64) * oracle.qlinear_fwd_z(X, Wp, sv, zv, 3, 32)))
+    h = np.float32(2.0 ** -8)
+    for (o, j) in [(0, 0), (1, 1), (4, 0)]:
+        zp_, zm_ = zf.copy(), zf.copy(); zp_[o, j] += h; zm_[o, j] -= h
+        fd = (L(s, zp_) - L(s, zm_)) / float(zp_[o, j] - zm_[o, j])
+        assert abs(fd - out["dz"][o, j]) < 1e-8 * max(1.0, abs(fd))
+        sp_, sm_ = s.copy(), s.copy(); sp_[o, j] += np.float32(2.0 ** -12); sm_[o, j] -= np.float32(2.0 ** -12)
+        fd = (L(sp_, zf) - L(sm_, zf)) / float(sp_[o, j] - sm_[o, j])
+        assert abs(fd - out["ds"][o, j]) < 1e-8 * max(1.0, abs(fd))
+
+
+def test_trainable_z_group_and_row_indexing_with_one_hot_inputs():
+    # one token, one active input column i0, one active output o0: dWhat = e_{o0} e_{i0}^T, so only group i0/g of
+    # row o0 gets a gradient: dz = -s[o0, j0], ds = code[o0, i0] - z[o0, j0]
+    X, W, s, z, dY, Wp, zp = _packed_case(66, bits=2)
+    codes, _ = oracle.unpack(Wp, zp, 64, 2, 32)
+    zf = (z + 0.25).astype(np.float32)
+    o0, i0 = 3, 45
+    x = np.zeros((1, 64), np.float32); x[0, i0] = 1
+    dy = np.zeros((1, W.shape[0]), np.float32); dy[0, o0] = 1
+    out = oracle.qlinear_bwd_z(x, Wp, s, zf, dy, 64, 2, 32)
+    exp_dz = np.zeros_like(out["dz"]); exp_dz[o0, i0 // 32] = -float(s[o0, i0 // 32])
+    exp_ds = np.zeros_like(out["ds"]); exp_ds[o0, i0 // 32] = float(codes[o0, i0]) - float(zf[o0, i0 // 32])
+    np.testing.assert_allclose(out["dz"], exp_dz, rtol=0, atol=1e-15)
+    np.testing.assert_allclose(out["ds"], exp_ds, rtol=1e-15, atol=1e-15)
+
+
+def test_avg_bits_of_the_trainable_parameter_ablation():
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "e2e_trainable_param_avg_bits.txt")) if l.strip() and not l.startswith("#")]
+    assert len(rows) == 3
+    for trained, bits, g, printed in rows:
+        bits, g = int(bits), int(g)
+        z_bits = bits if trained == "s" else 16          # a trained zero point is kept in FP16
+        assert round(bits + (16 + z_bits) / g, 2) == float(printed)
+
+
 def test_empty_token_batch_gives_zero_gradients():
     X, W, s, z, dY = _case(71)
     out = oracle.fq_linear_bwd(X[:0], W, s, z, dY[:0], 2, 32)
