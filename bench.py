@@ -9,8 +9,8 @@ device before the timed region; outputs and workspaces are pre-allocated.
 Prints ONE JSON line.  Besides the contract fields it carries
   roofline      the dominant kernel of the step against the bf16 MFMA peak (HIP events inside the library),
   cpu_baseline  the fp64 CPU oracle timed on a bounded sample of the same workload,
-  rows          the remaining rows of the hot path measured in the same run: E2E-QP fwd+bwd (4096 tokens),
-                eqat_pack and eqat_init_minmax (GB/s against the HBM peak).
+  rows          the remaining rows of the hot path measured in the same run: E2E-QP fwd+bwd (4096 tokens; step sizes
+                trained, and step sizes + zero points trained), eqat_pack and eqat_init_minmax (GB/s against the HBM peak).
 """
 from __future__ import annotations
 
@@ -190,6 +190,18 @@ def measure_other_rows(torch, eq, layers, bits, g, adt, dev, args):
     rows["e2e_qp_fwd_bwd"] = {"tokens": T2, "ms_per_step": round(dt * 1e3, 4), "tflops": round(fl / dt / 1e12, 2),
                               "pct_of_bf16_mfma_peak": round(100 * fl / dt / 1e12 / PEAK_BF16_TFLOPS, 2),
                               "tokens_per_s_per_layer": round(T2 / dt, 1)}
+    # the same step with step sizes AND zero points trained (zero points kept in floating point, dz from the same epilogue)
+    zf = [(L["z"].clamp(0, 2 ** bits - 1) + 0.25).contiguous() for L in layers]
+    outz = [{"dX": P["out"]["dX"], "ds": P["out"]["ds"], "dz": torch.empty_like(L["s"])} for L, P in zip(layers, packed)]
+
+    def e2e_sz_step():
+        for L, P, z2, o2 in zip(layers, packed, zf, outz):
+            eq.eqat_qlinear_fwd_z(P["X"], P["Wp"], L["s"], z2, bits, g, Y=P["Y"], ws=P["ws_f"])
+            eq.eqat_qlinear_bwd_z(P["X"], P["Wp"], L["s"], z2, P["dY"], L["I"], bits, g, out=o2, ws=P["ws_b"])
+
+    dt = timed(e2e_sz_step, args.steps)
+    rows["e2e_qp_fwd_bwd_trained_s_z"] = {"tokens": T2, "ms_per_step": round(dt * 1e3, 4), "tflops": round(fl / dt / 1e12, 2),
+                                          "pct_of_bf16_mfma_peak": round(100 * fl / dt / 1e12 / PEAK_BF16_TFLOPS, 2)}
     wbytes = 2 if adt == torch.bfloat16 else 4
 
     def pack_all():

@@ -141,6 +141,25 @@ eqat_status eqat_qlinear_bwd(const eqat_desc *d, const void *X, const uint8_t *W
                              void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * E2E-QP with trained zero points (Sec. 3.3 and the ablation on the trainable parameters of E2E-QP: training z
+ * promotes it from N bits to a floating-point tensor).  There is no Eq.(1) in this phase, so z enters Eq.(2) as it
+ * is, WITHOUT rounding:  What = (w_q - z) * s,  Y = X * What^T.
+ *   z [O,G] fp32 (device), any finite value.  Everything else as eqat_qlinear_fwd; workspace of EQAT_OP_Q_FWD.
+ */
+eqat_status eqat_qlinear_fwd_z(const eqat_desc *d, const void *X, const uint8_t *Wpacked, const float *s,
+                               const float *z, void *Y, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Backward of the above:  dX = dY * What,
+ *   ds[o,j] = sum over group of (dY^T X)[o,i] * (w_q[o,i] - z[o,j]),
+ *   dz[o,j] = -s[o,j] * sum over group of (dY^T X)[o,i]            (derivative of Eq.(2) with respect to z).
+ * dX, ds, dz may each be NULL (skipped).  Workspace of EQAT_OP_Q_BWD.  d->w_dtype is ignored.
+ */
+eqat_status eqat_qlinear_bwd_z(const eqat_desc *d, const void *X, const uint8_t *Wpacked, const float *s,
+                               const float *z, const void *dY, void *dX, float *ds, float *dz,
+                               void *ws, size_t ws_bytes, void *stream);
+
+/*
  * Optional per-kernel timing (measurement aid, not part of the paper's method).
  * Between eqat_profile_start() and eqat_profile_stop() every kernel launch of the
  * library is bracketed by a pair of HIP events recorded on the caller's stream.

@@ -24,7 +24,8 @@ STATUS_NAMES = ["EQAT_OK", "EQAT_ERR_NULL", "EQAT_ERR_SHAPE", "EQAT_ERR_BITS", "
 
 EXPORTS = ["eqat_status_string", "eqat_validate_desc", "eqat_packed_w_bytes", "eqat_packed_z_bytes",
            "eqat_workspace_bytes", "eqat_init_minmax", "eqat_fq_linear_fwd", "eqat_fq_linear_bwd", "eqat_pack",
-           "eqat_unpack", "eqat_qlinear_fwd", "eqat_qlinear_bwd", "eqat_profile_kernels", "eqat_profile_kernel_name",
+           "eqat_unpack", "eqat_qlinear_fwd", "eqat_qlinear_bwd", "eqat_qlinear_fwd_z", "eqat_qlinear_bwd_z",
+           "eqat_profile_kernels", "eqat_profile_kernel_name",
            "eqat_profile_start", "eqat_profile_stop"]
 
 
@@ -66,6 +67,8 @@ def lib():
         L.eqat_unpack.argtypes = [dp, vp, vp, vp, vp, vp]
         L.eqat_qlinear_fwd.argtypes = [dp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.eqat_qlinear_bwd.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.eqat_qlinear_fwd_z.argtypes = [dp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.eqat_qlinear_bwd_z.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.eqat_profile_kernel_name.restype = ctypes.c_char_p
         L.eqat_profile_kernel_name.argtypes = [ctypes.c_int]
         L.eqat_profile_stop.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64), ctypes.c_int]
@@ -195,6 +198,35 @@ def eqat_qlinear_bwd(X, Wpacked, s, zpacked, dY, in_features, bits, group, want=
     ws = workspace(d, OP_Q_BWD, dY.device) if ws is None else ws
     _check("eqat_qlinear_bwd", lib().eqat_qlinear_bwd(ctypes.byref(d), _p(X), _p(Wpacked), _p(s), _p(zpacked), _p(dY),
                                                       _p(out.get("dX")), _p(out.get("ds")), _p(ws), ws.numel(), _stream()))
+    return out
+
+
+def eqat_qlinear_fwd_z(X, Wpacked, s, z, bits, group, Y=None, ws=None):
+    """E2E-QP forward with floating-point (trained) zero points z [O,G]."""
+    T, I = X.shape
+    O = Wpacked.shape[0]
+    d = make_desc(T, I, O, bits, group, _dt(X), BF16)
+    Y = torch.empty((T, O), dtype=X.dtype, device=X.device) if Y is None else Y
+    ws = workspace(d, OP_Q_FWD, X.device) if ws is None else ws
+    _check("eqat_qlinear_fwd_z", lib().eqat_qlinear_fwd_z(ctypes.byref(d), _p(X), _p(Wpacked), _p(s), _p(z), _p(Y),
+                                                          _p(ws), ws.numel(), _stream()))
+    return Y
+
+
+def eqat_qlinear_bwd_z(X, Wpacked, s, z, dY, in_features, bits, group, want=("dX", "ds", "dz"), out=None, ws=None):
+    """E2E-QP backward with trained step sizes and zero points: dX, ds, dz."""
+    T, O = dY.shape
+    I = int(in_features)
+    d = make_desc(T, I, O, bits, group, _dt(dY), BF16)
+    out = {} if out is None else out
+    G = _groups(I, group)
+    if "dX" in want and "dX" not in out: out["dX"] = torch.empty((T, I), dtype=dY.dtype, device=dY.device)
+    if "ds" in want and "ds" not in out: out["ds"] = torch.empty((O, G), dtype=torch.float32, device=dY.device)
+    if "dz" in want and "dz" not in out: out["dz"] = torch.empty((O, G), dtype=torch.float32, device=dY.device)
+    ws = workspace(d, OP_Q_BWD, dY.device) if ws is None else ws
+    _check("eqat_qlinear_bwd_z", lib().eqat_qlinear_bwd_z(ctypes.byref(d), _p(X), _p(Wpacked), _p(s), _p(z), _p(dY),
+                                                          _p(out.get("dX")), _p(out.get("ds")), _p(out.get("dz")),
+                                                          _p(ws), ws.numel(), _stream()))
     return out
 
 

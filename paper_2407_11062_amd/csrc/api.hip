@@ -264,54 +264,93 @@ eqat_status eqat_fq_linear_bwd(const eqat_desc *d, const void *X, const void *W,
     return launch_status();
 }
 
-eqat_status eqat_qlinear_fwd(const eqat_desc *d, const void *X, const uint8_t *Wpacked, const float *s,
-                             const uint8_t *zpacked, void *Y, void *ws, size_t ws_bytes, void *stream)
+// E2E-QP forward / backward; the zero points come packed at N bits (zpacked) or as floats (zfloat), one of the two.
+static eqat_status qlinear_fwd_any(const eqat_desc *d, const void *X, const uint8_t *Wpacked, const float *s,
+                                   const uint8_t *zpacked, const float *zfloat, void *Y, void *ws, size_t ws_bytes,
+                                   void *stream)
 {
     Problem p;
     if (eqat_status e = check_desc(d, true, &p)) return e;
-    EQAT_REQUIRE(Wpacked); EQAT_REQUIRE(s); EQAT_REQUIRE(zpacked);
+    const void *zany = zpacked != nullptr ? (const void *)zpacked : (const void *)zfloat;   // NULL if the caller's was
+    EQAT_REQUIRE(Wpacked); EQAT_REQUIRE(s); EQAT_REQUIRE(zany);
     if (p.T > 0) { EQAT_REQUIRE(X); EQAT_REQUIRE(Y); }
-    EQAT_ALIGNED(X); EQAT_ALIGNED(Wpacked); EQAT_ALIGNED(s); EQAT_ALIGNED(zpacked); EQAT_ALIGNED(Y);
+    EQAT_ALIGNED(X); EQAT_ALIGNED(Wpacked); EQAT_ALIGNED(s); EQAT_ALIGNED(zany); EQAT_ALIGNED(Y);
     const WsLayout l = ws_layout(p, EQAT_OP_Q_FWD);
     if (eqat_status e = check_ws(l, ws, ws_bytes)) return e;
     if (p.T == 0) return EQAT_OK;
     hipStream_t st = (hipStream_t)stream;
     char *w8 = (char *)ws;
-    { ProfScope ps(eqat::PK_UNPACK_SZ, st); eqat::launch_unpack_sz(p, s, zpacked, w8 + l.sz, st); }
+    {
+        ProfScope ps(eqat::PK_UNPACK_SZ, st);
+        if (zpacked != nullptr) eqat::launch_unpack_sz(p, s, zpacked, w8 + l.sz, st);
+        else eqat::launch_pair_sz(p, s, zfloat, w8 + l.sz, st);
+    }
     if (p.act_bf16) { ProfScope ps(eqat::PK_REPACK, st); eqat::launch_repack(p, Wpacked, w8 + l.codes, st); }
     if (p.act_bf16) { ProfScope ps(eqat::PK_GEMM_FWD, st); eqat::launch_mfma_fwd(p, X, w8 + l.codes, w8 + l.sz, Y, st); }
     else { ProfScope ps(eqat::PK_F32, st); eqat::launch_f32_fwd(p, true, X, Wpacked, s, w8 + l.sz, Y, st); }
     return launch_status();
 }
 
-eqat_status eqat_qlinear_bwd(const eqat_desc *d, const void *X, const uint8_t *Wpacked, const float *s,
-                             const uint8_t *zpacked, const void *dY, void *dX, float *ds, void *ws, size_t ws_bytes,
-                             void *stream)
+static eqat_status qlinear_bwd_any(const eqat_desc *d, const void *X, const uint8_t *Wpacked, const float *s,
+                                   const uint8_t *zpacked, const float *zfloat, const void *dY, void *dX, float *ds,
+                                   float *dz, void *ws, size_t ws_bytes, void *stream)
 {
     Problem p;
     if (eqat_status e = check_desc(d, true, &p)) return e;
-    EQAT_REQUIRE(Wpacked); EQAT_REQUIRE(s); EQAT_REQUIRE(zpacked);
-    if (p.T > 0) { EQAT_REQUIRE(dY); if (ds != nullptr) EQAT_REQUIRE(X); }
-    EQAT_ALIGNED(X); EQAT_ALIGNED(Wpacked); EQAT_ALIGNED(s); EQAT_ALIGNED(zpacked); EQAT_ALIGNED(dY);
-    EQAT_ALIGNED(dX); EQAT_ALIGNED(ds);
+    const void *zany = zpacked != nullptr ? (const void *)zpacked : (const void *)zfloat;
+    EQAT_REQUIRE(Wpacked); EQAT_REQUIRE(s); EQAT_REQUIRE(zany);
+    const bool want_g = (ds != nullptr || dz != nullptr);
+    if (p.T > 0) { EQAT_REQUIRE(dY); if (want_g) EQAT_REQUIRE(X); }
+    EQAT_ALIGNED(X); EQAT_ALIGNED(Wpacked); EQAT_ALIGNED(s); EQAT_ALIGNED(zany); EQAT_ALIGNED(dY);
+    EQAT_ALIGNED(dX); EQAT_ALIGNED(ds); EQAT_ALIGNED(dz);
     const WsLayout l = ws_layout(p, EQAT_OP_Q_BWD);
     if (eqat_status e = check_ws(l, ws, ws_bytes)) return e;
-    if (dX == nullptr && ds == nullptr) return EQAT_OK;
+    if (dX == nullptr && !want_g) return EQAT_OK;
     hipStream_t st = (hipStream_t)stream;
     char *w8 = (char *)ws;
-    { ProfScope ps(eqat::PK_UNPACK_SZ, st); eqat::launch_unpack_sz(p, s, zpacked, w8 + l.sz, st); }
+    {
+        ProfScope ps(eqat::PK_UNPACK_SZ, st);
+        if (zpacked != nullptr) eqat::launch_unpack_sz(p, s, zpacked, w8 + l.sz, st);
+        else eqat::launch_pair_sz(p, s, zfloat, w8 + l.sz, st);
+    }
     if (p.act_bf16) {
         { ProfScope ps(eqat::PK_REPACK, st); eqat::launch_repack(p, Wpacked, w8 + l.codes, st); }
         if (dX != nullptr) { ProfScope ps(eqat::PK_GEMM_DX, st); eqat::launch_mfma_dx(p, dY, w8 + l.codes, w8 + l.sz, dX, st); }
-        if (ds != nullptr)
-            eqat::launch_mfma_dw(p, false, X, dY, nullptr, w8 + l.codes, nullptr, w8 + l.sz, s, nullptr, ds, nullptr,
+        if (want_g)
+            eqat::launch_mfma_dw(p, false, X, dY, nullptr, w8 + l.codes, nullptr, w8 + l.sz, s, nullptr, ds, dz,
                                  (float *)(w8 + l.part), st);
     } else {
         ProfScope ps(eqat::PK_F32, st);
         if (dX != nullptr && p.T > 0) eqat::launch_f32_dx(p, true, dY, Wpacked, s, w8 + l.sz, dX, st);
-        if (ds != nullptr) eqat::launch_f32_dw(p, false, X, dY, Wpacked, s, w8 + l.sz, (float *)(w8 + l.dwhat), nullptr, ds, nullptr, st);
+        if (want_g) eqat::launch_f32_dw(p, false, X, dY, Wpacked, s, w8 + l.sz, (float *)(w8 + l.dwhat), nullptr, ds, dz, st);
     }
     return launch_status();
+}
+
+eqat_status eqat_qlinear_fwd(const eqat_desc *d, const void *X, const uint8_t *Wpacked, const float *s,
+                             const uint8_t *zpacked, void *Y, void *ws, size_t ws_bytes, void *stream)
+{
+    return qlinear_fwd_any(d, X, Wpacked, s, zpacked, nullptr, Y, ws, ws_bytes, stream);
+}
+
+eqat_status eqat_qlinear_bwd(const eqat_desc *d, const void *X, const uint8_t *Wpacked, const float *s,
+                             const uint8_t *zpacked, const void *dY, void *dX, float *ds, void *ws, size_t ws_bytes,
+                             void *stream)
+{
+    return qlinear_bwd_any(d, X, Wpacked, s, zpacked, nullptr, dY, dX, ds, nullptr, ws, ws_bytes, stream);
+}
+
+eqat_status eqat_qlinear_fwd_z(const eqat_desc *d, const void *X, const uint8_t *Wpacked, const float *s,
+                               const float *z, void *Y, void *ws, size_t ws_bytes, void *stream)
+{
+    return qlinear_fwd_any(d, X, Wpacked, s, nullptr, z, Y, ws, ws_bytes, stream);
+}
+
+eqat_status eqat_qlinear_bwd_z(const eqat_desc *d, const void *X, const uint8_t *Wpacked, const float *s,
+                               const float *z, const void *dY, void *dX, float *ds, float *dz, void *ws,
+                               size_t ws_bytes, void *stream)
+{
+    return qlinear_bwd_any(d, X, Wpacked, s, nullptr, z, dY, dX, ds, dz, ws, ws_bytes, stream);
 }
 
 }  // extern "C"

@@ -110,19 +110,21 @@ __global__ __launch_bounds__(256) void k_f32_epilogue_block_ap(const float *__re
 template <int BITS>
 __global__ __launch_bounds__(256) void k_f32_epilogue_e2e(const float *__restrict__ dwhat, const uint32_t *__restrict__ codes,
                                                           const floatx2 *__restrict__ sz, float *__restrict__ ds,
-                                                          int O, int I, int g, int G)
+                                                          float *__restrict__ dz, int O, int I, int g, int G)
 {
     const int t = blockIdx.x * 256 + threadIdx.x;
     if (t >= O * G) return;
     const int o = t / G, j = t - o * G;
     const float zq = sz[t][1];
-    float gs = 0.0f;
+    float gs = 0.0f, gz = 0.0f;
     for (int i = j * g; i < (j + 1) * g; ++i) {
         const size_t e = (size_t)o * I + i;
         const uint32_t *seg = codes + (e & ~(size_t)31) / 32 * BITS;
         gs = __builtin_fmaf(dwhat[e], (float)code_at_rt<BITS>(seg, i & 31) - zq, gs);
+        gz += dwhat[e];
     }
-    ds[t] = gs;
+    if (ds != nullptr) ds[t] = gs;
+    if (dz != nullptr) dz[t] = -sz[t][0] * gz;
 }
 
 // ---- host ------------------------------------------------------------------------------------------
@@ -179,9 +181,9 @@ void launch_f32_dw(const Problem &p, bool block_ap, const void *X, const void *d
         else k_f32_epilogue_block_ap<float><<<grid, block, 0, st>>>(dwhat, (const float *)Wc, s, (const float *)zsz, (float *)dW, ds, dz, O, I, g, G, qmax);
     } else {
         const uint32_t *c = (const uint32_t *)Wc; const floatx2 *sz = (const floatx2 *)zsz;
-        if (p.bits == 2) k_f32_epilogue_e2e<2><<<grid, block, 0, st>>>(dwhat, c, sz, ds, O, I, g, G);
-        else if (p.bits == 3) k_f32_epilogue_e2e<3><<<grid, block, 0, st>>>(dwhat, c, sz, ds, O, I, g, G);
-        else k_f32_epilogue_e2e<4><<<grid, block, 0, st>>>(dwhat, c, sz, ds, O, I, g, G);
+        if (p.bits == 2) k_f32_epilogue_e2e<2><<<grid, block, 0, st>>>(dwhat, c, sz, ds, dz, O, I, g, G);
+        else if (p.bits == 3) k_f32_epilogue_e2e<3><<<grid, block, 0, st>>>(dwhat, c, sz, ds, dz, O, I, g, G);
+        else k_f32_epilogue_e2e<4><<<grid, block, 0, st>>>(dwhat, c, sz, ds, dz, O, I, g, G);
     }
 }
 

@@ -373,7 +373,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_q(const GemmQArgs a)
 // and, on the accumulators, for every weight (o, i):
 //   Block-AP:  clamped = bit of the clamp plane; q = code; r = q - zbar
 //              cs = clamped ? r : r - w/s ;  dW = clamped ? 0 : D ;  ds += D*cs ;  dz += clamped ? -s*D : 0
-//   E2E-QP  :  ds += D * (q - z)
+//   E2E-QP  :  ds += D * (q - z) ;  dz += -s*D  (dz only when asked for: zero points trained end to end)
 // M <-> i puts the 32 columns of a group segment into the registers of one lane pair, so the group sums
 // need one cross-lane exchange per 32x32 block.
 // ======================================================================================================
@@ -592,17 +592,22 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_dw(const GemmDwArgs a)
 #undef EQAT_QUAD
 #undef EQAT_ELEM
             } else {
-#define EQAT_ELEM(Q, B) sum_s = __builtin_fmaf(acc[i][j][(Q) * 4 + (B)], byte_to_float(cq[Q], B) - zb, sum_s);
+#define EQAT_ELEM(Q, B)                                                                                   \
+    {                                                                                                     \
+        const float d = acc[i][j][(Q) * 4 + (B)];                                                         \
+        sum_s = __builtin_fmaf(d, byte_to_float(cq[Q], B) - zb, sum_s);                                   \
+        sum_z += d;                                                                                       \
+    }
 #define EQAT_QUAD(Q) EQAT_ELEM(Q, 0) EQAT_ELEM(Q, 1) EQAT_ELEM(Q, 2) EQAT_ELEM(Q, 3)
                 EQAT_QUAD(0) EQAT_QUAD(1) EQAT_QUAD(2) EQAT_QUAD(3)
 #undef EQAT_QUAD
 #undef EQAT_ELEM
             }
             sum_s += __shfl_xor(sum_s, 32);
-            if (BLOCK_AP) sum_z += __shfl_xor(sum_z, 32);
+            sum_z += __shfl_xor(sum_z, 32);
             if (h == 0) {
                 p_ds[(wm * MI + i) * BN + ol] = sum_s;
-                if (BLOCK_AP) p_dz[(wm * MI + i) * BN + ol] = sum_z;
+                p_dz[(wm * MI + i) * BN + ol] = sum_z;
             }
             __builtin_amdgcn_sched_barrier(0);     // one 32x32 block at a time
         }
@@ -617,11 +622,11 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_dw(const GemmDwArgs a)
             float vs = 0.0f, vz = 0.0f;
             for (int k = 0; k < bpg; ++k) {
                 vs += p_ds[(gi * bpg + k) * BN + ol];
-                if (BLOCK_AP) vz += p_dz[(gi * bpg + k) * BN + ol];
+                vz += p_dz[(gi * bpg + k) * BN + ol];
             }
             const size_t gidx = (size_t)o * a.G + i0 / a.g;
             if (a.ds != nullptr) a.ds[gidx] = vs;
-            if (BLOCK_AP && a.dz != nullptr) a.dz[gidx] = -a.sz[gidx][0] * vz;
+            if (a.dz != nullptr) a.dz[gidx] = -a.sz[gidx][0] * vz;
         }
     } else {
         const int nb32 = a.I >> 5;
@@ -629,7 +634,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_dw(const GemmDwArgs a)
             const int ol = e % BN, blk = e / BN, o = n0 + ol, i0 = m0 + blk * 32;
             if (o >= a.O || i0 >= a.I) continue;
             a.part_ds[(size_t)o * nb32 + (i0 >> 5)] = p_ds[blk * BN + ol];
-            if (BLOCK_AP) a.part_dz[(size_t)o * nb32 + (i0 >> 5)] = p_dz[blk * BN + ol];
+            if (a.dz != nullptr) a.part_dz[(size_t)o * nb32 + (i0 >> 5)] = p_dz[blk * BN + ol];
         }
     }
 }
@@ -760,7 +765,7 @@ void launch_mfma_dw(const Problem &p, bool block_ap, const void *X, const void *
         ProfScope ps(PK_REDUCE, st);
         const uint32_t n_per = (uint32_t)(p.g / 32);
         if (ds != nullptr) launch_reduce_partials(a.part_ds, ds, s, (size_t)p.O * p.G, n_per, false, st);
-        if (block_ap && dz != nullptr) launch_reduce_partials(a.part_dz, dz, s, (size_t)p.O * p.G, n_per, true, st);
+        if (dz != nullptr) launch_reduce_partials(a.part_dz, dz, s, (size_t)p.O * p.G, n_per, true, st);
     }
 }
 

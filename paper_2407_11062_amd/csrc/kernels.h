@@ -22,6 +22,8 @@ void launch_quantize(const Problem &p, const void *W, const float *s, const floa
 void launch_repack(const Problem &p, const void *packed, void *work, hipStream_t st);
 inline size_t work_code_bytes(const Problem &p) { return (size_t)p.O * p.I / (p.bits == 2 ? 4 : 2); }
 void launch_unpack_sz(const Problem &p, const float *s, const void *zpacked, void *sz, hipStream_t st);
+// (s, z) pairs from two float arrays (zero points kept in floating point)
+void launch_pair_sz(const Problem &p, const float *s, const float *z, void *sz, hipStream_t st);
 void launch_unpack(const Problem &p, const void *Wpacked, const void *zpacked, int32_t *codes, int32_t *zcodes, hipStream_t st);
 void launch_init_minmax(const Problem &p, const void *W, float *s, float *z, hipStream_t st);
 void launch_reduce_partials(const float *part, float *out, const float *s, size_t n_out, uint32_t n_per, bool scale_by_s,
@@ -35,7 +37,7 @@ void launch_mfma_fwd(const Problem &p, const void *X, const void *codes, const v
 void launch_mfma_dx(const Problem &p, const void *dY, const void *codes, const void *sz, void *dX, hipStream_t st);
 // dWhat = dY^T X fused with the per-element / per-group epilogue.
 //   block_ap: needs W, clampbits; writes dW (W's dtype, may be NULL), ds, dz (may be NULL).
-//   e2e_qp  : W = clampbits = dW = dz = NULL; writes ds.
+//   e2e_qp  : W = clampbits = dW = NULL; writes ds and, if not NULL, dz = -s * group-sum dWhat.
 // `part` is scratch for [2][O, I/32] floats, used only when a group is wider than one tile (see dw_needs_partials).
 void launch_mfma_dw(const Problem &p, bool block_ap, const void *X, const void *dY, const void *W, const void *codes,
                     const void *clampbits, const void *sz, const float *s, void *dW, float *ds, float *dz, float *part,

@@ -224,6 +224,15 @@ __global__ __launch_bounds__(256) void k_unpack_sz(const float *__restrict__ s, 
 }
 
 // Test aid: codes [O,I] int32 from the packed stream (one thread per 32-code segment), zero points [O,G].
+__global__ __launch_bounds__(256) void k_pair_sz(const float *__restrict__ s, const float *__restrict__ z,
+                                                 floatx2 *__restrict__ sz, uint32_t n)
+{
+    const uint32_t t = blockIdx.x * 256u + threadIdx.x;
+    if (t >= n) return;
+    floatx2 o; o[0] = s[t]; o[1] = z[t];
+    sz[t] = o;
+}
+
 template <int BITS>
 __global__ __launch_bounds__(256) void k_unpack_codes(const uint32_t *__restrict__ packed, int32_t *__restrict__ out,
                                                       uint32_t n_segs)
@@ -392,6 +401,12 @@ void launch_unpack_sz(const Problem &p, const float *s, const void *zpacked, voi
     if (p.bits == 2) k_unpack_sz<2><<<grid, block, 0, st>>>(s, (const uint32_t *)zpacked, (floatx2 *)sz, (uint32_t)p.O, (uint32_t)p.G, row_words);
     else if (p.bits == 3) k_unpack_sz<3><<<grid, block, 0, st>>>(s, (const uint32_t *)zpacked, (floatx2 *)sz, (uint32_t)p.O, (uint32_t)p.G, row_words);
     else k_unpack_sz<4><<<grid, block, 0, st>>>(s, (const uint32_t *)zpacked, (floatx2 *)sz, (uint32_t)p.O, (uint32_t)p.G, row_words);
+}
+
+void launch_pair_sz(const Problem &p, const float *s, const float *z, void *sz, hipStream_t st)
+{
+    const size_t n = (size_t)p.O * p.G;
+    k_pair_sz<<<dim3(blocks_for(n)), dim3(256), 0, st>>>(s, z, (floatx2 *)sz, (uint32_t)n);
 }
 
 void launch_unpack(const Problem &p, const void *Wpacked, const void *zpacked, int32_t *codes, int32_t *zcodes, hipStream_t st)

@@ -211,3 +211,54 @@ def test_e2e_qp_bf16(tag, T, I, O, bits, g, wdt):
 def test_e2e_qp_fp32(bits, g):
     X, W, s, z, dY = make_case(("e2e32", bits, g), 70, 256, 44, bits, g, torch.float32, torch.float32)
     check_e2e(X, W, s, z, dY, bits, g, TOL[torch.float32])
+
+
+# ---------------------------------------------------------------- E2E-QP with trained (floating-point) zero points
+
+def check_e2e_trained_z(X, W, s, z, dY, bits, g, tol, seed):
+    I = W.shape[1]
+    qmax = 2 ** bits - 1
+    Xn, Wn, sn, dYn = npf(X), npf(W), s.numpy(), npf(dY)
+    Wp_ref, _ = oracle.pack(Wn, sn, z.clamp(0, qmax).numpy(), bits, g)
+    # zero points after some end-to-end training: no longer integral, slightly outside [0, Qmax] allowed
+    drift = synth.uniform(tuple(z.shape), -0.6, 0.6, seed)
+    zf = (z.clamp(0, qmax) + drift).contiguous()
+    zn = zf.numpy()
+    Y_ref = oracle.qlinear_fwd_z(Xn, Wp_ref, sn, zn, bits, g)
+    ref = oracle.qlinear_bwd_z(Xn, Wp_ref, sn, zn, dYn, I, bits, g)
+    Xd, sd, zd, dYd = dev(X), dev(s), dev(zf), dev(dY)
+    Wp = torch.from_numpy(Wp_ref).cuda()
+    Y = eq.eqat_qlinear_fwd_z(Xd, Wp, sd, zd, bits, g)
+    out = eq.eqat_qlinear_bwd_z(Xd, Wp, sd, zd, dYd, I, bits, g)
+    torch.cuda.synchronize()
+    errs = {"Y": relerr(Y, Y_ref), "dX": relerr(out["dX"], ref["dX"]), "ds": relerr(out["ds"], ref["ds"]),
+            "dz": relerr(out["dz"], ref["dz"])}
+    assert all(e <= tol for e in errs.values()), errs
+    # outputs are optional and do not depend on which others were asked for
+    only_dz = eq.eqat_qlinear_bwd_z(Xd, Wp, sd, zd, dYd, I, bits, g, want=("dz",))
+    assert torch.equal(only_dz["dz"], out["dz"]) and "ds" not in only_dz
+    only_ds = eq.eqat_qlinear_bwd_z(Xd, Wp, sd, zd, dYd, I, bits, g, want=("ds",))
+    assert torch.equal(only_ds["ds"], out["ds"])
+
+
+@pytest.mark.parametrize("tag,T,I,O,bits,g,wdt", BF16_CASES)
+def test_e2e_qp_trained_z_bf16(tag, T, I, O, bits, g, wdt):
+    X, W, s, z, dY = make_case(tag, T, I, O, bits, g, torch.bfloat16, wdt)
+    check_e2e_trained_z(X, W, s, z, dY, bits, g, TOL[torch.bfloat16], synth.seed_of(tag, "zdrift"))
+
+
+@pytest.mark.parametrize("bits,g", [(4, 128), (3, 32), (2, -1)])
+def test_e2e_qp_trained_z_fp32(bits, g):
+    X, W, s, z, dY = make_case(("e2ez32", bits, g), 70, 256, 44, bits, g, torch.float32, torch.float32)
+    check_e2e_trained_z(X, W, s, z, dY, bits, g, TOL[torch.float32], synth.seed_of("e2ez32", bits, g))
+
+
+def test_e2e_qp_trained_z_with_integral_z_matches_the_packed_z_entry_points():
+    X, W, s, z, dY = make_case("zint", 140, 256, 72, 3, 64, torch.bfloat16, torch.bfloat16)
+    zc = z.clamp(0, 7)
+    Xd, sd, dYd = dev(X), dev(s), dev(dY)
+    Wp, zp = eq.eqat_pack(dev(W), sd, dev(zc), 3, 64)
+    a = eq.eqat_qlinear_bwd(Xd, Wp, sd, zp, dYd, 256, 3, 64)
+    b = eq.eqat_qlinear_bwd_z(Xd, Wp, sd, dev(zc), dYd, 256, 3, 64)
+    assert torch.equal(eq.eqat_qlinear_fwd(Xd, Wp, sd, zp, 3, 64), eq.eqat_qlinear_fwd_z(Xd, Wp, sd, dev(zc), 3, 64))
+    assert torch.equal(a["dX"], b["dX"]) and torch.equal(a["ds"], b["ds"])
