@@ -260,7 +260,49 @@ def measure_other_rows(torch, eq, layers, bits, g, adt, dev, args):
     n2 = 2.0 * O2 * I2
     rows["eqat_pack_28672x8192"] = hbm_row(pack_big, n2 * (wbytes + 8.0 / g + bits / 8.0 + bits / (8.0 * g)))
     rows["eqat_init_minmax_28672x8192"] = hbm_row(init_big, n2 * (wbytes + 8.0 / g))
+    del big
+    rows["qlinear_fwd_1_token"] = decode_rows(torch, eq, bits, g, dev, args)
     return rows
+
+
+# out_features x in_features of the paper's matrix-vector table (App. "Speedup with BitBLAS"), and the INT2 latencies it
+# prints for an A100-80GB (context only: another machine, another kernel library)
+DECODE_SHAPES = [(4096, 4096, 9), (11008, 4096, 21), (5120, 5120, 11), (13824, 5120, 26), (8192, 8192, 24), (28672, 8192, 67)]
+
+
+def decode_rows(torch, eq, bits, g, dev, args):
+    """eqat_qlinear_fwd on ONE token at the six shapes of the paper's matrix-vector table: HBM-bound, N/8 bytes per weight.
+    Enough copies of each packed matrix are cycled through that nothing is served from the 256 MB last-level cache."""
+    out = {}
+    for O, I, a100_us in DECODE_SHAPES:
+        G = I // g
+        wb = O * I * bits // 8
+        copies = max(2, min(160, int(640e6 // wb) + 1))
+        gen = torch.Generator(device=dev); gen.manual_seed(O * 7 + I)
+        Wps = [torch.randint(0, 256, (O, I * bits // 8), dtype=torch.uint8, device=dev, generator=gen) for _ in range(copies)]
+        zp = torch.randint(0, 256, (O, 4 * ((G * bits + 31) // 32)), dtype=torch.uint8, device=dev, generator=gen)
+        s = torch.empty((O, G), dtype=torch.float32, device=dev).uniform_(0.005, 0.02, generator=gen)
+        x = torch.empty((1, I), dtype=torch.float32, device=dev).normal_(0, 1, generator=gen).bfloat16()
+        y = torch.empty((1, O), dtype=torch.bfloat16, device=dev)
+        ws = eq.workspace(eq.make_desc(1, I, O, bits, g, eq.BF16, eq.BF16), eq.OP_Q_FWD, dev)
+
+        def run():
+            for Wp in Wps:
+                eq.eqat_qlinear_fwd(x, Wp, s, zp, bits, g, Y=y, ws=ws)
+
+        run(); torch.cuda.synchronize()
+        eq.eqat_profile_start()
+        for _ in range(3):
+            run()
+        torch.cuda.synchronize()
+        prof = eq.eqat_profile_stop()
+        k_us = prof["gemv"][0] / prof["gemv"][1] * 1e3
+        nbytes = wb + O * G * 4 + O * 4 * ((G * bits + 31) // 32) + I * 2 + O * 2      # codes, s (fp32), z, x, y
+        out[f"{O}x{I}"] = {"kernel_us": round(k_us, 2), "gbs": round(nbytes / k_us / 1e3, 1),
+                           "frac_of_hbm_peak": round(nbytes / k_us / 1e3 / PEAK_HBM_GBS, 4), "bytes": nbytes,
+                           "paper_a100_int2_us": a100_us}
+        del Wps
+    return out
 
 
 def cpu_baseline(wl):

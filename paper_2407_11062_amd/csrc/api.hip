@@ -131,7 +131,7 @@ int eqat_profile_kernels(void) { return eqat::PK_COUNT; }
 const char *eqat_profile_kernel_name(int k)
 {
     static const char *names[eqat::PK_COUNT] = {"init_minmax", "quantize", "unpack_sz", "gemm_fwd", "gemm_dx",
-                                                "gemm_dw", "reduce_partials", "f32_path", "repack"};
+                                                "gemm_dw", "reduce_partials", "f32_path", "repack", "gemv"};
     return (k >= 0 && k < eqat::PK_COUNT) ? names[k] : "?";
 }
 
@@ -280,6 +280,11 @@ static eqat_status qlinear_fwd_any(const eqat_desc *d, const void *X, const uint
     if (p.T == 0) return EQAT_OK;
     hipStream_t st = (hipStream_t)stream;
     char *w8 = (char *)ws;
+    if (eqat::gemv_applies(p)) {          // a few tokens: one HBM-bound kernel on the caller's own packed arrays
+        ProfScope ps(eqat::PK_GEMV, st);
+        eqat::launch_gemv(p, X, Wpacked, s, zpacked, zfloat, Y, st);
+        return launch_status();
+    }
     {
         ProfScope ps(eqat::PK_UNPACK_SZ, st);
         if (zpacked != nullptr) eqat::launch_unpack_sz(p, s, zpacked, w8 + l.sz, st);

@@ -44,6 +44,12 @@ void launch_mfma_dw(const Problem &p, bool block_ap, const void *X, const void *
                     hipStream_t st);
 bool dw_needs_partials(const Problem &p);
 
+// ---- gemv.hip (E2E-QP forward for a few tokens, straight from the dense packed stream) -----------
+bool gemv_applies(const Problem &p);
+// exactly one of zpacked / zfloat is not NULL
+void launch_gemv(const Problem &p, const void *X, const void *Wpacked, const float *s, const void *zpacked,
+                 const float *zfloat, void *Y, hipStream_t st);
+
 // ---- gemm_f32.hip (fp32 activations; simple tiled FMA kernels, exact division everywhere) --------
 void launch_f32_fwd(const Problem &p, bool packed, const void *X, const void *W_or_codes, const float *s, const void *z_or_sz,
                     void *Y, hipStream_t st);

@@ -262,3 +262,54 @@ def test_e2e_qp_trained_z_with_integral_z_matches_the_packed_z_entry_points():
     b = eq.eqat_qlinear_bwd_z(Xd, Wp, sd, dev(zc), dYd, 256, 3, 64)
     assert torch.equal(eq.eqat_qlinear_fwd(Xd, Wp, sd, zp, 3, 64), eq.eqat_qlinear_fwd_z(Xd, Wp, sd, dev(zc), 3, 64))
     assert torch.equal(a["dX"], b["dX"]) and torch.equal(a["ds"], b["ds"])
+
+
+# ---------------------------------------------------------------- E2E-QP forward for a few tokens (matrix-vector kernel)
+
+GEMV_CASES = [
+    # tag, T, I, O, bits, g
+    ("v1", 1, 4096, 4096, 2, 64),          # the decode shape of the 7B attention projections
+    ("v2", 2, 416, 200, 2, 32),            # I not a multiple of 128 (ragged last chunk), O not a multiple of 16
+    ("v3", 5, 1024, 72, 3, 128),
+    ("v4", 16, 512, 136, 4, 64),           # the most tokens the kernel takes
+    ("v5", 3, 384, 40, 2, -1),             # one group per row
+    ("v6", 1, 96, 8, 3, 96),               # a single, partly filled chunk; one 8-row block
+    ("v7", 4, 2048, 264, 4, 32),
+    ("v8", 7, 160, 24, 3, 32),
+]
+
+
+@pytest.mark.parametrize("tag,T,I,O,bits,g", GEMV_CASES)
+def test_e2e_qp_forward_few_tokens(tag, T, I, O, bits, g):
+    X, W, s, z, dY = make_case(tag, T, I, O, bits, g, torch.bfloat16, torch.bfloat16)
+    qmax = 2 ** bits - 1
+    z = z.clamp(0, qmax)
+    Xn, sn = npf(X), s.numpy()
+    Wp_ref, zp_ref = oracle.pack(npf(W), sn, z.numpy(), bits, g)
+    Xd, sd = dev(X), dev(s)
+    Wp, zp = torch.from_numpy(Wp_ref).cuda(), torch.from_numpy(zp_ref).cuda()
+    Y = eq.eqat_qlinear_fwd(Xd, Wp, sd, zp, bits, g)
+    e = relerr(Y, oracle.qlinear_fwd(Xn, Wp_ref, sn, zp_ref, bits, g))
+    assert e <= TOL[torch.bfloat16], e
+    # trained (floating-point) zero points through the same kernel
+    zf = (z + synth.uniform(tuple(z.shape), -0.6, 0.6, synth.seed_of(tag, "zf"))).contiguous()
+    Yz = eq.eqat_qlinear_fwd_z(Xd, Wp, sd, dev(zf), bits, g)
+    e = relerr(Yz, oracle.qlinear_fwd_z(Xn, Wp_ref, sn, zf.numpy(), bits, g))
+    assert e <= TOL[torch.bfloat16], e
+    # deterministic, and rows do not leak into each other: token k alone gives the same row k
+    assert torch.equal(Y, eq.eqat_qlinear_fwd(Xd, Wp, sd, zp, bits, g))
+    if T > 1:
+        Yk = eq.eqat_qlinear_fwd(Xd[T - 1:T].contiguous(), Wp, sd, zp, bits, g)
+        assert relerr(Yk, npf(Y[T - 1:T]).astype(np.float64)) <= 1e-2
+
+
+def test_few_token_kernel_and_gemm_agree_across_the_switch():
+    # 16 tokens run the matrix-vector kernel, 17 the tiled GEMM: the first 16 rows must agree to bf16 accuracy
+    X, W, s, z, dY = make_case("switch", 17, 512, 64, 2, 64, torch.bfloat16, torch.bfloat16)
+    z = z.clamp(0, 3)
+    sd = dev(s)
+    Wp, zp = eq.eqat_pack(dev(W), sd, dev(z), 2, 64)
+    Xd = dev(X)
+    Y17 = eq.eqat_qlinear_fwd(Xd, Wp, sd, zp, 2, 64)
+    Y16 = eq.eqat_qlinear_fwd(Xd[:16].contiguous(), Wp, sd, zp, 2, 64)
+    assert relerr(Y16, npf(Y17[:16]).astype(np.float64)) <= 1e-2
