@@ -130,8 +130,8 @@ int eqat_profile_kernels(void) { return eqat::PK_COUNT; }
 
 const char *eqat_profile_kernel_name(int k)
 {
-    static const char *names[eqat::PK_COUNT] = {"init_minmax", "quantize", "unpack_sz", "gemm_fwd", "gemm_dx",
-                                                "gemm_dw", "reduce_partials", "f32_path", "repack", "gemv"};
+    static const char *names[eqat::PK_COUNT] = {"init_minmax", "quantize", "e2e_prepare", "gemm_fwd", "gemm_dx",
+                                                "gemm_dw", "reduce_partials", "f32_path", "gemv"};
     return (k >= 0 && k < eqat::PK_COUNT) ? names[k] : "?";
 }
 
@@ -286,11 +286,9 @@ static eqat_status qlinear_fwd_any(const eqat_desc *d, const void *X, const uint
         return launch_status();
     }
     {
-        ProfScope ps(eqat::PK_UNPACK_SZ, st);
-        if (zpacked != nullptr) eqat::launch_unpack_sz(p, s, zpacked, w8 + l.sz, st);
-        else eqat::launch_pair_sz(p, s, zfloat, w8 + l.sz, st);
+        ProfScope ps(eqat::PK_PREPARE, st);
+        eqat::launch_e2e_prepare(p, p.act_bf16 ? Wpacked : nullptr, w8 + l.codes, s, zpacked, zfloat, w8 + l.sz, st);
     }
-    if (p.act_bf16) { ProfScope ps(eqat::PK_REPACK, st); eqat::launch_repack(p, Wpacked, w8 + l.codes, st); }
     if (p.act_bf16) { ProfScope ps(eqat::PK_GEMM_FWD, st); eqat::launch_mfma_fwd(p, X, w8 + l.codes, w8 + l.sz, Y, st); }
     else { ProfScope ps(eqat::PK_F32, st); eqat::launch_f32_fwd(p, true, X, Wpacked, s, w8 + l.sz, Y, st); }
     return launch_status();
@@ -314,12 +312,10 @@ static eqat_status qlinear_bwd_any(const eqat_desc *d, const void *X, const uint
     hipStream_t st = (hipStream_t)stream;
     char *w8 = (char *)ws;
     {
-        ProfScope ps(eqat::PK_UNPACK_SZ, st);
-        if (zpacked != nullptr) eqat::launch_unpack_sz(p, s, zpacked, w8 + l.sz, st);
-        else eqat::launch_pair_sz(p, s, zfloat, w8 + l.sz, st);
+        ProfScope ps(eqat::PK_PREPARE, st);
+        eqat::launch_e2e_prepare(p, p.act_bf16 ? Wpacked : nullptr, w8 + l.codes, s, zpacked, zfloat, w8 + l.sz, st);
     }
     if (p.act_bf16) {
-        { ProfScope ps(eqat::PK_REPACK, st); eqat::launch_repack(p, Wpacked, w8 + l.codes, st); }
         if (dX != nullptr) { ProfScope ps(eqat::PK_GEMM_DX, st); eqat::launch_mfma_dx(p, dY, w8 + l.codes, w8 + l.sz, dX, st); }
         if (want_g)
             eqat::launch_mfma_dw(p, false, X, dY, nullptr, w8 + l.codes, nullptr, w8 + l.sz, s, nullptr, ds, dz,

@@ -18,12 +18,11 @@ struct Problem {
 // zpacked (may be NULL): the zero points at N bits are packed by extra workgroups of the same launch.
 void launch_quantize(const Problem &p, const void *W, const float *s, const float *z, void *codes, void *clampbits,
                      void *sz, void *zpacked, bool for_pack, hipStream_t st);
-// dense stream -> working layout
-void launch_repack(const Problem &p, const void *packed, void *work, hipStream_t st);
 inline size_t work_code_bytes(const Problem &p) { return (size_t)p.O * p.I / (p.bits == 2 ? 4 : 2); }
-void launch_unpack_sz(const Problem &p, const float *s, const void *zpacked, void *sz, hipStream_t st);
-// (s, z) pairs from two float arrays (zero points kept in floating point)
-void launch_pair_sz(const Problem &p, const float *s, const float *z, void *sz, hipStream_t st);
+// One launch before the GEMMs of an E2E-QP call: dense stream -> working layout (packed == NULL: skipped) and the
+// (s, z) pairs, z taken from the packed N-bit zero points or from a float array (exactly one of the two not NULL).
+void launch_e2e_prepare(const Problem &p, const void *packed, void *work, const float *s, const void *zpacked,
+                        const float *zfloat, void *sz, hipStream_t st);
 void launch_unpack(const Problem &p, const void *Wpacked, const void *zpacked, int32_t *codes, int32_t *zcodes, hipStream_t st);
 void launch_init_minmax(const Problem &p, const void *W, float *s, float *z, hipStream_t st);
 void launch_reduce_partials(const float *part, float *out, const float *s, size_t n_out, uint32_t n_per, bool scale_by_s,

@@ -193,10 +193,8 @@ __global__ __launch_bounds__(256) void k_quantize(const QuantizeArgs a)
 
 // The dense stream of the C ABI -> the working layout (one thread per 32-code segment).
 template <int BITS>
-__global__ __launch_bounds__(256) void k_repack(const uint32_t *__restrict__ packed, uint32_t *__restrict__ work, uint32_t n_segs)
+__device__ __forceinline__ void repack_segment(const uint32_t *__restrict__ packed, uint32_t *__restrict__ work, uint32_t t)
 {
-    const uint32_t t = blockIdx.x * 256u + threadIdx.x;
-    if (t >= n_segs) return;
     uint32_t in[BITS];
 #pragma unroll
     for (int k = 0; k < BITS; ++k) in[k] = packed[(size_t)t * BITS + k];
@@ -208,29 +206,41 @@ __global__ __launch_bounds__(256) void k_repack(const uint32_t *__restrict__ pac
     for (int k = 0; k < WorkCodes<BITS>::kWords; ++k) work[(size_t)t * WorkCodes<BITS>::kWords + k] = out[k];
 }
 
-// (s, z) pairs for the E2E-QP kernels: sz[o,j] = (s[o,j], float(zpacked code j of row o)).
+// (s, z) pair of group t for the E2E-QP kernels: z from the packed N-bit zero points, or from a float array.
 template <int BITS>
-__global__ __launch_bounds__(256) void k_unpack_sz(const float *__restrict__ s, const uint32_t *__restrict__ zpacked,
-                                                   floatx2 *__restrict__ sz, uint32_t O, uint32_t G, uint32_t row_words)
+__device__ __forceinline__ void pair_sz(const float *__restrict__ s, const uint32_t *__restrict__ zpacked,
+                                        const float *__restrict__ zfloat, floatx2 *__restrict__ sz, uint32_t t, uint32_t G,
+                                        uint32_t row_words)
 {
-    const uint32_t t = blockIdx.x * 256u + threadIdx.x;
-    if (t >= O * G) return;
-    const uint32_t row = t / G, j = t - row * G;
-    const uint32_t bit = j * BITS, wi = bit >> 5, sh = bit & 31u;
-    uint64_t two = zpacked[row * row_words + wi];
-    if (sh + BITS > 32u) two |= (uint64_t)zpacked[row * row_words + wi + 1] << 32;
-    floatx2 o; o[0] = s[t]; o[1] = (float)((uint32_t)(two >> sh) & ((1u << BITS) - 1u));
+    floatx2 o; o[0] = s[t];
+    if (zfloat != nullptr) {
+        o[1] = zfloat[t];
+    } else {
+        const uint32_t row = t / G, j = t - row * G;
+        const uint32_t bit = j * BITS, wi = bit >> 5, sh = bit & 31u;
+        uint64_t two = zpacked[row * row_words + wi];
+        if (sh + BITS > 32u) two |= (uint64_t)zpacked[row * row_words + wi + 1] << 32;
+        o[1] = (float)((uint32_t)(two >> sh) & ((1u << BITS) - 1u));
+    }
     sz[t] = o;
 }
 
-// Test aid: codes [O,I] int32 from the packed stream (one thread per 32-code segment), zero points [O,G].
-__global__ __launch_bounds__(256) void k_pair_sz(const float *__restrict__ s, const float *__restrict__ z,
-                                                 floatx2 *__restrict__ sz, uint32_t n)
+// What every E2E-QP call on the MFMA path needs before its GEMMs, in one launch: the first n_repack_blocks workgroups
+// re-lay the codes (packed == NULL: none), the rest write the (s, z) pairs.
+template <int BITS>
+__global__ __launch_bounds__(256) void k_e2e_prepare(const uint32_t *__restrict__ packed, uint32_t *__restrict__ work,
+                                                     uint32_t n_segs, uint32_t n_repack_blocks,
+                                                     const float *__restrict__ s, const uint32_t *__restrict__ zpacked,
+                                                     const float *__restrict__ zfloat, floatx2 *__restrict__ sz,
+                                                     uint32_t n_groups, uint32_t G, uint32_t row_words)
 {
-    const uint32_t t = blockIdx.x * 256u + threadIdx.x;
-    if (t >= n) return;
-    floatx2 o; o[0] = s[t]; o[1] = z[t];
-    sz[t] = o;
+    if (blockIdx.x < n_repack_blocks) {
+        const uint32_t t = blockIdx.x * 256u + threadIdx.x;
+        if (t < n_segs) repack_segment<BITS>(packed, work, t);
+    } else {
+        const uint32_t t = (blockIdx.x - n_repack_blocks) * 256u + threadIdx.x;
+        if (t < n_groups) pair_sz<BITS>(s, zpacked, zfloat, sz, t, G, row_words);
+    }
 }
 
 template <int BITS>
@@ -384,29 +394,18 @@ void launch_quantize(const Problem &p, const void *W, const float *s, const floa
 #undef EQAT_Q
 }
 
-void launch_repack(const Problem &p, const void *packed, void *work, hipStream_t st)
+void launch_e2e_prepare(const Problem &p, const void *packed, void *work, const float *s, const void *zpacked,
+                        const float *zfloat, void *sz, hipStream_t st)
 {
-    const uint32_t n_segs = (uint32_t)((size_t)p.O * p.I / 32);
-    const dim3 grid(blocks_for(n_segs)), block(256);
-    if (p.bits == 2) k_repack<2><<<grid, block, 0, st>>>((const uint32_t *)packed, (uint32_t *)work, n_segs);
-    else if (p.bits == 3) k_repack<3><<<grid, block, 0, st>>>((const uint32_t *)packed, (uint32_t *)work, n_segs);
-    else k_repack<4><<<grid, block, 0, st>>>((const uint32_t *)packed, (uint32_t *)work, n_segs);
-}
-
-void launch_unpack_sz(const Problem &p, const float *s, const void *zpacked, void *sz, hipStream_t st)
-{
+    const uint32_t n_segs = packed != nullptr ? (uint32_t)((size_t)p.O * p.I / 32) : 0u;
+    const uint32_t nb = blocks_for(n_segs), n_groups = (uint32_t)((size_t)p.O * p.G);
     const uint32_t row_words = (uint32_t)((p.G * p.bits + 31) / 32);
-    const size_t n = (size_t)p.O * p.G;
-    const dim3 grid(blocks_for(n)), block(256);
-    if (p.bits == 2) k_unpack_sz<2><<<grid, block, 0, st>>>(s, (const uint32_t *)zpacked, (floatx2 *)sz, (uint32_t)p.O, (uint32_t)p.G, row_words);
-    else if (p.bits == 3) k_unpack_sz<3><<<grid, block, 0, st>>>(s, (const uint32_t *)zpacked, (floatx2 *)sz, (uint32_t)p.O, (uint32_t)p.G, row_words);
-    else k_unpack_sz<4><<<grid, block, 0, st>>>(s, (const uint32_t *)zpacked, (floatx2 *)sz, (uint32_t)p.O, (uint32_t)p.G, row_words);
-}
-
-void launch_pair_sz(const Problem &p, const float *s, const float *z, void *sz, hipStream_t st)
-{
-    const size_t n = (size_t)p.O * p.G;
-    k_pair_sz<<<dim3(blocks_for(n)), dim3(256), 0, st>>>(s, z, (floatx2 *)sz, (uint32_t)n);
+    const dim3 grid(nb + blocks_for(n_groups)), block(256);
+#define EQAT_PREP(B) k_e2e_prepare<B><<<grid, block, 0, st>>>((const uint32_t *)packed, (uint32_t *)work, n_segs, nb, s, \
+                                                             (const uint32_t *)zpacked, zfloat, (floatx2 *)sz, n_groups, \
+                                                             (uint32_t)p.G, row_words)
+    if (p.bits == 2) EQAT_PREP(2); else if (p.bits == 3) EQAT_PREP(3); else EQAT_PREP(4);
+#undef EQAT_PREP
 }
 
 void launch_unpack(const Problem &p, const void *Wpacked, const void *zpacked, int32_t *codes, int32_t *zcodes, hipStream_t st)

@@ -18,7 +18,7 @@ import sys
 
 # kernel-name fragment -> name the library's own timers use
 KERNELS = (("k_gemm_q<", None), ("k_gemm_dw", "gemm_dw"), ("k_quantize", "quantize"), ("k_init_minmax", "init_minmax"),
-           ("k_repack", "repack"))
+           ("k_e2e_prepare", "e2e_prepare"))
 
 
 def _library_kernel(name: str):
