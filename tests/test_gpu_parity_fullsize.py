@@ -94,5 +94,17 @@ def test_fullsize_layer(wname, lname):
         errs["q.dX"] = relerr(npf(outq["dX"][trows]), oracle.qlinear_bwd(None, Wp_ref, s, zp_ref, dYs, I, bits, g, want=("dX",))["dX"])
         refq = oracle.qlinear_bwd(Xn_full, Wp_ref[orows], s[orows], zp_ref[orows], dY_cols, I, bits, g, want=("ds",))
         errs["q.ds"] = relerr(npf(outq["ds"][orows]), refq["ds"])
+        del Yq, outq
+        # zero points trained end to end (floats, not rounded): dz comes out of the same epilogue
+        zf = (z + synth.uniform(z.shape, -0.5, 0.5, synth.seed_of(wname, lname, "zf")).numpy()).astype(np.float32)
+        outz = eq.eqat_qlinear_bwd_z(Xd, Wp, sd, torch.from_numpy(zf).cuda(), dYd, I, bits, g, want=("ds", "dz"))
+        torch.cuda.synchronize()
+        refz = oracle.qlinear_bwd_z(Xn_full, Wp_ref[orows], s[orows], zf[orows], dY_cols, I, bits, g, want=("ds", "dz"))
+        errs["z.ds"] = relerr(npf(outz["ds"][orows]), refz["ds"])
+        errs["z.dz"] = relerr(npf(outz["dz"][orows]), refz["dz"])
+        # one token through the decode-time kernel, compared in full (the oracle can afford a single row)
+        y1 = eq.eqat_qlinear_fwd(Xd[:1].contiguous(), Wp, sd, zp, bits, g)
+        torch.cuda.synchronize()
+        errs["q.Y(1 token)"] = relerr(npf(y1), oracle.qlinear_fwd(npf(X[:1]), Wp_ref, s, zp_ref, bits, g))
     print("  errors:", {k: round(v, 5) for k, v in errs.items()}, flush=True)
     assert errs and all(e <= TOL for e in errs.values()), errs
