@@ -106,12 +106,17 @@ def main():
     for _ in range(args.warmup):
         block_ap_step()
     torch.cuda.synchronize()
-    eq.eqat_profile_start()
     t0 = time.perf_counter()
     for _ in range(args.steps):
         block_ap_step()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
+    # the same steps once more with the library's per-kernel event timers on (they cost a little, so `value` above is
+    # taken without them): average launch duration of every kernel on the stream it runs on
+    eq.eqat_profile_start()
+    for _ in range(args.steps):
+        block_ap_step()
+    torch.cuda.synchronize()
     prof = eq.eqat_profile_stop()
     ms_step = 1e3 * elapsed / args.steps
     tflops = flops_step / (elapsed / args.steps) / 1e12
