@@ -31,8 +31,9 @@
  *              quotient w/s (bf16 weights are widened first), so integer codes
  *              and packed bytes are identical on every implementation.
  *              zbar = round(z) is used in place of z; it is clamped to [0,2^N-1]
- *              only where it is packed.  Preconditions (not checked): s > 0 and
- *              finite, |z| <= 2^20, all inputs finite.
+ *              only where it is packed.  Preconditions (not checked): s a normal,
+ *              finite, positive binary32 number (>= 2^-126; the min/max rule
+ *              never gives less than 1e-10), |z| <= 2^20, all inputs finite.
  *   Determinism  Same inputs give bitwise the same outputs.
  */
 #ifndef EQAT_H_
@@ -127,6 +128,9 @@ eqat_status eqat_unpack(const eqat_desc *d, const uint8_t *Wpacked, const uint8_
 
 /*
  * E2E-QP forward (Sec. 3.3): What = (w_q - z) * s from the packed codes, Y = X * What^T.
+ * With bf16 activations and at most 16 tokens (T * I * 2 <= 64 KiB) this is one memory-bound
+ * matrix-vector kernel that reads the packed arrays as they are and uses no workspace (the
+ * decode-time case of the paper's App. "Speedup with BitBLAS"); otherwise the tiled MFMA GEMM.
  */
 eqat_status eqat_qlinear_fwd(const eqat_desc *d, const void *X, const uint8_t *Wpacked, const float *s,
                              const uint8_t *zpacked, void *Y, void *ws, size_t ws_bytes, void *stream);
