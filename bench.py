@@ -267,7 +267,31 @@ def measure_other_rows(torch, eq, layers, bits, g, adt, dev, args):
     rows["eqat_init_minmax_28672x8192"] = hbm_row(init_big, n2 * (wbytes + 8.0 / g))
     del big
     rows["qlinear_fwd_1_token"] = decode_rows(torch, eq, bits, g, dev, args)
+    rows["vendor_gemm_reference"] = vendor_gemm_rows(torch, layers, layers[0]["X"].shape[0], args)
     return rows
+
+
+def vendor_gemm_rows(torch, layers, T, args):
+    """Context only, not part of the product path: the vendor GEMM library (torch.matmul, bf16) on the three plain GEMMs
+    of the same seven linears with the weights already materialised in bf16: Y = X W^T (NT), dX = dY W (NN), dW = dY^T X (TN).
+    It rebuilds no weights and has no Eq.(3)-(5) epilogue; it shows what this machine gives a tuned bf16 GEMM on this data."""
+    out = {}
+    ops = {"nt_like_fwd": lambda L: torch.matmul(L["X"], L["W"].t()),
+           "nn_like_dx": lambda L: torch.matmul(L["dY"], L["W"]),
+           "tn_like_dw": lambda L: torch.matmul(L["dY"].t(), L["X"])}
+    flops = 2.0 * T * sum(L["O"] * L["I"] for L in layers)
+    for name, fn in ops.items():
+        for L in layers:
+            fn(L)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            for L in layers:
+                fn(L)
+        e1.record(); torch.cuda.synchronize()
+        out[name] = {"tflops": round(flops / (e0.elapsed_time(e1) * 1e-3 / args.steps) / 1e12, 1)}
+    return out
 
 
 # out_features x in_features of the paper's matrix-vector table (App. "Speedup with BitBLAS"), and the INT2 latencies it
