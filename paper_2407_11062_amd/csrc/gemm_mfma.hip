@@ -29,16 +29,27 @@ __device__ __forceinline__ bf16x8 frag_kc(const bf16_t *tile, int row0, int kk, 
 {
     return *reinterpret_cast<const bf16x8 *>(tile + (row0 + (lane & 31)) * LD + kk * 16 + (lane >> 5) * 8);
 }
-// KM tile: the transpose read hands lane i (of each 16-lane block) four k-consecutive values of column
-// i, gathered from the lanes that addressed rows k..k+3.  Block b = lane/16: columns 16*(b&1).., k half b>>1.
+// KM tile [k][n] (dX: What with K = O as the slow axis), rows padded by kPadKM.  The producer writes one 16-byte chunk
+// per lane and instruction; the 8 (or 4) lanes that fill one row sit 64 bytes apart.  A 128-bit LDS store is served 8
+// lanes per cycle over 32 four-byte banks (the model that reproduces the SQ_LDS_BANK_CONFLICT readings of every layout
+// tried here: 24 extra cycles per store unswizzled, 8 with a swizzle that only separated lanes 4 apart, 0 for the
+// forward kernel's [n][k] tile), so lanes 128 bytes apart in one row share their banks.  The four chunks of every
+// 32-column block are therefore XOR-permuted with km_chunk_swz(k, block): blocks two apart, and the blocks that a
+// second row of the same store cycle puts on the same banks, get different chunk positions.
+__device__ __forceinline__ int km_chunk_swz(int k, int colblock) { return ((colblock >> 1) + 2 * (k & 1)) & 3; }
+
+// The transpose read hands lane i (of each 16-lane block) four k-consecutive values of column i, gathered from the lanes
+// that addressed rows k..k+3.  Block b = lane/16: columns 16*(b&1).., k half b>>1.
 template <int LD>
 __device__ __forceinline__ bf16x8 frag_km(const bf16_t *tile, int col0, int kk, int lane)
 {
     const int i = lane & 15, b = lane >> 4;
-    const bf16_t *p = tile + (kk * 16 + (b >> 1) * 8 + (i >> 2)) * LD + col0 + (b & 1) * 16 + (i & 3) * 4;
+    const int k = kk * 16 + (b >> 1) * 8 + (i >> 2), col = col0 + (b & 1) * 16 + (i & 3) * 4;
+    const int pcol = (col & ~31) | ((((col >> 3) & 3) ^ km_chunk_swz(k, col >> 5)) << 3) | (col & 7);
+    const bf16_t *p = tile + k * LD + pcol;
     typedef short4v __attribute__((address_space(3))) * lds_p;
     const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_p)(p));
-    const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_p)(p + 4 * LD));
+    const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_p)(p + 4 * LD));      // (k + 4) & 3 == k & 3: same permutation
     typedef short short8v __attribute__((ext_vector_type(8)));
     short8v r = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     return __builtin_bit_cast(bf16x8, r);
@@ -251,10 +262,11 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_q(const GemmQArgs a)
             WhatTable<BITS> &tab = tabs[S][it];
             if constexpr (P == 0) tab.build(stS[S][it][0], stS[S][it][1]);     // piece 0 of a tile always runs first
             bf16x8 *dst = reinterpret_cast<bf16x8 *>(dB + r * LDB + c);
-            if ((it * 4 + 0) % KK == P) dst[0] = tab.template eight<0>(stC[S][it]);
-            if ((it * 4 + 1) % KK == P) dst[1] = tab.template eight<1>(stC[S][it]);
-            if ((it * 4 + 2) % KK == P) dst[2] = tab.template eight<2>(stC[S][it]);
-            if ((it * 4 + 3) % KK == P) dst[3] = tab.template eight<3>(stC[S][it]);
+            const int sw = BT ? km_chunk_swz(r, c >> 5) : 0;                    // KM tile: see km_chunk_swz
+            if ((it * 4 + 0) % KK == P) dst[0 ^ sw] = tab.template eight<0>(stC[S][it]);
+            if ((it * 4 + 1) % KK == P) dst[1 ^ sw] = tab.template eight<1>(stC[S][it]);
+            if ((it * 4 + 2) % KK == P) dst[2 ^ sw] = tab.template eight<2>(stC[S][it]);
+            if ((it * 4 + 3) % KK == P) dst[3 ^ sw] = tab.template eight<3>(stC[S][it]);
         }
     };
 

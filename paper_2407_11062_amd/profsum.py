@@ -3,11 +3,15 @@
   python -m paper_2407_11062_amd.profsum trace   <prefix>_kernel_stats.csv  <out.txt>  "<command that was profiled>" [bench.json]
   python -m paper_2407_11062_amd.profsum traffic <out.json> <workload> <fetch.csv> <write.csv> <copy_fetch.csv> <copy_write.csv> <copy_bytes>
 
+  python -m paper_2407_11062_amd.profsum counters <out.txt> "<command that was profiled>" <counter_collection.csv> [more.csv ...]
+
 `trace`   one line per kernel (calls, total and average duration, share) from `rocprofv3 --kernel-trace --stats`,
           followed by the bench line of the same run if given.
 `traffic` bytes per launch that crossed the L2 <-> memory-fabric boundary, per library kernel, from two
           `rocprofv3 --pmc` runs of the bench (FETCH_SIZE, then WRITE_SIZE; both in KiB per dispatch), each scaled by
           what the same counter reads for a plain device copy of `copy_bytes` bytes (bench.py --copy-calibration).
+`counters` mean reading per launch of every counter in the given `rocprofv3 --pmc` CSV files, per library kernel, plus
+          the MFMA pipe's share of the busy cycles where both counters are present.
 """
 from __future__ import annotations
 
@@ -89,11 +93,35 @@ def traffic(out_json, workload, fetch_csv, write_csv, copy_fetch_csv, copy_write
     print(json.dumps(out, indent=1))
 
 
+def counters(out_txt, command, *csvs) -> None:
+    acc = collections.defaultdict(lambda: collections.defaultdict(list))
+    for path in csvs:
+        for r in csv.DictReader(open(path)):
+            lab = _library_kernel(r["Kernel_Name"])
+            if lab:
+                acc[lab][r["Counter_Name"]].append(float(r["Counter_Value"]))
+    with open(out_txt, "w") as f:
+        f.write("rocprofv3 counter summary (MI355X, gfx950): mean per launch over the launches of one bench run\n")
+        f.write("command: %s\n\n" % command)
+        for lab in sorted(acc):
+            f.write("%s\n" % lab)
+            means = {c: sum(v) / len(v) for c, v in acc[lab].items()}
+            for c in sorted(means):
+                f.write("  %-34s %18.0f   (%d launches)\n" % (c, means[c], len(acc[lab][c])))
+            if "SQ_VALU_MFMA_BUSY_CYCLES" in means and "SQ_BUSY_CU_CYCLES" in means and means["SQ_BUSY_CU_CYCLES"] > 0:
+                # MFMA busy cycles are summed over the 4 SIMDs of a CU, CU busy cycles over the CUs
+                f.write("  MFMA pipe busy / (4 x CU busy cycles)  %.3f\n" % (means["SQ_VALU_MFMA_BUSY_CYCLES"] / (4.0 * means["SQ_BUSY_CU_CYCLES"])))
+            f.write("\n")
+    print(open(out_txt).read())
+
+
 def main(argv):
     if len(argv) >= 4 and argv[0] == "trace":
         trace(*argv[1:5])
     elif len(argv) == 8 and argv[0] == "traffic":
         traffic(*argv[1:])
+    elif len(argv) >= 4 and argv[0] == "counters":
+        counters(*argv[1:])
     else:
         print(__doc__)
         return 2
