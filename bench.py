@@ -66,42 +66,12 @@ def main():
     wl = synth.WORKLOADS[args.workload]
     T, bits, g = wl.tokens, wl.bits, wl.group
     adt = synth.torch_dtype(wl.act_dtype)
-    gen = torch.Generator(device=dev)
-
-    def randn(shape, std, seed, dtype):
-        gen.manual_seed(seed)
-        t = torch.empty(shape, dtype=torch.float32, device=dev).normal_(0.0, 1.0, generator=gen)
-        return (t * std).to(dtype) if std != 1.0 else t.to(dtype)
-
-    layers = []
-    for lin in wl.layers:
-        O, I = lin.out_features, lin.in_features
-        L = {"name": lin.name, "O": O, "I": I}
-        L["W"] = randn((O, I), wl.w_std, synth.seed_of(wl.name, lin.name, "W"), adt)
-        L["X"] = randn((T, I), 1.0, synth.seed_of(wl.name, lin.name, "X"), adt)
-        L["dY"] = randn((T, O), 1.0, synth.seed_of(wl.name, lin.name, "dY"), adt)
-        s, z = eq.eqat_init_minmax(L["W"], bits, g)
-        # move the fresh min/max state into a "trained" one so that the clamped branches run
-        gen.manual_seed(synth.seed_of(wl.name, lin.name, "sz"))
-        u = torch.empty_like(s).uniform_(0.7, 1.1, generator=gen)
-        d = torch.randint(-1, 2, s.shape, generator=gen, device=dev).float()
-        L["s"], L["z"] = (s * u).contiguous(), (z + d).clamp_(0, 2 ** bits - 1).contiguous()
-        G = I // g
-        L["Y"] = torch.empty((T, O), dtype=adt, device=dev)
-        L["out"] = {"dX": torch.empty((T, I), dtype=adt, device=dev), "dW": torch.empty((O, I), dtype=adt, device=dev),
-                    "ds": torch.empty((O, G), dtype=torch.float32, device=dev),
-                    "dz": torch.empty((O, G), dtype=torch.float32, device=dev)}
-        dsc = eq.make_desc(T, I, O, bits, g, eq._dt(L["X"]), eq._dt(L["W"]))
-        L["ws_f"] = eq.workspace(dsc, eq.OP_FQ_FWD, dev)
-        L["ws_b"] = eq.workspace(dsc, eq.OP_FQ_BWD, dev)
-        layers.append(L)
+    layers = build_layers(torch, eq, synth, wl, dev)
     sum_io = sum(L["O"] * L["I"] for L in layers)
     flops_step = 6.0 * T * sum_io
 
     def block_ap_step():
-        for L in layers:
-            eq.eqat_fq_linear_fwd(L["X"], L["W"], L["s"], L["z"], bits, g, Y=L["Y"], ws=L["ws_f"])
-            eq.eqat_fq_linear_bwd(L["X"], L["W"], L["s"], L["z"], L["dY"], bits, g, out=L["out"], ws=L["ws_b"])
+        run_block_ap_step(eq, layers, bits, g)
 
     for _ in range(args.warmup):
         block_ap_step()
@@ -160,6 +130,48 @@ def main():
         result["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(result))
     return 0
+
+
+def build_layers(torch, eq, synth, wl, dev):
+    """Seeded synthetic tensors, trained-state (s, z), preallocated outputs and workspaces for every linear of a workload."""
+    T, bits, g = wl.tokens, wl.bits, wl.group
+    adt = synth.torch_dtype(wl.act_dtype)
+    gen = torch.Generator(device=dev)
+
+    def randn(shape, std, seed, dtype):
+        gen.manual_seed(seed)
+        t = torch.empty(shape, dtype=torch.float32, device=dev).normal_(0.0, 1.0, generator=gen)
+        return (t * std).to(dtype) if std != 1.0 else t.to(dtype)
+
+    layers = []
+    for lin in wl.layers:
+        O, I = lin.out_features, lin.in_features
+        L = {"name": lin.name, "O": O, "I": I}
+        L["W"] = randn((O, I), wl.w_std, synth.seed_of(wl.name, lin.name, "W"), adt)
+        L["X"] = randn((T, I), 1.0, synth.seed_of(wl.name, lin.name, "X"), adt)
+        L["dY"] = randn((T, O), 1.0, synth.seed_of(wl.name, lin.name, "dY"), adt)
+        s, z = eq.eqat_init_minmax(L["W"], bits, g)
+        # move the fresh min/max state into a "trained" one so that the clamped branches run
+        gen.manual_seed(synth.seed_of(wl.name, lin.name, "sz"))
+        u = torch.empty_like(s).uniform_(0.7, 1.1, generator=gen)
+        d = torch.randint(-1, 2, s.shape, generator=gen, device=dev).float()
+        L["s"], L["z"] = (s * u).contiguous(), (z + d).clamp_(0, 2 ** bits - 1).contiguous()
+        G = s.shape[1]
+        L["Y"] = torch.empty((T, O), dtype=adt, device=dev)
+        L["out"] = {"dX": torch.empty((T, I), dtype=adt, device=dev), "dW": torch.empty((O, I), dtype=adt, device=dev),
+                    "ds": torch.empty((O, G), dtype=torch.float32, device=dev),
+                    "dz": torch.empty((O, G), dtype=torch.float32, device=dev)}
+        dsc = eq.make_desc(T, I, O, bits, g, eq._dt(L["X"]), eq._dt(L["W"]))
+        L["ws_f"] = eq.workspace(dsc, eq.OP_FQ_FWD, dev)
+        L["ws_b"] = eq.workspace(dsc, eq.OP_FQ_BWD, dev)
+        layers.append(L)
+    return layers
+
+
+def run_block_ap_step(eq, layers, bits, g):
+    for L in layers:
+        eq.eqat_fq_linear_fwd(L["X"], L["W"], L["s"], L["z"], bits, g, Y=L["Y"], ws=L["ws_f"])
+        eq.eqat_fq_linear_bwd(L["X"], L["W"], L["s"], L["z"], L["dY"], bits, g, out=L["out"], ws=L["ws_b"])
 
 
 def measure_other_rows(torch, eq, layers, bits, g, adt, dev, args):
@@ -267,8 +279,35 @@ def measure_other_rows(torch, eq, layers, bits, g, adt, dev, args):
     rows["eqat_init_minmax_28672x8192"] = hbm_row(init_big, n2 * (wbytes + 8.0 / g))
     del big
     rows["qlinear_fwd_1_token"] = decode_rows(torch, eq, bits, g, dev, args)
+    rows["block_ap_llama2_70b_w2g64"] = stacked_rows(torch, eq, dev, args)
     rows["vendor_gemm_reference"] = vendor_gemm_rows(torch, layers, layers[0]["X"].shape[0], args)
     return rows
+
+
+def stacked_rows(torch, eq, dev, args):
+    """Block-AP step of the 70B-shaped block (4096 tokens, grouped-query attention: k and v are 1024 x 8192), once as
+    seven launches and once with q|k|v and gate|up stacked along the output dimension (four launches).  Groups run
+    along the input dimension, so the stack is quantized row by row exactly like its parts."""
+    from paper_2407_11062_amd import synth
+    out = {}
+    for key, name in (("seven_linears", "llama2_70b_w2g64"), ("qkv_and_gate_up_stacked", "llama2_70b_w2g64_fused")):
+        wl = synth.WORKLOADS[name]
+        layers = build_layers(torch, eq, synth, wl, dev)
+        for _ in range(2):
+            run_block_ap_step(eq, layers, wl.bits, wl.group)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            run_block_ap_step(eq, layers, wl.bits, wl.group)
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / args.steps
+        fl = 6.0 * wl.tokens * sum(L["O"] * L["I"] for L in layers)
+        out[key] = {"tokens": wl.tokens, "launch_groups": len(layers), "ms_per_step": round(dt * 1e3, 4),
+                    "tflops": round(fl / dt / 1e12, 2),
+                    "pct_of_bf16_mfma_peak": round(100 * fl / dt / 1e12 / PEAK_BF16_TFLOPS, 2)}
+        del layers
+        torch.cuda.empty_cache()
+    return out
 
 
 def vendor_gemm_rows(torch, layers, T, args):

@@ -36,6 +36,16 @@ def llama_block(hidden: int, inter: int, kv: int | None = None):
     ]
 
 
+def llama_block_fused(hidden: int, inter: int, kv: int | None = None):
+    """The same block with the linears that share an input stacked along the output dimension (q|k|v and gate|up).
+    Groups run along the input dimension, so a stack of weight matrices is quantised exactly like its parts."""
+    kv = hidden if kv is None else kv
+    return [
+        Linear("qkv", hidden + 2 * kv, hidden), Linear("o", hidden, hidden),
+        Linear("gate_up", 2 * inter, hidden), Linear("down", hidden, inter),
+    ]
+
+
 @dataclass(frozen=True)
 class Workload:
     name: str
@@ -60,6 +70,8 @@ WORKLOADS = {
                                   ("block_ap", "e2e_qp")),
     "llama2_70b_w2g64": Workload("llama2_70b_w2g64", tuple(llama_block(8192, 28672, 1024)), 4096, 2, 64, 0.015,
                                  "bf16", ("block_ap", "e2e_qp")),
+    "llama2_70b_w2g64_fused": Workload("llama2_70b_w2g64_fused", tuple(llama_block_fused(8192, 28672, 1024)), 4096, 2,
+                                       64, 0.015, "bf16", ("block_ap", "e2e_qp")),
 }
 
 

@@ -313,3 +313,54 @@ def test_few_token_kernel_and_gemm_agree_across_the_switch():
     Y17 = eq.eqat_qlinear_fwd(Xd, Wp, sd, zp, 2, 64)
     Y16 = eq.eqat_qlinear_fwd(Xd[:16].contiguous(), Wp, sd, zp, 2, 64)
     assert relerr(Y16, npf(Y17[:16]).astype(np.float64)) <= 1e-2
+
+
+# ---------------------------------------------------------------- the rest of the paper's (N, g) grid; stacked linears
+
+# (N, g) pairs of the paper's bit-width / group-size tables that the cases above do not reach
+GRID_REST = [(2, 32), (2, 128), (2, 256), (3, 64), (3, 256), (3, -1), (4, 64), (4, -1)]
+
+
+@pytest.mark.parametrize("bits,g", GRID_REST)
+def test_grid_rest_block_ap_and_e2e(bits, g):
+    tag = ("grid", bits, g)
+    X, W, s, z, dY = make_case(tag, 200, 512, 72, bits, g, torch.bfloat16, torch.bfloat16)
+    check_block_ap(X, W, s, z, dY, bits, g, TOL[torch.bfloat16])
+    check_e2e(X, W, s, z, dY, bits, g, TOL[torch.bfloat16])
+    check_e2e_trained_z(X, W, s, z, dY, bits, g, TOL[torch.bfloat16], synth.seed_of(tag, "zdrift"))
+
+
+def test_stacked_linears_equal_their_parts():
+    """q|k|v (or gate|up) share their input; groups run along the input dimension, so the three weight matrices stacked
+    along the output dimension are ONE quantized linear whose every per-row result is that of the part it came from."""
+    bits, g, T, I = 2, 64, 300, 256
+    parts = [("q", 264), ("k", 40), ("v", 40)]
+    Xs = synth.normal((T, I), 1.0, synth.seed_of("stack", "X"), torch.bfloat16)
+    Ws, ss, zs, dYs = [], [], [], []
+    for name, O in parts:
+        _, W, s, z, dY = make_case(("stack", name), T, I, O, bits, g, torch.bfloat16, torch.bfloat16)
+        Ws.append(W), ss.append(s), zs.append(z), dYs.append(dY)
+    Xd = dev(Xs)
+    Wc, sc, zc, dYc = dev(torch.cat(Ws)), dev(torch.cat(ss)), dev(torch.cat(zs)), dev(torch.cat(dYs, dim=1))
+    Y = eq.eqat_fq_linear_fwd(Xd, Wc, sc, zc, bits, g)
+    out = eq.eqat_fq_linear_bwd(Xd, Wc, sc, zc, dYc, bits, g)
+    Wp, zp = eq.eqat_pack(Wc, sc, zc.clamp(0, 3), bits, g)
+    dX_sum = torch.zeros((T, I), dtype=torch.float64)
+    r0 = 0
+    for (name, O), W, s, z, dY in zip(parts, Ws, ss, zs, dYs):
+        Wd, sd, zd, dYd = dev(W), dev(s), dev(z), dev(dY)
+        rows = slice(r0, r0 + O)
+        # every output element is accumulated over the same contraction in the same order: bitwise equal
+        assert torch.equal(Y[:, rows], eq.eqat_fq_linear_fwd(Xd, Wd, sd, zd, bits, g)), name
+        part = eq.eqat_fq_linear_bwd(Xd, Wd, sd, zd, dYd, bits, g)
+        for k in ("dW", "ds", "dz"):
+            assert torch.equal(out[k][rows], part[k]), (name, k)
+        Wp1, zp1 = eq.eqat_pack(Wd, sd, zd.clamp(0, 3), bits, g)
+        assert torch.equal(Wp[rows], Wp1) and torch.equal(zp[rows], zp1), name
+        dX_sum += part["dX"].double().cpu()
+        r0 += O
+    # dX of the stack is the sum of the parts' dX (what the shared input receives), here up to bf16 rounding of the parts
+    assert relerr(out["dX"], dX_sum.numpy()) <= TOL[torch.bfloat16]
+    # and against the oracle on the stack itself
+    ref = oracle.fq_linear_bwd(None, npf(Wc), sc.cpu().numpy(), zc.cpu().numpy(), npf(dYc), bits, g, want=("dX",))
+    assert relerr(out["dX"], ref["dX"]) <= TOL[torch.bfloat16]

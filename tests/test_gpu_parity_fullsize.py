@@ -41,6 +41,7 @@ CASES = [
     ("llama2_7b_e2e_qp_w2g64", "q"), ("llama2_7b_e2e_qp_w2g64", "down"),
     ("llama2_13b_w3g128", "q"), ("llama2_13b_w3g128", "gate"),
     ("llama2_70b_w2g64", "k"), ("llama2_70b_w2g64", "gate"), ("llama2_70b_w2g64", "down"),
+    ("llama2_70b_w2g64_fused", "qkv"),      # q|k|v stacked along the output dimension: one launch instead of three
 ]
 
 
