@@ -208,3 +208,27 @@ def qlinear_bwd_z(X, Wp, s, z, dY, I, bits, g, want=("dX", "ds", "dz")):
     _check(_load().eqo_qlinear_bwd_z(pX, _ptr(Wp), ps, pz, pdY, _ll(T), _ll(I), _ll(O), int(bits), _ll(g),
                                      _ptr(out.get("dX")), _ptr(out.get("ds")), _ptr(out.get("dz"))), "qlinear_bwd_z")
     return out
+
+
+def recon_loss(Y, Yref, want_dY=True):
+    """Block reconstruction loss (Sec. 3.2; the form is our reading): mean squared error and its gradient 2 (Y - Yref) / n."""
+    Y, pY = _f32(Y); Yref, pR = _f32(Yref)
+    if Y.shape != Yref.shape:
+        raise ValueError("shapes differ")
+    loss = ctypes.c_double(0.0)
+    dY = np.empty(Y.shape, np.float64) if want_dY else None
+    _check(_load().eqo_recon_loss(pY, pR, _ll(Y.size), ctypes.byref(loss), _ptr(dY)), "recon_loss")
+    return float(loss.value), dY
+
+
+def adamw(p, grad, m, v, lr, beta1, beta2, eps, weight_decay, step):
+    """One AdamW step (decoupled weight decay, bias correction; step counted from 1).  Returns new (p, m, v) as fp64 arrays."""
+    p = np.array(p, dtype=np.float64, order="C"); m = np.array(m, dtype=np.float64, order="C")
+    v = np.array(v, dtype=np.float64, order="C")
+    grad, pg = _f32(grad)
+    if not (p.shape == grad.shape == m.shape == v.shape):
+        raise ValueError("shapes differ")
+    d = ctypes.c_double
+    _check(_load().eqo_adamw(_ptr(p), pg, _ptr(m), _ptr(v), _ll(p.size), d(lr), d(beta1), d(beta2), d(eps), d(weight_decay),
+                             int(step)), "adamw")
+    return p, m, v

@@ -545,3 +545,43 @@ int eqo_qlinear_bwd_z(const float *X, const uint8_t *Wpacked, const float *s, co
     }
     return fail ? -2 : 0;
 }
+
+/* ------------------------------------------------------------------------------------------------------------------
+ * Block-AP step glue (Sec. 3.2: a block is trained against the output of its full-precision counterpart with a
+ * reconstruction loss; Sec. 4.1 "Training": one learning rate for the quantization parameters, another for the weights).
+ * The paper names neither the form of the loss nor the optimizer.  Taken here: the mean squared error over all elements
+ * of the block output, and AdamW (Adam with bias correction and decoupled weight decay) as published by its authors.
+ * ------------------------------------------------------------------------------------------------------------------ */
+
+/* loss = (1/n) * sum (Y - Yref)^2 ;  dY = d loss / d Y = 2 (Y - Yref) / n.   dY may be NULL. */
+int eqo_recon_loss(const float *Y, const float *Yref, i64 n, double *loss, double *dY)
+{
+    if (n < 1 || !Y || !Yref || !loss) return -1;
+    double acc = 0.0;
+    for (i64 k = 0; k < n; ++k) {
+        const double e = (double)Y[k] - (double)Yref[k];
+        acc += e * e;
+        if (dY) dY[k] = 2.0 * e / (double)n;
+    }
+    *loss = acc / (double)n;
+    return 0;
+}
+
+/* One AdamW step on n parameters, in place (p, m, v), `step` counted from 1:
+ *   p <- p - lr * wd * p
+ *   m <- b1 m + (1 - b1) g ;  v <- b2 v + (1 - b2) g^2
+ *   p <- p - lr * (m / (1 - b1^step)) / (sqrt(v / (1 - b2^step)) + eps)                                              */
+int eqo_adamw(double *p, const float *grad, double *m, double *v, i64 n,
+              double lr, double b1, double b2, double eps, double wd, int step)
+{
+    if (n < 0 || step < 1 || (n > 0 && (!p || !grad || !m || !v))) return -1;
+    const double c1 = 1.0 - pow(b1, (double)step), c2 = 1.0 - pow(b2, (double)step);
+    for (i64 k = 0; k < n; ++k) {
+        const double gk = (double)grad[k];
+        p[k] -= lr * wd * p[k];
+        m[k] = b1 * m[k] + (1.0 - b1) * gk;
+        v[k] = b2 * v[k] + (1.0 - b2) * gk * gk;
+        p[k] -= lr * (m[k] / c1) / (sqrt(v[k] / c2) + eps);
+    }
+    return 0;
+}

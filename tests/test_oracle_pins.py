@@ -480,3 +480,74 @@ def test_a_planted_mistake_is_caught():
     X = np.zeros((1, 32), np.float32); X[0, 0] = 1
     out = oracle.fq_linear_bwd(X, W, np.full((1, 1), s0, np.float32), np.ones((1, 1), np.float32), np.ones((1, 1), np.float32), 2, 32)
     assert out["dz"][0, 0] != -1.0 and out["dz"][0, 0] == -s0
+
+
+# ---------------------------------------------------------------- Block-AP step glue: reconstruction loss and AdamW
+
+def test_recon_loss_against_the_library_mse_and_its_autograd_gradient():
+    import torch
+    r = rng(81)
+    Y = r.normal(size=(7, 33)).astype(np.float32)
+    R = r.normal(size=(7, 33)).astype(np.float32)
+    loss, dY = oracle.recon_loss(Y, R)
+    y = torch.tensor(Y, dtype=torch.float64, requires_grad=True)
+    ref = torch.nn.functional.mse_loss(y, torch.tensor(R, dtype=torch.float64))
+    ref.backward()
+    assert abs(loss - ref.item()) <= 1e-14 * abs(ref.item())
+    np.testing.assert_allclose(dY, y.grad.numpy(), rtol=1e-14, atol=0)
+
+
+def test_recon_loss_closed_forms():
+    R = rng(82).normal(size=(4, 16)).astype(np.float32)
+    loss, dY = oracle.recon_loss(R, R)
+    assert loss == 0.0 and not dY.any()
+    # a constant offset c (exact in binary32 next to these values): loss = c^2, every gradient entry 2c/n, sign of (Y - Yref)
+    Y = (R.astype(np.float64) + 0.5).astype(np.float32)
+    loss, dY = oracle.recon_loss(Y, R)
+    np.testing.assert_allclose(loss, 0.25, rtol=1e-6)
+    np.testing.assert_allclose(dY, np.full(R.shape, 2 * 0.5 / R.size), rtol=1e-6)
+    # a single differing element
+    Y = R.copy(); Y[2, 5] -= 2.0
+    loss, dY = oracle.recon_loss(Y, R)
+    e = float(Y[2, 5]) - float(R[2, 5])
+    assert abs(loss - e * e / R.size) < 1e-15 and dY[2, 5] == 2 * e / R.size and np.count_nonzero(dY) == 1
+
+
+@pytest.mark.parametrize("wd", [0.0, 0.01])
+def test_adamw_against_the_library_optimizer_over_several_steps(wd):
+    import torch
+    r = rng(83)
+    p0 = r.normal(size=(5, 12))
+    p_t = torch.tensor(p0, dtype=torch.float64, requires_grad=True)
+    opt = torch.optim.AdamW([p_t], lr=3e-3, betas=(0.9, 0.95), eps=1e-8, weight_decay=wd)
+    p, m, v = p0.copy(), np.zeros_like(p0), np.zeros_like(p0)
+    for step in range(1, 7):
+        g = r.normal(size=p0.shape).astype(np.float32)
+        p_t.grad = torch.tensor(g, dtype=torch.float64)
+        opt.step()
+        p, m, v = oracle.adamw(p, g, m, v, 3e-3, 0.9, 0.95, 1e-8, wd, step)
+        np.testing.assert_allclose(p, p_t.detach().numpy(), rtol=1e-12, atol=1e-15)
+    st = opt.state[p_t]
+    np.testing.assert_allclose(m, st["exp_avg"].numpy(), rtol=1e-12, atol=1e-18)
+    np.testing.assert_allclose(v, st["exp_avg_sq"].numpy(), rtol=1e-12, atol=1e-18)
+
+
+def test_adamw_first_step_closed_form_and_invariants():
+    # step 1 from zero moments: mhat = g, sqrt(vhat) = |g|  =>  p1 = p0 (1 - lr wd) - lr g / (|g| + eps)
+    p0 = np.array([1.0, -2.0, 0.5, 3.0]); g = np.array([0.5, -0.25, 0.0, 4.0], np.float32)
+    lr, wd, eps = 1e-2, 0.1, 1e-8
+    p, m, v = oracle.adamw(p0, g, np.zeros(4), np.zeros(4), lr, 0.9, 0.999, eps, wd, 1)
+    g64 = g.astype(np.float64)
+    np.testing.assert_allclose(p, p0 * (1 - lr * wd) - lr * g64 / (np.abs(g64) + eps), rtol=1e-13)
+    np.testing.assert_allclose(m, 0.1 * g64, rtol=1e-13)
+    np.testing.assert_allclose(v, 0.001 * g64 ** 2, rtol=1e-12)
+    # decoupled decay: with a zero gradient the parameter only shrinks by lr*wd, whatever its size
+    assert p[2] == 0.5 * (1 - lr * wd)
+    # scale invariance of Adam (eps = 0): multiplying every gradient by 8 changes no parameter
+    a = oracle.adamw(p0, g, 1e-3 * g64, 1e-4 * g64 * g64, lr, 0.9, 0.999, 0.0, 0.0, 3)[0]
+    b = oracle.adamw(p0, 8 * g, 8e-3 * g64, 64e-4 * g64 * g64, lr, 0.9, 0.999, 0.0, 0.0, 3)[0]
+    keep = g != 0
+    np.testing.assert_allclose(a[keep], b[keep], rtol=1e-13)
+    # the step counts from 1: step 0 is rejected (its bias correction divides by zero)
+    with pytest.raises(ValueError):
+        oracle.adamw(p0, g, np.zeros(4), np.zeros(4), lr, 0.9, 0.999, eps, wd, 0)
