@@ -280,6 +280,38 @@ def measure_other_rows(torch, eq, layers, bits, g, adt, dev, args):
     del big
     rows["qlinear_fwd_1_token"] = decode_rows(torch, eq, bits, g, dev, args)
     rows["block_ap_llama2_70b_w2g64"] = stacked_rows(torch, eq, dev, args)
+
+    # Block-AP step glue on the same block: reconstruction loss over the seven output tensors, then one AdamW launch
+    # per linear over {W, s, z} fed by the gradients of the last backward (copies of the parameters, so that the rows
+    # above keep their inputs).  Bytes per element: loss 3 x the activation size (Y, Yref in, dY out); update
+    # p, g in + p out in the parameter's dtype and two fp32 moments in and out.
+    asz = 2 if adt == torch.bfloat16 else 4
+    refs = [(L["Y"], torch.randn_like(L["Y"]), torch.empty_like(L["Y"])) for L in layers]
+    loss = torch.empty(1, dtype=torch.float32, device=dev)
+    lws = torch.empty(eq.lib().eqat_recon_loss_workspace_bytes(), dtype=torch.uint8, device=dev)
+
+    def loss_all():
+        for Y, R, dY in refs:
+            eq.eqat_recon_loss(Y, R, loss=loss, dY=dY, ws=lws)
+
+    rows["eqat_recon_loss"] = hbm_row(loss_all, 3.0 * asz * sum(Y.numel() for Y, _, _ in refs))
+    del refs
+    st = [{"W": L["W"].clone(), "s": L["s"].clone(), "z": L["z"].clone(),
+           "mW": torch.zeros(L["W"].shape, dtype=torch.float32, device=dev),
+           "vW": torch.zeros(L["W"].shape, dtype=torch.float32, device=dev),
+           "ms": torch.zeros_like(L["s"]), "vs": torch.zeros_like(L["s"]),
+           "mz": torch.zeros_like(L["s"]), "vz": torch.zeros_like(L["s"])} for L in layers]
+    hyper = eq.AdamW(2e-5, 1e-4, 0.9, 0.999, 1e-8, 0.0, 0.0, 1)      # Sec. 4.1: learning rates at 2 bit
+
+    def update_all():
+        for L, S in zip(layers, st):
+            eq.eqat_block_ap_update(hyper, bits, g, W=S["W"], dW=L["out"]["dW"], mW=S["mW"], vW=S["vW"],
+                                    s=S["s"], ds=L["out"]["ds"], ms=S["ms"], vs=S["vs"],
+                                    z=S["z"], dz=L["out"]["dz"], mz=S["mz"], vz=S["vz"])
+
+    n_sz = sum(L["s"].numel() for L in layers)
+    rows["eqat_block_ap_update"] = hbm_row(update_all, sum_io * (3.0 * wbytes + 16.0) + 2 * n_sz * 28.0)
+    del st
     rows["vendor_gemm_reference"] = vendor_gemm_rows(torch, layers, layers[0]["X"].shape[0], args)
     return rows
 

@@ -55,7 +55,8 @@ typedef enum {
     EQAT_ERR_DTYPE = 5,     /* unknown dtype value                               */
     EQAT_ERR_ALIGN = 6,     /* pointer not 16-byte (workspace: 256-byte) aligned */
     EQAT_ERR_WORKSPACE = 7, /* workspace missing or too small                    */
-    EQAT_ERR_DEVICE = 8     /* the HIP runtime refused a launch                  */
+    EQAT_ERR_DEVICE = 8,    /* the HIP runtime refused a launch                  */
+    EQAT_ERR_HYPER = 9      /* optimizer constants out of range                  */
 } eqat_status;
 
 typedef enum { EQAT_F32 = 0, EQAT_BF16 = 1 } eqat_dtype;
@@ -162,6 +163,44 @@ eqat_status eqat_qlinear_fwd_z(const eqat_desc *d, const void *X, const uint8_t 
 eqat_status eqat_qlinear_bwd_z(const eqat_desc *d, const void *X, const uint8_t *Wpacked, const float *s,
                                const float *z, const void *dY, void *dX, float *ds, float *dz,
                                void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Block-AP step glue.  Sec. 3.2 trains the quantized block against the output of its full-precision counterpart with
+ * a reconstruction loss; Sec. 4.1 ("Training") gives one learning rate for the quantization parameters and another
+ * for the weights.  The paper names neither the form of the loss nor the optimizer; taken here: the mean squared
+ * error over all elements, and AdamW (bias-corrected Adam with decoupled weight decay).
+ *
+ * eqat_recon_loss:   loss[0] = (1/n) sum (Y - Yref)^2,   dY = 2 (Y - Yref) / n   (dY may be NULL; it must not overlap Y or Yref).
+ *   Y, Yref, dY: n elements of `dtype` (eqat_dtype), device, 16-byte aligned; loss: one float, device.
+ *   ws: eqat_recon_loss_workspace_bytes() bytes, 256-byte aligned.  The sum is taken in a fixed order in binary32.
+ *   n < 1 gives EQAT_ERR_SHAPE.
+ */
+size_t eqat_recon_loss_workspace_bytes(void);
+eqat_status eqat_recon_loss(int64_t n, int32_t dtype, const void *Y, const void *Yref, float *loss, void *dY,
+                            void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * eqat_block_ap_update: one AdamW step, in place, on the three trained tensors of a linear in ONE launch, taking the
+ * gradients as eqat_fq_linear_bwd wrote them (dW in W's dtype, ds and dz fp32).  Per element, in binary32:
+ *   p <- p - lr wd p;  m <- b1 m + (1-b1) g;  v <- b2 v + (1-b2) g^2;
+ *   p <- p - lr (m / (1 - b1^step)) / (sqrt(v / (1 - b2^step)) + eps)
+ * with lr = lr_w, wd = weight_decay_w for W and lr_q, weight_decay_q for s and z.  Moments are fp32 arrays of the
+ * parameter's shape, zero before the first step, owned by the caller.  A NULL parameter pointer (W, s or z) skips that
+ * tensor together with its gradient and moments (E2E-QP trains s alone).  d->tokens and d->act_dtype are ignored.
+ * A bf16 W is rounded to nearest even after the update; steps smaller than half an ulp are lost, so W should be kept
+ * in fp32 while it is trained.  Constants outside 0 <= beta < 1, eps >= 0, step >= 1 give EQAT_ERR_HYPER.
+ * Nothing keeps s positive: the caller must (eqat_fq_linear_* require a positive, normal s).
+ */
+typedef struct eqat_adamw {
+    float lr_w;             /* learning rate of the weights (Sec. 4.1: 2e-5 at 2 bit, 1e-5 at 3 and 4 bit)   */
+    float lr_q;             /* learning rate of step sizes and zero points (Sec. 4.1: 1e-4)                  */
+    float beta1, beta2, eps;
+    float weight_decay_w, weight_decay_q;
+    int32_t step;           /* number of this update, counted from 1                                         */
+} eqat_adamw;
+eqat_status eqat_block_ap_update(const eqat_desc *d, const eqat_adamw *h, void *W, float *s, float *z,
+                                 const void *dW, const float *ds, const float *dz, float *mW, float *vW,
+                                 float *ms, float *vs, float *mz, float *vz, void *stream);
 
 /*
  * Optional per-kernel timing (measurement aid, not part of the paper's method).

@@ -20,11 +20,12 @@ F32, BF16 = 0, 1
 OP_FQ_FWD, OP_FQ_BWD, OP_Q_FWD, OP_Q_BWD = 0, 1, 2, 3
 
 STATUS_NAMES = ["EQAT_OK", "EQAT_ERR_NULL", "EQAT_ERR_SHAPE", "EQAT_ERR_BITS", "EQAT_ERR_GROUP", "EQAT_ERR_DTYPE",
-                "EQAT_ERR_ALIGN", "EQAT_ERR_WORKSPACE", "EQAT_ERR_DEVICE"]
+                "EQAT_ERR_ALIGN", "EQAT_ERR_WORKSPACE", "EQAT_ERR_DEVICE", "EQAT_ERR_HYPER"]
 
 EXPORTS = ["eqat_status_string", "eqat_validate_desc", "eqat_packed_w_bytes", "eqat_packed_z_bytes",
            "eqat_workspace_bytes", "eqat_init_minmax", "eqat_fq_linear_fwd", "eqat_fq_linear_bwd", "eqat_pack",
            "eqat_unpack", "eqat_qlinear_fwd", "eqat_qlinear_bwd", "eqat_qlinear_fwd_z", "eqat_qlinear_bwd_z",
+           "eqat_recon_loss_workspace_bytes", "eqat_recon_loss", "eqat_block_ap_update",
            "eqat_profile_kernels", "eqat_profile_kernel_name",
            "eqat_profile_start", "eqat_profile_stop"]
 
@@ -33,6 +34,12 @@ class Desc(ctypes.Structure):
     _fields_ = [("tokens", ctypes.c_int64), ("in_features", ctypes.c_int64), ("out_features", ctypes.c_int64),
                 ("bits", ctypes.c_int32), ("group", ctypes.c_int32), ("act_dtype", ctypes.c_int32),
                 ("w_dtype", ctypes.c_int32)]
+
+
+class AdamW(ctypes.Structure):
+    _fields_ = [("lr_w", ctypes.c_float), ("lr_q", ctypes.c_float), ("beta1", ctypes.c_float), ("beta2", ctypes.c_float),
+                ("eps", ctypes.c_float), ("weight_decay_w", ctypes.c_float), ("weight_decay_q", ctypes.c_float),
+                ("step", ctypes.c_int32)]
 
 
 class EqatError(RuntimeError):
@@ -69,6 +76,9 @@ def lib():
         L.eqat_qlinear_bwd.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.eqat_qlinear_fwd_z.argtypes = [dp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.eqat_qlinear_bwd_z.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.eqat_recon_loss_workspace_bytes.restype, L.eqat_recon_loss_workspace_bytes.argtypes = sz, []
+        L.eqat_recon_loss.argtypes = [ctypes.c_int64, ctypes.c_int32, vp, vp, vp, vp, vp, sz, vp]
+        L.eqat_block_ap_update.argtypes = [dp, ctypes.POINTER(AdamW)] + [vp] * 13
         L.eqat_profile_kernel_name.restype = ctypes.c_char_p
         L.eqat_profile_kernel_name.argtypes = [ctypes.c_int]
         L.eqat_profile_stop.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64), ctypes.c_int]
@@ -228,6 +238,30 @@ def eqat_qlinear_bwd_z(X, Wpacked, s, z, dY, in_features, bits, group, want=("dX
                                                           _p(out.get("dX")), _p(out.get("ds")), _p(out.get("dz")),
                                                           _p(ws), ws.numel(), _stream()))
     return out
+
+
+def eqat_recon_loss(Y, Yref, want_dY=True, loss=None, dY=None, ws=None):
+    """(loss, dY): loss is a 1-element fp32 device tensor, dY has Y's dtype (None if not wanted)."""
+    n = Y.numel()
+    loss = torch.empty(1, dtype=torch.float32, device=Y.device) if loss is None else loss
+    if want_dY and dY is None:
+        dY = torch.empty_like(Y)
+    if ws is None:
+        ws = torch.empty(lib().eqat_recon_loss_workspace_bytes(), dtype=torch.uint8, device=Y.device)
+    _check("eqat_recon_loss", lib().eqat_recon_loss(n, _dt(Y), _p(Y), _p(Yref), _p(loss), _p(dY if want_dY else None),
+                                                    _p(ws), ws.numel(), _stream()))
+    return loss, (dY if want_dY else None)
+
+
+def eqat_block_ap_update(hyper: AdamW, bits, group, W=None, dW=None, mW=None, vW=None, s=None, ds=None, ms=None, vs=None,
+                         z=None, dz=None, mz=None, vz=None, shape=None):
+    """One AdamW step in place on whichever of W, s, z is given (with its gradient and two fp32 moment tensors).
+    `shape` = (O, I) is needed only when W is not given."""
+    O, I = W.shape if W is not None else shape
+    d = make_desc(0, I, O, bits, group, BF16, _dt(W) if W is not None else F32)
+    _check("eqat_block_ap_update", lib().eqat_block_ap_update(
+        ctypes.byref(d), ctypes.byref(hyper), _p(W), _p(s), _p(z), _p(dW), _p(ds), _p(dz), _p(mW), _p(vW), _p(ms), _p(vs),
+        _p(mz), _p(vz), _stream()))
 
 
 def eqat_profile_start():

@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.environ.get("EQAT_OBJ_DIR", os.path.join(HERE, "_build"))
 LIB = os.environ.get("EQAT_LIB_OUT", os.path.join(HERE, "libeqat.so"))
-SOURCES = ["api.hip", "quant.hip", "gemm_f32.hip", "gemm_mfma.hip", "gemv.hip"]
+SOURCES = ["api.hip", "quant.hip", "gemm_f32.hip", "gemm_mfma.hip", "gemv.hip", "train_step.hip"]
 FLAGS = [*os.environ.get("EQAT_EXTRA_FLAGS", "").split(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off", "-Wall", "-Wno-unused-function", "-Wno-inline-asm",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

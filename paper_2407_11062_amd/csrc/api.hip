@@ -120,6 +120,7 @@ const char *eqat_status_string(int status)
     case EQAT_ERR_ALIGN: return "pointer not 16-byte aligned (workspace: 256-byte)";
     case EQAT_ERR_WORKSPACE: return "workspace missing or too small";
     case EQAT_ERR_DEVICE: return "HIP launch failed";
+    case EQAT_ERR_HYPER: return "optimizer constants out of range (0 <= beta < 1, eps >= 0, step >= 1)";
     default: return "unknown status";
     }
 }
@@ -130,8 +131,9 @@ int eqat_profile_kernels(void) { return eqat::PK_COUNT; }
 
 const char *eqat_profile_kernel_name(int k)
 {
-    static const char *names[eqat::PK_COUNT] = {"init_minmax", "quantize", "e2e_prepare", "gemm_fwd", "gemm_dx",
-                                                "gemm_dw", "reduce_partials", "f32_path", "gemv"};
+    static const char *names[] = {"init_minmax", "quantize", "e2e_prepare", "gemm_fwd", "gemm_dx",
+                                                "gemm_dw", "reduce_partials", "f32_path", "gemv", "recon_loss", "adamw_update"};
+    static_assert(sizeof(names) / sizeof(names[0]) == eqat::PK_COUNT, "one name per kernel class");
     return (k >= 0 && k < eqat::PK_COUNT) ? names[k] : "?";
 }
 
@@ -352,6 +354,46 @@ eqat_status eqat_qlinear_bwd_z(const eqat_desc *d, const void *X, const uint8_t 
                                size_t ws_bytes, void *stream)
 {
     return qlinear_bwd_any(d, X, Wpacked, s, nullptr, z, dY, dX, ds, dz, ws, ws_bytes, stream);
+}
+
+size_t eqat_recon_loss_workspace_bytes(void) { return eqat::recon_loss_ws_bytes(); }
+
+eqat_status eqat_recon_loss(int64_t n, int32_t dtype, const void *Y, const void *Yref, float *loss, void *dY, void *ws,
+                            size_t ws_bytes, void *stream)
+{
+    if (dtype != EQAT_F32 && dtype != EQAT_BF16) return EQAT_ERR_DTYPE;
+    if (n < 1) return EQAT_ERR_SHAPE;
+    EQAT_REQUIRE(Y); EQAT_REQUIRE(Yref); EQAT_REQUIRE(loss);
+    EQAT_ALIGNED(Y); EQAT_ALIGNED(Yref); EQAT_ALIGNED(dY);
+    if (!aligned(loss, 4)) return EQAT_ERR_ALIGN;
+    if (ws == nullptr || ws_bytes < eqat::recon_loss_ws_bytes()) return EQAT_ERR_WORKSPACE;
+    if (!aligned(ws, 256)) return EQAT_ERR_ALIGN;
+    hipStream_t st = (hipStream_t)stream;
+    { ProfScope ps(eqat::PK_LOSS, st); eqat::launch_recon_loss(n, dtype == EQAT_BF16, Y, Yref, loss, dY, static_cast<float *>(ws), st); }
+    return launch_status();
+}
+
+eqat_status eqat_block_ap_update(const eqat_desc *d, const eqat_adamw *h, void *W, float *s, float *z, const void *dW,
+                                 const float *ds, const float *dz, float *mW, float *vW, float *ms, float *vs, float *mz,
+                                 float *vz, void *stream)
+{
+    Problem p;
+    if (eqat_status e = check_desc(d, false, &p)) return e;
+    if (h == nullptr) return EQAT_ERR_NULL;
+    if (!(h->beta1 >= 0.f && h->beta1 < 1.f && h->beta2 >= 0.f && h->beta2 < 1.f && h->eps >= 0.f) || h->step < 1)
+        return EQAT_ERR_HYPER;
+    if (W != nullptr) { EQAT_REQUIRE(dW); EQAT_REQUIRE(mW); EQAT_REQUIRE(vW); EQAT_ALIGNED(W); EQAT_ALIGNED(dW); EQAT_ALIGNED(mW); EQAT_ALIGNED(vW); }
+    if (s != nullptr) { EQAT_REQUIRE(ds); EQAT_REQUIRE(ms); EQAT_REQUIRE(vs); EQAT_ALIGNED(s); EQAT_ALIGNED(ds); EQAT_ALIGNED(ms); EQAT_ALIGNED(vs); }
+    if (z != nullptr) { EQAT_REQUIRE(dz); EQAT_REQUIRE(mz); EQAT_REQUIRE(vz); EQAT_ALIGNED(z); EQAT_ALIGNED(dz); EQAT_ALIGNED(mz); EQAT_ALIGNED(vz); }
+    if (W == nullptr && s == nullptr && z == nullptr) return EQAT_OK;
+    const eqat::AdamGroup groups[3] = {
+        {W, dW, mW, vW, p.O * p.I, h->lr_w, h->weight_decay_w, p.w_bf16},
+        {s, ds, ms, vs, p.O * p.G, h->lr_q, h->weight_decay_q, false},
+        {z, dz, mz, vz, p.O * p.G, h->lr_q, h->weight_decay_q, false},
+    };
+    hipStream_t st = (hipStream_t)stream;
+    { ProfScope ps(eqat::PK_UPDATE, st); eqat::launch_adamw(groups, h->beta1, h->beta2, h->eps, h->step, st); }
+    return launch_status();
 }
 
 }  // extern "C"

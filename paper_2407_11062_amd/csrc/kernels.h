@@ -49,6 +49,20 @@ bool gemv_applies(const Problem &p);
 void launch_gemv(const Problem &p, const void *X, const void *Wpacked, const float *s, const void *zpacked,
                  const float *zfloat, void *Y, hipStream_t st);
 
+// ---- train_step.hip (Block-AP step glue: reconstruction loss, AdamW over {W, s, z}) --------------------
+size_t recon_loss_ws_bytes();
+// loss[0] = mean (Y - Yref)^2, dY (may be NULL) = 2 (Y - Yref) / n; `partial` = recon_loss_ws_bytes() of scratch.
+void launch_recon_loss(int64_t n, bool bf16, const void *Y, const void *Yref, float *loss, void *dY, float *partial,
+                       hipStream_t st);
+struct AdamGroup {                      // one parameter tensor; p == NULL: absent
+    void *p; const void *g; float *m; float *v;
+    int64_t n;
+    float lr, weight_decay;
+    bool bf16;                          // dtype of p and g (moments are always fp32)
+};
+// One launch over three parameter groups (weights, step sizes, zero points); step counts from 1.
+void launch_adamw(const AdamGroup *groups, float beta1, float beta2, float eps, int step, hipStream_t st);
+
 // ---- gemm_f32.hip (fp32 activations; simple tiled FMA kernels, exact division everywhere) --------
 void launch_f32_fwd(const Problem &p, bool packed, const void *X, const void *W_or_codes, const float *s, const void *z_or_sz,
                     void *Y, hipStream_t st);

@@ -6,7 +6,7 @@
 namespace eqat {
 
 enum ProfKernel {
-    PK_INIT_MINMAX = 0, PK_QUANTIZE, PK_PREPARE, PK_GEMM_FWD, PK_GEMM_DX, PK_GEMM_DW, PK_REDUCE, PK_F32, PK_GEMV, PK_COUNT
+    PK_INIT_MINMAX = 0, PK_QUANTIZE, PK_PREPARE, PK_GEMM_FWD, PK_GEMM_DX, PK_GEMM_DW, PK_REDUCE, PK_F32, PK_GEMV, PK_LOSS, PK_UPDATE, PK_COUNT
 };
 
 extern bool g_prof_on;

@@ -22,7 +22,7 @@ import sys
 
 # kernel-name fragment -> name the library's own timers use
 KERNELS = (("k_gemm_q<", None), ("k_gemm_dw", "gemm_dw"), ("k_quantize", "quantize"), ("k_init_minmax", "init_minmax"),
-           ("k_e2e_prepare", "e2e_prepare"))
+           ("k_e2e_prepare", "e2e_prepare"), ("k_gemv", "gemv"), ("k_recon_loss", "recon_loss"), ("k_adamw", "adamw_update"))
 
 
 def _library_kernel(name: str):

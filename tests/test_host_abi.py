@@ -29,8 +29,8 @@ def test_library_exports_every_declared_symbol():
 
 def test_status_strings():
     L = eq.lib()
-    seen = {L.eqat_status_string(i) for i in range(9)}
-    assert len(seen) == 9 and all(s for s in seen)
+    seen = {L.eqat_status_string(i) for i in range(10)}
+    assert len(seen) == 10 and all(s for s in seen)
     assert L.eqat_status_string(99) == b"unknown status"
 
 
@@ -108,6 +108,41 @@ def test_null_alignment_and_workspace_errors_come_back_before_any_launch():
     bad = d(bits=9)
     assert L.eqat_fq_linear_fwd(ctypes.byref(bad), None, None, None, None, None, None, 0, None) == BITS
     assert L.eqat_pack(ctypes.byref(d(group=50)), P, P, P, P, P, None) == GROUP
+
+
+def test_every_kernel_class_has_a_name():
+    L = eq.lib()
+    names = [L.eqat_profile_kernel_name(k) for k in range(L.eqat_profile_kernels())]
+    assert all(n and n != b"?" for n in names) and len(set(names)) == len(names)
+    assert L.eqat_profile_kernel_name(len(names)) == b"?"
+
+
+def test_step_glue_errors_come_back_before_any_launch():
+    L = eq.lib()
+    need = L.eqat_recon_loss_workspace_bytes()
+    assert 0 < need <= 1 << 16
+    assert L.eqat_recon_loss(0, eq.BF16, P, P, P, P, P, need, None) == SHAPE
+    assert L.eqat_recon_loss(64, 5, P, P, P, P, P, need, None) == DTYPE
+    assert L.eqat_recon_loss(64, eq.F32, None, P, P, P, P, need, None) == NULL
+    assert L.eqat_recon_loss(64, eq.F32, P, P, None, P, P, need, None) == NULL
+    assert L.eqat_recon_loss(64, eq.F32, P, P + 4, P, P, P, need, None) == ALIGN
+    assert L.eqat_recon_loss(64, eq.F32, P, P, P, None, P, need - 1, None) == WORKSPACE
+    assert L.eqat_recon_loss(64, eq.F32, P, P, P, None, None, need, None) == WORKSPACE
+    r = ctypes.byref(d())
+    ok = eq.AdamW(2e-5, 1e-4, 0.9, 0.999, 1e-8, 0.0, 0.0, 1)
+    HYPER = eq.STATUS_NAMES.index("EQAT_ERR_HYPER")
+    for bad in (eq.AdamW(2e-5, 1e-4, 1.0, 0.999, 1e-8, 0, 0, 1), eq.AdamW(2e-5, 1e-4, 0.9, -0.1, 1e-8, 0, 0, 1),
+                eq.AdamW(2e-5, 1e-4, 0.9, 0.999, -1.0, 0, 0, 1), eq.AdamW(2e-5, 1e-4, 0.9, 0.999, 1e-8, 0, 0, 0),
+                eq.AdamW(2e-5, 1e-4, float("nan"), 0.999, 1e-8, 0, 0, 1)):
+        assert L.eqat_block_ap_update(r, ctypes.byref(bad), *([P] * 12), None) == HYPER
+    assert L.eqat_block_ap_update(r, None, *([P] * 12), None) == NULL
+    # a parameter that is given needs its gradient and both moments: W, s, z, dW, ds, dz, mW, vW, ms, vs, mz, vz
+    assert L.eqat_block_ap_update(r, ctypes.byref(ok), P, None, None, None, None, None, P, P, None, None, None, None, None) == NULL
+    assert L.eqat_block_ap_update(r, ctypes.byref(ok), None, P, None, None, P, None, None, None, P, None, None, None, None) == NULL
+    assert L.eqat_block_ap_update(r, ctypes.byref(ok), None, None, P, None, None, P, None, None, None, None, P + 8, P, None) == ALIGN
+    assert L.eqat_block_ap_update(ctypes.byref(d(bits=7)), ctypes.byref(ok), *([None] * 12), None) == BITS
+    # nothing to update: fine, and nothing is launched
+    assert L.eqat_block_ap_update(r, ctypes.byref(ok), *([None] * 12), None) == OK
 
 
 def test_nothing_to_do_returns_ok_without_a_device():
