@@ -10,6 +10,9 @@
 `traffic` bytes per launch that crossed the L2 <-> memory-fabric boundary, per library kernel, from two
           `rocprofv3 --pmc` runs of the bench (FETCH_SIZE, then WRITE_SIZE; both in KiB per dispatch), each scaled by
           what the same counter reads for a plain device copy of `copy_bytes` bytes (bench.py --copy-calibration).
+`traffic-rows` the same two counters for every library kernel of a run with launches of several sizes (the benchmark's
+          rows): one line per kernel and grid size (work-items of the launch), so that each matrix shape stands alone.
+          python -m paper_2407_11062_amd.profsum traffic-rows <out.txt> "<command>" <fetch.csv> <write.csv> <copy_fetch.csv> <copy_write.csv> <copy_bytes>
 `counters` mean reading per launch of every counter in the given `rocprofv3 --pmc` CSV files, per library kernel, plus
           the MFMA pipe's share of the busy cycles where both counters are present.
 """
@@ -93,6 +96,34 @@ def traffic(out_json, workload, fetch_csv, write_csv, copy_fetch_csv, copy_write
     print(json.dumps(out, indent=1))
 
 
+def _copy_factor(path, copy_bytes):
+    mean, _ = _mean_per_kernel(path)
+    k = max(mean, key=lambda x: mean[x])          # the copy kernel is the one with the largest mean reading
+    return float(copy_bytes) / (mean[k] * 1024.0)
+
+
+def traffic_rows(out_txt, command, fetch_csv, write_csv, copy_fetch_csv, copy_write_csv, copy_bytes) -> None:
+    f_fac, w_fac = _copy_factor(copy_fetch_csv, copy_bytes), _copy_factor(copy_write_csv, copy_bytes)
+    per = collections.defaultdict(lambda: {"fetch": [], "write": []})
+    for path, fac, key in ((fetch_csv, f_fac, "fetch"), (write_csv, w_fac, "write")):
+        for r in csv.DictReader(open(path)):
+            lab = _library_kernel(r["Kernel_Name"])
+            if lab:
+                per[(lab, int(r["Grid_Size"]))][key].append(float(r["Counter_Value"]) * 1024.0 * fac)
+    with open(out_txt, "w") as f:
+        f.write("rocprofv3 FETCH_SIZE / WRITE_SIZE per launch (MI355X, gfx950): bytes that crossed the L2 <-> memory-fabric\n"
+                "boundary, mean over the launches of one kernel at one grid size; counters scaled by what they read for a\n"
+                "device copy of %d bytes (FETCH_SIZE x%.3f, WRITE_SIZE x%.3f)\n" % (int(float(copy_bytes)), f_fac, w_fac))
+        f.write("command (FETCH_SIZE, then WRITE_SIZE in a run of its own): %s\n\n" % command)
+        f.write("%-16s %12s %9s %14s %14s %14s\n" % ("kernel", "work-items", "launches", "fetch_bytes", "write_bytes", "total_bytes"))
+        for (lab, grid) in sorted(per):
+            d = per[(lab, grid)]
+            fe = sum(d["fetch"]) / max(1, len(d["fetch"]))
+            wr = sum(d["write"]) / max(1, len(d["write"]))
+            f.write("%-16s %12d %9d %14.0f %14.0f %14.0f\n" % (lab, grid, len(d["fetch"]), fe, wr, fe + wr))
+    print(open(out_txt).read())
+
+
 def counters(out_txt, command, *csvs) -> None:
     acc = collections.defaultdict(lambda: collections.defaultdict(list))
     for path in csvs:
@@ -120,6 +151,8 @@ def main(argv):
         trace(*argv[1:5])
     elif len(argv) == 8 and argv[0] == "traffic":
         traffic(*argv[1:])
+    elif len(argv) == 8 and argv[0] == "traffic-rows":
+        traffic_rows(*argv[1:])
     elif len(argv) >= 4 and argv[0] == "counters":
         counters(*argv[1:])
     else:
