@@ -175,6 +175,18 @@ __device__ __forceinline__ void load_to_lds16(const RawRsrc &r, bf16_t *lds_wave
                  :: "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(voffset), "s"(r.w) : "memory", "m0");
 }
 
+// The same with the LDS destination given as a 32-bit LDS address that the caller has built from wave-uniform scalars
+// (so that M0 costs one scalar instruction instead of a 64-bit pointer computation and a v_readfirstlane per load).
+__device__ __forceinline__ uint32_t lds_addr_of(const void *p)
+{
+    return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void *)p;
+}
+__device__ __forceinline__ void load_to_lds16_at(const RawRsrc &r, uint32_t lds_addr_uniform, uint32_t voffset)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                 :: "s"(lds_addr_uniform), "v"(voffset), "s"(r.w) : "memory", "m0");
+}
+
 // Workgroup barrier behind "everything I issued has completed".  The wait is the builtin, not assembly text, so that the
 // compiler's own wait-count bookkeeping knows that its register loads are complete here and inserts no further vmcnt
 // wait while the (untracked) direct-to-LDS loads of the next tile are in flight: such a wait counts ALL outstanding
@@ -213,7 +225,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_q(const GemmQArgs a)
     int tm, tn;
     tile_of_block(a.tiles_m, a.tiles_n, tm, tn, a.band);
     const int m0 = tm * BM, n0 = tn * BN;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wm = wave / WGN, wn = wave % WGN;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WGN, wn = wave % WGN;
 
     const RawRsrc rA = make_raw_rsrc(a.A, a.a_bytes);
     const __amdgpu_buffer_rsrc_t rC = make_rsrc(a.codes, a.codes_bytes);
@@ -224,16 +237,37 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_q(const GemmQArgs a)
     floatx2 stS[2][B_SEGS];
     WhatTable<BITS> tabs[2][B_SEGS];
 
-    // activation tile at k0 -> LDS buffer `buf` (asynchronous)
-    auto load_a = [&](int k0, int buf) {
+    // Activation tiles stream into LDS strictly in order (k0 = 0, BK, 2 BK, ...): every direct-to-LDS instruction keeps
+    // a running byte offset that advances by one tile row segment per call, and M0 comes from wave-uniform scalars.
+    // No test against K: columns past K of a row read the start of the next row (or, behind the last row, fail the
+    // range check and give zeros); they meet weights that are exactly zero (step size and zero point of a column past
+    // the end load as 0), and inputs are finite by contract.
+    const uint32_t ldsA = lds_addr_of(sA);
+    uint32_t offA[A_LOADS];
 #pragma unroll
-        for (int it = 0; it < A_LOADS; ++it) {
-            const int rb = (wave * A_LOADS + it) * 8;                 // first of 8 rows, wave-uniform
-            const int row = rb + (lane >> 3), k = k0 + kc_swz(row, lane & 7) * 8;
-            uint32_t off = (k < a.K) ? ((uint32_t)(m0 + row) * (uint32_t)a.K + (uint32_t)k) * 2u : kOobOffset;
-            load_to_lds16(rA, sA + buf * A_ELEMS + rb * 64, off);
-        }
+    for (int it = 0; it < A_LOADS; ++it) {
+        const int row = (wave * A_LOADS + it) * 8 + (lane >> 3);
+        const uint64_t o = ((uint64_t)(m0 + row) * (uint64_t)a.K + (uint64_t)(kc_swz(row, lane & 7) * 8)) * 2u;
+        offA[it] = o < kOobOffset ? (uint32_t)o : kOobOffset;       // rows past the matrix stay out of range for good
+    }
+    auto load_a_one = [&](int it, int buf) {
+        load_to_lds16_at(rA, ldsA + (uint32_t)((buf * A_ELEMS + (wave * A_LOADS + it) * 8 * 64) * 2), offA[it]);
+        offA[it] += BK * 2;
     };
+    auto load_a = [&](int buf) {
+#pragma unroll
+        for (int it = 0; it < A_LOADS; ++it) load_a_one(it, buf);
+    };
+    // Weight codes and (s, zbar) pairs, also strictly in order.  Forward: a segment's group index wcol / g is carried
+    // from call to call (a tile advances wcol by BK <= 2 g, so two conditional steps replace a division per K tile).
+    int grp[B_SEGS], rem[B_SEGS];
+#pragma unroll
+    for (int it = 0; it < B_SEGS; ++it) {
+        const int sidx = it * NT + tid;
+        const int wcol = BT ? n0 + (sidx % (BN / 32)) * 32 : (sidx % (BK / 32)) * 32;
+        grp[it] = wcol / (int)a.g;
+        rem[it] = wcol % (int)a.g;
+    }
     auto load_codes = [&](auto set, int k0) {
         constexpr int S = decltype(set)::value;
 #pragma unroll
@@ -244,9 +278,18 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_q(const GemmQArgs a)
             else     { wrow = k0 + sidx / (BN / 32); wcol = n0 + (sidx % (BN / 32)) * 32; }
             const bool ok = wcol < a.I;
             stC[S][it] = load_work_codes<BITS>(rC, (uint32_t)wrow * code_row_bytes + (uint32_t)(wcol >> 5) * (4u * WorkCodes<BITS>::kWords));
-            const intx2 sv = buf_load8(rS, ok ? ((uint32_t)wrow * (uint32_t)a.G + (uint32_t)(wcol / a.g)) * 8u : kOobOffset);
+            const intx2 sv = buf_load8(rS, ok ? ((uint32_t)wrow * (uint32_t)a.G + (uint32_t)grp[it]) * 8u : kOobOffset);
             stS[S][it][0] = __int_as_float(sv[0]);
             stS[S][it][1] = __int_as_float(sv[1]);
+            if (!BT) {
+#pragma unroll
+                for (int h = 0; h < BK / 32; ++h) {
+                    rem[it] += 32;
+                    const bool wrap = rem[it] >= (int)a.g;
+                    rem[it] = wrap ? rem[it] - (int)a.g : rem[it];
+                    grp[it] += wrap ? 1 : 0;
+                }
+            }
         }
     };
     // piece P of KK: every KK-th 16-byte store of the staged weight tile
@@ -334,7 +377,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_q(const GemmQArgs a)
         wait_all_and_barrier();   // next activation tile landed, my LDS traffic done
         // last slice of this tile, overlapped with the start of the next two tiles.  (The codes fetched here are first
         // used behind the next barrier, so the compiler never needs a vmcnt wait while the activation loads fly.)
-        load_a((kt + 2) * BK, PAR);
+        load_a(PAR);
         read_frags(0, sA + (PAR ^ 1) * A_ELEMS, sB + (PAR ^ 1) * B_ELEMS, 0);
         mfma_slice(1);
         commit_piece(IC<PAR>{}, IC<0>{}, PAR);
@@ -345,7 +388,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_q(const GemmQArgs a)
 
     const int nk = (a.K + BK - 1) / BK;
     load_codes(IC<0>{}, 0);
-    load_a(0, 0);
+    load_a(0);
     load_codes(IC<1>{}, BK);
     commit_piece(IC<0>{}, IC<0>{}, 0);
     commit_piece(IC<0>{}, IC<1>{}, 0);
@@ -353,7 +396,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_q(const GemmQArgs a)
     commit_piece(IC<0>{}, IC<3>{}, 0);
     wait_all_and_barrier();
     load_codes(IC<0>{}, 2 * BK);
-    load_a(BK, 1);
+    load_a(1);
     commit_piece(IC<1>{}, IC<0>{}, 1);
     read_frags(0, sA, sB, 0);
     // Two tiles per trip, unconditionally (the register staging sets alternate at compile time, and a branch
@@ -447,21 +490,34 @@ __device__ __forceinline__ bf16x8 frag_km_swz(const bf16_t *tile, int col0, int 
     return __builtin_bit_cast(bf16x8, r);
 }
 
-// rows [k0, k0 + BK) x columns [col0, col0 + COLS) of a row-major [rows][ld] bf16 matrix -> LDS tile (asynchronous)
+// Streams consecutive [BK][COLS] row blocks of a row-major [rows][ld] bf16 matrix into LDS tiles, one direct-to-LDS
+// instruction at a time (LOADS per wave and tile, RPI rows each).  Every instruction keeps its own running byte offset,
+// so issuing one costs a scalar move to M0, the load and one add.  Columns past `ld` start at an out-of-range offset and
+// never advance (no wrap-around into range); rows past the end of the matrix fail the buffer's range check.
 template <int BK, int COLS, int NW>
-__device__ __forceinline__ void load_km_tile(const RawRsrc &r, int ld, int col0, int k0, bf16_t *tile, int wave, int lane)
-{
-    constexpr int CPR = COLS / 8, RPI = 64 / CPR, LOADS = BK / RPI / NW;   // chunks per row, rows per instruction
+struct KmLoader {
+    static constexpr int CPR = COLS / 8, RPI = 64 / CPR, LOADS = BK / RPI / NW;   // chunks per row, rows per instruction
     static_assert(BK % (RPI * NW) == 0 && CPR <= 64, "tile / wave mismatch");
+    uint32_t off[LOADS], adv[LOADS];
+    __device__ __forceinline__ void init(int ld, int col0, int wave, int lane)
+    {
 #pragma unroll
-    for (int it = 0; it < LOADS; ++it) {
-        const int rb = (wave * LOADS + it) * RPI;                 // wave-uniform first row
-        const int k = rb + lane / CPR, p = lane % CPR;
-        const int col = col0 + (((p >> 2) ^ (k & 3)) << 5) + (p & 3) * 8;
-        const uint32_t off = (col < ld) ? ((uint32_t)(k0 + k) * (uint32_t)ld + (uint32_t)col) * 2u : kOobOffset;
-        load_to_lds16(r, tile + rb * COLS, off);
+        for (int it = 0; it < LOADS; ++it) {
+            const int rb = (wave * LOADS + it) * RPI;                 // wave-uniform first row
+            const int k = rb + lane / CPR, p = lane % CPR;
+            const int col = col0 + (((p >> 2) ^ (k & 3)) << 5) + (p & 3) * 8;
+            const bool ok = col < ld;
+            off[it] = ok ? ((uint32_t)k * (uint32_t)ld + (uint32_t)col) * 2u : kOobOffset;
+            adv[it] = ok ? (uint32_t)BK * (uint32_t)ld * 2u : 0u;
+        }
     }
-}
+    // instruction `it` of the next tile for this instruction slot; tile_lds = LDS address of the destination tile
+    __device__ __forceinline__ void issue(const RawRsrc &r, int it, uint32_t tile_lds, int wave)
+    {
+        load_to_lds16_at(r, tile_lds + (uint32_t)((wave * LOADS + it) * RPI * COLS * 2), off[it]);
+        off[it] += adv[it];
+    }
+};
 
 template <int BITS, typename WT, bool BLOCK_AP, int BM, int BN, int BK, int WGM, int WGN>
 __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_dw(const GemmDwArgs a)
@@ -479,14 +535,25 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_dw(const GemmDwArgs a)
     int tm, tn;
     tile_of_block(a.tiles_m, a.tiles_n, tm, tn);
     const int m0 = tm * BM, n0 = tn * BN;      // m0: first in-feature i, n0: first out-feature o
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wm = wave / WGN, wn = wave % WGN;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WGN, wn = wave % WGN;
 
     const RawRsrc rX = make_raw_rsrc(a.X, a.x_bytes);
     const RawRsrc rY = make_raw_rsrc(a.dY, a.dy_bytes);
-
-    auto load_tiles = [&](int k0, int buf) {
-        load_km_tile<BK, BM, NW>(rX, a.I, m0, k0, sA + buf * A_ELEMS, wave, lane);
-        load_km_tile<BK, BN, NW>(rY, a.O, n0, k0, sB + buf * B_ELEMS, wave, lane);
+    const uint32_t ldsA = lds_addr_of(sA), ldsB = lds_addr_of(sB);
+    KmLoader<BK, BM, NW> ldX;
+    KmLoader<BK, BN, NW> ldY;
+    ldX.init((int)a.I, m0, wave, lane);
+    ldY.init((int)a.O, n0, wave, lane);
+    constexpr int LA = KmLoader<BK, BM, NW>::LOADS, LB = KmLoader<BK, BN, NW>::LOADS, ND = LA + LB;
+    // load number d (0 .. ND-1) of the NEXT K tile (tiles are fetched strictly in order) into LDS buffer `buf`
+    auto issue_load = [&](int d, int buf) {
+        if (d < LA) ldX.issue(rX, d, ldsA + (uint32_t)(buf * A_ELEMS * 2), wave);
+        else ldY.issue(rY, d - LA, ldsB + (uint32_t)(buf * B_ELEMS * 2), wave);
+    };
+    auto load_tiles = [&](int buf) {
+#pragma unroll
+        for (int d = 0; d < ND; ++d) issue_load(d, buf);
     };
 
     floatx16 acc[MI][NI];
@@ -535,19 +602,33 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_dw(const GemmDwArgs a)
         weave();
         __builtin_amdgcn_sched_barrier(0);
         wait_all_and_barrier();
-        load_tiles((kt + 2) * BK, buf);
-        __builtin_amdgcn_sched_barrier(0);
-        read_frags(0, buf ^ 1, 0);
-        mfma_slice(1);
-        weave();
-        __builtin_amdgcn_sched_barrier(0);
+        // Last slice, in a fixed order: an MFMA first, then in its shadow one or two of the loads for the tile after the
+        // next and a fragment of the next tile's first slice.  (Issued as a block in front of the MFMAs, the loads kept
+        // the MFMA pipe of both waves of a SIMD empty for their whole issue sequence right after every barrier.)
+        constexpr int NQ = MI * NI, NF = NI + MI;
+#pragma unroll
+        for (int q = 0; q < NQ; ++q) {
+            const int i = q / NI, j = q % NI;
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[1][i], fb[1][j], acc[i][j], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int d = 0; d < ND; ++d)
+                if (d * NQ / ND == q) issue_load(d, buf);
+#pragma unroll
+            for (int f = 0; f < NF; ++f) {
+                if (f * NQ / NF != q) continue;
+                if (f < NI) fb[0][f] = frag_km_swz<BN>(sB + (buf ^ 1) * B_ELEMS, wn * WTN + f * 32, 0, lane);
+                else fa[0][f - NI] = frag_km_swz<BM>(sA + (buf ^ 1) * A_ELEMS, wm * WTM + (f - NI) * 32, 0, lane);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
     };
 
     const int nk = (a.T + BK - 1) / BK;
     if (nk > 0) {
-        load_tiles(0, 0);
+        load_tiles(0);
         wait_all_and_barrier();
-        load_tiles(BK, 1);
+        load_tiles(1);
         read_frags(0, 0, 0);
         for (int kt = 0; kt < nk; ++kt) step(kt & 1, kt);
     }
