@@ -20,7 +20,7 @@
  *              are always fp32.  act bf16 selects the MFMA path (needs O % 8 == 0);
  *              act fp32 selects the fp32 path.
  *   Shapes     I % 32 == 0; g > 0, g % 32 == 0, g | I (group = -1 means g = I);
- *              bits in {2,3,4}; T >= 0, O >= 1.
+ *              bits in {2,3,4}; T >= 0, O >= 1; with bf16 activations I, O < 2^22.
  *   Stream     `stream` is a hipStream_t (NULL = default stream).  All work is
  *              enqueued there; no call synchronises.  Outputs are overwritten.
  *   Workspace  Caller-provided scratch of at least eqat_workspace_bytes(desc, op)
@@ -50,6 +50,7 @@ typedef enum {
     EQAT_OK = 0,
     EQAT_ERR_NULL = 1,      /* a required pointer is NULL                        */
     EQAT_ERR_SHAPE = 2,     /* T < 0, I or O < 1, I % 32, O % 8 (bf16), >= 2 GiB */
+                            /* or, with bf16 activations, I or O >= 2^22         */
     EQAT_ERR_BITS = 3,      /* bits not in {2,3,4}                               */
     EQAT_ERR_GROUP = 4,     /* group not -1 and (<= 0, % 32 != 0 or not | I)     */
     EQAT_ERR_DTYPE = 5,     /* unknown dtype value                               */

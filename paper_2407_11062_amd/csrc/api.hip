@@ -55,6 +55,8 @@ eqat_status check_desc(const eqat_desc *d, bool with_tokens, Problem *p)
     if (O * I * dsize(d->w_dtype) >= kMaxTensorBytes) return EQAT_ERR_SHAPE;
     if (with_tokens) {
         if (d->act_dtype == EQAT_BF16 && O % 8 != 0) return EQAT_ERR_SHAPE;
+        // the MFMA kernels keep running 32-bit byte offsets that step a few K tiles past the end of a tensor
+        if (d->act_dtype == EQAT_BF16 && (I >= ((int64_t)1 << 22) || O >= ((int64_t)1 << 22))) return EQAT_ERR_SHAPE;
         if (T * I * dsize(d->act_dtype) >= kMaxTensorBytes || T * O * dsize(d->act_dtype) >= kMaxTensorBytes)
             return EQAT_ERR_SHAPE;
     }
@@ -113,7 +115,7 @@ const char *eqat_status_string(int status)
     switch (status) {
     case EQAT_OK: return "ok";
     case EQAT_ERR_NULL: return "a required pointer is NULL";
-    case EQAT_ERR_SHAPE: return "bad shape (T<0, I or O < 1, I % 32 != 0, O % 8 != 0 with bf16 activations, or a tensor of 2 GiB or more)";
+    case EQAT_ERR_SHAPE: return "bad shape (T<0, I or O < 1, I % 32 != 0, with bf16 activations O % 8 != 0 or I or O >= 2^22, or a tensor of 2 GiB or more)";
     case EQAT_ERR_BITS: return "bits must be 2, 3 or 4";
     case EQAT_ERR_GROUP: return "group must be -1 or a positive multiple of 32 that divides in_features";
     case EQAT_ERR_DTYPE: return "unknown dtype";

@@ -519,18 +519,21 @@ struct KmLoader {
     }
 };
 
-template <int BITS, typename WT, bool BLOCK_AP, int BM, int BN, int BK, int WGM, int WGN>
+// s_waitcnt operand: "at most N vector-memory operations still outstanding, all LDS operations complete".
+constexpr int waitcnt_vm_lgkm0(int n) { return (n & 15) | 0x70 | ((n >> 4) << 14); }
+
+template <int BITS, typename WT, bool BLOCK_AP, int BM, int BN, int BK, int NS, int WGM, int WGN>
 __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_dw(const GemmDwArgs a)
 {
     constexpr int NT = 64 * WGM * WGN, NW = WGM * WGN, WTM = BM / WGM, WTN = BN / WGN, MI = WTM / 32, NI = WTN / 32;
-    constexpr int A_ELEMS = BK * BM, B_ELEMS = BK * BN;
-    static_assert(BK == 64, "four 16-wide slices per tile");
-    static_assert(2 * (A_ELEMS + B_ELEMS) * 2 >= 2 * (BM / 32) * BN * 4, "partials must fit in the tile buffers");
+    constexpr int A_ELEMS = BK * BM, B_ELEMS = BK * BN, KK = BK / 16;
+    static_assert(BK % 16 == 0 && KK >= 2 && NS >= 2, "16-wide slices, at least two per tile; at least two LDS stages");
+    static_assert(NS * (A_ELEMS + B_ELEMS) * 2 >= 2 * (BM / 32) * BN * 4, "partials must fit in the tile buffers");
 
     want_agpr_accumulators<MI * NI * 16>();
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-    bf16_t *sA = reinterpret_cast<bf16_t *>(smem_raw);
-    bf16_t *sB = sA + 2 * A_ELEMS;
+    bf16_t *sA = reinterpret_cast<bf16_t *>(smem_raw);            // [NS][A_ELEMS]
+    bf16_t *sB = sA + NS * A_ELEMS;                               // [NS][B_ELEMS]
 
     int tm, tn;
     tile_of_block(a.tiles_m, a.tiles_n, tm, tn);
@@ -579,8 +582,14 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_dw(const GemmDwArgs a)
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[slot][i], fb[slot][j], acc[i][j], 0, 0, 0);
     };
     // Same pipeline as the forward kernel: the barrier sits before the last slice, whose MFMAs then cover the first
-    // fragment reads of the next tile and the issue of the loads for the tile after it.
-    auto step = [&](int buf, int kt) {
+    // fragment reads of the next tile and the issue of the loads for a later tile.  The K tiles go round a ring of NS
+    // LDS stages: behind the barrier of tile kt the stage of tile kt itself is free (its last fragments are in
+    // registers) and takes tile kt + NS, so a load has NS - 1 tile times to land; the barrier waits only for the loads
+    // of tile kt + 1 (vector-memory operations complete in order: "all but the newest (NS - 2) batches").
+    // P = fragment slot that holds slice 0 of this tile; slices alternate slots, so the next tile starts in slot
+    // (P + KK) & 1.
+    auto step = [&](auto par, int buf, int nxt) {
+        constexpr int P = decltype(par)::value;
         // fragment reads of the next slice spread between the MFMAs of this one (see the forward kernel)
         auto weave = [&]() {
 #pragma unroll
@@ -589,27 +598,25 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_dw(const GemmDwArgs a)
                 __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);
             }
         };
-        read_frags(1, buf, 1);
-        mfma_slice(0);
-        weave();
-        __builtin_amdgcn_sched_barrier(0);
-        read_frags(0, buf, 2);
-        mfma_slice(1);
-        weave();
-        __builtin_amdgcn_sched_barrier(0);
-        read_frags(1, buf, 3);
-        mfma_slice(0);
-        weave();
-        __builtin_amdgcn_sched_barrier(0);
-        wait_all_and_barrier();
-        // Last slice, in a fixed order: an MFMA first, then in its shadow one or two of the loads for the tile after the
-        // next and a fragment of the next tile's first slice.  (Issued as a block in front of the MFMAs, the loads kept
-        // the MFMA pipe of both waves of a SIMD empty for their whole issue sequence right after every barrier.)
-        constexpr int NQ = MI * NI, NF = NI + MI;
+#pragma unroll
+        for (int kk = 0; kk + 1 < KK; ++kk) {
+            read_frags((P + kk + 1) & 1, buf, kk + 1);
+            mfma_slice((P + kk) & 1);
+            weave();
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0((NS - 2) * ND));
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        // Last slice, in a fixed order: an MFMA first, then in its shadow one or two of the loads for tile kt + NS and
+        // a fragment of the next tile's first slice.  (Issued as a block in front of the MFMAs, the loads kept the MFMA
+        // pipe of both waves of a SIMD empty for their whole issue sequence right after every barrier.)
+        constexpr int NQ = MI * NI, NF = NI + MI, SL = (P + KK - 1) & 1, SN = SL ^ 1;
 #pragma unroll
         for (int q = 0; q < NQ; ++q) {
             const int i = q / NI, j = q % NI;
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[1][i], fb[1][j], acc[i][j], 0, 0, 0);
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[SL][i], fb[SL][j], acc[i][j], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int d = 0; d < ND; ++d)
@@ -617,8 +624,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_dw(const GemmDwArgs a)
 #pragma unroll
             for (int f = 0; f < NF; ++f) {
                 if (f * NQ / NF != q) continue;
-                if (f < NI) fb[0][f] = frag_km_swz<BN>(sB + (buf ^ 1) * B_ELEMS, wn * WTN + f * 32, 0, lane);
-                else fa[0][f - NI] = frag_km_swz<BM>(sA + (buf ^ 1) * A_ELEMS, wm * WTM + (f - NI) * 32, 0, lane);
+                if (f < NI) fb[SN][f] = frag_km_swz<BN>(sB + nxt * B_ELEMS, wn * WTN + f * 32, 0, lane);
+                else fa[SN][f - NI] = frag_km_swz<BM>(sA + nxt * A_ELEMS, wm * WTM + (f - NI) * 32, 0, lane);
             }
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -626,11 +633,23 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_dw(const GemmDwArgs a)
 
     const int nk = (a.T + BK - 1) / BK;
     if (nk > 0) {
-        load_tiles(0);
-        wait_all_and_barrier();
-        load_tiles(1);
+#pragma unroll
+        for (int st = 0; st < NS; ++st) load_tiles(st);            // tiles 0 .. NS-1 (past T: zeros)
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0((NS - 1) * ND));      // tile 0 has landed
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
         read_frags(0, 0, 0);
-        for (int kt = 0; kt < nk; ++kt) step(kt & 1, kt);
+        // Two tiles per trip, so that the fragment slots alternate at compile time when a tile has an odd number of
+        // slices; with an odd tile count the extra tile lies past T and multiplies zeros.
+        int buf = 0;
+        for (int kt = 0; kt < nk; kt += 2) {
+            int nxt = buf + 1 == NS ? 0 : buf + 1;
+            step(IC<0>{}, buf, nxt);
+            buf = nxt; nxt = buf + 1 == NS ? 0 : buf + 1;
+            step(IC<(KK & 1)>{}, buf, nxt);
+            buf = nxt;
+        }
     }
     wait_all_and_barrier();   // tile buffers become the partial-sum arrays
 
@@ -742,6 +761,15 @@ template <int BM_, int BN_, int BK_, int WGM_, int WGN_> struct Tile {
 };
 typedef Tile<128, 128, 64, 2, 2> TileSmall;   // 4 waves, 64x64 per wave: problems with few big tiles
 typedef Tile<256, 256, 64, 2, 4> TileBig;     // 8 waves, 128x64 per wave
+// dW: same output tiles.  The kernel takes any number of LDS stages NS and any K-tile width; measured, two stages of 64
+// win: the big tile fits three stages only with 48-wide K tiles (3 x 48 KB), whose extra barriers cost what the deeper
+// prefetch gains (-1 %); the small tile with three stages (96 KB) loses the second workgroup per CU (-17 %).
+template <int BM_, int BN_, int BK_, int NS_, int WGM_, int WGN_> struct DwTile {
+    static constexpr int BM = BM_, BN = BN_, BK = BK_, NS = NS_, WGM = WGM_, WGN = WGN_;
+};
+typedef DwTile<128, 128, 64, 2, 2, 2> DwTileSmall;
+typedef DwTile<256, 256, 64, 2, 2, 4> DwTileBig;
+static_assert(DwTileSmall::BM == TileSmall::BM && DwTileBig::BM == TileBig::BM, "group-fits-in-tile tests use Tile*::BM");
 
 // EQAT_TILE=0/1 forces the small / big tile (tuning aid)
 int tile_override()
@@ -784,8 +812,9 @@ void launch_q_bits(int bits, const GemmQArgs &a, hipStream_t st)
 template <int BITS, typename WT, bool AP, typename TS>
 void launch_dw_t(const GemmDwArgs &args, hipStream_t st)
 {
-    constexpr size_t smem = 2 * (size_t)TS::BK * (TS::BM + TS::BN) * sizeof(bf16_t);
-    auto kern = k_gemm_dw<BITS, WT, AP, TS::BM, TS::BN, TS::BK, TS::WGM, TS::WGN>;
+    constexpr size_t smem = (size_t)TS::NS * TS::BK * (TS::BM + TS::BN) * sizeof(bf16_t);
+    static_assert(smem <= 160 * 1024, "LDS of one CU");
+    auto kern = k_gemm_dw<BITS, WT, AP, TS::BM, TS::BN, TS::BK, TS::NS, TS::WGM, TS::WGN>;
     static bool attr_set = false;
     if (!attr_set) { (void)hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem); attr_set = true; }
     GemmDwArgs a = args;
@@ -799,7 +828,7 @@ template <typename WT, bool AP>
 bool launch_dw_bits(int bits, const GemmDwArgs &a, hipStream_t st)      // returns whether per-segment partials were written
 {
     const bool small = use_small_tile(a.I, a.O);
-#define EQAT_GO(B) do { if (small) launch_dw_t<B, WT, AP, TileSmall>(a, st); else launch_dw_t<B, WT, AP, TileBig>(a, st); } while (0)
+#define EQAT_GO(B) do { if (small) launch_dw_t<B, WT, AP, DwTileSmall>(a, st); else launch_dw_t<B, WT, AP, DwTileBig>(a, st); } while (0)
     if (bits == 2) EQAT_GO(2); else if (bits == 3) EQAT_GO(3); else EQAT_GO(4);
 #undef EQAT_GO
     return ((small ? TileSmall::BM : TileBig::BM) % a.g) != 0;

@@ -42,6 +42,8 @@ def test_status_strings():
     (dict(act=2), DTYPE), (dict(w=7), DTYPE),
     (dict(T=40000, I=28672), SHAPE),                      # X would be 2 GiB or more
     (dict(O=32768, I=32768, w=eq.F32), SHAPE),            # W would be 4 GiB
+    (dict(T=8, O=8, I=1 << 22), SHAPE),                   # bf16 path: I, O < 2^22
+    (dict(T=8, O=8, I=(1 << 22) - 32, group=-1), OK),
     (dict(), OK), (dict(group=-1), OK), (dict(O=12, act=eq.F32), OK), (dict(T=0), OK), (dict(I=96, group=96, bits=3), OK),
 ])
 def test_descriptor_validation(kw, code):
