@@ -450,10 +450,15 @@ template <> struct WQuad<bf16_t> {
         v[0] = __uint_as_float((uint32_t)u[0] << 16); v[1] = __uint_as_float((uint32_t)u[0] & 0xFFFF0000u);
         v[2] = __uint_as_float((uint32_t)u[1] << 16); v[3] = __uint_as_float((uint32_t)u[1] & 0xFFFF0000u);
     }
-    static __device__ __forceinline__ void store(void *base, size_t elem, const float (&d)[4])
+    // through a buffer resource: an element index past the buffer (or a resource of zero bytes) drops the store
+    static __device__ __forceinline__ void store(__amdgpu_buffer_rsrc_t r, uint32_t elem, const float (&d)[4])
     {
-        bf16x4 o; o[0] = (bf16_t)d[0]; o[1] = (bf16_t)d[1]; o[2] = (bf16_t)d[2]; o[3] = (bf16_t)d[3];
-        *reinterpret_cast<bf16x4 *>(reinterpret_cast<bf16_t *>(base) + elem) = o;
+        floatx2 lo, hi;
+        lo[0] = d[0]; lo[1] = d[1]; hi[0] = d[2]; hi[1] = d[3];
+        const bf16x2 a = __builtin_convertvector(lo, bf16x2), b = __builtin_convertvector(hi, bf16x2);   // one packed convert each
+        intx2 o;
+        o[0] = __builtin_bit_cast(int, a); o[1] = __builtin_bit_cast(int, b);
+        __builtin_amdgcn_raw_buffer_store_b64(o, r, (int)(elem * 2u), 0, 0);
     }
 };
 template <> struct WQuad<float> {
@@ -463,10 +468,11 @@ template <> struct WQuad<float> {
         const intx4 u = buf_load16(r, elem * 4u);
         v[0] = __int_as_float(u[0]); v[1] = __int_as_float(u[1]); v[2] = __int_as_float(u[2]); v[3] = __int_as_float(u[3]);
     }
-    static __device__ __forceinline__ void store(void *base, size_t elem, const float (&d)[4])
+    static __device__ __forceinline__ void store(__amdgpu_buffer_rsrc_t r, uint32_t elem, const float (&d)[4])
     {
-        floatx4 o; o[0] = d[0]; o[1] = d[1]; o[2] = d[2]; o[3] = d[3];
-        *reinterpret_cast<floatx4 *>(reinterpret_cast<float *>(base) + elem) = o;
+        intx4 o;
+        o[0] = __float_as_int(d[0]); o[1] = __float_as_int(d[1]); o[2] = __float_as_int(d[2]); o[3] = __float_as_int(d[3]);
+        __builtin_amdgcn_raw_buffer_store_b128(o, r, (int)(elem * 4u), 0, 0);
     }
 };
 
@@ -660,49 +666,79 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_dw(const GemmDwArgs a)
     const __amdgpu_buffer_rsrc_t rS = make_rsrc(a.sz, a.sz_bytes);
     const __amdgpu_buffer_rsrc_t rW = make_rsrc(a.W, a.w_bytes);
     const __amdgpu_buffer_rsrc_t rB = make_rsrc(a.clampbits, a.clamp_bytes);
+    const __amdgpu_buffer_rsrc_t rDW = make_rsrc(a.dW, a.dW != nullptr ? a.w_bytes : 0u);    // no dW wanted: stores dropped
     const uint32_t code_row_bytes = (uint32_t)a.I / 32u * (4u * WorkCodes<BITS>::kWords);
     const int h = lane >> 5;
 
+    // Two passes per output row of the wave: first EVERY global load of its MI blocks is issued (codes, (s, zbar), clamp
+    // bits, the 16 weights of this lane per block), then the blocks are worked through as the data arrives.  One block
+    // at a time (load, wait, compute, store, next block) put two memory round trips and the acknowledgement of the
+    // previous block's stores on the critical path of each of the 8 blocks.
+    struct BlockOps { WorkCodes<BITS> cw; intx2 sv; uint32_t ncl; WQuad<WT> wq[4]; };
 #pragma unroll
     for (int j = 0; j < NI; ++j) {
         const int ol = wn * WTN + j * 32 + (lane & 31), o = n0 + ol;
+        BlockOps ops[MI];
 #pragma unroll
         for (int i = 0; i < MI; ++i) {
             const int ib = m0 + wm * WTM + i * 32;                 // first of 32 in-features; whole block valid or not
             const bool valid = (o < a.O) && (ib < a.I);
-            const WorkCodes<BITS> cw = load_work_codes<BITS>(rC, valid ? (uint32_t)o * code_row_bytes + (uint32_t)(ib >> 5) * (4u * WorkCodes<BITS>::kWords) : kOobOffset);
-            // this lane owns codes 8a + 4h + b (a, b in 0..3): four consecutive codes per a, h fields further along
-            const uint32_t pre = (uint32_t)h * WorkCodes<BITS>::kField;
-            const uint32_t cq[4] = {cw.four(0, pre), cw.four(8, pre), cw.four(16, pre), cw.four(24, pre)};
-            const intx2 sv = buf_load8(rS, valid ? ((uint32_t)o * (uint32_t)a.G + (uint32_t)(ib / a.g)) * 8u : kOobOffset);
-            const float s = __int_as_float(sv[0]), zb = __int_as_float(sv[1]);
-            float sum_s = 0.0f, sum_z = 0.0f;
+            ops[i].cw = load_work_codes<BITS>(rC, valid ? (uint32_t)o * code_row_bytes + (uint32_t)(ib >> 5) * (4u * WorkCodes<BITS>::kWords) : kOobOffset);
+            ops[i].sv = buf_load8(rS, valid ? ((uint32_t)o * (uint32_t)a.G + (uint32_t)(ib / a.g)) * 8u : kOobOffset);
             if constexpr (BLOCK_AP) {
-                const uint32_t cl = (uint32_t)buf_load4(rB, valid ? (uint32_t)o * (uint32_t)(a.I >> 3) + (uint32_t)(ib >> 3) : kOobOffset) >> (4 * h);
-                const float rinv = valid ? 1.0f / s : 0.0f;
-                WQuad<WT> wq[4];
+                ops[i].ncl = (uint32_t)buf_load4(rB, valid ? (uint32_t)o * (uint32_t)(a.I >> 3) + (uint32_t)(ib >> 3) : kOobOffset);
 #pragma unroll
                 for (int q = 0; q < 4; ++q)
-                    wq[q].load(rW, valid ? (uint32_t)o * (uint32_t)a.I + (uint32_t)(ib + 8 * q + 4 * h) : (kOobOffset / (uint32_t)sizeof(WT)));
+                    ops[i].wq[q].load(rW, valid ? (uint32_t)o * (uint32_t)a.I + (uint32_t)(ib + 8 * q + 4 * h) : (kOobOffset / (uint32_t)sizeof(WT)));
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < MI; ++i) {
+            const int ib = m0 + wm * WTM + i * 32;
+            const bool valid = (o < a.O) && (ib < a.I);
+            const WorkCodes<BITS> &cw = ops[i].cw;
+            // this lane owns codes 8a + 4h + b (a, b in 0..3): four consecutive codes per a, h fields further along
+            const uint32_t pre = (uint32_t)h * WorkCodes<BITS>::kField;
+            uint32_t cq[4] = {cw.four(0, pre), cw.four(8, pre), cw.four(16, pre), cw.four(24, pre)};
+            // keep the four masked words as they are: folded into one bit-field extract per code, the byte-to-float
+            // conversions (v_cvt_f32_ubyte0..3, one instruction per code) would each need an extract in front
+#pragma unroll
+            for (int q = 0; q < 4; ++q) asm volatile("" : "+v"(cq[q]));
+            const float s = __int_as_float(ops[i].sv[0]), zb = __int_as_float(ops[i].sv[1]);
+            float sum_s = 0.0f, sum_z = 0.0f;
+            if constexpr (BLOCK_AP) {
+                // keep-bits: 1 where Eq.(1) did NOT clamp the weight
+                const uint32_t ncl = ~(ops[i].ncl >> (4 * h));
+                const float rinv = valid ? 1.0f / s : 0.0f;
+                const WQuad<WT> (&wq)[4] = ops[i].wq;
+                // Per weight, with keep = all ones where it was not clamped (one bit-field extract) and bitwise ANDs
+                // in place of selects:  du = D & keep (this is dW),  cs = (q - (w & keep) / s) - zbar, which is
+                // r - w/s in range and r = q - zbar where clamped,  sum over clamped D = sum D - sum du.
+                float sum_d = 0.0f, sum_u = 0.0f;
 #define EQAT_ELEM(Q, B)                                                                                   \
     {                                                                                                     \
         const float d = acc[i][j][(Q) * 4 + (B)];                                                         \
-        const float r = byte_to_float(cq[Q], B) - zb;                                                     \
-        const bool clamped = (cl >> ((Q) * 8 + (B))) & 1u;                                                \
-        const float cs = clamped ? r : r - wq[Q].v[B] * rinv;                                             \
+        const uint32_t keep = (uint32_t)((int32_t)(ncl << (31 - ((Q) * 8 + (B)))) >> 31);                 \
+        const float du = __uint_as_float(__float_as_uint(d) & keep);                                      \
+        const float wm = __uint_as_float(__float_as_uint(wq[Q].v[B]) & keep);                             \
+        const float cs = __builtin_fmaf(-wm, rinv, byte_to_float(cq[Q], B)) - zb;                         \
         sum_s = __builtin_fmaf(d, cs, sum_s);                                                             \
-        sum_z += clamped ? d : 0.0f;                                                                      \
-        dwv[B] = clamped ? 0.0f : d;                                                                      \
+        sum_d += d;                                                                                       \
+        sum_u += du;                                                                                      \
+        dwv[B] = du;                                                                                      \
     }
 #define EQAT_QUAD(Q)                                                                                      \
     {                                                                                                     \
         float dwv[4];                                                                                     \
         EQAT_ELEM(Q, 0) EQAT_ELEM(Q, 1) EQAT_ELEM(Q, 2) EQAT_ELEM(Q, 3)                                   \
-        if (a.dW != nullptr && valid) WQuad<WT>::store(a.dW, (size_t)o * a.I + (ib + 8 * (Q) + 4 * h), dwv); \
+        WQuad<WT>::store(rDW, valid ? (uint32_t)o * (uint32_t)a.I + (uint32_t)(ib + 8 * (Q) + 4 * h)      \
+                                    : (kOobOffset / (uint32_t)sizeof(WT)), dwv);                          \
     }
                 EQAT_QUAD(0) EQAT_QUAD(1) EQAT_QUAD(2) EQAT_QUAD(3)
 #undef EQAT_QUAD
 #undef EQAT_ELEM
+                sum_z = sum_d - sum_u;
             } else {
 #define EQAT_ELEM(Q, B)                                                                                   \
     {                                                                                                     \
