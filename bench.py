@@ -109,7 +109,8 @@ def main():
     for k in gemms:
         kernels[k]["tflops"] = round(flop_per_launch / (gemms[k][0] / gemms[k][1] * 1e-3) / 1e12, 2)
     if "quantize" in prof:
-        qb = sum(L["O"] * L["I"] for L in layers) / len(layers) * (2 + bits / 8 + 8.0 / g)   # fwd pass: W in, codes + (s,z) out
+        # W and (s, z) in; codes, clamp bit-plane and (s, zbar) pairs out
+        qb = sum(L["O"] * L["I"] for L in layers) / len(layers) * (2 + 8.0 / g + bits / 8 + 1.0 / 8 + 8.0 / g)
         kernels["quantize"]["approx_gbs"] = round(qb / (prof["quantize"][0] / prof["quantize"][1] * 1e-3) / 1e9, 1)
 
     result = {
@@ -169,9 +170,11 @@ def build_layers(torch, eq, synth, wl, dev):
 
 
 def run_block_ap_step(eq, layers, bits, g):
+    # as a training step runs them: the forward keeps its Eq.(1) results in the workspace for the backward of the same
+    # (W, s, z), so every linear is quantized once per step
     for L in layers:
-        eq.eqat_fq_linear_fwd(L["X"], L["W"], L["s"], L["z"], bits, g, Y=L["Y"], ws=L["ws_f"])
-        eq.eqat_fq_linear_bwd(L["X"], L["W"], L["s"], L["z"], L["dY"], bits, g, out=L["out"], ws=L["ws_b"])
+        eq.eqat_fq_linear_fwd(L["X"], L["W"], L["s"], L["z"], bits, g, Y=L["Y"], ws=L["ws_b"], keep=True)
+        eq.eqat_fq_linear_bwd(L["X"], L["W"], L["s"], L["z"], L["dY"], bits, g, out=L["out"], ws=L["ws_b"], kept=True)
 
 
 def measure_other_rows(torch, eq, layers, bits, g, adt, dev, args):

@@ -114,6 +114,20 @@ eqat_status eqat_fq_linear_bwd(const eqat_desc *d, const void *X, const void *W,
                                void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * The same pair for a training step that runs both on unchanged (W, s, z): the forward leaves what Eq.(1) produced
+ * (codes, which weights were clamped, the (s, zbar) pairs) in the workspace and the backward uses it instead of
+ * running Eq.(1) a second time.  Both take a workspace of EQAT_OP_FQ_BWD size.  Precondition of _bwd_kept (not
+ * checked): `ws` is untouched since eqat_fq_linear_fwd_keep ran on the same descriptor (any token count), W, s and z.
+ * Results are bitwise those of eqat_fq_linear_fwd / eqat_fq_linear_bwd.  (With fp32 activations nothing is kept and
+ * the backward works from W as always.)
+ */
+eqat_status eqat_fq_linear_fwd_keep(const eqat_desc *d, const void *X, const void *W, const float *s,
+                                    const float *z, void *Y, void *ws, size_t ws_bytes, void *stream);
+eqat_status eqat_fq_linear_bwd_kept(const eqat_desc *d, const void *X, const void *W, const float *s,
+                                    const float *z, const void *dY, void *dX, void *dW, float *ds, float *dz,
+                                    void *ws, size_t ws_bytes, void *stream);
+
+/*
  * Freeze after Block-AP (Sec. 3.2 last paragraph; App. E): W_q and z at N bits.
  * Layout (the paper fixes none): each row is a little-endian bit stream, code i
  * of the row in bits [i*N,(i+1)*N), stored as bytes, least significant first.

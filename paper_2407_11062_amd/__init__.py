@@ -23,7 +23,8 @@ STATUS_NAMES = ["EQAT_OK", "EQAT_ERR_NULL", "EQAT_ERR_SHAPE", "EQAT_ERR_BITS", "
                 "EQAT_ERR_ALIGN", "EQAT_ERR_WORKSPACE", "EQAT_ERR_DEVICE", "EQAT_ERR_HYPER"]
 
 EXPORTS = ["eqat_status_string", "eqat_validate_desc", "eqat_packed_w_bytes", "eqat_packed_z_bytes",
-           "eqat_workspace_bytes", "eqat_init_minmax", "eqat_fq_linear_fwd", "eqat_fq_linear_bwd", "eqat_pack",
+           "eqat_workspace_bytes", "eqat_init_minmax", "eqat_fq_linear_fwd", "eqat_fq_linear_bwd",
+           "eqat_fq_linear_fwd_keep", "eqat_fq_linear_bwd_kept", "eqat_pack",
            "eqat_unpack", "eqat_qlinear_fwd", "eqat_qlinear_bwd", "eqat_qlinear_fwd_z", "eqat_qlinear_bwd_z",
            "eqat_recon_loss_workspace_bytes", "eqat_recon_loss", "eqat_block_ap_update",
            "eqat_profile_kernels", "eqat_profile_kernel_name",
@@ -70,6 +71,8 @@ def lib():
         L.eqat_init_minmax.argtypes = [dp, vp, vp, vp, vp]
         L.eqat_fq_linear_fwd.argtypes = [dp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.eqat_fq_linear_bwd.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.eqat_fq_linear_fwd_keep.argtypes = L.eqat_fq_linear_fwd.argtypes
+        L.eqat_fq_linear_bwd_kept.argtypes = L.eqat_fq_linear_bwd.argtypes
         L.eqat_pack.argtypes = [dp, vp, vp, vp, vp, vp, vp]
         L.eqat_unpack.argtypes = [dp, vp, vp, vp, vp, vp]
         L.eqat_qlinear_fwd.argtypes = [dp, vp, vp, vp, vp, vp, vp, sz, vp]
@@ -138,18 +141,21 @@ def eqat_init_minmax(W, bits, group, s=None, z=None):
     return s, z
 
 
-def eqat_fq_linear_fwd(X, W, s, z, bits, group, Y=None, ws=None):
+def eqat_fq_linear_fwd(X, W, s, z, bits, group, Y=None, ws=None, keep=False):
+    """keep=True: `ws` (EQAT_OP_FQ_BWD size, must then be given) is left holding what eqat_fq_linear_bwd(kept=True) needs."""
     T, I = X.shape
     O = W.shape[0]
     d = make_desc(T, I, O, bits, group, _dt(X), _dt(W))
     Y = torch.empty((T, O), dtype=X.dtype, device=X.device) if Y is None else Y
+    if keep and ws is None:
+        raise ValueError("keep=True needs the caller's workspace (it is the thing that is kept)")
     ws = workspace(d, OP_FQ_FWD, X.device) if ws is None else ws
-    _check("eqat_fq_linear_fwd", lib().eqat_fq_linear_fwd(ctypes.byref(d), _p(X), _p(W), _p(s), _p(z), _p(Y), _p(ws),
-                                                          ws.numel(), _stream()))
+    name = "eqat_fq_linear_fwd_keep" if keep else "eqat_fq_linear_fwd"
+    _check(name, getattr(lib(), name)(ctypes.byref(d), _p(X), _p(W), _p(s), _p(z), _p(Y), _p(ws), ws.numel(), _stream()))
     return Y
 
 
-def eqat_fq_linear_bwd(X, W, s, z, dY, bits, group, want=("dX", "dW", "ds", "dz"), out=None, ws=None):
+def eqat_fq_linear_bwd(X, W, s, z, dY, bits, group, want=("dX", "dW", "ds", "dz"), out=None, ws=None, kept=False):
     T, O = dY.shape
     I = W.shape[1]
     d = make_desc(T, I, O, bits, group, _dt(dY), _dt(W))
@@ -159,8 +165,11 @@ def eqat_fq_linear_bwd(X, W, s, z, dY, bits, group, want=("dX", "dW", "ds", "dz"
     if "dW" in want and "dW" not in out: out["dW"] = torch.empty((O, I), dtype=W.dtype, device=dY.device)
     if "ds" in want and "ds" not in out: out["ds"] = torch.empty((O, G), dtype=torch.float32, device=dY.device)
     if "dz" in want and "dz" not in out: out["dz"] = torch.empty((O, G), dtype=torch.float32, device=dY.device)
+    if kept and ws is None:
+        raise ValueError("kept=True needs the workspace the forward call left")
     ws = workspace(d, OP_FQ_BWD, dY.device) if ws is None else ws
-    _check("eqat_fq_linear_bwd", lib().eqat_fq_linear_bwd(
+    name = "eqat_fq_linear_bwd_kept" if kept else "eqat_fq_linear_bwd"
+    _check(name, getattr(lib(), name)(
         ctypes.byref(d), _p(X), _p(W), _p(s), _p(z), _p(dY), _p(out.get("dX")), _p(out.get("dW")), _p(out.get("ds")),
         _p(out.get("dz")), _p(ws), ws.numel(), _stream()))
     return out

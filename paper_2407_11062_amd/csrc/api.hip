@@ -216,31 +216,70 @@ eqat_status eqat_unpack(const eqat_desc *d, const uint8_t *Wpacked, const uint8_
     return launch_status();
 }
 
-eqat_status eqat_fq_linear_fwd(const eqat_desc *d, const void *X, const void *W, const float *s, const float *z,
-                               void *Y, void *ws, size_t ws_bytes, void *stream)
+}  // extern "C"
+
+// keep: the workspace has the layout of the backward pass and is left holding what Eq.(1) produced (codes, clamp
+// bit-plane, (s, zbar) pairs), so that a backward call on the same (W, s, z) need not run Eq.(1) again.
+static eqat_status fq_fwd_any(const eqat_desc *d, const void *X, const void *W, const float *s, const float *z, void *Y,
+                              void *ws, size_t ws_bytes, void *stream, bool keep)
 {
     Problem p;
     if (eqat_status e = check_desc(d, true, &p)) return e;
     EQAT_REQUIRE(W); EQAT_REQUIRE(s); EQAT_REQUIRE(z);
     if (p.T > 0) { EQAT_REQUIRE(X); EQAT_REQUIRE(Y); }
     EQAT_ALIGNED(X); EQAT_ALIGNED(W); EQAT_ALIGNED(s); EQAT_ALIGNED(z); EQAT_ALIGNED(Y);
-    const WsLayout l = ws_layout(p, EQAT_OP_FQ_FWD);
+    const WsLayout l = ws_layout(p, keep ? EQAT_OP_FQ_BWD : EQAT_OP_FQ_FWD);
     if (eqat_status e = check_ws(l, ws, ws_bytes)) return e;
-    if (p.T == 0) return EQAT_OK;
+    if (p.T == 0 && !(keep && p.act_bf16)) return EQAT_OK;
     hipStream_t st = (hipStream_t)stream;
     char *w8 = (char *)ws;
     if (p.act_bf16) {
-        { ProfScope ps(eqat::PK_QUANTIZE, st); eqat::launch_quantize(p, W, s, z, w8 + l.codes, nullptr, w8 + l.sz, nullptr, false, st); }
-        { ProfScope ps(eqat::PK_GEMM_FWD, st); eqat::launch_mfma_fwd(p, X, w8 + l.codes, w8 + l.sz, Y, st); }
+        { ProfScope ps(eqat::PK_QUANTIZE, st); eqat::launch_quantize(p, W, s, z, w8 + l.codes, keep ? w8 + l.clamp : nullptr, w8 + l.sz, nullptr, false, st); }
+        if (p.T > 0) { ProfScope ps(eqat::PK_GEMM_FWD, st); eqat::launch_mfma_fwd(p, X, w8 + l.codes, w8 + l.sz, Y, st); }
     } else {
         { ProfScope ps(eqat::PK_F32, st); eqat::launch_f32_fwd(p, false, X, W, s, z, Y, st); }
     }
     return launch_status();
 }
 
+// kept: the workspace still holds what fq_fwd_any(keep) left there for the same (W, s, z).
+static eqat_status fq_bwd_any(const eqat_desc *d, const void *X, const void *W, const float *s, const float *z,
+                              const void *dY, void *dX, void *dW, float *ds, float *dz, void *ws, size_t ws_bytes,
+                              void *stream, bool kept);
+
+extern "C" {
+
+eqat_status eqat_fq_linear_fwd(const eqat_desc *d, const void *X, const void *W, const float *s, const float *z,
+                               void *Y, void *ws, size_t ws_bytes, void *stream)
+{
+    return fq_fwd_any(d, X, W, s, z, Y, ws, ws_bytes, stream, false);
+}
+
+eqat_status eqat_fq_linear_fwd_keep(const eqat_desc *d, const void *X, const void *W, const float *s, const float *z,
+                                    void *Y, void *ws, size_t ws_bytes, void *stream)
+{
+    return fq_fwd_any(d, X, W, s, z, Y, ws, ws_bytes, stream, true);
+}
+
 eqat_status eqat_fq_linear_bwd(const eqat_desc *d, const void *X, const void *W, const float *s, const float *z,
                                const void *dY, void *dX, void *dW, float *ds, float *dz, void *ws, size_t ws_bytes,
                                void *stream)
+{
+    return fq_bwd_any(d, X, W, s, z, dY, dX, dW, ds, dz, ws, ws_bytes, stream, false);
+}
+
+eqat_status eqat_fq_linear_bwd_kept(const eqat_desc *d, const void *X, const void *W, const float *s, const float *z,
+                                    const void *dY, void *dX, void *dW, float *ds, float *dz, void *ws, size_t ws_bytes,
+                                    void *stream)
+{
+    return fq_bwd_any(d, X, W, s, z, dY, dX, dW, ds, dz, ws, ws_bytes, stream, true);
+}
+
+}  // extern "C"
+
+static eqat_status fq_bwd_any(const eqat_desc *d, const void *X, const void *W, const float *s, const float *z,
+                              const void *dY, void *dX, void *dW, float *ds, float *dz, void *ws, size_t ws_bytes,
+                              void *stream, bool kept)
 {
     Problem p;
     if (eqat_status e = check_desc(d, true, &p)) return e;
@@ -255,7 +294,7 @@ eqat_status eqat_fq_linear_bwd(const eqat_desc *d, const void *X, const void *W,
     hipStream_t st = (hipStream_t)stream;
     char *w8 = (char *)ws;
     if (p.act_bf16) {
-        { ProfScope ps(eqat::PK_QUANTIZE, st); eqat::launch_quantize(p, W, s, z, w8 + l.codes, w8 + l.clamp, w8 + l.sz, nullptr, false, st); }
+        if (!kept) { ProfScope ps(eqat::PK_QUANTIZE, st); eqat::launch_quantize(p, W, s, z, w8 + l.codes, w8 + l.clamp, w8 + l.sz, nullptr, false, st); }
         if (dX != nullptr) { ProfScope ps(eqat::PK_GEMM_DX, st); eqat::launch_mfma_dx(p, dY, w8 + l.codes, w8 + l.sz, dX, st); }
         if (want_w)
             eqat::launch_mfma_dw(p, true, X, dY, W, w8 + l.codes, w8 + l.clamp, w8 + l.sz, s, dW, ds, dz,
@@ -267,6 +306,8 @@ eqat_status eqat_fq_linear_bwd(const eqat_desc *d, const void *X, const void *W,
     }
     return launch_status();
 }
+
+extern "C" {
 
 // E2E-QP forward / backward; the zero points come packed at N bits (zpacked) or as floats (zfloat), one of the two.
 static eqat_status qlinear_fwd_any(const eqat_desc *d, const void *X, const uint8_t *Wpacked, const float *s,

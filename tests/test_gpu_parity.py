@@ -166,6 +166,43 @@ def test_block_ap_outputs_are_optional_and_deterministic():
     assert torch.equal(only_dx["dX"], full["dX"])
 
 
+@pytest.mark.parametrize("tag,T,I,O,bits,g,wdt", [c for c in BF16_CASES if c[0] in ("b2g64", "b3g128", "b2g64w32", "b2perchan", "t1")])
+def test_forward_that_keeps_its_quantization_for_the_backward(tag, T, I, O, bits, g, wdt):
+    """eqat_fq_linear_fwd_keep + eqat_fq_linear_bwd_kept run Eq.(1) once per step instead of twice: bitwise the results of
+    the plain pair (which the tests above hold against the oracle)."""
+    X, W, s, z, dY = make_case(tag, T, I, O, bits, g, torch.bfloat16, wdt)
+    Xd, Wd, sd, zd, dYd = dev(X), dev(W), dev(s), dev(z), dev(dY)
+    d = eq.make_desc(T, I, O, bits, g, eq.BF16, eq._dt(Wd))
+    ws = eq.workspace(d, eq.OP_FQ_BWD, Xd.device)
+    ws.random_(0, 256)                                    # nothing may depend on what the workspace held before
+    Y = eq.eqat_fq_linear_fwd(Xd, Wd, sd, zd, bits, g, ws=ws, keep=True)
+    out = eq.eqat_fq_linear_bwd(Xd, Wd, sd, zd, dYd, bits, g, ws=ws, kept=True)
+    again = eq.eqat_fq_linear_bwd(Xd, Wd, sd, zd, dYd, bits, g, ws=ws, kept=True, want=("ds", "dX"))   # the kept state survives a backward
+    assert torch.equal(Y, eq.eqat_fq_linear_fwd(Xd, Wd, sd, zd, bits, g))
+    ref = eq.eqat_fq_linear_bwd(Xd, Wd, sd, zd, dYd, bits, g)
+    for k in ("dX", "dW", "ds", "dz"):
+        assert torch.equal(out[k], ref[k]), k
+    assert torch.equal(again["ds"], ref["ds"]) and torch.equal(again["dX"], ref["dX"])
+    # and against the oracle directly
+    r = oracle.fq_linear_bwd(npf(X), npf(W), s.numpy(), z.numpy(), npf(dY), bits, g, want=("ds", "dz"))
+    assert relerr(out["ds"], r["ds"]) <= TOL[torch.bfloat16] and relerr(out["dz"], r["dz"]) <= TOL[torch.bfloat16]
+
+
+def test_keep_with_no_tokens_still_leaves_a_usable_workspace():
+    X, W, s, z, dY = make_case("keep0", 4, 128, 16, 2, 64, torch.bfloat16, torch.bfloat16)
+    Wd, sd, zd = dev(W), dev(s), dev(z)
+    d = eq.make_desc(0, 128, 16, 2, 64, eq.BF16, eq.BF16)
+    ws = eq.workspace(d, eq.OP_FQ_BWD, Wd.device)
+    ws.fill_(255)
+    Xe = torch.empty((0, 128), dtype=torch.bfloat16, device="cuda")
+    dYe = torch.empty((0, 16), dtype=torch.bfloat16, device="cuda")
+    eq.eqat_fq_linear_fwd(Xe, Wd, sd, zd, 2, 64, ws=ws, keep=True)
+    out = eq.eqat_fq_linear_bwd(Xe, Wd, sd, zd, dYe, 2, 64, ws=ws, kept=True)
+    torch.cuda.synchronize()
+    for k in ("dW", "ds", "dz"):
+        assert not out[k].float().abs().sum().item() and torch.isfinite(out[k].float()).all(), k
+
+
 def test_empty_token_batch():
     X, W, s, z, dY = make_case("empty", 4, 128, 16, 2, 64, torch.bfloat16, torch.bfloat16)
     Wd, sd, zd = dev(W), dev(s), dev(z)

@@ -106,6 +106,14 @@ def test_null_alignment_and_workspace_errors_come_back_before_any_launch():
     assert L.eqat_fq_linear_fwd(r, P, P, P, P, P, P, 0, None) == WORKSPACE
     assert L.eqat_qlinear_fwd(r, P, P, P, P, P, None, 0, None) == WORKSPACE
     assert L.eqat_qlinear_bwd(r, P, P, P, P, P, P, P, P, 16, None) == WORKSPACE
+    # the keep / kept pair checks like the plain pair, with the backward's workspace size for both
+    ws_fwd = L.eqat_workspace_bytes(r, eq.OP_FQ_FWD)
+    assert ws_fwd < ws_need
+    assert L.eqat_fq_linear_fwd_keep(r, P, P, P, P, P, P, ws_fwd, None) == WORKSPACE
+    assert L.eqat_fq_linear_fwd_keep(r, None, P, P, P, P, P, ws_need, None) == NULL
+    assert L.eqat_fq_linear_bwd_kept(r, P, P, P, P, P, P, P, P, P, P, ws_need - 1, None) == WORKSPACE
+    assert L.eqat_fq_linear_bwd_kept(r, P, P, P, P, None, P, P, P, P, P, ws_need, None) == NULL
+    assert L.eqat_fq_linear_bwd_kept(r, P, P, P, P, P, None, None, None, None, P, ws_need, None) == OK      # nothing wanted
     # descriptor errors win over everything else
     bad = d(bits=9)
     assert L.eqat_fq_linear_fwd(ctypes.byref(bad), None, None, None, None, None, None, 0, None) == BITS
