@@ -108,15 +108,22 @@ template <int BITS> struct WhatTable {
 // Consecutive workgroup ids go round-robin over the 8 XCDs, each with its own L2.  Give every XCD a
 // contiguous range of tile ids, then walk the tiles in bands of 8 tile-rows so that the tiles resident on
 // one XCD at a time share their operand panels.
-__device__ __forceinline__ void tile_of_block(int tiles_m, int tiles_n, int &tm, int &tn, int kBand = 8)
+// nb = number of tiles; (xcd, loc) = the loc-th tile of XCD xcd.  Returns false past the end of that XCD's range.
+__device__ __forceinline__ bool tile_of_xcd_slot(int nb, int xcd, int loc, int tiles_m, int tiles_n, int &tm, int &tn, int kBand)
 {
-    const int nb = gridDim.x, bid = blockIdx.x;
-    const int xcd = bid & 7, loc = bid >> 3, per = nb >> 3, rem = nb & 7;
+    const int per = nb >> 3, rem = nb & 7;
+    if (loc >= per + (xcd < rem ? 1 : 0)) return false;
     const int pid = (xcd < rem ? xcd * (per + 1) : rem * (per + 1) + (xcd - rem) * per) + loc;
     const int width = kBand * tiles_n, band = pid / width, first = band * kBand;
     const int rows = min(tiles_m - first, kBand), in = pid - band * width;
     tm = first + in % rows;
     tn = in / rows;
+    return true;
+}
+// one tile per workgroup
+__device__ __forceinline__ void tile_of_block(int tiles_m, int tiles_n, int &tm, int &tn, int kBand = 8)
+{
+    (void)tile_of_xcd_slot((int)gridDim.x, (int)(blockIdx.x & 7), (int)(blockIdx.x >> 3), tiles_m, tiles_n, tm, tn, kBand);
 }
 
 // ======================================================================================================
@@ -131,6 +138,7 @@ struct GemmQArgs {
     uint32_t a_bytes, codes_bytes, sz_bytes;
     int tiles_m, tiles_n;
     int band;              // tile rows walked together by one XCD (see tile_of_block)
+    int walk;              // 1: the grid is smaller than the tile count and every workgroup walks several tiles
 };
 
 template <int V> struct IC { static constexpr int value = V; };
@@ -222,11 +230,24 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_q(const GemmQArgs a)
     bf16_t *sA = reinterpret_cast<bf16_t *>(smem_raw);            // [2][A_ELEMS]
     bf16_t *sB = sA + 2 * A_ELEMS;                                // [2][B_ELEMS]
 
-    int tm, tn;
-    tile_of_block(a.tiles_m, a.tiles_n, tm, tn, a.band);
-    const int m0 = tm * BM, n0 = tn * BN;
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WGN, wn = wave % WGN;
+
+    // Tiles of this workgroup.  One tile each when the grid covers all tiles; otherwise (a.walk) workgroup b walks the
+    // tiles that a one-tile-per-workgroup grid would have handed to the workgroups b, b + G, b + 2 G, ... of its XCD
+    // slot, and the K loop runs THROUGH the tile boundaries: the loaders below each keep their own position in that
+    // sequence, two (activations) and three (codes) K tiles ahead of the MFMAs, so that the first K tiles of the next
+    // output tile are in LDS and in registers when the last MFMA of the current one issues.
+    const int ntiles = a.tiles_m * a.tiles_n, xcd = (int)(blockIdx.x & 7), loc0 = (int)(blockIdx.x >> 3);
+    const int loc_step = a.walk ? (int)(gridDim.x >> 3) : ntiles;          // no second tile without a.walk
+    auto tile_origin = [&](int j, int &m0, int &n0) -> bool {              // j-th tile of this workgroup
+        int tm, tn;
+        const bool ok = tile_of_xcd_slot(a.walk ? ntiles : (int)gridDim.x, xcd, loc0 + j * loc_step, a.tiles_m, a.tiles_n, tm, tn, a.band);
+        m0 = ok ? tm * BM : a.tiles_m * BM;                                // past the end: rows / columns out of range
+        n0 = ok ? tn * BN : a.tiles_n * BN;
+        return ok;
+    };
+    const int nk = (a.K + BK - 1) / BK, nk2 = (nk + 1) & ~1;              // K tiles per output tile, two per trip
 
     const RawRsrc rA = make_raw_rsrc(a.A, a.a_bytes);
     const __amdgpu_buffer_rsrc_t rC = make_rsrc(a.codes, a.codes_bytes);
@@ -237,45 +258,61 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_q(const GemmQArgs a)
     floatx2 stS[2][B_SEGS];
     WhatTable<BITS> tabs[2][B_SEGS];
 
-    // Activation tiles stream into LDS strictly in order (k0 = 0, BK, 2 BK, ...): every direct-to-LDS instruction keeps
-    // a running byte offset that advances by one tile row segment per call, and M0 comes from wave-uniform scalars.
-    // No test against K: columns past K of a row read the start of the next row (or, behind the last row, fail the
-    // range check and give zeros); they meet weights that are exactly zero (step size and zero point of a column past
-    // the end load as 0), and inputs are finite by contract.
+    // Activation tiles stream into LDS strictly in order (k0 = 0, BK, 2 BK, ... of one output tile, then of the next):
+    // every direct-to-LDS instruction keeps a running byte offset that advances by one tile row segment per call, and
+    // M0 comes from wave-uniform scalars.  No test against K: columns past K of a row read the start of the next row
+    // (or, behind the last row, fail the range check and give zeros); they meet weights that are exactly zero (step
+    // size and zero point of a column past the end load as 0), and inputs are finite by contract.
     const uint32_t ldsA = lds_addr_of(sA);
     uint32_t offA[A_LOADS];
+    int a_tile = 0, a_left = 0;                     // loader position: tile ordinal, K tiles left in it
+    auto a_enter_tile = [&]() {
+        int m0, n0;
+        (void)tile_origin(a_tile, m0, n0);
 #pragma unroll
-    for (int it = 0; it < A_LOADS; ++it) {
-        const int row = (wave * A_LOADS + it) * 8 + (lane >> 3);
-        const uint64_t o = ((uint64_t)(m0 + row) * (uint64_t)a.K + (uint64_t)(kc_swz(row, lane & 7) * 8)) * 2u;
-        offA[it] = o < kOobOffset ? (uint32_t)o : kOobOffset;       // rows past the matrix stay out of range for good
-    }
-    auto load_a_one = [&](int it, int buf) {
-        load_to_lds16_at(rA, ldsA + (uint32_t)((buf * A_ELEMS + (wave * A_LOADS + it) * 8 * 64) * 2), offA[it]);
-        offA[it] += BK * 2;
+        for (int it = 0; it < A_LOADS; ++it) {
+            const int row = (wave * A_LOADS + it) * 8 + (lane >> 3);
+            const uint64_t o = ((uint64_t)(m0 + row) * (uint64_t)a.K + (uint64_t)(kc_swz(row, lane & 7) * 8)) * 2u;
+            offA[it] = o < kOobOffset ? (uint32_t)o : kOobOffset;   // rows past the matrix stay out of range for good
+        }
+        a_left = nk2;
+        ++a_tile;
     };
     auto load_a = [&](int buf) {
+        --a_left;
 #pragma unroll
-        for (int it = 0; it < A_LOADS; ++it) load_a_one(it, buf);
+        for (int it = 0; it < A_LOADS; ++it) {
+            load_to_lds16_at(rA, ldsA + (uint32_t)((buf * A_ELEMS + (wave * A_LOADS + it) * 8 * 64) * 2), offA[it]);
+            offA[it] += BK * 2;
+        }
     };
-    // Weight codes and (s, zbar) pairs, also strictly in order.  Forward: a segment's group index wcol / g is carried
-    // from call to call (a tile advances wcol by BK <= 2 g, so two conditional steps replace a division per K tile).
+    // Weight codes and (s, zbar) pairs, in the same order.  Forward: a segment's group index wcol / g is carried from
+    // call to call (a K tile advances wcol by BK <= 2 g, so two conditional steps replace a division per K tile).
     int grp[B_SEGS], rem[B_SEGS];
+    int c_tile = 0, c_left = 0, c_n0 = 0, c_k0 = 0;
+    auto c_enter_tile = [&]() {
+        int m0;
+        (void)tile_origin(c_tile, m0, c_n0);
 #pragma unroll
-    for (int it = 0; it < B_SEGS; ++it) {
-        const int sidx = it * NT + tid;
-        const int wcol = BT ? n0 + (sidx % (BN / 32)) * 32 : (sidx % (BK / 32)) * 32;
-        grp[it] = wcol / (int)a.g;
-        rem[it] = wcol % (int)a.g;
-    }
-    auto load_codes = [&](auto set, int k0) {
+        for (int it = 0; it < B_SEGS; ++it) {
+            const int sidx = it * NT + tid;
+            const int wcol = BT ? c_n0 + (sidx % (BN / 32)) * 32 : (sidx % (BK / 32)) * 32;
+            grp[it] = wcol / (int)a.g;
+            rem[it] = wcol % (int)a.g;
+        }
+        c_k0 = 0;
+        c_left = nk2;
+        ++c_tile;
+    };
+    auto load_codes = [&](auto set) {
         constexpr int S = decltype(set)::value;
+        --c_left;
 #pragma unroll
         for (int it = 0; it < B_SEGS; ++it) {
             const int sidx = it * NT + tid;
             int wrow, wcol;   // position in the weight matrix [O][I]
-            if (!BT) { wrow = n0 + sidx / (BK / 32); wcol = k0 + (sidx % (BK / 32)) * 32; }
-            else     { wrow = k0 + sidx / (BN / 32); wcol = n0 + (sidx % (BN / 32)) * 32; }
+            if (!BT) { wrow = c_n0 + sidx / (BK / 32); wcol = c_k0 + (sidx % (BK / 32)) * 32; }
+            else     { wrow = c_k0 + sidx / (BN / 32); wcol = c_n0 + (sidx % (BN / 32)) * 32; }
             const bool ok = wcol < a.I;
             stC[S][it] = load_work_codes<BITS>(rC, (uint32_t)wrow * code_row_bytes + (uint32_t)(wcol >> 5) * (4u * WorkCodes<BITS>::kWords));
             const intx2 sv = buf_load8(rS, ok ? ((uint32_t)wrow * (uint32_t)a.G + (uint32_t)grp[it]) * 8u : kOobOffset);
@@ -291,6 +328,13 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_q(const GemmQArgs a)
                 }
             }
         }
+        c_k0 += BK;
+    };
+    // A loader steps into the next output tile BETWEEN K steps (and between the loads of the start-up sequence): a
+    // branch inside a K step would cut the instruction schedule of the step in two.
+    auto loaders_advance = [&]() {
+        if (a_left == 0) a_enter_tile();
+        if (c_left == 0) c_enter_tile();
     };
     // piece P of KK: every KK-th 16-byte store of the staged weight tile
     auto commit_piece = [&](auto set, auto piece, int buf) {
@@ -345,7 +389,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_q(const GemmQArgs a)
             for (int j = 0; j < NI; ++j)
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[slot][i], fb[slot][j], acc[i][j], 0, 0, 0);
     };
-    auto step = [&](auto par, int kt) {
+    auto step = [&](auto par) {
         constexpr int PAR = decltype(par)::value;
         const bf16_t *cA = sA + PAR * A_ELEMS, *cB = sB + PAR * B_ELEMS;
         // stage kk: start the reads of slice kk+1, multiply slice kk, convert a quarter of the next weight tile
@@ -382,45 +426,57 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_q(const GemmQArgs a)
         mfma_slice(1);
         commit_piece(IC<PAR>{}, IC<0>{}, PAR);
         interleave();
-        load_codes(IC<PAR ^ 1>{}, (kt + 3) * BK);
+        load_codes(IC<PAR ^ 1>{});
         __builtin_amdgcn_sched_barrier(0);
     };
 
-    const int nk = (a.K + BK - 1) / BK;
-    load_codes(IC<0>{}, 0);
+    // start-up of the first tile: K tiles 0 and 1 of the activations, 0, 1 and 2 of the codes, weight tile 0 rebuilt
+    loaders_advance();
+    load_codes(IC<0>{});
     load_a(0);
-    load_codes(IC<1>{}, BK);
+    loaders_advance();
+    load_codes(IC<1>{});
     commit_piece(IC<0>{}, IC<0>{}, 0);
     commit_piece(IC<0>{}, IC<1>{}, 0);
     commit_piece(IC<0>{}, IC<2>{}, 0);
     commit_piece(IC<0>{}, IC<3>{}, 0);
     wait_all_and_barrier();
-    load_codes(IC<0>{}, 2 * BK);
+    loaders_advance();
+    load_codes(IC<0>{});
     load_a(1);
     commit_piece(IC<1>{}, IC<0>{}, 1);
     read_frags(0, sA, sB, 0);
-    // Two tiles per trip, unconditionally (the register staging sets alternate at compile time, and a branch
-    // between the two halves makes the accumulators flow through a merge that costs hundreds of copies).  With an
-    // odd tile count the extra tile lies past K and multiplies zeros.
-    for (int kt = 0; kt < nk; kt += 2) {
-        step(IC<0>{}, kt);
-        step(IC<1>{}, kt + 1);
-    }
-    __builtin_amdgcn_s_waitcnt(0x0070);       // the loads issued for tiles past K (all zeros) have landed too
 
-    // C[m][n]: lane holds column n = l % 32 and rows 8*(r/4) + 4*(l/32) + r%4 of each 32x32 block
-#pragma unroll
-    for (int i = 0; i < MI; ++i)
-#pragma unroll
-        for (int j = 0; j < NI; ++j) {
-            const int n = n0 + wn * WTN + j * 32 + (lane & 31);
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int m = m0 + wm * WTM + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-                if (m < a.M && n < a.N) a.C[(size_t)m * a.N + n] = (bf16_t)acc[i][j][r];
-            }
-            __builtin_amdgcn_sched_barrier(0);     // one 32x32 block at a time: keeps the accumulator copies few
+    for (int jt = 0;; ++jt) {
+        int m0, n0;
+        if (!tile_origin(jt, m0, n0)) break;
+        // Two K tiles per trip, unconditionally (the register staging sets alternate at compile time, and a branch
+        // between the two halves makes the accumulators flow through a merge that costs hundreds of copies).  With an
+        // odd K-tile count the extra tile lies past K and multiplies zeros.  The last trips of this loop already fetch
+        // (and rebuild) the first K tiles of the next output tile.
+        for (int kt = 0; kt < nk2; kt += 2) {
+            loaders_advance();
+            step(IC<0>{});
+            loaders_advance();
+            step(IC<1>{});
         }
+
+        // C[m][n]: lane holds column n = l % 32 and rows 8*(r/4) + 4*(l/32) + r%4 of each 32x32 block
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int j = 0; j < NI; ++j) {
+                const int n = n0 + wn * WTN + j * 32 + (lane & 31);
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int m = m0 + wm * WTM + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                    if (m < a.M && n < a.N) a.C[(size_t)m * a.N + n] = (bf16_t)acc[i][j][r];
+                    acc[i][j][r] = 0.0f;
+                }
+                __builtin_amdgcn_sched_barrier(0);     // one 32x32 block at a time: keeps the accumulator copies few
+            }
+    }
+    __builtin_amdgcn_s_waitcnt(0x0070);       // the loads issued past the last tile (all zeros) have landed too
 }
 
 // ======================================================================================================
@@ -821,6 +877,20 @@ bool use_small_tile(int64_t m, int64_t n)
     return ((m + 255) / 256) * ((n + 255) / 256) < 160;
 }
 
+// Workgroups of `smem` bytes of LDS that the device runs at the same time (LDS is what limits these kernels), rounded
+// down to a multiple of 8.
+int resident_workgroups(size_t smem)
+{
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 8) n = 256;
+        cus = n;
+    }
+    const int per_cu = smem * 2 <= 160 * 1024 ? 2 : 1;
+    return (cus * per_cu) & ~7;
+}
+
 template <int BITS, bool BT, typename TS>
 void launch_q(const GemmQArgs &args, hipStream_t st)
 {
@@ -833,7 +903,11 @@ void launch_q(const GemmQArgs &args, hipStream_t st)
     a.tiles_m = (a.M + TS::BM - 1) / TS::BM;
     a.tiles_n = (a.N + TS::BN - 1) / TS::BN;
     a.band = 8;
-    kern<<<dim3(a.tiles_m * a.tiles_n), dim3(64 * TS::WGM * TS::WGN), smem, st>>>(a);
+    // At most as many workgroups as the chip holds at once; with more tiles than that every workgroup walks several
+    // (grid a multiple of 8, one share per XCD).
+    const int ntiles = a.tiles_m * a.tiles_n, resident = resident_workgroups(smem);
+    a.walk = ntiles > resident ? 1 : 0;
+    kern<<<dim3(a.walk ? resident : ntiles), dim3(64 * TS::WGM * TS::WGN), smem, st>>>(a);
 }
 
 template <bool BT>
