@@ -153,6 +153,22 @@ def test_block_ap_bf16(tag, T, I, O, bits, g, wdt):
     check_block_ap(X, W, s, z, dY, bits, g, TOL[torch.bfloat16])
 
 
+# More output tiles than the chip holds workgroups: every workgroup of the fwd / dX kernel then walks several tiles with
+# its K loop running through the tile boundaries.  Ragged in every dimension, K-tile counts 5 (odd: one padding K tile
+# per output tile) and 6; the third case walks with the small (128 x 128) tile (144 big tiles = 576 small ones).
+WALK_CASES = [
+    ("walk_fwd", 4400, 320, 4104, 2, 64),      # fwd: 18 x 17 = 306 tiles of 256 x 256
+    ("walk_dx", 4400, 4128, 328, 3, 32),       # dX: 18 x 17 tiles, K = O = 328
+    ("walk_small", 4096, 256, 2304, 4, 128),   # fwd: 32 x 18 = 576 tiles of 128 x 128
+]
+
+
+@pytest.mark.parametrize("tag,T,I,O,bits,g", WALK_CASES)
+def test_block_ap_bf16_more_tiles_than_resident_workgroups(tag, T, I, O, bits, g):
+    X, W, s, z, dY = make_case(tag, T, I, O, bits, g, torch.bfloat16, torch.bfloat16)
+    check_block_ap(X, W, s, z, dY, bits, g, TOL[torch.bfloat16])
+
+
 def test_block_ap_outputs_are_optional_and_deterministic():
     X, W, s, z, dY = make_case("opt", 140, 256, 136, 2, 64, torch.bfloat16, torch.bfloat16)
     Xd, Wd, sd, zd, dYd = dev(X), dev(W), dev(s), dev(z), dev(dY)
