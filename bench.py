@@ -191,8 +191,8 @@ def measure_other_rows(torch, eq, layers, bits, g, adt, dev, args):
 
     def e2e_step():
         for L, P in zip(layers, packed):
-            eq.eqat_qlinear_fwd(P["X"], P["Wp"], L["s"], P["zp"], bits, g, Y=P["Y"], ws=P["ws_f"])
-            eq.eqat_qlinear_bwd(P["X"], P["Wp"], L["s"], P["zp"], P["dY"], L["I"], bits, g, out=P["out"], ws=P["ws_b"])
+            eq.eqat_qlinear_fwd(P["X"], P["Wp"], L["s"], P["zp"], bits, g, Y=P["Y"], ws=P["ws_b"], keep=True)
+            eq.eqat_qlinear_bwd(P["X"], P["Wp"], L["s"], P["zp"], P["dY"], L["I"], bits, g, out=P["out"], ws=P["ws_b"], kept=True)
 
     def timed(fn, n):
         for _ in range(2):

@@ -161,6 +161,20 @@ eqat_status eqat_qlinear_bwd(const eqat_desc *d, const void *X, const uint8_t *W
                              void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * The E2E-QP pair for a training step that runs forward and backward on unchanged (Wpacked, s, zpacked): the forward
+ * leaves the codes in the library's working layout and the (s, z) pairs in the workspace, the backward uses them.
+ * Both take a workspace of EQAT_OP_Q_BWD size; the forward always runs the tiled GEMM (no few-token kernel).
+ * Precondition of _bwd_kept (not checked): `ws` untouched since eqat_qlinear_fwd_keep ran on the same descriptor (any
+ * token count), Wpacked, s and zpacked.  Results are bitwise those of eqat_qlinear_fwd (more than 16 tokens) /
+ * eqat_qlinear_bwd.
+ */
+eqat_status eqat_qlinear_fwd_keep(const eqat_desc *d, const void *X, const uint8_t *Wpacked, const float *s,
+                                  const uint8_t *zpacked, void *Y, void *ws, size_t ws_bytes, void *stream);
+eqat_status eqat_qlinear_bwd_kept(const eqat_desc *d, const void *X, const uint8_t *Wpacked, const float *s,
+                                  const uint8_t *zpacked, const void *dY, void *dX, float *ds,
+                                  void *ws, size_t ws_bytes, void *stream);
+
+/*
  * E2E-QP with trained zero points (Sec. 3.3 and the ablation on the trainable parameters of E2E-QP: training z
  * promotes it from N bits to a floating-point tensor).  There is no Eq.(1) in this phase, so z enters Eq.(2) as it
  * is, WITHOUT rounding:  What = (w_q - z) * s,  Y = X * What^T.

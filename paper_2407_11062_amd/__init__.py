@@ -25,7 +25,8 @@ STATUS_NAMES = ["EQAT_OK", "EQAT_ERR_NULL", "EQAT_ERR_SHAPE", "EQAT_ERR_BITS", "
 EXPORTS = ["eqat_status_string", "eqat_validate_desc", "eqat_packed_w_bytes", "eqat_packed_z_bytes",
            "eqat_workspace_bytes", "eqat_init_minmax", "eqat_fq_linear_fwd", "eqat_fq_linear_bwd",
            "eqat_fq_linear_fwd_keep", "eqat_fq_linear_bwd_kept", "eqat_pack",
-           "eqat_unpack", "eqat_qlinear_fwd", "eqat_qlinear_bwd", "eqat_qlinear_fwd_z", "eqat_qlinear_bwd_z",
+           "eqat_unpack", "eqat_qlinear_fwd", "eqat_qlinear_bwd", "eqat_qlinear_fwd_keep", "eqat_qlinear_bwd_kept",
+           "eqat_qlinear_fwd_z", "eqat_qlinear_bwd_z",
            "eqat_recon_loss_workspace_bytes", "eqat_recon_loss", "eqat_block_ap_update",
            "eqat_profile_kernels", "eqat_profile_kernel_name",
            "eqat_profile_start", "eqat_profile_stop"]
@@ -77,6 +78,8 @@ def lib():
         L.eqat_unpack.argtypes = [dp, vp, vp, vp, vp, vp]
         L.eqat_qlinear_fwd.argtypes = [dp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.eqat_qlinear_bwd.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.eqat_qlinear_fwd_keep.argtypes = L.eqat_qlinear_fwd.argtypes
+        L.eqat_qlinear_bwd_kept.argtypes = L.eqat_qlinear_bwd.argtypes
         L.eqat_qlinear_fwd_z.argtypes = [dp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.eqat_qlinear_bwd_z.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.eqat_recon_loss_workspace_bytes.restype, L.eqat_recon_loss_workspace_bytes.argtypes = sz, []
@@ -196,27 +199,35 @@ def eqat_unpack(Wpacked, zpacked, in_features, bits, group):
     return codes, zc
 
 
-def eqat_qlinear_fwd(X, Wpacked, s, zpacked, bits, group, Y=None, ws=None):
+def eqat_qlinear_fwd(X, Wpacked, s, zpacked, bits, group, Y=None, ws=None, keep=False):
+    """keep=True: `ws` (EQAT_OP_Q_BWD size, must then be given) is left holding what eqat_qlinear_bwd(kept=True) needs."""
     T, I = X.shape
     O = Wpacked.shape[0]
     d = make_desc(T, I, O, bits, group, _dt(X), BF16)
     Y = torch.empty((T, O), dtype=X.dtype, device=X.device) if Y is None else Y
+    if keep and ws is None:
+        raise ValueError("keep=True needs the caller's workspace (it is the thing that is kept)")
     ws = workspace(d, OP_Q_FWD, X.device) if ws is None else ws
-    _check("eqat_qlinear_fwd", lib().eqat_qlinear_fwd(ctypes.byref(d), _p(X), _p(Wpacked), _p(s), _p(zpacked), _p(Y),
-                                                      _p(ws), ws.numel(), _stream()))
+    name = "eqat_qlinear_fwd_keep" if keep else "eqat_qlinear_fwd"
+    _check(name, getattr(lib(), name)(ctypes.byref(d), _p(X), _p(Wpacked), _p(s), _p(zpacked), _p(Y), _p(ws), ws.numel(),
+                                      _stream()))
     return Y
 
 
-def eqat_qlinear_bwd(X, Wpacked, s, zpacked, dY, in_features, bits, group, want=("dX", "ds"), out=None, ws=None):
+def eqat_qlinear_bwd(X, Wpacked, s, zpacked, dY, in_features, bits, group, want=("dX", "ds"), out=None, ws=None,
+                     kept=False):
     T, O = dY.shape
     I = int(in_features)
     d = make_desc(T, I, O, bits, group, _dt(dY), BF16)
     out = {} if out is None else out
     if "dX" in want and "dX" not in out: out["dX"] = torch.empty((T, I), dtype=dY.dtype, device=dY.device)
     if "ds" in want and "ds" not in out: out["ds"] = torch.empty((O, _groups(I, group)), dtype=torch.float32, device=dY.device)
+    if kept and ws is None:
+        raise ValueError("kept=True needs the workspace the forward call left")
     ws = workspace(d, OP_Q_BWD, dY.device) if ws is None else ws
-    _check("eqat_qlinear_bwd", lib().eqat_qlinear_bwd(ctypes.byref(d), _p(X), _p(Wpacked), _p(s), _p(zpacked), _p(dY),
-                                                      _p(out.get("dX")), _p(out.get("ds")), _p(ws), ws.numel(), _stream()))
+    name = "eqat_qlinear_bwd_kept" if kept else "eqat_qlinear_bwd"
+    _check(name, getattr(lib(), name)(ctypes.byref(d), _p(X), _p(Wpacked), _p(s), _p(zpacked), _p(dY),
+                                      _p(out.get("dX")), _p(out.get("ds")), _p(ws), ws.numel(), _stream()))
     return out
 
 

@@ -312,7 +312,7 @@ extern "C" {
 // E2E-QP forward / backward; the zero points come packed at N bits (zpacked) or as floats (zfloat), one of the two.
 static eqat_status qlinear_fwd_any(const eqat_desc *d, const void *X, const uint8_t *Wpacked, const float *s,
                                    const uint8_t *zpacked, const float *zfloat, void *Y, void *ws, size_t ws_bytes,
-                                   void *stream)
+                                   void *stream, bool keep = false)
 {
     Problem p;
     if (eqat_status e = check_desc(d, true, &p)) return e;
@@ -320,12 +320,13 @@ static eqat_status qlinear_fwd_any(const eqat_desc *d, const void *X, const uint
     EQAT_REQUIRE(Wpacked); EQAT_REQUIRE(s); EQAT_REQUIRE(zany);
     if (p.T > 0) { EQAT_REQUIRE(X); EQAT_REQUIRE(Y); }
     EQAT_ALIGNED(X); EQAT_ALIGNED(Wpacked); EQAT_ALIGNED(s); EQAT_ALIGNED(zany); EQAT_ALIGNED(Y);
-    const WsLayout l = ws_layout(p, EQAT_OP_Q_FWD);
+    // keep: backward-sized workspace, left holding the codes in the working layout and the (s, z) pairs
+    const WsLayout l = ws_layout(p, keep ? EQAT_OP_Q_BWD : EQAT_OP_Q_FWD);
     if (eqat_status e = check_ws(l, ws, ws_bytes)) return e;
-    if (p.T == 0) return EQAT_OK;
+    if (p.T == 0 && !keep) return EQAT_OK;
     hipStream_t st = (hipStream_t)stream;
     char *w8 = (char *)ws;
-    if (eqat::gemv_applies(p)) {          // a few tokens: one HBM-bound kernel on the caller's own packed arrays
+    if (!keep && eqat::gemv_applies(p)) { // a few tokens: one HBM-bound kernel on the caller's own packed arrays
         ProfScope ps(eqat::PK_GEMV, st);
         eqat::launch_gemv(p, X, Wpacked, s, zpacked, zfloat, Y, st);
         return launch_status();
@@ -334,6 +335,7 @@ static eqat_status qlinear_fwd_any(const eqat_desc *d, const void *X, const uint
         ProfScope ps(eqat::PK_PREPARE, st);
         eqat::launch_e2e_prepare(p, p.act_bf16 ? Wpacked : nullptr, w8 + l.codes, s, zpacked, zfloat, w8 + l.sz, st);
     }
+    if (p.T == 0) return launch_status();
     if (p.act_bf16) { ProfScope ps(eqat::PK_GEMM_FWD, st); eqat::launch_mfma_fwd(p, X, w8 + l.codes, w8 + l.sz, Y, st); }
     else { ProfScope ps(eqat::PK_F32, st); eqat::launch_f32_fwd(p, true, X, Wpacked, s, w8 + l.sz, Y, st); }
     return launch_status();
@@ -341,7 +343,7 @@ static eqat_status qlinear_fwd_any(const eqat_desc *d, const void *X, const uint
 
 static eqat_status qlinear_bwd_any(const eqat_desc *d, const void *X, const uint8_t *Wpacked, const float *s,
                                    const uint8_t *zpacked, const float *zfloat, const void *dY, void *dX, float *ds,
-                                   float *dz, void *ws, size_t ws_bytes, void *stream)
+                                   float *dz, void *ws, size_t ws_bytes, void *stream, bool kept = false)
 {
     Problem p;
     if (eqat_status e = check_desc(d, true, &p)) return e;
@@ -356,7 +358,7 @@ static eqat_status qlinear_bwd_any(const eqat_desc *d, const void *X, const uint
     if (dX == nullptr && !want_g) return EQAT_OK;
     hipStream_t st = (hipStream_t)stream;
     char *w8 = (char *)ws;
-    {
+    if (!kept) {
         ProfScope ps(eqat::PK_PREPARE, st);
         eqat::launch_e2e_prepare(p, p.act_bf16 ? Wpacked : nullptr, w8 + l.codes, s, zpacked, zfloat, w8 + l.sz, st);
     }
@@ -384,6 +386,19 @@ eqat_status eqat_qlinear_bwd(const eqat_desc *d, const void *X, const uint8_t *W
                              void *stream)
 {
     return qlinear_bwd_any(d, X, Wpacked, s, zpacked, nullptr, dY, dX, ds, nullptr, ws, ws_bytes, stream);
+}
+
+eqat_status eqat_qlinear_fwd_keep(const eqat_desc *d, const void *X, const uint8_t *Wpacked, const float *s,
+                                  const uint8_t *zpacked, void *Y, void *ws, size_t ws_bytes, void *stream)
+{
+    return qlinear_fwd_any(d, X, Wpacked, s, zpacked, nullptr, Y, ws, ws_bytes, stream, true);
+}
+
+eqat_status eqat_qlinear_bwd_kept(const eqat_desc *d, const void *X, const uint8_t *Wpacked, const float *s,
+                                  const uint8_t *zpacked, const void *dY, void *dX, float *ds, void *ws, size_t ws_bytes,
+                                  void *stream)
+{
+    return qlinear_bwd_any(d, X, Wpacked, s, zpacked, nullptr, dY, dX, ds, nullptr, ws, ws_bytes, stream, true);
 }
 
 eqat_status eqat_qlinear_fwd_z(const eqat_desc *d, const void *X, const uint8_t *Wpacked, const float *s,

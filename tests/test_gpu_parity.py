@@ -266,6 +266,24 @@ def test_e2e_qp_fp32(bits, g):
     check_e2e(X, W, s, z, dY, bits, g, TOL[torch.float32])
 
 
+@pytest.mark.parametrize("tag,T,I,O,bits,g,wdt", [c for c in BF16_CASES if c[0] in ("b2g64", "b3g128", "b4g32", "b2perchan")])
+def test_e2e_forward_that_keeps_its_prepared_codes_for_the_backward(tag, T, I, O, bits, g, wdt):
+    X, W, s, z, dY = make_case(tag, T, I, O, bits, g, torch.bfloat16, wdt)
+    z = z.clamp(0, 2 ** bits - 1)
+    Xd, sd, dYd = dev(X), dev(s), dev(dY)
+    Wp, zp = eq.eqat_pack(dev(W), sd, dev(z), bits, g)
+    d = eq.make_desc(T, I, O, bits, g, eq.BF16, eq.BF16)
+    ws = eq.workspace(d, eq.OP_Q_BWD, Xd.device)
+    ws.random_(0, 256)
+    Y = eq.eqat_qlinear_fwd(Xd, Wp, sd, zp, bits, g, ws=ws, keep=True)
+    out = eq.eqat_qlinear_bwd(Xd, Wp, sd, zp, dYd, I, bits, g, ws=ws, kept=True)
+    ref = eq.eqat_qlinear_bwd(Xd, Wp, sd, zp, dYd, I, bits, g)
+    assert torch.equal(out["dX"], ref["dX"]) and torch.equal(out["ds"], ref["ds"])
+    assert relerr(Y, oracle.qlinear_fwd(npf(X), Wp.cpu().numpy(), s.numpy(), zp.cpu().numpy(), bits, g)) <= TOL[torch.bfloat16]
+    if T > 16:      # the plain forward runs the same GEMM (at most 16 tokens: its matrix-vector kernel)
+        assert torch.equal(Y, eq.eqat_qlinear_fwd(Xd, Wp, sd, zp, bits, g))
+
+
 # ---------------------------------------------------------------- E2E-QP with trained (floating-point) zero points
 
 def check_e2e_trained_z(X, W, s, z, dY, bits, g, tol, seed):

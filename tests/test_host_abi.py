@@ -114,6 +114,13 @@ def test_null_alignment_and_workspace_errors_come_back_before_any_launch():
     assert L.eqat_fq_linear_bwd_kept(r, P, P, P, P, P, P, P, P, P, P, ws_need - 1, None) == WORKSPACE
     assert L.eqat_fq_linear_bwd_kept(r, P, P, P, P, None, P, P, P, P, P, ws_need, None) == NULL
     assert L.eqat_fq_linear_bwd_kept(r, P, P, P, P, P, None, None, None, None, P, ws_need, None) == OK      # nothing wanted
+    wq_f, wq_b = L.eqat_workspace_bytes(r, eq.OP_Q_FWD), L.eqat_workspace_bytes(r, eq.OP_Q_BWD)
+    assert wq_f <= wq_b
+    assert L.eqat_qlinear_fwd_keep(r, P, P, P, P, P, P, wq_b - 1, None) == WORKSPACE
+    assert L.eqat_qlinear_fwd_keep(r, P, None, P, P, P, P, wq_b, None) == NULL
+    assert L.eqat_qlinear_bwd_kept(r, P, P, P, P, P, P, P, P, wq_b - 1, None) == WORKSPACE
+    assert L.eqat_qlinear_bwd_kept(r, None, P, P, P, P, None, P, P, wq_b, None) == NULL      # ds wanted, X missing
+    assert L.eqat_qlinear_bwd_kept(r, P, P, P, P, P, None, None, P, wq_b, None) == OK        # nothing wanted
     # descriptor errors win over everything else
     bad = d(bits=9)
     assert L.eqat_fq_linear_fwd(ctypes.byref(bad), None, None, None, None, None, None, 0, None) == BITS
