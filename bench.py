@@ -282,7 +282,9 @@ def measure_other_rows(torch, eq, layers, bits, g, adt, dev, args):
     rows["eqat_init_minmax_28672x8192"] = hbm_row(init_big, n2 * (wbytes + 8.0 / g))
     del big
     rows["qlinear_fwd_1_token"] = decode_rows(torch, eq, bits, g, dev, args)
-    rows["block_ap_llama2_70b_w2g64"] = stacked_rows(torch, eq, dev, args)
+    rows["block_ap_llama2_70b_w2g64"] = stacked_rows(torch, eq, dev, args, "llama2_70b_w2g64", "llama2_70b_w2g64_fused")
+    # the headline block again with q|k|v and gate|up stacked (context: BASELINE's configuration is the seven linears)
+    rows["block_ap_llama2_7b_w2g64_stacked"] = stacked_rows(torch, eq, dev, args, None, "llama2_7b_block_ap_w2g64_fused")
 
     # Block-AP step glue on the same block: reconstruction loss over the seven output tensors, then one AdamW launch
     # per linear over {W, s, z} fed by the gradients of the last backward (copies of the parameters, so that the rows
@@ -319,13 +321,16 @@ def measure_other_rows(torch, eq, layers, bits, g, adt, dev, args):
     return rows
 
 
-def stacked_rows(torch, eq, dev, args):
-    """Block-AP step of the 70B-shaped block (4096 tokens, grouped-query attention: k and v are 1024 x 8192), once as
-    seven launches and once with q|k|v and gate|up stacked along the output dimension (four launches).  Groups run
-    along the input dimension, so the stack is quantized row by row exactly like its parts."""
+def stacked_rows(torch, eq, dev, args, separate, stacked):
+    """Block-AP step of a block (e.g. the 70B-shaped one: 4096 tokens, grouped-query attention, k and v 1024 x 8192), as
+    seven launches (workload `separate`, skipped if None) and with q|k|v and gate|up stacked along the output dimension
+    (workload `stacked`: four launches).  Groups run along the input dimension, so the stack is quantized row by row
+    exactly like its parts."""
     from paper_2407_11062_amd import synth
     out = {}
-    for key, name in (("seven_linears", "llama2_70b_w2g64"), ("qkv_and_gate_up_stacked", "llama2_70b_w2g64_fused")):
+    for key, name in (("seven_linears", separate), ("qkv_and_gate_up_stacked", stacked)):
+        if name is None:
+            continue
         wl = synth.WORKLOADS[name]
         layers = build_layers(torch, eq, synth, wl, dev)
         for _ in range(2):

@@ -70,6 +70,8 @@ WORKLOADS = {
                                   ("block_ap", "e2e_qp")),
     "llama2_70b_w2g64": Workload("llama2_70b_w2g64", tuple(llama_block(8192, 28672, 1024)), 4096, 2, 64, 0.015,
                                  "bf16", ("block_ap", "e2e_qp")),
+    "llama2_7b_block_ap_w2g64_fused": Workload("llama2_7b_block_ap_w2g64_fused", tuple(llama_block_fused(4096, 11008)),
+                                               8192, 2, 64, 0.02, "bf16", ("block_ap",)),
     "llama2_70b_w2g64_fused": Workload("llama2_70b_w2g64_fused", tuple(llama_block_fused(8192, 28672, 1024)), 4096, 2,
                                        64, 0.015, "bf16", ("block_ap", "e2e_qp")),
 }
