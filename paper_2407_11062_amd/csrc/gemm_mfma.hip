@@ -207,13 +207,15 @@ __device__ __forceinline__ void wait_all_and_barrier()
     asm volatile("" ::: "memory");
 }
 
-// Software pipeline of the main loop (one workgroup, K tile kt):
-//   - the activation tile kt+1 streams from global memory straight into the idle LDS buffer;
-//   - the weight codes of tile kt+2 are fetched into registers (two staging sets);
-//   - while the MFMAs consume LDS buffer kt&1, the staged codes of tile kt+1 become bf16 What in the idle
-//     weight buffer, a quarter after each 16-wide K slice, so that this VALU / LDS-write work hides under the
-//     MFMAs of the same wave; fragments of slice kk+1 are read while slice kk multiplies.
-// Loads past the end of K return zeros (buffer range check), so the tail needs no branches.
+// Software pipeline of the main loop (one workgroup, K tile kt, LDS buffer kt & 1):
+//   - behind the barrier of tile kt (which sits before its last 16-wide slice) the activation tile kt+2 starts to
+//     stream from global memory straight into LDS buffer kt & 1, whose last fragments are in registers by then;
+//   - the weight codes and (s, zbar) pairs of tile kt+3 are fetched into registers (two staging sets);
+//   - while the MFMAs consume buffer kt & 1, the staged codes of tile kt+1 become bf16 What in the other weight
+//     buffer, a quarter after each slice, so that this VALU / LDS-write work hides under the MFMAs of the same
+//     wave; fragments of slice kk+1 are read while slice kk multiplies.
+// K tiles past the end of K multiply zeros: the weights there are exactly zero (see load_a below).
+// A workgroup may own several output tiles; the pipeline then runs on through the tile boundaries.
 template <int BITS, bool BT, int BM, int BN, int BK, int WGM, int WGN>
 __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_q(const GemmQArgs a)
 {
