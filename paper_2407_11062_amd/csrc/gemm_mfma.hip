@@ -879,18 +879,31 @@ bool use_small_tile(int64_t m, int64_t n)
     return ((m + 255) / 256) * ((n + 255) / 256) < 160;
 }
 
+// The kernels need more dynamic LDS than the default limit; the attribute is per kernel AND per device, so it is set
+// once for every (instantiation, device) pair.  `done` is the caller's static mask of devices already served.
+template <typename K> void allow_dynamic_lds(K kern, size_t smem, uint64_t &done)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev > 63) dev = 0;
+    if ((done >> dev) & 1u) return;
+    (void)hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    done |= (uint64_t)1 << dev;
+}
+
 // Workgroups of `smem` bytes of LDS that the device runs at the same time (LDS is what limits these kernels), rounded
 // down to a multiple of 8.
 int resident_workgroups(size_t smem)
 {
-    static int cus = 0;
-    if (cus == 0) {
-        int dev = 0, n = 0;
-        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 8) n = 256;
-        cus = n;
+    static int cus_of[64] = {0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev > 63) dev = 0;
+    if (cus_of[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 8) n = 256;
+        cus_of[dev] = n;
     }
     const int per_cu = smem * 2 <= 160 * 1024 ? 2 : 1;
-    return (cus * per_cu) & ~7;
+    return (cus_of[dev] * per_cu) & ~7;
 }
 
 template <int BITS, bool BT, typename TS>
@@ -899,8 +912,8 @@ void launch_q(const GemmQArgs &args, hipStream_t st)
     constexpr int LDB = BT ? TS::BN + kPadKM : TS::BK + kPadKC;
     constexpr size_t smem = 2 * (size_t)(TS::BM * TS::BK + (BT ? TS::BK * LDB : TS::BN * LDB)) * sizeof(bf16_t);
     auto kern = k_gemm_q<BITS, BT, TS::BM, TS::BN, TS::BK, TS::WGM, TS::WGN>;
-    static bool attr_set = false;
-    if (!attr_set) { (void)hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem); attr_set = true; }
+    static uint64_t attr_done = 0;
+    allow_dynamic_lds(kern, smem, attr_done);
     GemmQArgs a = args;
     a.tiles_m = (a.M + TS::BM - 1) / TS::BM;
     a.tiles_n = (a.N + TS::BN - 1) / TS::BN;
@@ -927,8 +940,8 @@ void launch_dw_t(const GemmDwArgs &args, hipStream_t st)
     constexpr size_t smem = (size_t)TS::NS * TS::BK * (TS::BM + TS::BN) * sizeof(bf16_t);
     static_assert(smem <= 160 * 1024, "LDS of one CU");
     auto kern = k_gemm_dw<BITS, WT, AP, TS::BM, TS::BN, TS::BK, TS::NS, TS::WGM, TS::WGN>;
-    static bool attr_set = false;
-    if (!attr_set) { (void)hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem); attr_set = true; }
+    static uint64_t attr_done = 0;
+    allow_dynamic_lds(kern, smem, attr_done);
     GemmDwArgs a = args;
     a.tiles_m = (a.I + TS::BM - 1) / TS::BM;
     a.tiles_n = (a.O + TS::BN - 1) / TS::BN;
