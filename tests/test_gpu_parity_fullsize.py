@@ -42,16 +42,20 @@ CASES = [
     ("llama2_13b_w3g128", "q"), ("llama2_13b_w3g128", "gate"),
     ("llama2_70b_w2g64", "k"), ("llama2_70b_w2g64", "gate"), ("llama2_70b_w2g64", "down"),
     ("llama2_70b_w2g64_fused", "qkv"),      # q|k|v stacked along the output dimension: one launch instead of three
+    ("llama2_7b_w4g128", "q"), ("llama2_7b_w4g128", "up"),
+    ("llama2_7b_block_ap_w2g64", "o", "fp32 master weights"),
 ]
 
 
-@pytest.mark.parametrize("wname,lname", CASES)
-def test_fullsize_layer(wname, lname):
+@pytest.mark.parametrize("case", CASES, ids=lambda c: "-".join(c).replace(" ", "_"))
+def test_fullsize_layer(case):
+    wname, lname = case[0], case[1]
+    wdt = torch.float32 if len(case) > 2 else torch.bfloat16          # W and dW dtype; activations are bf16 throughout
     wl = synth.WORKLOADS[wname]
     lin = layer_of(wl, lname)
     T, O, I, bits, g = wl.tokens, lin.out_features, lin.in_features, wl.bits, wl.group
     print(f"case {wname}/{lname}: T={T} O={O} I={I} w{bits}g{g}", flush=True)
-    W = synth.normal((O, I), wl.w_std, synth.seed_of(wname, lname, "W"), torch.bfloat16)
+    W = synth.normal((O, I), wl.w_std, synth.seed_of(wname, lname, "W"), wdt)
     X = synth.normal((T, I), 1.0, synth.seed_of(wname, lname, "X"), torch.bfloat16)
     dY = synth.normal((T, O), 1.0, synth.seed_of(wname, lname, "dY"), torch.bfloat16)
     Wn = npf(W)
