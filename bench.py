@@ -133,10 +133,12 @@ def main():
     return 0
 
 
-def build_layers(torch, eq, synth, wl, dev):
-    """Seeded synthetic tensors, trained-state (s, z), preallocated outputs and workspaces for every linear of a workload."""
+def build_layers(torch, eq, synth, wl, dev, w_dtype=None):
+    """Seeded synthetic tensors, trained-state (s, z), preallocated outputs and workspaces for every linear of a workload.
+    w_dtype: dtype of W and dW (default: the activation dtype)."""
     T, bits, g = wl.tokens, wl.bits, wl.group
     adt = synth.torch_dtype(wl.act_dtype)
+    wdt = adt if w_dtype is None else w_dtype
     gen = torch.Generator(device=dev)
 
     def randn(shape, std, seed, dtype):
@@ -148,7 +150,7 @@ def build_layers(torch, eq, synth, wl, dev):
     for lin in wl.layers:
         O, I = lin.out_features, lin.in_features
         L = {"name": lin.name, "O": O, "I": I}
-        L["W"] = randn((O, I), wl.w_std, synth.seed_of(wl.name, lin.name, "W"), adt)
+        L["W"] = randn((O, I), wl.w_std, synth.seed_of(wl.name, lin.name, "W"), wdt)
         L["X"] = randn((T, I), 1.0, synth.seed_of(wl.name, lin.name, "X"), adt)
         L["dY"] = randn((T, O), 1.0, synth.seed_of(wl.name, lin.name, "dY"), adt)
         s, z = eq.eqat_init_minmax(L["W"], bits, g)
@@ -159,7 +161,7 @@ def build_layers(torch, eq, synth, wl, dev):
         L["s"], L["z"] = (s * u).contiguous(), (z + d).clamp_(0, 2 ** bits - 1).contiguous()
         G = s.shape[1]
         L["Y"] = torch.empty((T, O), dtype=adt, device=dev)
-        L["out"] = {"dX": torch.empty((T, I), dtype=adt, device=dev), "dW": torch.empty((O, I), dtype=adt, device=dev),
+        L["out"] = {"dX": torch.empty((T, I), dtype=adt, device=dev), "dW": torch.empty((O, I), dtype=wdt, device=dev),
                     "ds": torch.empty((O, G), dtype=torch.float32, device=dev),
                     "dz": torch.empty((O, G), dtype=torch.float32, device=dev)}
         dsc = eq.make_desc(T, I, O, bits, g, eq._dt(L["X"]), eq._dt(L["W"]))
@@ -284,6 +286,7 @@ def measure_other_rows(torch, eq, layers, bits, g, adt, dev, args):
     rows["qlinear_fwd_1_token"] = decode_rows(torch, eq, bits, g, dev, args)
     rows["block_ap_llama2_70b_w2g64"] = stacked_rows(torch, eq, dev, args, "llama2_70b_w2g64", "llama2_70b_w2g64_fused")
     # the headline block again with q|k|v and gate|up stacked (context: BASELINE's configuration is the seven linears)
+    rows["block_ap_llama2_7b_w2g64_fp32_weights"] = master_weight_row(torch, eq, dev, args, "llama2_7b_block_ap_w2g64")
     rows["block_ap_llama2_7b_w2g64_stacked"] = stacked_rows(torch, eq, dev, args, None, "llama2_7b_block_ap_w2g64_fused")
 
     # Block-AP step glue on the same block: reconstruction loss over the seven output tensors, then one AdamW launch
@@ -319,6 +322,25 @@ def measure_other_rows(torch, eq, layers, bits, g, adt, dev, args):
     del st
     rows["vendor_gemm_reference"] = vendor_gemm_rows(torch, layers, layers[0]["X"].shape[0], args)
     return rows
+
+
+def master_weight_row(torch, eq, dev, args, name):
+    """The Block-AP step of workload `name` with W and dW in fp32 (master weights) and bf16 activations: the quantize pass
+    reads twice the bytes and the dW epilogue reads and writes 4-byte weights; fwd and dX are unchanged."""
+    from paper_2407_11062_amd import synth
+    wl = synth.WORKLOADS[name]
+    layers = build_layers(torch, eq, synth, wl, dev, w_dtype=torch.float32)
+    for _ in range(2):
+        run_block_ap_step(eq, layers, wl.bits, wl.group)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        run_block_ap_step(eq, layers, wl.bits, wl.group)
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / args.steps
+    fl = 6.0 * wl.tokens * sum(L["O"] * L["I"] for L in layers)
+    return {"tokens": wl.tokens, "ms_per_step": round(dt * 1e3, 4), "tflops": round(fl / dt / 1e12, 2),
+            "pct_of_bf16_mfma_peak": round(100 * fl / dt / 1e12 / PEAK_BF16_TFLOPS, 2)}
 
 
 def stacked_rows(torch, eq, dev, args, separate, stacked):
