@@ -111,5 +111,5 @@ def test_fullsize_layer(case):
         y1 = eq.eqat_qlinear_fwd(Xd[:1].contiguous(), Wp, sd, zp, bits, g)
         torch.cuda.synchronize()
         errs["q.Y(1 token)"] = relerr(npf(y1), oracle.qlinear_fwd(npf(X[:1]), Wp_ref, s, zp_ref, bits, g))
-    print("  errors:", {k: round(v, 5) for k, v in errs.items()}, flush=True)
+    print("  errors:", {k: float(f"{v:.2e}") for k, v in errs.items()}, flush=True)
     assert errs and all(e <= TOL for e in errs.values()), errs
