@@ -185,3 +185,42 @@ def test_block_ap_steps_of_one_linear_against_the_oracle_and_the_loss_goes_down(
     torch.cuda.synchronize()
     losses = [l.item() for l in losses]
     assert losses[-1] < losses[0], losses
+
+
+# ---------------------------------------------------------------- at the sizes bench.py times
+
+def test_loss_and_update_at_full_size():
+    """The loss over one [8192, 4096] bf16 output of the 7B block (the workspace's 2048 partial sums in full use) and the
+    AdamW launch over a 4096 x 4096 linear with its 262144 step sizes and zero points, compared in full."""
+    T, O, I, g = 8192, 4096, 4096, 64
+    Y = synth.normal((T, O), 1.0, synth.seed_of("fullglue", "Y"), torch.bfloat16)
+    R = (Y.float() + synth.normal((T, O), 0.2, synth.seed_of("fullglue", "R"))).to(torch.bfloat16)
+    ref_loss, ref_dY = oracle.recon_loss(npf(Y), npf(R))
+    loss, dY = eq.eqat_recon_loss(Y.cuda(), R.cuda())
+    torch.cuda.synchronize()
+    assert abs(loss.item() - ref_loss) <= 1e-5 * ref_loss
+    assert relerr(dY, ref_dY) <= TOL[torch.bfloat16]
+    del Y, R, dY, ref_dY
+
+    tag = "fullglue"
+    lr_w, lr_q, b1, b2, eps = (f32(x) for x in (2e-5, 1e-4, 0.9, 0.999, 1e-8))
+    W, s, z = _state(tag, O, I, g, torch.bfloat16)
+    gW, gs, gz = _grads(tag, 1, O, I, g, torch.bfloat16)
+    Wd, sd, zd = W.cuda(), s.cuda(), z.cuda()
+    mom = [torch.zeros(t.shape, dtype=torch.float32, device="cuda") for t in (Wd, Wd, sd, sd, zd, zd)]
+    # two steps, so that the second starts from non-zero moments
+    ref = {"W": npf(W).astype(np.float64), "s": npf(s).astype(np.float64), "z": npf(z).astype(np.float64)}
+    rm = {k: np.zeros_like(v) for k, v in ref.items()}
+    rv = {k: np.zeros_like(v) for k, v in ref.items()}
+    for step in (1, 2):
+        h = eq.AdamW(lr_w, lr_q, b1, b2, eps, 0.0, 0.0, step)
+        eq.eqat_block_ap_update(h, 2, g, W=Wd, dW=gW.cuda(), mW=mom[0], vW=mom[1], s=sd, ds=gs.cuda(), ms=mom[2], vs=mom[3],
+                                z=zd, dz=gz.cuda(), mz=mom[4], vz=mom[5])
+        for k, gr, lr in (("W", gW, lr_w), ("s", gs, lr_q), ("z", gz, lr_q)):
+            ref[k], rm[k], rv[k] = oracle.adamw(ref[k], npf(gr), rm[k], rv[k], lr, b1, b2, eps, 0.0, step)
+        ref["W"] = npf(torch.from_numpy(ref["W"]).to(torch.bfloat16)).astype(np.float64)
+    torch.cuda.synchronize()
+    assert relerr(Wd, ref["W"]) <= 2.0 ** -7
+    assert relerr(sd, ref["s"]) <= 1e-5 and relerr(zd, ref["z"]) <= 1e-5
+    assert relerr(mom[0], rm["W"]) <= 1e-5 and relerr(mom[1], rv["W"]) <= 1e-5
+    assert relerr(mom[2], rm["s"]) <= 1e-5 and relerr(mom[5], rv["z"]) <= 1e-5
