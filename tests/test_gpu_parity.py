@@ -160,6 +160,8 @@ WALK_CASES = [
     ("walk_fwd", 4400, 320, 4104, 2, 64),      # fwd: 18 x 17 = 306 tiles of 256 x 256
     ("walk_dx", 4400, 4128, 328, 3, 32),       # dX: 18 x 17 tiles, K = O = 328
     ("walk_small", 4096, 256, 2304, 4, 128),   # fwd: 32 x 18 = 576 tiles of 128 x 128
+    ("walk_k64", 4400, 64, 4104, 2, 64),       # fwd: one K tile per output tile (the start-up loads already reach into the next)
+    ("walk_dx_k128", 4400, 4128, 128, 2, 32),  # dX: two K tiles per output tile
 ]
 
 
