@@ -71,6 +71,10 @@ WORKLOADS = {
     # the paper's 4-bit setting (w4g128) on the 7B shapes; not a BASELINE configuration, used by the full-size parity tests
     "llama2_7b_w4g128": Workload("llama2_7b_w4g128", tuple(llama_block(4096, 11008)), 4096, 4, 128, 0.02, "bf16",
                                  ("block_ap", "e2e_qp")),
+    # one group per row (the paper's group-size table ends at 256; per-channel is the limit case): the dW kernel then
+    # writes per-32-column partials and a second kernel reduces them
+    "llama2_7b_w2_per_channel": Workload("llama2_7b_w2_per_channel", tuple(llama_block(4096, 11008)), 4096, 2, -1, 0.02,
+                                         "bf16", ("block_ap", "e2e_qp")),
     "llama2_70b_w2g64": Workload("llama2_70b_w2g64", tuple(llama_block(8192, 28672, 1024)), 4096, 2, 64, 0.015,
                                  "bf16", ("block_ap", "e2e_qp")),
     "llama2_7b_block_ap_w2g64_fused": Workload("llama2_7b_block_ap_w2g64_fused", tuple(llama_block_fused(4096, 11008)),

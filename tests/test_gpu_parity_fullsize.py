@@ -43,6 +43,7 @@ CASES = [
     ("llama2_70b_w2g64", "k"), ("llama2_70b_w2g64", "gate"), ("llama2_70b_w2g64", "down"),
     ("llama2_70b_w2g64_fused", "qkv"),      # q|k|v stacked along the output dimension: one launch instead of three
     ("llama2_7b_w4g128", "q"), ("llama2_7b_w4g128", "up"),
+    ("llama2_7b_w2_per_channel", "q"), ("llama2_7b_w2_per_channel", "down"),
     ("llama2_7b_block_ap_w2g64", "o", "fp32 master weights"),
 ]
 
