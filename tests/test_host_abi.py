@@ -27,6 +27,37 @@ def test_library_exports_every_declared_symbol():
         assert hasattr(L, name), name
 
 
+def test_header_is_plain_c_and_cxx(tmp_path):
+    """The boundary is a C ABI: the header must compile on its own as C99 and as C++11, and a C program that calls the
+    host-only helpers must link against the library and agree with the Python binding on the descriptor's layout."""
+    import subprocess
+    hdr = os.path.join(ROOT, "include", "eqat.h")
+    subprocess.run(["gcc", "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", "-fsyntax-only", "-x", "c", hdr], check=True)
+    subprocess.run(["g++", "-std=c++11", "-Wall", "-Wextra", "-Werror", "-fsyntax-only", "-x", "c++", hdr], check=True)
+    src = tmp_path / "use.c"
+    src.write_text(
+        '#include <stdio.h>\n#include "eqat.h"\n'
+        "int main(void) {\n"
+        "  eqat_desc d = {8192, 4096, 11008, 2, 64, EQAT_BF16, EQAT_BF16};\n"
+        '  printf("%d %zu %zu %zu %zu\\n", (int)eqat_validate_desc(&d), sizeof(eqat_desc), eqat_packed_w_bytes(&d),\n'
+        "         eqat_packed_z_bytes(&d), eqat_workspace_bytes(&d, EQAT_OP_FQ_BWD));\n"
+        "  d.bits = 5;\n"
+        '  printf("%s\\n", eqat_status_string(eqat_validate_desc(&d)));\n'
+        "  return 0;\n}\n")
+    exe = tmp_path / "use"
+    libdir = os.path.dirname(eq.LIB_PATH)
+    subprocess.run(["gcc", "-std=c99", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe), "-L", libdir,
+                    "-l:" + os.path.basename(eq.LIB_PATH), "-Wl,-rpath," + libdir], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split("\n")
+    status, size, wb, zb, ws = (int(x) for x in out[0].split())
+    dd = d(T=8192, I=4096, O=11008)
+    L = eq.lib()
+    assert status == OK and size == ctypes.sizeof(eq.Desc)
+    assert wb == L.eqat_packed_w_bytes(ctypes.byref(dd)) == 11008 * 4096 * 2 // 8
+    assert zb == L.eqat_packed_z_bytes(ctypes.byref(dd)) and ws == L.eqat_workspace_bytes(ctypes.byref(dd), eq.OP_FQ_BWD)
+    assert out[1] == "bits must be 2, 3 or 4"
+
+
 def test_status_strings():
     L = eq.lib()
     seen = {L.eqat_status_string(i) for i in range(10)}
