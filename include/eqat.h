@@ -209,6 +209,21 @@ eqat_status eqat_recon_loss(int64_t n, int32_t dtype, const void *Y, const void 
                             void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * eqat_recon_loss for callers that cannot allocate device memory or pass a workspace: code under HIP graph capture,
+ * tight serving or training loops, harnesses that forbid hipMalloc.  Same kernels, same results (bitwise) as
+ * eqat_recon_loss; the workgroup partials live in an 8 KiB array inside the library's device image (one copy per GPU,
+ * held until the process ends) instead of `ws`.  The call allocates and frees nothing.
+ *   Limit: none on n; the array holds the 2048 partials that are the most a launch ever uses (a library built with a
+ *   larger eqat_recon_loss_workspace_bytes() returns EQAT_ERR_WORKSPACE here).
+ *   The address of the array is looked up on the first call on each device (hipGetSymbolAddress; failure gives
+ *   EQAT_ERR_DEVICE): make that first call outside stream capture.
+ *   All calls on one GPU share the array: calls that may run at the same time on one GPU (different streams) race on
+ *   it and must be ordered by the caller.  Nothing needs clearing between calls.
+ */
+eqat_status eqat_recon_loss_static(int64_t n, int32_t dtype, const void *Y, const void *Yref, float *loss, void *dY,
+                                   void *stream);
+
+/*
  * eqat_block_ap_update: one AdamW step, in place, on the three trained tensors of a linear in ONE launch, taking the
  * gradients as eqat_fq_linear_bwd wrote them (dW in W's dtype, ds and dz fp32).  Per element, in binary32:
  *   p <- p - lr wd p;  m <- b1 m + (1-b1) g;  v <- b2 v + (1-b2) g^2;

@@ -27,7 +27,7 @@ EXPORTS = ["eqat_status_string", "eqat_validate_desc", "eqat_packed_w_bytes", "e
            "eqat_fq_linear_fwd_keep", "eqat_fq_linear_bwd_kept", "eqat_pack",
            "eqat_unpack", "eqat_qlinear_fwd", "eqat_qlinear_bwd", "eqat_qlinear_fwd_keep", "eqat_qlinear_bwd_kept",
            "eqat_qlinear_fwd_z", "eqat_qlinear_bwd_z",
-           "eqat_recon_loss_workspace_bytes", "eqat_recon_loss", "eqat_block_ap_update",
+           "eqat_recon_loss_workspace_bytes", "eqat_recon_loss", "eqat_recon_loss_static", "eqat_block_ap_update",
            "eqat_profile_kernels", "eqat_profile_kernel_name",
            "eqat_profile_start", "eqat_profile_stop"]
 
@@ -84,6 +84,7 @@ def lib():
         L.eqat_qlinear_bwd_z.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.eqat_recon_loss_workspace_bytes.restype, L.eqat_recon_loss_workspace_bytes.argtypes = sz, []
         L.eqat_recon_loss.argtypes = [ctypes.c_int64, ctypes.c_int32, vp, vp, vp, vp, vp, sz, vp]
+        L.eqat_recon_loss_static.argtypes = [ctypes.c_int64, ctypes.c_int32, vp, vp, vp, vp, vp]
         L.eqat_block_ap_update.argtypes = [dp, ctypes.POINTER(AdamW)] + [vp] * 13
         L.eqat_profile_kernel_name.restype = ctypes.c_char_p
         L.eqat_profile_kernel_name.argtypes = [ctypes.c_int]
@@ -271,6 +272,13 @@ def eqat_recon_loss(Y, Yref, want_dY=True, loss=None, dY=None, ws=None):
     _check("eqat_recon_loss", lib().eqat_recon_loss(n, _dt(Y), _p(Y), _p(Yref), _p(loss), _p(dY if want_dY else None),
                                                     _p(ws), ws.numel(), _stream()))
     return loss, (dY if want_dY else None)
+
+
+def eqat_recon_loss_static(Y, Yref, loss, dY=None):
+    """eqat_recon_loss without a workspace and without any allocation: the caller passes every output."""
+    _check("eqat_recon_loss_static", lib().eqat_recon_loss_static(Y.numel(), _dt(Y), _p(Y), _p(Yref), _p(loss), _p(dY),
+                                                                  _stream()))
+    return loss, dY
 
 
 def eqat_block_ap_update(hyper: AdamW, bits, group, W=None, dW=None, mW=None, vW=None, s=None, ds=None, ms=None, vs=None,

@@ -5,6 +5,7 @@
 #include "kernels.h"
 #include "prof.h"
 
+#include <atomic>
 #include <vector>
 
 using eqat::Problem;
@@ -428,6 +429,49 @@ eqat_status eqat_recon_loss(int64_t n, int32_t dtype, const void *Y, const void 
     if (!aligned(ws, 256)) return EQAT_ERR_ALIGN;
     hipStream_t st = (hipStream_t)stream;
     { ProfScope ps(eqat::PK_LOSS, st); eqat::launch_recon_loss(n, dtype == EQAT_BF16, Y, Yref, loss, dY, static_cast<float *>(ws), st); }
+    return launch_status();
+}
+
+// ---- eqat_recon_loss for callers that cannot allocate ---------------------------------------------------------------
+// The workgroup partials of the loss live in this file-scope device array instead of a caller's workspace.  Every GPU
+// the library runs on holds its own copy at its own address; host code never uses the array's name as a pointer, only
+// the address hipGetSymbolAddress() returns for the device that is current, looked up once per device and kept.
+static __device__ __align__(256) float scratch[2048];
+static std::atomic<float *> g_scratch_of_device[64];
+
+static eqat_status scratch_of_current_device(float **out)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return EQAT_ERR_DEVICE;
+    float *p = g_scratch_of_device[dev].load(std::memory_order_acquire);
+    if (p == nullptr) {
+        void *sym = nullptr;
+        if (hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch)) != hipSuccess || sym == nullptr) {
+            (void)hipGetLastError();
+            return EQAT_ERR_DEVICE;
+        }
+        p = static_cast<float *>(sym);
+        g_scratch_of_device[dev].store(p, std::memory_order_release);     // every thread finds the same address
+    }
+    *out = p;
+    return EQAT_OK;
+}
+
+eqat_status eqat_recon_loss_static(int64_t n, int32_t dtype, const void *Y, const void *Yref, float *loss, void *dY,
+                                   void *stream)
+{
+    if (dtype != EQAT_F32 && dtype != EQAT_BF16) return EQAT_ERR_DTYPE;
+    if (n < 1) return EQAT_ERR_SHAPE;
+    EQAT_REQUIRE(Y); EQAT_REQUIRE(Yref); EQAT_REQUIRE(loss);
+    EQAT_ALIGNED(Y); EQAT_ALIGNED(Yref); EQAT_ALIGNED(dY);
+    if (!aligned(loss, 4)) return EQAT_ERR_ALIGN;
+    // the launch never uses more partials than eqat_recon_loss_workspace_bytes() holds, whatever n is
+    if (eqat::recon_loss_ws_bytes() > sizeof(float) * 2048) return EQAT_ERR_WORKSPACE;
+    float *partial = nullptr;
+    if (eqat_status e = scratch_of_current_device(&partial)) return e;
+    hipStream_t st = (hipStream_t)stream;
+    // every partial the second kernel reads is written by the first one of the same call: nothing to clear
+    { ProfScope ps(eqat::PK_LOSS, st); eqat::launch_recon_loss(n, dtype == EQAT_BF16, Y, Yref, loss, dY, partial, st); }
     return launch_status();
 }
 
