@@ -30,8 +30,11 @@
  *   Numerics   round() is round-half-to-even of the correctly rounded binary32
  *              quotient w/s (bf16 weights are widened first), so integer codes
  *              and packed bytes are identical on every implementation.
- *              zbar = round(z) is used in place of z; it is clamped to [0,2^N-1]
- *              only where it is packed.  Preconditions (not checked): s a normal,
+ *              zbar = clamp(round(z), 0, 2^N-1) is used in place of z in every
+ *              entry point (the zero point is stored at N bits when Block-AP ends,
+ *              so the packed layer is exactly the layer Block-AP trained); the
+ *              gradient passes straight through the rounding and the clamp.
+ *              Preconditions (not checked): s a normal,
  *              finite, positive binary32 number (>= 2^-126; the min/max rule
  *              never gives less than 1e-10), |z| <= 2^20, all inputs finite.
  *   Determinism  Same inputs give bitwise the same outputs.
@@ -132,7 +135,7 @@ eqat_status eqat_fq_linear_bwd_kept(const eqat_desc *d, const void *X, const voi
  * Layout (the paper fixes none): each row is a little-endian bit stream, code i
  * of the row in bits [i*N,(i+1)*N), stored as bytes, least significant first.
  *   Wpacked [O, I*N/8] bytes, zpacked [O, 4*ceil(G*N/32)] bytes (tail bits 0).
- * zbar is clamped to [0, 2^N-1] here.  d->tokens is ignored.
+ * zbar = clamp(round(z), 0, 2^N-1) as in the Block-AP calls.  d->tokens is ignored.
  */
 eqat_status eqat_pack(const eqat_desc *d, const void *W, const float *s, const float *z,
                       uint8_t *Wpacked, uint8_t *zpacked, void *stream);

@@ -27,9 +27,14 @@
  *  - Eq.(4) prints d what / d z = -1 outside the clamp range.  The derivative
  *    of Eq.(2) with W_int pinned at a clamp bound is -s (z is in integer
  *    units); -s is used.  The printed form is dz / s.
- *  - z is learnable, yet W_int must be an integer: the forward uses
- *    zbar = round_half_even(z) and passes the gradient straight through.
- *    zbar is clamped to [0, Qmax] only when it is packed into N bits.
+ *  - z is learnable, yet W_int must be an integer and z is stored at N bits
+ *    once Block-AP ends (Sec. 3.2 last paragraph; the N/g term of App. E's
+ *    bits per parameter), and E2E-QP starts from exactly the model Block-AP
+ *    trained (Sec. 3.3).  So the zero point Eqs.(1),(2) use must be one that
+ *    N bits can hold: zbar = clamp(round_half_even(z), 0, Qmax) everywhere,
+ *    in the fake-quant forward and backward as well as in the packed file,
+ *    with the gradient passed straight through both the rounding and the
+ *    clamp (d zbar / d z = 1).
  *  - The in-range condition is taken on round(w/s) + zbar BEFORE clamping,
  *    bounds inclusive, exactly as the case conditions of Eqs.(3)-(5) read.
  *
@@ -87,7 +92,13 @@ static quant1 quantize_one(float w, float s, double zbar, double qmax)
     return a;
 }
 
-static double zbar_of(float z) { return rint((double)z); }
+static double zbar_of(float z, double qmax)
+{
+    double zb = rint((double)z);
+    if (zb < 0.0) zb = 0.0;
+    if (zb > qmax) zb = qmax;
+    return zb;
+}
 
 /* ---- per-group min/max initialisation of s and z ------------------------- */
 /* Not in the paper (it never says how s, z start); the usual asymmetric
@@ -132,7 +143,7 @@ int eqo_quantize(const float *W, const float *s, const float *z, i64 O, i64 I, i
     for (i64 o = 0; o < O; ++o)
         for (i64 i = 0; i < I; ++i) {
             const i64 j = i / g;
-            quant1 a = quantize_one(W[o * I + i], s[o * G + j], zbar_of(z[o * G + j]), qmax);
+            quant1 a = quantize_one(W[o * I + i], s[o * G + j], zbar_of(z[o * G + j], qmax), qmax);
             codes[o * I + i] = (int32_t)a.q;
             if (side) side[o * I + i] = (int8_t)a.side;
         }
@@ -145,7 +156,7 @@ static void dequant_row(const float *Wrow, const float *srow, const float *zrow,
 {
     for (i64 i = 0; i < I; ++i) {
         const i64 j = i / g;
-        const double zb = zbar_of(zrow[j]);
+        const double zb = zbar_of(zrow[j], qmax);
         quant1 a = quantize_one(Wrow[i], srow[j], zb, qmax);
         out[i] = (a.q - zb) * (double)srow[j];
     }
@@ -268,7 +279,7 @@ int eqo_fq_linear_bwd(const float *X, const float *W, const float *s, const floa
             dwhat_row(X, dY, T, I, O, o, acc);
             for (i64 j = 0; j < G; ++j) {
                 const float sj = s[o * G + j];
-                const double zb = zbar_of(z[o * G + j]);
+                const double zb = zbar_of(z[o * G + j], qmax);
                 double gs = 0.0, gz = 0.0;
                 for (i64 i = j * g; i < (j + 1) * g; ++i) {
                     quant1 a = quantize_one(W[o * I + i], sj, zb, qmax);
@@ -329,11 +340,8 @@ int eqo_pack(const float *W, const float *s, const float *z, i64 O, i64 I, int b
         memset(wr, 0, (size_t)wrb);
         memset(zr, 0, (size_t)zrb);
         for (i64 j = 0; j < G; ++j) {
-            const double zb = zbar_of(z[o * G + j]);
-            double zp = zb;
-            if (zp < 0.0) zp = 0.0;
-            if (zp > qmax) zp = qmax;
-            put_bits(zr, j, bits, (unsigned)zp);
+            const double zb = zbar_of(z[o * G + j], qmax);      /* in [0, Qmax]: the zero point Block-AP used */
+            put_bits(zr, j, bits, (unsigned)zb);
             for (i64 i = j * g; i < (j + 1) * g; ++i) {
                 quant1 a = quantize_one(W[o * I + i], s[o * G + j], zb, qmax);
                 put_bits(wr, i, bits, (unsigned)a.q);

@@ -122,6 +122,13 @@ __device__ __forceinline__ float byte_to_float(uint32_t v, int b)      // b comp
     return (float)((v >> (8 * b)) & 0xFFu);                            // selected as v_cvt_f32_ubyte<b>
 }
 
+// The zero point Eqs.(1),(2) use: round(z), held inside what N bits can store (it is stored at N bits once Block-AP
+// ends, and E2E-QP must start from the very model Block-AP trained); the gradient passes straight through both.
+__device__ __forceinline__ float zbar_of(float z, float qmax)
+{
+    return __builtin_amdgcn_fmed3f(__builtin_rintf(z), 0.0f, qmax);
+}
+
 __device__ __forceinline__ float to_float(float v) { return v; }
 __device__ __forceinline__ float to_float(bf16_t v) { return (float)v; }
 

@@ -18,7 +18,7 @@ template <typename WT> struct FakeQuantW {   // What[o][i] from W, s, z  (Eqs.(1
     {
         if (o >= O || i >= I) return 0.0f;
         const int j = i / g;
-        const float sv = s[(size_t)o * G + j], zb = __builtin_rintf(z[(size_t)o * G + j]);
+        const float sv = s[(size_t)o * G + j], zb = zbar_of(z[(size_t)o * G + j], qmax);
         const float r = __builtin_rintf(to_float(W[(size_t)o * I + i]) / sv);
         const float q = __builtin_fminf(__builtin_fmaxf(r + zb, 0.0f), qmax);
         return (q - zb) * sv;
@@ -88,7 +88,7 @@ __global__ __launch_bounds__(256) void k_f32_epilogue_block_ap(const float *__re
     const int t = blockIdx.x * 256 + threadIdx.x;
     if (t >= O * G) return;
     const int o = t / G, j = t - o * G;
-    const float sv = s[t], zb = __builtin_rintf(z[t]);
+    const float sv = s[t], zb = zbar_of(z[t], qmax);
     float gs = 0.0f, gz = 0.0f;
     for (int i = j * g; i < (j + 1) * g; ++i) {
         const size_t e = (size_t)o * I + i;

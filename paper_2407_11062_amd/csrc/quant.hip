@@ -6,20 +6,10 @@
 namespace eqat {
 
 // ---------------------------------------------------------------------------------------------
-// Eq.(1) for one weight.  The code must equal clamp(round_half_even(fl32(w/s)) + zbar, 0, Qmax)
-// exactly.  fl32(w/s) costs a dozen instructions, so the common case uses w * (1/s), which is within
-// 2^-23 relative of the true quotient; only when that product lies within 2^-20 (relative) of a
-// rounding tie - where the cheap and the exact quotient could round differently - is the exact
-// division evaluated.  Far from a tie both quotients round to the same integer, so the code is exact.
-// Returns round(w/s); `tie` is set when the caller must redo the element with quant_exact().
-__device__ __forceinline__ float quant_fast(float w, float rinv, bool &tie)
-{
-    const float t = w * rinv;
-    const float r = __builtin_rintf(t);
-    const float thr = __builtin_fmaf(__builtin_fabsf(t), -0x1p-20f, 0.5f - 0x1p-20f);
-    tie = __builtin_fabsf(t - r) >= thr;
-    return r;
-}
+// Eq.(1) for one weight.  The code must equal clamp(round_half_even(fl32(w/s)) + zbar, 0, Qmax) exactly.  The exact
+// quotient costs a dozen instructions, so k_quantize first uses w * (1/s), which is within 2^-22 relative of it; only
+// a chunk in which some product lies too close to a rounding tie - where the cheap and the exact quotient could round
+// differently - is redone with this exact division.
 __device__ __forceinline__ float quant_exact(float w, float s) { return __builtin_rintf(w / s); }
 
 template <typename WT> struct Chunk8;   // 8 consecutive weights of one lane
@@ -59,7 +49,7 @@ __device__ __forceinline__ uint32_t quad_bcast(uint32_t v, int k)
 // quad own one 32-code segment, i.e. BITS output words, assembled with quad permutes.
 //   codes     [O, I*BITS/32] words      packed stream (same layout as eqat_pack's Wpacked)
 //   clampbits [O, I/8] bytes (CLAMPBITS) bit k of byte e/8: weight e was clamped by Eq.(1)
-//   sz        [O, G] float2 or NULL     (s, zbar) per group, zbar = round(z) (clamped iff CLAMP_Z)
+//   sz        [O, G] float2 or NULL     (s, zbar) per group, zbar = clamp(round(z), 0, Qmax)
 // Rows are contiguous and g divides I, so weight e belongs to group e / g of the flattened [O*G] arrays.
 // Per weight the common path costs: widen, multiply, round, two ops of tie test, clamp, convert, shift-add.
 // The clamp is applied to round(w/s) against [-zbar, Qmax - zbar] and zbar is added once, as an integer, to
@@ -76,7 +66,7 @@ __device__ __forceinline__ void pack_z_word(const float *__restrict__ z, uint32_
     uint32_t j = bit0 / BITS;                   // first code with bits in this word
     uint64_t acc = 0;
     for (; j < G && j * BITS < bit0 + 32u; ++j) {
-        const uint32_t code = (uint32_t)__builtin_amdgcn_fmed3f(__builtin_rintf(z[row * G + j]), 0.0f, qmax);
+        const uint32_t code = (uint32_t)zbar_of(z[row * G + j], qmax);
         const int sh = (int)(j * BITS) - (int)bit0;         // may be negative for a code straddling in from the left
         acc |= sh >= 0 ? ((uint64_t)code << sh) : ((uint64_t)code >> (-sh));
     }
@@ -93,7 +83,7 @@ struct QuantizeArgs {
 
 constexpr int kQuantUnroll = 4;     // chunks per thread: 64 B (bf16) / 128 B (fp32) of W in flight per lane
 
-template <typename WT, int BITS, bool CLAMP_Z, bool CLAMPBITS, bool WORK>
+template <typename WT, int BITS, bool CLAMPBITS, bool WORK>
 __global__ __launch_bounds__(256) void k_quantize(const QuantizeArgs a)
 {
     constexpr int U = kQuantUnroll;
@@ -125,8 +115,7 @@ __global__ __launch_bounds__(256) void k_quantize(const QuantizeArgs a)
         const uint32_t c = c0 + u * 256u;
         if (c >= a.n_chunks) break;
         const uint32_t e = c * 8u;
-        float zbar = __builtin_rintf(zb[u]);
-        if (CLAMP_Z) zbar = __builtin_amdgcn_fmed3f(zbar, 0.0f, qmax);
+        const float zbar = zbar_of(zb[u], qmax);
         if (a.sz != nullptr && e == gi[u] * a.g) { floatx2 o; o[0] = sv[u]; o[1] = zbar; a.sz[gi[u]] = o; }
         const float rinv = __builtin_amdgcn_rcpf(sv[u]);          // 1 ulp; s is a normal number
         const float lo = -zbar, hi = qmax - zbar;
@@ -378,11 +367,11 @@ static void quantize_t(const Problem &p, const void *W, const float *s, const fl
     a.zpacked = (uint32_t *)zpacked; a.G = (uint32_t)p.G; a.row_words = (uint32_t)((p.G * p.bits + 31) / 32);
     a.n_zwords = zpacked != nullptr ? (uint32_t)p.O * a.row_words : 0u;
     const dim3 grid(a.n_quant_blocks + blocks_for(a.n_zwords)), block(256);
-    // eqat_pack: dense stream, no clamp plane (zbar does not enter the codes, it is clamped where it is packed);
+    // eqat_pack: dense stream, no clamp plane;
     // the quantize pass of the Block-AP calls: working layout, clamp plane for the backward
-    if (for_pack) k_quantize<WT, BITS, false, false, false><<<grid, block, 0, st>>>(a);
-    else if (clampbits != nullptr) k_quantize<WT, BITS, false, true, true><<<grid, block, 0, st>>>(a);
-    else k_quantize<WT, BITS, false, false, true><<<grid, block, 0, st>>>(a);
+    if (for_pack) k_quantize<WT, BITS, false, false><<<grid, block, 0, st>>>(a);
+    else if (clampbits != nullptr) k_quantize<WT, BITS, true, true><<<grid, block, 0, st>>>(a);
+    else k_quantize<WT, BITS, false, true><<<grid, block, 0, st>>>(a);
 }
 
 void launch_quantize(const Problem &p, const void *W, const float *s, const float *z, void *codes, void *clampbits,

@@ -238,8 +238,7 @@ def test_empty_token_batch():
 
 def check_e2e(X, W, s, z, dY, bits, g, tol):
     I = W.shape[1]
-    qmax = 2 ** bits - 1
-    z = z.clamp(0, qmax)
+    # z as Block-AP left it, -1 and Qmax + 1 included: Eqs.(1),(2) and the packed file use the same N-bit zero point
     Xn, Wn, sn, zn, dYn = npf(X), npf(W), s.numpy(), z.numpy(), npf(dY)
     Wp_ref, zp_ref = oracle.pack(Wn, sn, zn, bits, g)
     Y_ref = oracle.qlinear_fwd(Xn, Wp_ref, sn, zp_ref, bits, g)
@@ -266,6 +265,39 @@ def test_e2e_qp_bf16(tag, T, I, O, bits, g, wdt):
 def test_e2e_qp_fp32(bits, g):
     X, W, s, z, dY = make_case(("e2e32", bits, g), 70, 256, 44, bits, g, torch.float32, torch.float32)
     check_e2e(X, W, s, z, dY, bits, g, TOL[torch.float32])
+
+
+@pytest.mark.parametrize("act", [torch.bfloat16, torch.float32])
+@pytest.mark.parametrize("bits,g", [(2, 64), (3, 128), (4, 32)])
+def test_packed_layer_is_the_layer_block_ap_trained_for_any_zero_point(bits, g, act):
+    # Sec. 3.3: E2E-QP starts from the Block-AP result.  With zero points that left the N-bit range during training
+    # (-1.4, -1, Qmax + 1, Qmax + 2.5) the packed layer must give the very Y and dX of the fake-quant layer: both GEMM
+    # paths consume the same codes and the same (s, zbar) pairs, so the comparison is bitwise.
+    T, I, O = 140, 256, 72
+    qmax = 2 ** bits - 1
+    X, W, s, z, dY = make_case(("handoff", bits, g), T, I, O, bits, g, act, act)
+    z[0::5] = -1.0
+    z[1::5] = qmax + 1.0
+    z[2::5, 0] = -1.4
+    z[3::5, 0] = qmax + 2.5
+    Xd, Wd, sd, zd, dYd = dev(X), dev(W), dev(s), dev(z), dev(dY)
+    Wp, zp = eq.eqat_pack(Wd, sd, zd, bits, g)
+    Wp_ref, zp_ref = oracle.pack(npf(W), s.numpy(), z.numpy(), bits, g)
+    assert np.array_equal(Wp.cpu().numpy(), Wp_ref) and np.array_equal(zp.cpu().numpy(), zp_ref)
+    Y_fq = eq.eqat_fq_linear_fwd(Xd, Wd, sd, zd, bits, g)
+    Y_q = eq.eqat_qlinear_fwd(Xd, Wp, sd, zp, bits, g)
+    dX_fq = eq.eqat_fq_linear_bwd(Xd, Wd, sd, zd, dYd, bits, g, want=("dX",))["dX"]
+    dX_q = eq.eqat_qlinear_bwd(Xd, Wp, sd, zp, dYd, I, bits, g, want=("dX",))["dX"]
+    torch.cuda.synchronize()
+    if act == torch.bfloat16:
+        assert torch.equal(Y_fq, Y_q) and torch.equal(dX_fq, dX_q)
+    else:       # the fp32 path multiplies (q - z) * s in both, in the same order, from different kernels' operands
+        assert relerr(Y_q, npf(Y_fq).astype(np.float64)) <= 1e-6 and relerr(dX_q, npf(dX_fq).astype(np.float64)) <= 1e-6
+    assert relerr(Y_q, oracle.fq_linear_fwd(npf(X), npf(W), s.numpy(), z.numpy(), bits, g)) <= TOL[act]
+    ref = oracle.fq_linear_bwd(npf(X), npf(W), s.numpy(), z.numpy(), npf(dY), bits, g)
+    out = eq.eqat_fq_linear_bwd(Xd, Wd, sd, zd, dYd, bits, g)
+    for k in ("dX", "dW", "ds", "dz"):
+        assert relerr(out[k], ref[k]) <= TOL[act], k
 
 
 @pytest.mark.parametrize("tag,T,I,O,bits,g,wdt", [c for c in BF16_CASES if c[0] in ("b2g64", "b3g128", "b4g32", "b2perchan")])

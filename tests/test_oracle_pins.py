@@ -106,12 +106,14 @@ def test_quotient_is_the_binary32_quotient():
     assert codes[0, 0] == 2        # tie 1.5 -> even 2 ; an fp64 quotient would have given 1
 
 
-def test_zero_point_is_rounded_but_not_clamped_in_fake_quant():
-    # zbar = round_half_even(z); z = -1 leaves the code range but must still be honoured
+def test_zero_point_is_rounded_and_kept_inside_n_bits_in_fake_quant():
+    # zbar = clamp(round_half_even(z), 0, Qmax): the zero point is stored at N bits when Block-AP ends (Sec. 3.2 last
+    # paragraph, App. E) and E2E-QP starts from the model Block-AP trained (Sec. 3.3), so Eqs.(1),(2) must not use a
+    # zero point the N-bit file cannot hold
     W = np.zeros((1, 32), np.float32)
     W[0, :4] = [0.0, 1.0, 2.0, 5.0]
     s = np.ones((1, 1), np.float32)
-    for zval, zbar in [(-1.0, -1.0), (0.5, 0.0), (1.5, 2.0), (2.4, 2.0)]:
+    for zval, zbar in [(-1.0, 0.0), (-0.6, 0.0), (0.5, 0.0), (1.5, 2.0), (2.4, 2.0), (3.4, 3.0), (3.6, 3.0), (9.0, 3.0)]:
         z = np.full((1, 1), zval, np.float32)
         What = oracle.fake_quant(W, s, z, 2, 32)
         expect = np.clip(np.array([0, 1, 2, 5]) + zbar, 0, 3) - zbar
@@ -251,11 +253,12 @@ def test_brute_force_branches_on_a_small_lattice():
                 fl = u.numerator // u.denominator
                 frac = u - fl
                 r = fl + (1 if frac > Fraction(1, 2) else 0) if frac != Fraction(1, 2) else (fl if fl % 2 == 0 else fl + 1)
-                pre = r + zi
+                zc = min(max(zi, 0), qmax)          # the zero point N bits can hold
+                pre = r + zc
                 q = min(max(pre, 0), qmax)
                 assert codes[0, n] == q
                 assert side[0, n] == (-1 if pre < 0 else (1 if pre > qmax else 0))
-                assert What[0, n] == float((q - zi) * s_f)
+                assert What[0, n] == float((q - zc) * s_f)
 
 
 # ---------------------------------------------------------------- init
@@ -328,6 +331,46 @@ def test_pack_unpack_round_trip(bits, g):
     assert Wp.shape == (O, I * bits // 8)
     c2, z2 = oracle.unpack(Wp, zp, I, bits, g)
     assert np.array_equal(c2, codes) and np.array_equal(z2, z.astype(np.int32))
+
+
+def test_packed_model_is_the_model_block_ap_trained_also_for_zero_points_outside_n_bits():
+    # Sec. 3.3: E2E-QP starts from the Block-AP result.  Whatever z Block-AP ends with (here also -1.3, -1, Qmax + 1,
+    # Qmax + 2.6: outside what N bits hold), the packed layer must compute the same What, Y, dX as the fake-quant layer,
+    # and E2E-QP's ds must be the fake-quant ds with the straight-through term of Eq.(3) replaced by (q - zbar).
+    r = rng(77)
+    for bits in (2, 3, 4):
+        qmax = 2 ** bits - 1
+        T, I, O, g = 6, 64, 5, 32
+        W = r.normal(0, 0.02, (O, I)).astype(np.float32)
+        X = r.normal(0, 1, (T, I)).astype(np.float32); dY = r.normal(0, 1, (T, O)).astype(np.float32)
+        s, _ = oracle.init_minmax(W, bits, g)
+        z = np.array([[-1.3, -1.0], [0.0, 1.0], [qmax, qmax + 1.0], [qmax + 2.6, 0.4], [1.5, 2.5]], np.float32)
+        Wp, zp = oracle.pack(W, s, z, bits, g)
+        _, zc = oracle.unpack(Wp, zp, I, bits, g)
+        assert np.array_equal(zc, np.clip(np.rint(z), 0, qmax).astype(np.int32))
+        assert np.array_equal(oracle.qlinear_fwd(X, Wp, s, zp, bits, g), oracle.fq_linear_fwd(X, W, s, z, bits, g))
+        a = oracle.qlinear_bwd(X, Wp, s, zp, dY, I, bits, g)
+        b = oracle.fq_linear_bwd(X, W, s, z, dY, bits, g)
+        assert np.array_equal(a["dX"], b["dX"])
+        # the same forward with z already inside the range gives the same result: clamping is all that happens
+        assert np.array_equal(oracle.fake_quant(W, s, z, bits, g), oracle.fake_quant(W, s, np.clip(z, 0, qmax), bits, g))
+
+
+def test_zero_point_gradient_passes_straight_through_the_clamp():
+    # z = -1 is held at zbar = 0; Eq.(4)'s branches are evaluated with that zbar and d zbar / d z = 1 (straight through),
+    # so dz is exactly what z = 0 gives
+    r = rng(78)
+    T, I, O, g, bits = 4, 32, 3, 32, 2
+    W = r.normal(0, 0.05, (O, I)).astype(np.float32)
+    X = r.normal(0, 1, (T, I)).astype(np.float32); dY = r.normal(0, 1, (T, O)).astype(np.float32)
+    s = np.full((O, 1), 0.02, np.float32)
+    out_lo = oracle.fq_linear_bwd(X, W, s, np.full((O, 1), -1.0, np.float32), dY, bits, g)
+    out_0 = oracle.fq_linear_bwd(X, W, s, np.zeros((O, 1), np.float32), dY, bits, g)
+    out_hi = oracle.fq_linear_bwd(X, W, s, np.full((O, 1), 4.0, np.float32), dY, bits, g)
+    out_3 = oracle.fq_linear_bwd(X, W, s, np.full((O, 1), 3.0, np.float32), dY, bits, g)
+    for k in ("dX", "dW", "ds", "dz"):
+        assert np.array_equal(out_lo[k], out_0[k]) and np.array_equal(out_hi[k], out_3[k])
+    assert np.abs(out_lo["dz"]).max() > 0
 
 
 def test_pack_clamps_zero_point_into_n_bits():
