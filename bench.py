@@ -7,10 +7,15 @@ seven linears of a Llama-2-7B-shaped decoder block, 8192 tokens, 2-bit codes, gr
 device before the timed region; outputs and workspaces are pre-allocated.
 
 Prints ONE JSON line.  Besides the contract fields it carries
-  roofline      the dominant kernel of the step against the bf16 MFMA peak (HIP events inside the library),
-  cpu_baseline  the fp64 CPU oracle timed on a bounded sample of the same workload,
-  rows          the remaining rows of the hot path measured in the same run: E2E-QP fwd+bwd (4096 tokens; step sizes
-                trained, and step sizes + zero points trained), eqat_pack and eqat_init_minmax (GB/s against the HBM peak).
+  roofline        the dominant kernel of the step against the bf16 MFMA peak (HIP events inside the library), and against
+                  the rate a bare MFMA loop reaches on this chip in this run (measured_peaks),
+  measured_peaks  a loop of nothing but MFMAs (zeros and random operands) and a plain device copy, timed in this run,
+  cpu_baseline    the fp64 CPU oracle timed on a bounded sample of the same workload,
+  rows            the other rows of the hot path and the other configurations, measured in the same run: E2E-QP on the
+                  7B block; Block-AP, pack and E2E-QP on the 13B block (3 bit, group 128) and on the 70B block; pack, init,
+                  loss, update (GB/s against the HBM peak and the measured copy rate); the few-token forward.
+Step times: `value` / `ms_per_step` are the wall-clock mean over exactly --steps steps between two synchronisations;
+`ms_per_step_median` / `_min` come from HIP events recorded between the steps on the stream the kernels run on.
 """
 from __future__ import annotations
 
@@ -31,14 +36,115 @@ COPY_CALIBRATION_BYTES = 1 << 30
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=25)
+    ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="llama2_7b_block_ap_w2g64")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-rows", action="store_true", help="skip the E2E-QP / pack / init measurements")
+    ap.add_argument("--no-rows", action="store_true", help="skip the rows beside the headline step")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a few 1 GiB device copies: the reference reading for the FETCH_SIZE / WRITE_SIZE counters")
     return ap.parse_args()
+
+
+def time_steps(torch, fn, steps, warmup):
+    """`warmup` untimed calls of fn, then exactly `steps` timed ones between two synchronisations (wall clock), with a HIP
+    event recorded on the current stream (the one the library launches on) before every step and after the last."""
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    t0 = time.perf_counter()
+    for i in range(steps):
+        ev[i].record()
+        fn()
+    ev[steps].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    per = sorted(ev[i].elapsed_time(ev[i + 1]) for i in range(steps))
+    return {"mean_ms": 1e3 * wall / steps, "median_ms": per[len(per) // 2], "min_ms": per[0]}
+
+
+def profile_kernels(torch, eq, fn, steps):
+    """Average launch duration of every kernel class of the library over `steps` calls of fn (HIP events inside the
+    library, on the stream each kernel runs on; they cost a little, so step times are taken without them)."""
+    eq.eqat_profile_start()
+    for _ in range(steps):
+        fn()
+    torch.cuda.synchronize()
+    return eq.eqat_profile_stop()
+
+
+def step_row(torch, eq, fn, flops, tokens, flop_per_launch, args, peaks):
+    """One fwd+bwd step of a block: step time (mean / median / min), TFLOP/s, and the three GEMM kernels per launch."""
+    t = time_steps(torch, fn, args.steps, 2)
+    prof = profile_kernels(torch, eq, fn, max(5, args.steps // 2))
+    tf = flops / (t["mean_ms"] * 1e-3) / 1e12
+    row = {"tokens": tokens, "ms_per_step": round(t["mean_ms"], 4), "ms_per_step_median": round(t["median_ms"], 4),
+           "ms_per_step_min": round(t["min_ms"], 4), "tflops": round(tf, 2),
+           "tflops_at_median": round(flops / (t["median_ms"] * 1e-3) / 1e12, 2),
+           "pct_of_bf16_mfma_peak": round(100 * tf / PEAK_BF16_TFLOPS, 2),
+           "frac_of_measured_mfma_peak": frac_measured(tf, peaks),
+           "tokens_per_s_per_layer": round(tokens / (t["mean_ms"] * 1e-3), 1),
+           "kernels": kernel_table(prof, flop_per_launch, peaks)}
+    return row
+
+
+def frac_measured(tflops, peaks):
+    m = peaks.get("mfma_bf16_random_operands_tflops") if peaks else None
+    return round(tflops / m, 4) if m else None
+
+
+def kernel_table(prof, flop_per_launch, peaks):
+    out = {}
+    for k, (ms, n) in prof.items():
+        out[k] = {"launches": n, "avg_ms": round(ms / n, 4)}
+        if k.startswith("gemm_"):
+            tf = flop_per_launch / (ms / n * 1e-3) / 1e12
+            out[k].update({"tflops": round(tf, 2), "frac": round(tf / PEAK_BF16_TFLOPS, 4),
+                           "frac_of_measured_peak": frac_measured(tf, peaks)})
+    return out
+
+
+def measured_peaks(torch, dev, args):
+    """What this chip gives, in this run: (a) a loop of nothing but v_mfma_f32_32x32x16_bf16, two waves per SIMD on all
+    compute units, on all-zero and on random bf16 operands (the clock the chip holds depends on the bits it multiplies);
+    (b) a plain copy kernel and the runtime's device copy on a 1 GiB buffer.  Bench-only kernels (libeqat_peaks.so)."""
+    import ctypes
+    path = os.path.join(ROOT, "paper_2407_11062_amd", "libeqat_peaks.so")
+    if not os.path.exists(path):
+        return {"error": "libeqat_peaks.so not built"}
+    L = ctypes.CDLL(path)
+    vp = ctypes.c_void_p
+    L.eqat_peak_mfma_flop.restype = ctypes.c_double
+    L.eqat_peak_mfma_flop.argtypes = [ctypes.c_int, ctypes.c_int]
+    L.eqat_peak_mfma_loop.argtypes = [vp, ctypes.c_size_t, ctypes.c_int, ctypes.c_int, vp, vp]
+    L.eqat_peak_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
+    cus = torch.cuda.get_device_properties(dev).multi_processor_count
+    groups, iters = cus, 20000                      # one workgroup of 8 waves per compute unit; about 1 ms per launch
+    sink = torch.zeros(1, dtype=torch.float32, device=dev)
+    out = {"compute_units": cus}
+    stream = lambda: vp(torch.cuda.current_stream().cuda_stream)
+    for name, data in (("zero", torch.zeros(1 << 20, dtype=torch.bfloat16, device=dev)),
+                       ("random", torch.randn(1 << 20, device=dev).bfloat16())):
+        def run():
+            rc = L.eqat_peak_mfma_loop(vp(data.data_ptr()), data.numel() * 2, groups, iters, vp(sink.data_ptr()), stream())
+            assert rc == 0
+        t = time_steps(torch, run, 20, 3)
+        out[f"mfma_bf16_{name}_operands_tflops"] = round(L.eqat_peak_mfma_flop(groups, iters) / (t["median_ms"] * 1e-3) / 1e12, 1)
+    nbytes = 1 << 30
+    src = torch.empty(nbytes, dtype=torch.uint8, device=dev).random_(0, 256)
+    dst = torch.empty_like(src)
+
+    def kcopy():
+        assert L.eqat_peak_copy(vp(dst.data_ptr()), vp(src.data_ptr()), nbytes, stream()) == 0
+
+    t = time_steps(torch, kcopy, 20, 3)
+    out["copy_kernel_gbs"] = round(2.0 * nbytes / (t["median_ms"] * 1e-3) / 1e9, 1)      # bytes read + bytes written
+    t = time_steps(torch, lambda: dst.copy_(src), 20, 3)
+    out["runtime_copy_gbs"] = round(2.0 * nbytes / (t["median_ms"] * 1e-3) / 1e9, 1)
+    out["note"] = ("median of 20 launches by HIP events; copy rates count bytes read plus bytes written of a 1 GiB buffer; "
+                   "published peaks: 2500 TFLOP/s dense bf16, 8000 GB/s")
+    return out
 
 
 def main():
@@ -73,23 +179,12 @@ def main():
     def block_ap_step():
         run_block_ap_step(eq, layers, bits, g)
 
-    for _ in range(args.warmup):
-        block_ap_step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        block_ap_step()
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    # the same steps once more with the library's per-kernel event timers on (they cost a little, so `value` above is
-    # taken without them): average launch duration of every kernel on the stream it runs on
-    eq.eqat_profile_start()
-    for _ in range(args.steps):
-        block_ap_step()
-    torch.cuda.synchronize()
-    prof = eq.eqat_profile_stop()
-    ms_step = 1e3 * elapsed / args.steps
-    tflops = flops_step / (elapsed / args.steps) / 1e12
+    # the headline: W warm-up steps, then exactly K steps between two synchronisations
+    t = time_steps(torch, block_ap_step, args.steps, args.warmup)
+    prof = profile_kernels(torch, eq, block_ap_step, args.steps)
+    peaks = measured_peaks(torch, dev, args)
+    ms_step = t["mean_ms"]
+    tflops = flops_step / (ms_step * 1e-3) / 1e12
 
     # dominant kernel of the step: all three GEMM kernels do 2*T*I*O flop per launch
     gemms = {k: v for k, v in prof.items() if k.startswith("gemm_")}
@@ -102,16 +197,19 @@ def main():
     if os.path.exists(tpath):
         traffic = json.load(open(tpath)).get(args.workload, {}).get(dom)
     roofline = {"bound": "mfma", "kernel": dom, "achieved": round(dom_tflops, 2), "peak": PEAK_BF16_TFLOPS,
-                "unit": "TFLOP/s", "frac": round(dom_tflops / PEAK_BF16_TFLOPS, 4), "traffic": traffic,
+                "unit": "TFLOP/s", "frac": round(dom_tflops / PEAK_BF16_TFLOPS, 4),
+                "measured_peak": peaks.get("mfma_bf16_random_operands_tflops"),
+                "frac_of_measured_peak": frac_measured(dom_tflops, peaks),
+                "traffic": traffic, "traffic_source": "profiles/hbm_traffic.json (rocprofv3 --pmc runs of this bench, committed)",
                 "avg_launch_ms": round(dom_ms / dom_n, 4), "launches": dom_n,
                 "flop_per_launch": flop_per_launch}
-    kernels = {k: {"total_ms": round(v[0], 3), "launches": v[1], "avg_ms": round(v[0] / v[1], 4)} for k, v in prof.items()}
-    for k in gemms:
-        kernels[k]["tflops"] = round(flop_per_launch / (gemms[k][0] / gemms[k][1] * 1e-3) / 1e12, 2)
+    kernels = kernel_table(prof, flop_per_launch, peaks)
     if "quantize" in prof:
         # W and (s, z) in; codes, clamp bit-plane and (s, zbar) pairs out
-        qb = sum(L["O"] * L["I"] for L in layers) / len(layers) * (2 + 8.0 / g + bits / 8 + 1.0 / 8 + 8.0 / g)
-        kernels["quantize"]["approx_gbs"] = round(qb / (prof["quantize"][0] / prof["quantize"][1] * 1e-3) / 1e9, 1)
+        qb = sum_io / len(layers) * (2 + 8.0 / g + bits / 8 + 1.0 / 8 + 8.0 / g)
+        gbs = qb / (prof["quantize"][0] / prof["quantize"][1] * 1e-3) / 1e9
+        kernels["quantize"].update({"approx_gbs": round(gbs, 1), "frac_of_hbm_peak": round(gbs / PEAK_HBM_GBS, 4),
+                                    "frac_of_measured_copy": round(gbs / peaks["copy_kernel_gbs"], 4) if peaks.get("copy_kernel_gbs") else None})
 
     result = {
         "metric": "quantized-linear fwd+bwd TFLOP/s (% bf16 MFMA peak) and tokens/s per layer",
@@ -120,13 +218,16 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": wl.name, "phase": "block_ap", "tokens": T, "bits": bits, "group": g,
                    "layers": [[L["name"], L["O"], L["I"]] for L in layers], "flop_per_step": flops_step},
+        "ms_per_step_median": round(t["median_ms"], 4), "ms_per_step_min": round(t["min_ms"], 4),
+        "value_at_median": round(flops_step / (t["median_ms"] * 1e-3) / 1e12, 2),
         "pct_of_bf16_mfma_peak": round(100.0 * tflops / PEAK_BF16_TFLOPS, 2),
-        "tokens_per_s_per_layer": round(T / (elapsed / args.steps), 1),
-        "roofline": roofline, "kernels": kernels,
+        "frac_of_measured_mfma_peak": frac_measured(tflops, peaks),
+        "tokens_per_s_per_layer": round(T / (ms_step * 1e-3), 1),
+        "roofline": roofline, "measured_peaks": peaks, "kernels": kernels,
     }
 
     if not args.no_rows:
-        result["rows"] = measure_other_rows(torch, eq, layers, bits, g, adt, dev, args)
+        result["rows"] = measure_other_rows(torch, eq, layers, bits, g, adt, dev, args, peaks)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(result))
@@ -179,10 +280,9 @@ def run_block_ap_step(eq, layers, bits, g):
         eq.eqat_fq_linear_bwd(L["X"], L["W"], L["s"], L["z"], L["dY"], bits, g, out=L["out"], ws=L["ws_b"], kept=True)
 
 
-def measure_other_rows(torch, eq, layers, bits, g, adt, dev, args):
-    """E2E-QP fwd+bwd at 4096 tokens, eqat_pack and eqat_init_minmax on the same seven weight matrices."""
-    T2 = 4096
-    rows = {}
+def pack_block(torch, eq, layers, bits, g, T2, dev):
+    """The block after Block-AP: packed codes and zero points of every linear, with views and workspaces for an E2E-QP
+    step on the first T2 tokens of the block's activations."""
     packed = []
     for L in layers:
         Wp, zp = eq.eqat_pack(L["W"], L["s"], L["z"], bits, g)
@@ -190,28 +290,71 @@ def measure_other_rows(torch, eq, layers, bits, g, adt, dev, args):
         packed.append({"Wp": Wp, "zp": zp, "X": L["X"][:T2], "dY": L["dY"][:T2], "Y": L["Y"][:T2],
                        "out": {"dX": L["out"]["dX"][:T2], "ds": L["out"]["ds"]},
                        "ws_f": eq.workspace(dsc, eq.OP_Q_FWD, dev), "ws_b": eq.workspace(dsc, eq.OP_Q_BWD, dev)})
+    return packed
 
-    def e2e_step():
-        for L, P in zip(layers, packed):
-            eq.eqat_qlinear_fwd(P["X"], P["Wp"], L["s"], P["zp"], bits, g, Y=P["Y"], ws=P["ws_b"], keep=True)
-            eq.eqat_qlinear_bwd(P["X"], P["Wp"], L["s"], P["zp"], P["dY"], L["I"], bits, g, out=P["out"], ws=P["ws_b"], kept=True)
 
-    def timed(fn, n):
-        for _ in range(2):
-            fn()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(n):
-            fn()
-        torch.cuda.synchronize()
-        return (time.perf_counter() - t0) / n
+def run_e2e_step(eq, layers, packed, bits, g):
+    for L, P in zip(layers, packed):
+        eq.eqat_qlinear_fwd(P["X"], P["Wp"], L["s"], P["zp"], bits, g, Y=P["Y"], ws=P["ws_b"], keep=True)
+        eq.eqat_qlinear_bwd(P["X"], P["Wp"], L["s"], P["zp"], P["dY"], L["I"], bits, g, out=P["out"], ws=P["ws_b"], kept=True)
 
+
+def hbm_row(torch, eq, fn, nbytes, args, peaks):
+    """A memory-bound pass: summed GPU time of the library's kernels inside fn (HIP events), bytes / time against the
+    published HBM peak and against the copy kernel's rate of this run."""
+    for _ in range(2):
+        fn()
+    torch.cuda.synchronize()
+    eq.eqat_profile_start()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        fn()
+    torch.cuda.synchronize()
+    wall = (time.perf_counter() - t0) / args.steps
+    prof = eq.eqat_profile_stop()
+    gpu = sum(v[0] for v in prof.values()) * 1e-3 / args.steps
+    gbs = nbytes / gpu / 1e9
+    return {"kernel_ms": round(gpu * 1e3, 4), "wall_ms": round(wall * 1e3, 4), "gbs": round(gbs, 1),
+            "frac_of_hbm_peak": round(gbs / PEAK_HBM_GBS, 4),
+            "frac_of_measured_copy": round(gbs / peaks["copy_kernel_gbs"], 4) if peaks.get("copy_kernel_gbs") else None,
+            "bytes": nbytes, "kernels_ms": {k: round(v[0] / args.steps, 4) for k, v in prof.items()}}
+
+
+def config_rows(torch, eq, synth, dev, args, peaks, name, phases=("block_ap", "eqat_pack", "e2e_qp")):
+    """Another BASELINE configuration (workload `name`), every phase it names: the Block-AP step, eqat_pack of the block
+    and the E2E-QP step, each timed like the headline and with its GEMM kernels per launch."""
+    wl = synth.WORKLOADS[name]
+    layers = build_layers(torch, eq, synth, wl, dev)
+    T, bits, g = wl.tokens, wl.bits, wl.group
     sum_io = sum(L["O"] * L["I"] for L in layers)
-    dt = timed(e2e_step, args.steps)
+    fpl = 2.0 * T * sum_io / len(layers)
+    out = {"tokens": T, "bits": bits, "group": g, "linears": len(layers)}
+    if "block_ap" in phases:
+        out["block_ap"] = step_row(torch, eq, lambda: run_block_ap_step(eq, layers, bits, g), 6.0 * T * sum_io, T, fpl, args, peaks)
+    packed = pack_block(torch, eq, layers, bits, g, T, dev)
+    if "eqat_pack" in phases:
+        def pack_all():
+            for L, P in zip(layers, packed):
+                eq.eqat_pack(L["W"], L["s"], L["z"], bits, g, Wpacked=P["Wp"], zpacked=P["zp"])
+        out["eqat_pack"] = hbm_row(torch, eq, pack_all, sum_io * (2 + 8.0 / g + bits / 8.0 + bits / (8.0 * g)), args, peaks)
+    if "e2e_qp" in phases:
+        out["e2e_qp"] = step_row(torch, eq, lambda: run_e2e_step(eq, layers, packed, bits, g), 6.0 * T * sum_io, T, fpl, args, peaks)
+    del layers, packed
+    torch.cuda.empty_cache()
+    return out
+
+
+def measure_other_rows(torch, eq, layers, bits, g, adt, dev, args, peaks):
+    """The other rows of the hot path on the headline block, and the other BASELINE configurations."""
+    from paper_2407_11062_amd import synth
+    T2 = 4096
+    rows = {}
+    packed = pack_block(torch, eq, layers, bits, g, T2, dev)
+    sum_io = sum(L["O"] * L["I"] for L in layers)
     fl = 6.0 * T2 * sum_io
-    rows["e2e_qp_fwd_bwd"] = {"tokens": T2, "ms_per_step": round(dt * 1e3, 4), "tflops": round(fl / dt / 1e12, 2),
-                              "pct_of_bf16_mfma_peak": round(100 * fl / dt / 1e12 / PEAK_BF16_TFLOPS, 2),
-                              "tokens_per_s_per_layer": round(T2 / dt, 1)}
+    fpl = 2.0 * T2 * sum_io / len(layers)
+    # BASELINE configuration 3: E2E-QP on the 7B block, 4096 tokens
+    rows["e2e_qp_fwd_bwd"] = step_row(torch, eq, lambda: run_e2e_step(eq, layers, packed, bits, g), fl, T2, fpl, args, peaks)
     # the same step with step sizes AND zero points trained (zero points kept in floating point, dz from the same epilogue)
     zf = [(L["z"].clamp(0, 2 ** bits - 1) + 0.25).contiguous() for L in layers]
     outz = [{"dX": P["out"]["dX"], "ds": P["out"]["ds"], "dz": torch.empty_like(L["s"])} for L, P in zip(layers, packed)]
@@ -221,36 +364,15 @@ def measure_other_rows(torch, eq, layers, bits, g, adt, dev, args):
             eq.eqat_qlinear_fwd_z(P["X"], P["Wp"], L["s"], z2, bits, g, Y=P["Y"], ws=P["ws_f"])
             eq.eqat_qlinear_bwd_z(P["X"], P["Wp"], L["s"], z2, P["dY"], L["I"], bits, g, out=o2, ws=P["ws_b"])
 
-    dt = timed(e2e_sz_step, args.steps)
-    rows["e2e_qp_fwd_bwd_trained_s_z"] = {"tokens": T2, "ms_per_step": round(dt * 1e3, 4), "tflops": round(fl / dt / 1e12, 2),
-                                          "pct_of_bf16_mfma_peak": round(100 * fl / dt / 1e12 / PEAK_BF16_TFLOPS, 2)}
+    rows["e2e_qp_fwd_bwd_trained_s_z"] = step_row(torch, eq, e2e_sz_step, fl, T2, fpl, args, peaks)
     wbytes = 2 if adt == torch.bfloat16 else 4
 
     def pack_all():
         for L, P in zip(layers, packed):
             eq.eqat_pack(L["W"], L["s"], L["z"], bits, g, Wpacked=P["Wp"], zpacked=P["zp"])
 
-    def timed_kernels(fn, n):
-        """Wall time per call of fn and the summed GPU time of the library's kernels inside it (HIP events)."""
-        for _ in range(2):
-            fn()
-        torch.cuda.synchronize()
-        eq.eqat_profile_start()
-        t0 = time.perf_counter()
-        for _ in range(n):
-            fn()
-        torch.cuda.synchronize()
-        wall = (time.perf_counter() - t0) / n
-        prof = eq.eqat_profile_stop()
-        return wall, sum(v[0] for v in prof.values()) * 1e-3 / n, {k: round(v[0] / n, 4) for k, v in prof.items()}
-
-    def hbm_row(fn, nbytes):
-        wall, gpu, per_kernel = timed_kernels(fn, args.steps)
-        return {"kernel_ms": round(gpu * 1e3, 4), "wall_ms": round(wall * 1e3, 4), "gbs": round(nbytes / gpu / 1e9, 1),
-                "frac_of_hbm_peak": round(nbytes / gpu / 1e9 / PEAK_HBM_GBS, 4), "bytes": nbytes, "kernels_ms": per_kernel}
-
     b = sum_io * (wbytes + 8.0 / g + bits / 8.0 + bits / (8.0 * g))
-    rows["eqat_pack"] = hbm_row(pack_all, b)
+    rows["eqat_pack"] = hbm_row(torch, eq, pack_all, b, args, peaks)
     sz = [(torch.empty_like(L["s"]), torch.empty_like(L["z"])) for L in layers]
 
     def init_all():
@@ -258,7 +380,7 @@ def measure_other_rows(torch, eq, layers, bits, g, adt, dev, args):
             eq.eqat_init_minmax(L["W"], bits, g, s=s, z=z)
 
     b = sum_io * (wbytes + 8.0 / g)
-    rows["eqat_init_minmax"] = hbm_row(init_all, b)
+    rows["eqat_init_minmax"] = hbm_row(torch, eq, init_all, b, args, peaks)
 
     # The 7B matrices are 34-90 MB: each launch lasts 10-25 us, a good part of it ramp-up and the timing events
     # themselves.  The same two passes on the largest matrix of the 70B block (gate/up, 28672 x 8192 = 470 MB, two
@@ -280,14 +402,10 @@ def measure_other_rows(torch, eq, layers, bits, g, adt, dev, args):
             eq.eqat_init_minmax(W, bits, g, s=s2, z=z2)
 
     n2 = 2.0 * O2 * I2
-    rows["eqat_pack_28672x8192"] = hbm_row(pack_big, n2 * (wbytes + 8.0 / g + bits / 8.0 + bits / (8.0 * g)))
-    rows["eqat_init_minmax_28672x8192"] = hbm_row(init_big, n2 * (wbytes + 8.0 / g))
+    rows["eqat_pack_28672x8192"] = hbm_row(torch, eq, pack_big, n2 * (wbytes + 8.0 / g + bits / 8.0 + bits / (8.0 * g)), args, peaks)
+    rows["eqat_init_minmax_28672x8192"] = hbm_row(torch, eq, init_big, n2 * (wbytes + 8.0 / g), args, peaks)
     del big
     rows["qlinear_fwd_1_token"] = decode_rows(torch, eq, bits, g, dev, args)
-    rows["block_ap_llama2_70b_w2g64"] = stacked_rows(torch, eq, dev, args, "llama2_70b_w2g64", "llama2_70b_w2g64_fused")
-    # the headline block again with q|k|v and gate|up stacked (context: BASELINE's configuration is the seven linears)
-    rows["block_ap_llama2_7b_w2g64_fp32_weights"] = master_weight_row(torch, eq, dev, args, "llama2_7b_block_ap_w2g64")
-    rows["block_ap_llama2_7b_w2g64_stacked"] = stacked_rows(torch, eq, dev, args, None, "llama2_7b_block_ap_w2g64_fused")
 
     # Block-AP step glue on the same block: reconstruction loss over the seven output tensors, then one AdamW launch
     # per linear over {W, s, z} fed by the gradients of the last backward (copies of the parameters, so that the rows
@@ -302,7 +420,7 @@ def measure_other_rows(torch, eq, layers, bits, g, adt, dev, args):
         for Y, R, dY in refs:
             eq.eqat_recon_loss(Y, R, loss=loss, dY=dY, ws=lws)
 
-    rows["eqat_recon_loss"] = hbm_row(loss_all, 3.0 * asz * sum(Y.numel() for Y, _, _ in refs))
+    rows["eqat_recon_loss"] = hbm_row(torch, eq, loss_all, 3.0 * asz * sum(Y.numel() for Y, _, _ in refs), args, peaks)
     del refs
     st = [{"W": L["W"].clone(), "s": L["s"].clone(), "z": L["z"].clone(),
            "mW": torch.zeros(L["W"].shape, dtype=torch.float32, device=dev),
@@ -318,58 +436,38 @@ def measure_other_rows(torch, eq, layers, bits, g, adt, dev, args):
                                     z=S["z"], dz=L["out"]["dz"], mz=S["mz"], vz=S["vz"])
 
     n_sz = sum(L["s"].numel() for L in layers)
-    rows["eqat_block_ap_update"] = hbm_row(update_all, sum_io * (3.0 * wbytes + 16.0) + 2 * n_sz * 28.0)
+    rows["eqat_block_ap_update"] = hbm_row(torch, eq, update_all, sum_io * (3.0 * wbytes + 16.0) + 2 * n_sz * 28.0, args, peaks)
     del st
     rows["vendor_gemm_reference"] = vendor_gemm_rows(torch, layers, layers[0]["X"].shape[0], args)
+    del packed, zf, outz, sz
+
+    # BASELINE configuration 4: the 13B-shaped block, 3 bit, group 128, 4096 tokens: Block-AP, pack, E2E-QP
+    rows["llama2_13b_w3g128"] = config_rows(torch, eq, synth, dev, args, peaks, "llama2_13b_w3g128")
+    # BASELINE configuration 5: the 70B-shaped block (grouped-query attention: k, v 1024 x 8192), 2 bit, group 64,
+    # 4096 tokens: both phases; and the Block-AP step with q|k|v and gate|up stacked along the output dimension
+    rows["llama2_70b_w2g64"] = config_rows(torch, eq, synth, dev, args, peaks, "llama2_70b_w2g64")
+    rows["llama2_70b_w2g64"]["block_ap_qkv_and_gate_up_stacked"] = config_rows(
+        torch, eq, synth, dev, args, peaks, "llama2_70b_w2g64_fused", phases=("block_ap",))["block_ap"]
+    # the headline block again with fp32 master weights, and with q|k|v and gate|up stacked (context: BASELINE's
+    # configuration is the seven linears in bf16)
+    rows["block_ap_llama2_7b_w2g64_fp32_weights"] = master_weight_row(torch, eq, dev, args, peaks, "llama2_7b_block_ap_w2g64")
+    rows["block_ap_llama2_7b_w2g64_stacked"] = config_rows(
+        torch, eq, synth, dev, args, peaks, "llama2_7b_block_ap_w2g64_fused", phases=("block_ap",))["block_ap"]
     return rows
 
 
-def master_weight_row(torch, eq, dev, args, name):
+def master_weight_row(torch, eq, dev, args, peaks, name):
     """The Block-AP step of workload `name` with W and dW in fp32 (master weights) and bf16 activations: the quantize pass
     reads twice the bytes and the dW epilogue reads and writes 4-byte weights; fwd and dX are unchanged."""
     from paper_2407_11062_amd import synth
     wl = synth.WORKLOADS[name]
     layers = build_layers(torch, eq, synth, wl, dev, w_dtype=torch.float32)
-    for _ in range(2):
-        run_block_ap_step(eq, layers, wl.bits, wl.group)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        run_block_ap_step(eq, layers, wl.bits, wl.group)
-    torch.cuda.synchronize()
-    dt = (time.perf_counter() - t0) / args.steps
-    fl = 6.0 * wl.tokens * sum(L["O"] * L["I"] for L in layers)
-    return {"tokens": wl.tokens, "ms_per_step": round(dt * 1e3, 4), "tflops": round(fl / dt / 1e12, 2),
-            "pct_of_bf16_mfma_peak": round(100 * fl / dt / 1e12 / PEAK_BF16_TFLOPS, 2)}
-
-
-def stacked_rows(torch, eq, dev, args, separate, stacked):
-    """Block-AP step of a block (e.g. the 70B-shaped one: 4096 tokens, grouped-query attention, k and v 1024 x 8192), as
-    seven launches (workload `separate`, skipped if None) and with q|k|v and gate|up stacked along the output dimension
-    (workload `stacked`: four launches).  Groups run along the input dimension, so the stack is quantized row by row
-    exactly like its parts."""
-    from paper_2407_11062_amd import synth
-    out = {}
-    for key, name in (("seven_linears", separate), ("qkv_and_gate_up_stacked", stacked)):
-        if name is None:
-            continue
-        wl = synth.WORKLOADS[name]
-        layers = build_layers(torch, eq, synth, wl, dev)
-        for _ in range(2):
-            run_block_ap_step(eq, layers, wl.bits, wl.group)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(args.steps):
-            run_block_ap_step(eq, layers, wl.bits, wl.group)
-        torch.cuda.synchronize()
-        dt = (time.perf_counter() - t0) / args.steps
-        fl = 6.0 * wl.tokens * sum(L["O"] * L["I"] for L in layers)
-        out[key] = {"tokens": wl.tokens, "launch_groups": len(layers), "ms_per_step": round(dt * 1e3, 4),
-                    "tflops": round(fl / dt / 1e12, 2),
-                    "pct_of_bf16_mfma_peak": round(100 * fl / dt / 1e12 / PEAK_BF16_TFLOPS, 2)}
-        del layers
-        torch.cuda.empty_cache()
-    return out
+    sum_io = sum(L["O"] * L["I"] for L in layers)
+    row = step_row(torch, eq, lambda: run_block_ap_step(eq, layers, wl.bits, wl.group), 6.0 * wl.tokens * sum_io, wl.tokens,
+                   2.0 * wl.tokens * sum_io / len(layers), args, peaks)
+    del layers
+    torch.cuda.empty_cache()
+    return row
 
 
 def vendor_gemm_rows(torch, layers, T, args):

@@ -71,7 +71,7 @@ eqat_status check_desc(const eqat_desc *d, bool with_tokens, Problem *p)
     return EQAT_OK;
 }
 
-struct WsLayout { size_t codes, clamp, sz, part, dwhat, total; };
+struct WsLayout { size_t codes, clamp, sz, part, dwhat, sk_ctr, sk_ctr_bytes, sk_part, sk_part_bytes, total; };
 
 WsLayout ws_layout(const Problem &p, int op)
 {
@@ -86,6 +86,12 @@ WsLayout ws_layout(const Problem &p, int op)
         if (fq && bwd) l.clamp = take(clamp_b);
         l.sz = take(sz_b);
         if (bwd && eqat::dw_needs_partials(p)) l.part = take(2 * part_b);
+        // GEMM launches that cut tiles along K: arrival counters (cleared by the first kernel of every call; their
+        // size and place do not depend on the token count) and, last, the accumulator parts (large, sparsely touched,
+        // never initialised; present only for shapes whose tiles are cut).
+        eqat::sk_scratch_bytes(p, bwd, &l.sk_part_bytes, &l.sk_ctr_bytes);
+        l.sk_ctr = take(l.sk_ctr_bytes);
+        l.sk_part = take(l.sk_part_bytes);
     } else {
         if (!fq) l.sz = take(sz_b);
         if (bwd) l.dwhat = take(dwhat_b);
@@ -100,6 +106,13 @@ eqat_status check_ws(const WsLayout &l, const void *ws, size_t ws_bytes)
     if (ws == nullptr || ws_bytes < l.total) return EQAT_ERR_WORKSPACE;
     if (!aligned(ws, 256)) return EQAT_ERR_ALIGN;
     return EQAT_OK;
+}
+
+inline eqat::SkScratch sk_of(const WsLayout &l, char *w8)
+{
+    if (l.sk_ctr_bytes == 0) return eqat::SkScratch{nullptr, nullptr};
+    return eqat::SkScratch{l.sk_part_bytes != 0 ? reinterpret_cast<float *>(w8 + l.sk_part) : nullptr,
+                           reinterpret_cast<uint32_t *>(w8 + l.sk_ctr)};
 }
 
 inline eqat_status launch_status() { return hipGetLastError() == hipSuccess ? EQAT_OK : EQAT_ERR_DEVICE; }
@@ -202,7 +215,7 @@ eqat_status eqat_pack(const eqat_desc *d, const void *W, const float *s, const f
     EQAT_REQUIRE(W); EQAT_REQUIRE(s); EQAT_REQUIRE(z); EQAT_REQUIRE(Wpacked); EQAT_REQUIRE(zpacked);
     EQAT_ALIGNED(W); EQAT_ALIGNED(s); EQAT_ALIGNED(z); EQAT_ALIGNED(Wpacked); EQAT_ALIGNED(zpacked);
     hipStream_t st = (hipStream_t)stream;
-    { ProfScope ps(eqat::PK_QUANTIZE, st); eqat::launch_quantize(p, W, s, z, Wpacked, nullptr, nullptr, zpacked, true, st); }
+    { ProfScope ps(eqat::PK_QUANTIZE, st); eqat::launch_quantize(p, W, s, z, Wpacked, nullptr, nullptr, zpacked, true, nullptr, 0, st); }
     return launch_status();
 }
 
@@ -235,8 +248,9 @@ static eqat_status fq_fwd_any(const eqat_desc *d, const void *X, const void *W, 
     hipStream_t st = (hipStream_t)stream;
     char *w8 = (char *)ws;
     if (p.act_bf16) {
-        { ProfScope ps(eqat::PK_QUANTIZE, st); eqat::launch_quantize(p, W, s, z, w8 + l.codes, keep ? w8 + l.clamp : nullptr, w8 + l.sz, nullptr, false, st); }
-        if (p.T > 0) { ProfScope ps(eqat::PK_GEMM_FWD, st); eqat::launch_mfma_fwd(p, X, w8 + l.codes, w8 + l.sz, Y, st); }
+        const eqat::SkScratch sk = sk_of(l, w8);
+        { ProfScope ps(eqat::PK_QUANTIZE, st); eqat::launch_quantize(p, W, s, z, w8 + l.codes, keep ? w8 + l.clamp : nullptr, w8 + l.sz, nullptr, false, sk.counters, (uint32_t)(l.sk_ctr_bytes / 4), st); }
+        if (p.T > 0) { ProfScope ps(eqat::PK_GEMM_FWD, st); eqat::launch_mfma_fwd(p, X, w8 + l.codes, w8 + l.sz, Y, sk, st); }
     } else {
         { ProfScope ps(eqat::PK_F32, st); eqat::launch_f32_fwd(p, false, X, W, s, z, Y, st); }
     }
@@ -295,8 +309,9 @@ static eqat_status fq_bwd_any(const eqat_desc *d, const void *X, const void *W, 
     hipStream_t st = (hipStream_t)stream;
     char *w8 = (char *)ws;
     if (p.act_bf16) {
-        if (!kept) { ProfScope ps(eqat::PK_QUANTIZE, st); eqat::launch_quantize(p, W, s, z, w8 + l.codes, w8 + l.clamp, w8 + l.sz, nullptr, false, st); }
-        if (dX != nullptr) { ProfScope ps(eqat::PK_GEMM_DX, st); eqat::launch_mfma_dx(p, dY, w8 + l.codes, w8 + l.sz, dX, st); }
+        const eqat::SkScratch sk = sk_of(l, w8);
+        if (!kept) { ProfScope ps(eqat::PK_QUANTIZE, st); eqat::launch_quantize(p, W, s, z, w8 + l.codes, w8 + l.clamp, w8 + l.sz, nullptr, false, sk.counters, (uint32_t)(l.sk_ctr_bytes / 4), st); }
+        if (dX != nullptr) { ProfScope ps(eqat::PK_GEMM_DX, st); eqat::launch_mfma_dx(p, dY, w8 + l.codes, w8 + l.sz, dX, sk, st); }
         if (want_w)
             eqat::launch_mfma_dw(p, true, X, dY, W, w8 + l.codes, w8 + l.clamp, w8 + l.sz, s, dW, ds, dz,
                                  (float *)(w8 + l.part), st);
@@ -332,12 +347,14 @@ static eqat_status qlinear_fwd_any(const eqat_desc *d, const void *X, const uint
         eqat::launch_gemv(p, X, Wpacked, s, zpacked, zfloat, Y, st);
         return launch_status();
     }
+    const eqat::SkScratch sk = sk_of(l, w8);
     {
         ProfScope ps(eqat::PK_PREPARE, st);
-        eqat::launch_e2e_prepare(p, p.act_bf16 ? Wpacked : nullptr, w8 + l.codes, s, zpacked, zfloat, w8 + l.sz, st);
+        eqat::launch_e2e_prepare(p, p.act_bf16 ? Wpacked : nullptr, w8 + l.codes, s, zpacked, zfloat, w8 + l.sz,
+                                 sk.counters, (uint32_t)(l.sk_ctr_bytes / 4), st);
     }
     if (p.T == 0) return launch_status();
-    if (p.act_bf16) { ProfScope ps(eqat::PK_GEMM_FWD, st); eqat::launch_mfma_fwd(p, X, w8 + l.codes, w8 + l.sz, Y, st); }
+    if (p.act_bf16) { ProfScope ps(eqat::PK_GEMM_FWD, st); eqat::launch_mfma_fwd(p, X, w8 + l.codes, w8 + l.sz, Y, sk, st); }
     else { ProfScope ps(eqat::PK_F32, st); eqat::launch_f32_fwd(p, true, X, Wpacked, s, w8 + l.sz, Y, st); }
     return launch_status();
 }
@@ -359,12 +376,14 @@ static eqat_status qlinear_bwd_any(const eqat_desc *d, const void *X, const uint
     if (dX == nullptr && !want_g) return EQAT_OK;
     hipStream_t st = (hipStream_t)stream;
     char *w8 = (char *)ws;
+    const eqat::SkScratch sk = sk_of(l, w8);
     if (!kept) {
         ProfScope ps(eqat::PK_PREPARE, st);
-        eqat::launch_e2e_prepare(p, p.act_bf16 ? Wpacked : nullptr, w8 + l.codes, s, zpacked, zfloat, w8 + l.sz, st);
+        eqat::launch_e2e_prepare(p, p.act_bf16 ? Wpacked : nullptr, w8 + l.codes, s, zpacked, zfloat, w8 + l.sz,
+                                 sk.counters, (uint32_t)(l.sk_ctr_bytes / 4), st);
     }
     if (p.act_bf16) {
-        if (dX != nullptr) { ProfScope ps(eqat::PK_GEMM_DX, st); eqat::launch_mfma_dx(p, dY, w8 + l.codes, w8 + l.sz, dX, st); }
+        if (dX != nullptr) { ProfScope ps(eqat::PK_GEMM_DX, st); eqat::launch_mfma_dx(p, dY, w8 + l.codes, w8 + l.sz, dX, sk, st); }
         if (want_g)
             eqat::launch_mfma_dw(p, false, X, dY, nullptr, w8 + l.codes, nullptr, w8 + l.sz, s, nullptr, ds, dz,
                                  (float *)(w8 + l.part), st);

@@ -47,11 +47,6 @@ __device__ __forceinline__ int buf_load4(__amdgpu_buffer_rsrc_t r, uint32_t off)
     return __builtin_amdgcn_raw_buffer_load_b32(r, (int)off, 0, 0);
 }
 
-__device__ __forceinline__ float bf16_bits_to_float(uint32_t hi16_in_low)
-{
-    return __uint_as_float(hi16_in_low << 16);
-}
-
 // N words (N = BITS) hold 32 codes of BITS bits, little-endian bit stream.
 template <int BITS> struct CodeWords { uint32_t w[BITS]; };
 

@@ -15,7 +15,7 @@
 #include "kernels.h"
 #include "prof.h"
 
-#include <stdlib.h>
+#include <algorithm>
 
 namespace eqat {
 
@@ -126,6 +126,137 @@ __device__ __forceinline__ void tile_of_block(int tiles_m, int tiles_n, int &tm,
     (void)tile_of_xcd_slot((int)gridDim.x, (int)(blockIdx.x & 7), (int)(blockIdx.x >> 3), tiles_m, tiles_n, tm, tn, kBand);
 }
 
+// ---- work of one workgroup: whole tiles, then a share of the tiles that do not fill a round ---------------
+// A grid of G workgroups (all resident at once, G / 8 per XCD) covers nb tiles.  When nb is between one and two rounds
+// of G (the 13B-shaped linears at 4096 tokens give 1.25 rounds of 256 x 256 tiles) the second round would run on a
+// fraction of the chip.  Instead the tiles beyond the last whole round but one are cut along K: their K-tile pairs,
+// laid end to end per XCD, are dealt out in equal contiguous runs, so a workgroup's run may begin and end in the middle
+// of a tile.  A run is at least one tile long, so a tile has at most two contributors.  The contributor that arrives
+// first writes its fp32 accumulators to memory and raises the tile's flag; the one that arrives second waits for the
+// flag (a wait for a workgroup that is already running and itself waits for nobody), adds that part to its own
+// accumulators (a + b = b + a: the result does not depend on who came first) and runs the tile's epilogue.  Counter
+// and flag of a tile are back at zero when its second contributor is done, so a launch leaves them as it found them.
+// Whether cutting pays is a measured matter (host side, plan_tiles): a partly filled round costs less than its share
+// of a full one on this power-limited chip, and every part costs a trip of 256 KB through memory.
+struct SkPlan {
+    int walk;              // 0: the grid has one workgroup per tile and none of the below applies
+    int dp_rounds;         // whole tiles per workgroup: tiles loc0 + r * (G / 8) of its XCD, r < dp_rounds
+    int pairs;             // K-tile pairs per output tile
+    float *partials;       // [G][2] accumulator tiles (a run has at most a head and a tail piece)
+    uint32_t *counters;    // [2][2 G], zero: arrivals, then flags, one each per tile that may be cut (at most 2 G / 8 per XCD)
+};
+struct SkItem {
+    int tm, tn, ctr;       // tile, and the index of its counter when it is cut
+    int kb, ke;            // K-tile pairs [kb, ke) of the tile
+    int parts, first;      // number of contributors (1: the whole tile is mine) and the first one's index in the XCD
+    int first_slot;        // which of its two buffers the first contributor used (all others use buffer 0)
+};
+__device__ __forceinline__ int sk_owner_of_pair(int p, int base, int extra)
+{
+    const int cut = extra * (base + 1);
+    return p < cut ? p / (base + 1) : extra + (p - cut) / (base > 0 ? base : 1);
+}
+// item number j of this workgroup; false past its last one
+__device__ __forceinline__ bool sk_item(const SkPlan &sk, int nb, int tiles_m, int tiles_n, int band, int j, SkItem &it)
+{
+    const int xcd = (int)(blockIdx.x & 7), loc0 = (int)(blockIdx.x >> 3);
+    it.kb = 0; it.ke = sk.pairs; it.parts = 1; it.first = 0; it.first_slot = 0; it.ctr = 0;
+    if (!sk.walk) return j == 0 && tile_of_xcd_slot((int)gridDim.x, xcd, loc0, tiles_m, tiles_n, it.tm, it.tn, band);
+    const int W = (int)(gridDim.x >> 3);
+    if (j < sk.dp_rounds) return tile_of_xcd_slot(nb, xcd, loc0 + j * W, tiles_m, tiles_n, it.tm, it.tn, band);
+    const int n_sk = (nb >> 3) + (xcd < (nb & 7) ? 1 : 0) - sk.dp_rounds * W;
+    if (n_sk <= 0) return false;
+    const int P = sk.pairs, total = n_sk * P, base = total / W, extra = total % W;
+    const int start = loc0 * base + min(loc0, extra), end = start + base + (loc0 < extra ? 1 : 0);
+    const int t = start / P + (j - sk.dp_rounds);
+    if (start >= end || t * P >= end) return false;
+    it.kb = max(start, t * P) - t * P;
+    it.ke = min(end, (t + 1) * P) - t * P;
+    if (it.kb > 0 || it.ke < P) {
+        it.first = sk_owner_of_pair(t * P, base, extra);
+        it.parts = sk_owner_of_pair((t + 1) * P - 1, base, extra) - it.first + 1;
+        const int fstart = it.first * base + min(it.first, extra);
+        it.first_slot = fstart / P == t ? 0 : 1;
+        it.ctr = xcd * 2 * W + t;          // t < n_sk <= 2 W: the plan never cuts more than two rounds
+    }
+    return tile_of_xcd_slot(nb, xcd, sk.dp_rounds * W + t, tiles_m, tiles_n, it.tm, it.tn, band);
+}
+
+// One of the two contributors of a tile cut along K is done with its K range.  Returns false in the one that arrived
+// first (its part is in memory, its work on the tile done) and true in the second, with the first one's part added to `acc`.
+// Layout of a part: the float4 number q of accumulator block (i, j) of thread t at ((i * NI + j) * 4 + q) * NT + t.
+// The two may sit on different XCDs, each with its own L2, so part and flag are written and read with device-scope
+// accesses (cache policy sc1: written through to memory, read from memory); no cache is flushed or invalidated as a
+// whole (a device-scope fence writes back and invalidates the entire L2 of the XCD, operand panels included: measured,
+// that alone cost more than cutting the tiles gained).  Order on the writing side: every wave waits for its stores to
+// complete, the workgroup meets, then one thread raises the flag.
+constexpr int kAuxDeviceScope = 16;      // "sc1" of the raw buffer intrinsics on gfx940 and later
+constexpr int kSkSpinLimit = 1 << 22;    // polls of ~1 us: a bound that is never reached, so that no wave can spin for ever
+__device__ __forceinline__ void wait_all_and_barrier();
+template <int MI, int NI, int NT>
+__device__ __forceinline__ bool sk_hand_in(const SkPlan &sk, const SkItem &it, floatx16 (&acc)[MI][NI], int tid)
+{
+    __shared__ uint32_t s_second;
+    constexpr size_t kTile = (size_t)MI * NI * 16 * NT;          // floats per part
+    constexpr uint32_t kTileBytes = (uint32_t)(kTile * sizeof(float));
+    const int xcd = (int)(blockIdx.x & 7), me = (int)(blockIdx.x >> 3) - it.first;       // me: 0 or 1
+    uint32_t *arrivals = sk.counters + it.ctr, *flag = sk.counters + 2 * (int)gridDim.x + it.ctr;
+    if (tid == 0) s_second = atomicInc(arrivals, 1u);            // 0 -> 1 -> 0
+    __syncthreads();
+    const bool second = s_second != 0u;
+    // Straight-line code for both roles (branches around the accumulators make the register allocator spill them):
+    // the second contributor's stores and the first one's loads go to an out-of-range offset, where a buffer store is
+    // dropped and a buffer load returns zeros.
+    const uint32_t st_base = second ? kOobOffset : (uint32_t)tid * 16u, ld_base = second ? (uint32_t)tid * 16u : kOobOffset;
+    const size_t other = (size_t)(it.first + (1 - me)) * 8 + xcd;
+    const __amdgpu_buffer_rsrc_t mine =
+        make_rsrc(sk.partials + ((size_t)blockIdx.x * 2 + (me == 0 ? it.first_slot : 0)) * kTile, kTileBytes);
+    const __amdgpu_buffer_rsrc_t theirs = make_rsrc(sk.partials + (other * 2 + (me == 1 ? it.first_slot : 0)) * kTile, kTileBytes);
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NI; ++j) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                intx4 v;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) v[e] = __float_as_int(acc[i][j][4 * q + e]);
+                __builtin_amdgcn_raw_buffer_store_b128(v, mine, st_base + (uint32_t)(((i * NI + j) * 4 + q) * NT * 16), 0, kAuxDeviceScope);
+            }
+            __builtin_amdgcn_sched_barrier(0);      // one 32 x 32 block at a time: few register copies
+        }
+    wait_all_and_barrier();                // every store of the workgroup has completed
+    if (tid == 0) {
+        if (!second) {
+            __hip_atomic_store(flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        } else {
+            int polls = 0;
+            while (__hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u && ++polls < kSkSpinLimit)
+                __builtin_amdgcn_s_sleep(32);
+            __hip_atomic_store(flag, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+    __syncthreads();
+    // two 32 x 32 blocks (32 registers) in flight at a time: all of them at once would not fit beside the accumulators
+#pragma unroll
+    for (int b0 = 0; b0 < MI * NI; b0 += 2) {
+        intx4 v[2][4];
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                v[b][q] = __builtin_amdgcn_raw_buffer_load_b128(theirs, ld_base + (uint32_t)(((b0 + b) * 4 + q) * NT * 16), 0, kAuxDeviceScope);
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) acc[(b0 + b) / NI][(b0 + b) % NI][4 * q + e] += __int_as_float(v[b][q][e]);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    return second;
+}
+
 // ======================================================================================================
 // fwd / dX:  C[M,N] = A[M,K] * B,  A plain bf16 (K contiguous), B = What rebuilt from codes.
 //   BT = false (fwd): B element (k, n) = What[n][k]   -> weight tile is KC  [BN][BK]
@@ -137,8 +268,8 @@ struct GemmQArgs {
     int I, G, g;           // weight matrix geometry: row length, groups per row, group size
     uint32_t a_bytes, codes_bytes, sz_bytes;
     int tiles_m, tiles_n;
-    int band;              // tile rows walked together by one XCD (see tile_of_block)
-    int walk;              // 1: the grid is smaller than the tile count and every workgroup walks several tiles
+    int band;              // tile rows walked together by one XCD (see tile_of_xcd_slot)
+    SkPlan sk;             // which tiles, or parts of tiles, a workgroup computes
 };
 
 template <int V> struct IC { static constexpr int value = V; };
@@ -176,15 +307,8 @@ __device__ __forceinline__ RawRsrc make_raw_rsrc(const void *p, uint32_t bytes)
     r.w[0] = (int)(uint32_t)a; r.w[1] = (int)(uint32_t)((a >> 32) & 0xFFFFu); r.w[2] = (int)bytes; r.w[3] = 0x00020000;
     return r;
 }
-__device__ __forceinline__ void load_to_lds16(const RawRsrc &r, bf16_t *lds_wave_base, uint32_t voffset)
-{
-    const uint32_t lds_addr = (uint32_t)(uintptr_t)lds_wave_base;      // LDS pointers are 32-bit offsets; wave-uniform
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
-                 :: "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(voffset), "s"(r.w) : "memory", "m0");
-}
-
-// The same with the LDS destination given as a 32-bit LDS address that the caller has built from wave-uniform scalars
-// (so that M0 costs one scalar instruction instead of a 64-bit pointer computation and a v_readfirstlane per load).
+// The LDS destination is a 32-bit LDS address that the caller has built from wave-uniform scalars (so that M0 costs
+// one scalar instruction instead of a 64-bit pointer computation and a v_readfirstlane per load).
 __device__ __forceinline__ uint32_t lds_addr_of(const void *p)
 {
     return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void *)p;
@@ -216,7 +340,8 @@ __device__ __forceinline__ void wait_all_and_barrier()
 //     wave; fragments of slice kk+1 are read while slice kk multiplies.
 // K tiles past the end of K multiply zeros: the weights there are exactly zero (see load_a below).
 // A workgroup may own several output tiles; the pipeline then runs on through the tile boundaries.
-template <int BITS, bool BT, int BM, int BN, int BK, int WGM, int WGN>
+// CUT: the launch cuts tiles along K (SkPlan::dp_rounds == 0 with walk); the other instantiation carries none of that code.
+template <int BITS, bool BT, bool CUT, int BM, int BN, int BK, int WGM, int WGN>
 __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_q(const GemmQArgs a)
 {
     constexpr int NT = 64 * WGM * WGN, NW = WGM * WGN, WTM = BM / WGM, WTN = BN / WGN, MI = WTM / 32, NI = WTN / 32;
@@ -235,21 +360,30 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_q(const GemmQArgs a)
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WGN, wn = wave % WGN;
 
-    // Tiles of this workgroup.  One tile each when the grid covers all tiles; otherwise (a.walk) workgroup b walks the
-    // tiles that a one-tile-per-workgroup grid would have handed to the workgroups b, b + G, b + 2 G, ... of its XCD
-    // slot, and the K loop runs THROUGH the tile boundaries: the loaders below each keep their own position in that
-    // sequence, two (activations) and three (codes) K tiles ahead of the MFMAs, so that the first K tiles of the next
-    // output tile are in LDS and in registers when the last MFMA of the current one issues.
-    const int ntiles = a.tiles_m * a.tiles_n, xcd = (int)(blockIdx.x & 7), loc0 = (int)(blockIdx.x >> 3);
-    const int loc_step = a.walk ? (int)(gridDim.x >> 3) : ntiles;          // no second tile without a.walk
-    auto tile_origin = [&](int j, int &m0, int &n0) -> bool {              // j-th tile of this workgroup
-        int tm, tn;
-        const bool ok = tile_of_xcd_slot(a.walk ? ntiles : (int)gridDim.x, xcd, loc0 + j * loc_step, a.tiles_m, a.tiles_n, tm, tn, a.band);
-        m0 = ok ? tm * BM : a.tiles_m * BM;                                // past the end: rows / columns out of range
-        n0 = ok ? tn * BN : a.tiles_n * BN;
+    // Items of this workgroup (see SkPlan): whole tiles, then possibly pieces of tiles cut along K.  The K loop runs
+    // THROUGH the item boundaries: the loaders below each keep their own position in that sequence, two (activations)
+    // and three (codes) K tiles ahead of the MFMAs, so that the first K tiles of the next item are in LDS and in
+    // registers when the last MFMA of the current one issues.
+    const int ntiles = a.tiles_m * a.tiles_n;
+    const int nk = (a.K + BK - 1) / BK, nk2 = (nk + 1) & ~1;              // K tiles per output tile, two per trip
+    // item j: origin of its tile, first K tile and number of K tiles (even); past the last item: rows and columns out
+    // of range (the loaders then fetch zeros)
+    const int grid = (int)gridDim.x, xcd = (int)(blockIdx.x & 7), loc0 = (int)(blockIdx.x >> 3);
+    const int loc_step = a.sk.walk ? grid >> 3 : ntiles;          // no second tile without a.sk.walk
+    auto item_of = [&](int j, SkItem &it, int &m0, int &n0) -> bool {
+        bool ok;
+        if constexpr (CUT) {
+            ok = sk_item(a.sk, ntiles, a.tiles_m, a.tiles_n, a.band, j, it);
+            if (!ok) { it.kb = 0; it.ke = nk2 / 2; it.parts = 1; }
+        } else {
+            // whole tiles only: tile loc0 + j * (G / 8) of this XCD's range (walk), or the one tile of this workgroup
+            ok = tile_of_xcd_slot(a.sk.walk ? ntiles : grid, xcd, loc0 + j * loc_step, a.tiles_m, a.tiles_n, it.tm, it.tn, a.band);
+            it.kb = 0; it.ke = nk2 / 2; it.parts = 1;
+        }
+        m0 = ok ? it.tm * BM : a.tiles_m * BM;
+        n0 = ok ? it.tn * BN : a.tiles_n * BN;
         return ok;
     };
-    const int nk = (a.K + BK - 1) / BK, nk2 = (nk + 1) & ~1;              // K tiles per output tile, two per trip
 
     const RawRsrc rA = make_raw_rsrc(a.A, a.a_bytes);
     const __amdgpu_buffer_rsrc_t rC = make_rsrc(a.codes, a.codes_bytes);
@@ -270,14 +404,15 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_q(const GemmQArgs a)
     int a_tile = 0, a_left = 0;                     // loader position: tile ordinal, K tiles left in it
     auto a_enter_tile = [&]() {
         int m0, n0;
-        (void)tile_origin(a_tile, m0, n0);
+        SkItem si;
+        (void)item_of(a_tile, si, m0, n0);
 #pragma unroll
         for (int it = 0; it < A_LOADS; ++it) {
             const int row = (wave * A_LOADS + it) * 8 + (lane >> 3);
-            const uint64_t o = ((uint64_t)(m0 + row) * (uint64_t)a.K + (uint64_t)(kc_swz(row, lane & 7) * 8)) * 2u;
+            const uint64_t o = ((uint64_t)(m0 + row) * (uint64_t)a.K + (uint64_t)((CUT ? si.kb * 2 * BK : 0) + kc_swz(row, lane & 7) * 8)) * 2u;
             offA[it] = o < kOobOffset ? (uint32_t)o : kOobOffset;   // rows past the matrix stay out of range for good
         }
-        a_left = nk2;
+        a_left = CUT ? 2 * (si.ke - si.kb) : nk2;
         ++a_tile;
     };
     auto load_a = [&](int buf) {
@@ -294,16 +429,17 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_q(const GemmQArgs a)
     int c_tile = 0, c_left = 0, c_n0 = 0, c_k0 = 0;
     auto c_enter_tile = [&]() {
         int m0;
-        (void)tile_origin(c_tile, m0, c_n0);
+        SkItem si;
+        (void)item_of(c_tile, si, m0, c_n0);
+        c_k0 = CUT ? si.kb * 2 * BK : 0;
 #pragma unroll
         for (int it = 0; it < B_SEGS; ++it) {
             const int sidx = it * NT + tid;
-            const int wcol = BT ? c_n0 + (sidx % (BN / 32)) * 32 : (sidx % (BK / 32)) * 32;
+            const int wcol = BT ? c_n0 + (sidx % (BN / 32)) * 32 : c_k0 + (sidx % (BK / 32)) * 32;
             grp[it] = wcol / (int)a.g;
             rem[it] = wcol % (int)a.g;
         }
-        c_k0 = 0;
-        c_left = nk2;
+        c_left = CUT ? 2 * (si.ke - si.kb) : nk2;
         ++c_tile;
     };
     auto load_codes = [&](auto set) {
@@ -451,16 +587,29 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_q(const GemmQArgs a)
 
     for (int jt = 0;; ++jt) {
         int m0, n0;
-        if (!tile_origin(jt, m0, n0)) break;
+        SkItem si;
+        if (!item_of(jt, si, m0, n0)) break;
         // Two K tiles per trip, unconditionally (the register staging sets alternate at compile time, and a branch
         // between the two halves makes the accumulators flow through a merge that costs hundreds of copies).  With an
         // odd K-tile count the extra tile lies past K and multiplies zeros.  The last trips of this loop already fetch
-        // (and rebuild) the first K tiles of the next output tile.
-        for (int kt = 0; kt < nk2; kt += 2) {
+        // (and rebuild) the first K tiles of the next item.
+        for (int kt = CUT ? 2 * si.kb : 0; kt < (CUT ? 2 * si.ke : nk2); kt += 2) {
             loaders_advance();
             step(IC<0>{});
             loaders_advance();
             step(IC<1>{});
+        }
+        // a tile cut along K: only the contributor that arrives last stores it, from the sum of all parts
+        bool mine_to_store = true;
+        if constexpr (CUT) mine_to_store = si.parts == 1 || sk_hand_in<MI, NI, NT>(a.sk, si, acc, tid);
+        if (!mine_to_store) {
+#pragma unroll
+            for (int i = 0; i < MI; ++i)
+#pragma unroll
+                for (int j = 0; j < NI; ++j)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+            continue;
         }
 
         // C[m][n]: lane holds column n = l % 32 and rows 8*(r/4) + 4*(l/32) + r%4 of each 32x32 block
@@ -865,17 +1014,9 @@ typedef DwTile<128, 128, 64, 2, 2, 2> DwTileSmall;
 typedef DwTile<256, 256, 64, 2, 2, 4> DwTileBig;
 static_assert(DwTileSmall::BM == TileSmall::BM && DwTileBig::BM == TileBig::BM, "group-fits-in-tile tests use Tile*::BM");
 
-// EQAT_TILE=0/1 forces the small / big tile (tuning aid)
-int tile_override()
-{
-    static int c = -2;
-    if (c == -2) { const char *e = getenv("EQAT_TILE"); c = e ? atoi(e) : -1; }
-    return c;
-}
 // the big tile unless it would leave a large part of the 256 CUs without a workgroup
 bool use_small_tile(int64_t m, int64_t n)
 {
-    if (tile_override() >= 0) return tile_override() == 0;
     return ((m + 255) / 256) * ((n + 255) / 256) < 160;
 }
 
@@ -892,6 +1033,8 @@ template <typename K> void allow_dynamic_lds(K kern, size_t smem, uint64_t &done
 
 // Workgroups of `smem` bytes of LDS that the device runs at the same time (LDS is what limits these kernels), rounded
 // down to a multiple of 8.
+constexpr int kMaxCus = 256;            // compute units of an MI355X; the workspace is sized for this many
+constexpr int kSkCounterWords = 2 * 2 * 2 * kMaxCus;  // 2 G arrival counters and 2 G flags, G <= 2 workgroups per compute unit
 int resident_workgroups(size_t smem)
 {
     static int cus_of[64] = {0};
@@ -899,11 +1042,28 @@ int resident_workgroups(size_t smem)
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev > 63) dev = 0;
     if (cus_of[dev] == 0) {
         int n = 0;
-        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 8) n = 256;
-        cus_of[dev] = n;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 8) n = kMaxCus;
+        cus_of[dev] = n < kMaxCus ? n : kMaxCus;
     }
     const int per_cu = smem * 2 <= 160 * 1024 ? 2 : 1;
     return (cus_of[dev] * per_cu) & ~7;
+}
+
+// How `resident` workgroups share `ntiles` tiles of `pairs` K-tile pairs each (see SkPlan).  One workgroup per tile
+// when they all fit; otherwise whole tiles, except that between one and two rounds of tiles, with K long enough, every
+// tile is cut along K.  With more rounds cutting the last 1.x of them measured slower than leaving the last round
+// partly filled (7B gate, 5.4 rounds: -3 %; 13B gate, 3.4 rounds: -4 %; 13B q and down, 1.25 rounds: +3 to +11 %).
+SkPlan plan_tiles(int ntiles, int pairs, int resident, float *partials, uint32_t *counters)
+{
+    SkPlan sk{};
+    sk.pairs = pairs; sk.partials = partials; sk.counters = counters;
+    if (ntiles <= resident) return sk;                       // walk = 0
+    sk.walk = 1;
+    const int W = resident / 8, per = ntiles / 8, full = per / W;
+    const bool even = (per % W == 0) && (ntiles % 8 == 0);
+    const bool cut = !even && full == 1 && pairs >= 4 && partials != nullptr && counters != nullptr;
+    sk.dp_rounds = cut ? 0 : (per + (ntiles % 8 ? 1 : 0) + W - 1) / W;
+    return sk;
 }
 
 template <int BITS, bool BT, typename TS>
@@ -911,9 +1071,6 @@ void launch_q(const GemmQArgs &args, hipStream_t st)
 {
     constexpr int LDB = BT ? TS::BN + kPadKM : TS::BK + kPadKC;
     constexpr size_t smem = 2 * (size_t)(TS::BM * TS::BK + (BT ? TS::BK * LDB : TS::BN * LDB)) * sizeof(bf16_t);
-    auto kern = k_gemm_q<BITS, BT, TS::BM, TS::BN, TS::BK, TS::WGM, TS::WGN>;
-    static uint64_t attr_done = 0;
-    allow_dynamic_lds(kern, smem, attr_done);
     GemmQArgs a = args;
     a.tiles_m = (a.M + TS::BM - 1) / TS::BM;
     a.tiles_n = (a.N + TS::BN - 1) / TS::BN;
@@ -921,8 +1078,19 @@ void launch_q(const GemmQArgs &args, hipStream_t st)
     // At most as many workgroups as the chip holds at once; with more tiles than that every workgroup walks several
     // (grid a multiple of 8, one share per XCD).
     const int ntiles = a.tiles_m * a.tiles_n, resident = resident_workgroups(smem);
-    a.walk = ntiles > resident ? 1 : 0;
-    kern<<<dim3(a.walk ? resident : ntiles), dim3(64 * TS::WGM * TS::WGN), smem, st>>>(a);
+    a.sk = plan_tiles(ntiles, ((a.K + TS::BK - 1) / TS::BK + 1) / 2, resident, a.sk.partials, a.sk.counters);
+    const dim3 grid(a.sk.walk ? resident : ntiles), block(64 * TS::WGM * TS::WGN);
+    if (a.sk.walk && a.sk.dp_rounds == 0) {
+        auto kern = k_gemm_q<BITS, BT, true, TS::BM, TS::BN, TS::BK, TS::WGM, TS::WGN>;
+        static uint64_t attr_done = 0;
+        allow_dynamic_lds(kern, smem, attr_done);
+        kern<<<grid, block, smem, st>>>(a);
+    } else {
+        auto kern = k_gemm_q<BITS, BT, false, TS::BM, TS::BN, TS::BK, TS::WGM, TS::WGN>;
+        static uint64_t attr_done = 0;
+        allow_dynamic_lds(kern, smem, attr_done);
+        kern<<<grid, block, smem, st>>>(a);
+    }
 }
 
 template <bool BT>
@@ -964,20 +1132,46 @@ bool launch_dw_bits(int bits, const GemmDwArgs &a, hipStream_t st)      // retur
 // workspace reservation: either tile shape may be picked at launch
 bool dw_needs_partials(const Problem &p) { return (TileSmall::BM % p.g) != 0; }
 
-void launch_mfma_fwd(const Problem &p, const void *X, const void *codes, const void *sz, void *Y, hipStream_t st)
+// Scratch that cutting tiles along K needs, for whichever of the fwd / dX GEMMs of a problem may do so (bwd: both,
+// else the forward alone): the larger of the two tile shapes' needs, with the full complement of compute units.
+void sk_scratch_bytes(const Problem &p, bool bwd, size_t *partial_bytes, size_t *counter_bytes)
+{
+    *partial_bytes = 0;
+    *counter_bytes = p.act_bf16 ? (size_t)kSkCounterWords * sizeof(uint32_t) : 0;     // whatever the token count
+    if (!p.act_bf16 || p.T == 0) return;
+    float *const some_p = reinterpret_cast<float *>(16); uint32_t *const some_c = reinterpret_cast<uint32_t *>(16);
+    auto one = [&](int64_t m, int64_t n, int64_t k) {
+        const bool small = use_small_tile(m, n);
+        const int b = small ? TileSmall::BM : TileBig::BM, resident = kMaxCus * (small ? 2 : 1);
+        const int ntiles = (int)(((m + b - 1) / b) * ((n + b - 1) / b));
+        const SkPlan sk = plan_tiles(ntiles, (int)(((k + 63) / 64 + 1) / 2), resident, some_p, some_c);
+        if (!sk.walk) return;
+        const int W = resident / 8, n_sk = (ntiles + 7) / 8 - sk.dp_rounds * W;
+        if (n_sk <= 0) return;
+        *partial_bytes = std::max(*partial_bytes, (size_t)resident * 2 * b * b * sizeof(float));
+    };
+    one(p.T, p.O, p.I);
+    if (bwd) one(p.T, p.I, p.O);
+}
+
+void launch_mfma_fwd(const Problem &p, const void *X, const void *codes, const void *sz, void *Y, const SkScratch &sk,
+                     hipStream_t st)
 {
     if (p.T == 0) return;
     GemmQArgs a{};
+    a.sk.partials = sk.partials; a.sk.counters = sk.counters;
     a.A = (const bf16_t *)X; a.codes = (const uint32_t *)codes; a.sz = (const floatx2 *)sz; a.C = (bf16_t *)Y;
     a.M = (int)p.T; a.N = (int)p.O; a.K = (int)p.I; a.I = (int)p.I; a.G = (int)p.G; a.g = (int)p.g;
     a.a_bytes = (uint32_t)(p.T * p.I * 2); a.codes_bytes = (uint32_t)work_code_bytes(p); a.sz_bytes = (uint32_t)(p.O * p.G * 8);
     launch_q_bits<false>(p.bits, a, st);
 }
 
-void launch_mfma_dx(const Problem &p, const void *dY, const void *codes, const void *sz, void *dX, hipStream_t st)
+void launch_mfma_dx(const Problem &p, const void *dY, const void *codes, const void *sz, void *dX, const SkScratch &sk,
+                    hipStream_t st)
 {
     if (p.T == 0) return;
     GemmQArgs a{};
+    a.sk.partials = sk.partials; a.sk.counters = sk.counters;
     a.A = (const bf16_t *)dY; a.codes = (const uint32_t *)codes; a.sz = (const floatx2 *)sz; a.C = (bf16_t *)dX;
     a.M = (int)p.T; a.N = (int)p.I; a.K = (int)p.O; a.I = (int)p.I; a.G = (int)p.G; a.g = (int)p.g;
     a.a_bytes = (uint32_t)(p.T * p.O * 2); a.codes_bytes = (uint32_t)work_code_bytes(p); a.sz_bytes = (uint32_t)(p.O * p.G * 8);

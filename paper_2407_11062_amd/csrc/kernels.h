@@ -16,24 +16,31 @@ struct Problem {
 // Eq.(1): W,s,z -> codes (+ optional clamp bit-plane [O,I/8] bytes, + optional (s,zbar) pairs [O,G]).
 // for_pack: the dense stream of the C ABI; otherwise the working layout the GEMM kernels read (work_code_bytes()).
 // zpacked (may be NULL): the zero points at N bits are packed by extra workgroups of the same launch.
+// zero_words (may be NULL): n_zero 32-bit words that the launch also clears (the arrival counters of the GEMMs).
 void launch_quantize(const Problem &p, const void *W, const float *s, const float *z, void *codes, void *clampbits,
-                     void *sz, void *zpacked, bool for_pack, hipStream_t st);
+                     void *sz, void *zpacked, bool for_pack, uint32_t *zero_words, uint32_t n_zero, hipStream_t st);
 inline size_t work_code_bytes(const Problem &p) { return (size_t)p.O * p.I / (p.bits == 2 ? 4 : 2); }
 // One launch before the GEMMs of an E2E-QP call: dense stream -> working layout (packed == NULL: skipped) and the
 // (s, z) pairs, z taken from the packed N-bit zero points or from a float array (exactly one of the two not NULL).
 void launch_e2e_prepare(const Problem &p, const void *packed, void *work, const float *s, const void *zpacked,
-                        const float *zfloat, void *sz, hipStream_t st);
+                        const float *zfloat, void *sz, uint32_t *zero_words, uint32_t n_zero, hipStream_t st);
 void launch_unpack(const Problem &p, const void *Wpacked, const void *zpacked, int32_t *codes, int32_t *zcodes, hipStream_t st);
 void launch_init_minmax(const Problem &p, const void *W, float *s, float *z, hipStream_t st);
 void launch_reduce_partials(const float *part, float *out, const float *s, size_t n_out, uint32_t n_per, bool scale_by_s,
                             hipStream_t st);
-void launch_fill_zero(void *p, size_t bytes, hipStream_t st);
 
 // ---- gemm_mfma.hip (bf16 activations) -----------------------------------------------------------
+// Scratch of the GEMM launches that cut the tiles of a partly filled last round along K: one buffer of fp32 accumulator
+// tiles and one arrival counter per tile.  The counters must be zero when a launch starts; every launch leaves them zero.
+// Either pointer NULL: tiles are never cut.
+struct SkScratch { float *partials; uint32_t *counters; };
+void sk_scratch_bytes(const Problem &p, bool bwd, size_t *partial_bytes, size_t *counter_bytes);
 // Y[T,O] = X[T,I] * What[O,I]^T with What = (code - zbar) * s rebuilt per tile from packed codes.
-void launch_mfma_fwd(const Problem &p, const void *X, const void *codes, const void *sz, void *Y, hipStream_t st);
+void launch_mfma_fwd(const Problem &p, const void *X, const void *codes, const void *sz, void *Y, const SkScratch &sk,
+                     hipStream_t st);
 // dX[T,I] = dY[T,O] * What[O,I]
-void launch_mfma_dx(const Problem &p, const void *dY, const void *codes, const void *sz, void *dX, hipStream_t st);
+void launch_mfma_dx(const Problem &p, const void *dY, const void *codes, const void *sz, void *dX, const SkScratch &sk,
+                    hipStream_t st);
 // dWhat = dY^T X fused with the per-element / per-group epilogue.
 //   block_ap: needs W, clampbits; writes dW (W's dtype, may be NULL), ds, dz (may be NULL).
 //   e2e_qp  : W = clampbits = dW = NULL; writes ds and, if not NULL, dz = -s * group-sum dWhat.

@@ -79,7 +79,14 @@ struct QuantizeArgs {
     uint32_t n_chunks, g; int g_shift;
     // eqat_pack only: the blocks past n_quant_blocks pack the zero points (one thread per word)
     uint32_t *zpacked; uint32_t n_quant_blocks, n_zwords, G, row_words;
+    // words the launch clears on the side (arrival counters of the GEMM launches that follow); NULL: none
+    uint32_t *zero_words; uint32_t n_zero;
 };
+
+__device__ __forceinline__ void clear_words(uint32_t *__restrict__ w, uint32_t n)
+{
+    for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) w[i] = 0u;
+}
 
 constexpr int kQuantUnroll = 4;     // chunks per thread: 64 B (bf16) / 128 B (fp32) of W in flight per lane
 
@@ -87,6 +94,7 @@ template <typename WT, int BITS, bool CLAMPBITS, bool WORK>
 __global__ __launch_bounds__(256) void k_quantize(const QuantizeArgs a)
 {
     constexpr int U = kQuantUnroll;
+    if (a.zero_words != nullptr) clear_words(a.zero_words, a.n_zero);
     if (blockIdx.x >= a.n_quant_blocks) {
         const uint32_t t = (blockIdx.x - a.n_quant_blocks) * 256u + threadIdx.x;
         if (t < a.n_zwords) pack_z_word<BITS>(a.z, a.zpacked, t, a.G, a.row_words);
@@ -221,8 +229,10 @@ __global__ __launch_bounds__(256) void k_e2e_prepare(const uint32_t *__restrict_
                                                      uint32_t n_segs, uint32_t n_repack_blocks,
                                                      const float *__restrict__ s, const uint32_t *__restrict__ zpacked,
                                                      const float *__restrict__ zfloat, floatx2 *__restrict__ sz,
-                                                     uint32_t n_groups, uint32_t G, uint32_t row_words)
+                                                     uint32_t n_groups, uint32_t G, uint32_t row_words,
+                                                     uint32_t *__restrict__ zero_words, uint32_t n_zero)
 {
+    if (zero_words != nullptr) clear_words(zero_words, n_zero);
     if (blockIdx.x < n_repack_blocks) {
         const uint32_t t = blockIdx.x * 256u + threadIdx.x;
         if (t < n_segs) repack_segment<BITS>(packed, work, t);
@@ -338,13 +348,6 @@ __global__ __launch_bounds__(256) void k_reduce_partials(const float *__restrict
     out[t] = scale_by_s ? -s[t] * acc : acc;
 }
 
-__global__ __launch_bounds__(256) void k_fill_zero(uint32_t *__restrict__ p, size_t n_words)
-{
-    size_t i = (size_t)blockIdx.x * 256u + threadIdx.x;
-    const size_t stride = (size_t)gridDim.x * 256u;
-    for (; i < n_words; i += stride) p[i] = 0u;
-}
-
 // ---------------------------------------------------------------------------------------------
 // host-side launchers
 
@@ -358,9 +361,10 @@ static inline int pow2_shift(int64_t v)
 
 template <typename WT, int BITS>
 static void quantize_t(const Problem &p, const void *W, const float *s, const float *z, void *codes, void *clampbits,
-                       void *sz, void *zpacked, bool for_pack, hipStream_t st)
+                       void *sz, void *zpacked, bool for_pack, uint32_t *zero_words, uint32_t n_zero, hipStream_t st)
 {
     QuantizeArgs a{};
+    a.zero_words = zero_words; a.n_zero = n_zero;
     a.W = W; a.s = s; a.z = z; a.codes = (uint32_t *)codes; a.clampbits = (uint8_t *)clampbits; a.sz = (floatx2 *)sz;
     a.n_chunks = (uint32_t)((size_t)p.O * p.I / 8); a.g = (uint32_t)p.g; a.g_shift = pow2_shift(p.g);
     a.n_quant_blocks = blocks_for(a.n_chunks, 256 * kQuantUnroll);
@@ -375,16 +379,16 @@ static void quantize_t(const Problem &p, const void *W, const float *s, const fl
 }
 
 void launch_quantize(const Problem &p, const void *W, const float *s, const float *z, void *codes, void *clampbits,
-                     void *sz, void *zpacked, bool for_pack, hipStream_t st)
+                     void *sz, void *zpacked, bool for_pack, uint32_t *zero_words, uint32_t n_zero, hipStream_t st)
 {
-#define EQAT_Q(WT, B) quantize_t<WT, B>(p, W, s, z, codes, clampbits, sz, zpacked, for_pack, st)
+#define EQAT_Q(WT, B) quantize_t<WT, B>(p, W, s, z, codes, clampbits, sz, zpacked, for_pack, zero_words, n_zero, st)
     if (p.w_bf16) { if (p.bits == 2) EQAT_Q(bf16_t, 2); else if (p.bits == 3) EQAT_Q(bf16_t, 3); else EQAT_Q(bf16_t, 4); }
     else          { if (p.bits == 2) EQAT_Q(float, 2);  else if (p.bits == 3) EQAT_Q(float, 3);  else EQAT_Q(float, 4); }
 #undef EQAT_Q
 }
 
 void launch_e2e_prepare(const Problem &p, const void *packed, void *work, const float *s, const void *zpacked,
-                        const float *zfloat, void *sz, hipStream_t st)
+                        const float *zfloat, void *sz, uint32_t *zero_words, uint32_t n_zero, hipStream_t st)
 {
     const uint32_t n_segs = packed != nullptr ? (uint32_t)((size_t)p.O * p.I / 32) : 0u;
     const uint32_t nb = blocks_for(n_segs), n_groups = (uint32_t)((size_t)p.O * p.G);
@@ -392,7 +396,7 @@ void launch_e2e_prepare(const Problem &p, const void *packed, void *work, const 
     const dim3 grid(nb + blocks_for(n_groups)), block(256);
 #define EQAT_PREP(B) k_e2e_prepare<B><<<grid, block, 0, st>>>((const uint32_t *)packed, (uint32_t *)work, n_segs, nb, s, \
                                                              (const uint32_t *)zpacked, zfloat, (floatx2 *)sz, n_groups, \
-                                                             (uint32_t)p.G, row_words)
+                                                             (uint32_t)p.G, row_words, zero_words, n_zero)
     if (p.bits == 2) EQAT_PREP(2); else if (p.bits == 3) EQAT_PREP(3); else EQAT_PREP(4);
 #undef EQAT_PREP
 }
@@ -446,15 +450,6 @@ void launch_reduce_partials(const float *part, float *out, const float *s, size_
                             hipStream_t st)
 {
     k_reduce_partials<<<dim3(blocks_for(n_out)), dim3(256), 0, st>>>(part, out, s, (uint32_t)n_out, n_per, scale_by_s ? 1 : 0);
-}
-
-void launch_fill_zero(void *p, size_t bytes, hipStream_t st)
-{
-    if (bytes == 0) return;
-    const size_t n_words = bytes / 4;
-    unsigned blocks = blocks_for(n_words);
-    if (blocks > 4096) blocks = 4096;
-    k_fill_zero<<<dim3(blocks), dim3(256), 0, st>>>((uint32_t *)p, n_words);
 }
 
 }  // namespace eqat

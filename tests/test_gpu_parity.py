@@ -171,6 +171,46 @@ def test_block_ap_bf16_more_tiles_than_resident_workgroups(tag, T, I, O, bits, g
     check_block_ap(X, W, s, z, dY, bits, g, TOL[torch.bfloat16])
 
 
+# Tile counts that do not fill whole rounds of the resident workgroups, with K long enough to be cut: the last 1.x
+# rounds of tiles are then shared out along K, and a tile's parts are added up by whichever contributor arrives last.
+SPLIT_CASES = [
+    ("cut_fwd", 4400, 512, 4104, 2, 64),       # fwd: 18 x 17 = 306 tiles of 256 x 256, 4 K-tile pairs each
+    ("cut_dx", 4400, 4128, 520, 3, 32),        # dX: 306 tiles, K = O = 520: 5 pairs, the last one half past the end
+    ("cut_dw", 600, 4416, 4104, 2, 64),        # dW: 18 x 17 tiles, K = T = 600
+    ("cut_small", 4096, 512, 2304, 4, 128),    # fwd: 576 tiles of 128 x 128 on 512 resident workgroups
+    ("cut_dw_perchan", 520, 4352, 4096, 2, -1),  # dW, 17 x 16 tiles, one group per row (partials + reduce kernel)
+]
+
+
+@pytest.mark.parametrize("tag,T,I,O,bits,g", SPLIT_CASES)
+def test_block_ap_and_e2e_with_tiles_cut_along_k(tag, T, I, O, bits, g):
+    X, W, s, z, dY = make_case(tag, T, I, O, bits, g, torch.bfloat16, torch.bfloat16)
+    check_block_ap(X, W, s, z, dY, bits, g, TOL[torch.bfloat16])
+    check_e2e(X, W, s, z, dY, bits, g, TOL[torch.bfloat16])
+
+
+def test_cut_tiles_are_deterministic_and_ignore_what_the_workspace_held():
+    tag, T, I, O, bits, g = SPLIT_CASES[2]
+    X, W, s, z, dY = make_case(tag, T, I, O, bits, g, torch.bfloat16, torch.bfloat16)
+    Xd, Wd, sd, zd, dYd = dev(X), dev(W), dev(s), dev(z), dev(dY)
+    d = eq.make_desc(T, I, O, bits, g, eq.BF16, eq.BF16)
+    ws = eq.workspace(d, eq.OP_FQ_BWD, Xd.device)
+    outs = []
+    for fill in (0, 255, 171):
+        ws.fill_(fill)
+        Y = eq.eqat_fq_linear_fwd(Xd, Wd, sd, zd, bits, g, ws=ws, keep=True)
+        out = eq.eqat_fq_linear_bwd(Xd, Wd, sd, zd, dYd, bits, g, ws=ws, kept=True)
+        out2 = eq.eqat_fq_linear_bwd(Xd, Wd, sd, zd, dYd, bits, g, ws=ws, kept=True)      # counters were left at zero
+        torch.cuda.synchronize()
+        for k in out:
+            assert torch.equal(out[k], out2[k]), k
+        outs.append((Y, out))
+    for Y, out in outs[1:]:
+        assert torch.equal(Y, outs[0][0])
+        for k in out:
+            assert torch.equal(out[k], outs[0][1][k]), k
+
+
 def test_block_ap_outputs_are_optional_and_deterministic():
     X, W, s, z, dY = make_case("opt", 140, 256, 136, 2, 64, torch.bfloat16, torch.bfloat16)
     Xd, Wd, sd, zd, dYd = dev(X), dev(W), dev(s), dev(z), dev(dY)
