@@ -281,22 +281,28 @@ def run_block_ap_step(eq, layers, bits, g):
 
 
 def pack_block(torch, eq, layers, bits, g, T2, dev):
-    """The block after Block-AP: packed codes and zero points of every linear, with views and workspaces for an E2E-QP
-    step on the first T2 tokens of the block's activations."""
+    """The block after Block-AP: packed codes and zero points of every linear, each prepared once for E2E-QP (Sec. 3.3
+    freezes W_q in that phase, so the re-layout of the codes is no part of a training step), with views and workspaces
+    for a step on the first T2 tokens of the block's activations."""
     packed = []
     for L in layers:
         Wp, zp = eq.eqat_pack(L["W"], L["s"], L["z"], bits, g)
         dsc = eq.make_desc(T2, L["I"], L["O"], bits, g, eq.BF16, eq.BF16)
-        packed.append({"Wp": Wp, "zp": zp, "X": L["X"][:T2], "dY": L["dY"][:T2], "Y": L["Y"][:T2],
+        packed.append({"Wp": Wp, "zp": zp, "prep": eq.eqat_qlinear_prepare(Wp, zp, L["I"], bits, g),
+                       "X": L["X"][:T2], "dY": L["dY"][:T2], "Y": L["Y"][:T2],
                        "out": {"dX": L["out"]["dX"][:T2], "ds": L["out"]["ds"]},
-                       "ws_f": eq.workspace(dsc, eq.OP_Q_FWD, dev), "ws_b": eq.workspace(dsc, eq.OP_Q_BWD, dev)})
+                       "ws_b": eq.workspace(dsc, eq.OP_QP_BWD, dev)})
     return packed
 
 
-def run_e2e_step(eq, layers, packed, bits, g):
-    for L, P in zip(layers, packed):
-        eq.eqat_qlinear_fwd(P["X"], P["Wp"], L["s"], P["zp"], bits, g, Y=P["Y"], ws=P["ws_b"], keep=True)
-        eq.eqat_qlinear_bwd(P["X"], P["Wp"], L["s"], P["zp"], P["dY"], L["I"], bits, g, out=P["out"], ws=P["ws_b"], kept=True)
+def run_e2e_step(eq, layers, packed, bits, g, zf=None, outs=None):
+    """fwd + bwd (dX, ds; with float zero points zf also dz) of every linear on its prepared layer."""
+    for k, (L, P) in enumerate(zip(layers, packed)):
+        z = None if zf is None else zf[k]
+        eq.eqat_qlinear_fwd_prepared(P["X"], P["prep"], L["s"], L["O"], bits, g, z=z, Y=P["Y"], ws=P["ws_b"])
+        eq.eqat_qlinear_bwd_prepared(P["X"], P["prep"], L["s"], P["dY"], L["I"], bits, g, z=z,
+                                     want=("dX", "ds") if z is None else ("dX", "ds", "dz"),
+                                     out=P["out"] if outs is None else outs[k], ws=P["ws_b"])
 
 
 def hbm_row(torch, eq, fn, nbytes, args, peaks):
@@ -359,12 +365,8 @@ def measure_other_rows(torch, eq, layers, bits, g, adt, dev, args, peaks):
     zf = [(L["z"].clamp(0, 2 ** bits - 1) + 0.25).contiguous() for L in layers]
     outz = [{"dX": P["out"]["dX"], "ds": P["out"]["ds"], "dz": torch.empty_like(L["s"])} for L, P in zip(layers, packed)]
 
-    def e2e_sz_step():
-        for L, P, z2, o2 in zip(layers, packed, zf, outz):
-            eq.eqat_qlinear_fwd_z(P["X"], P["Wp"], L["s"], z2, bits, g, Y=P["Y"], ws=P["ws_f"])
-            eq.eqat_qlinear_bwd_z(P["X"], P["Wp"], L["s"], z2, P["dY"], L["I"], bits, g, out=o2, ws=P["ws_b"])
-
-    rows["e2e_qp_fwd_bwd_trained_s_z"] = step_row(torch, eq, e2e_sz_step, fl, T2, fpl, args, peaks)
+    rows["e2e_qp_fwd_bwd_trained_s_z"] = step_row(torch, eq, lambda: run_e2e_step(eq, layers, packed, bits, g, zf, outz),
+                                                  fl, T2, fpl, args, peaks)
     wbytes = 2 if adt == torch.bfloat16 else 4
 
     def pack_all():

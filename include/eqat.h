@@ -66,8 +66,13 @@ typedef enum {
 typedef enum { EQAT_F32 = 0, EQAT_BF16 = 1 } eqat_dtype;
 
 typedef enum {
-    EQAT_OP_FQ_FWD = 0, EQAT_OP_FQ_BWD = 1, EQAT_OP_Q_FWD = 2, EQAT_OP_Q_BWD = 3
+    EQAT_OP_FQ_FWD = 0, EQAT_OP_FQ_BWD = 1, EQAT_OP_Q_FWD = 2, EQAT_OP_Q_BWD = 3,
+    EQAT_OP_QP_FWD = 4, EQAT_OP_QP_BWD = 5      /* eqat_qlinear_fwd_prepared / _bwd_prepared */
 } eqat_op;
+
+/* What eqat_unpack_state reads: the workspace left by eqat_fq_linear_fwd_keep, the one left by
+ * eqat_qlinear_fwd_keep, or a layer prepared by eqat_qlinear_prepare. */
+typedef enum { EQAT_STATE_FQ_KEPT = 0, EQAT_STATE_Q_KEPT = 1, EQAT_STATE_PREPARED = 2 } eqat_state_kind;
 
 typedef struct eqat_desc {
     int64_t tokens;        /* T                                                  */
@@ -176,6 +181,44 @@ eqat_status eqat_qlinear_fwd_keep(const eqat_desc *d, const void *X, const uint8
 eqat_status eqat_qlinear_bwd_kept(const eqat_desc *d, const void *X, const uint8_t *Wpacked, const float *s,
                                   const uint8_t *zpacked, const void *dY, void *dX, float *ds,
                                   void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * E2E-QP on a layer prepared once (Sec. 3.3: W_q is frozen in this phase and only s, or s and z, train).  The codes are
+ * brought into the layout the GEMM kernels read and the packed zero points become floats, one time; a call then runs its
+ * GEMMs behind one small launch that pairs the current step sizes with the zero points (O*G pairs: s changes every step).
+ *   eqat_prepared_bytes    size of the prepared layer for this descriptor (tokens ignored; act_dtype matters:
+ *                          with fp32 activations the prepared layer holds the dense stream); 0 for a bad descriptor.
+ *   eqat_qlinear_prepare   Wpacked, zpacked (as eqat_pack wrote them) -> prepared (device, 256-byte aligned, owned by
+ *                          the caller, at least eqat_prepared_bytes; too small gives EQAT_ERR_WORKSPACE).  Enqueues one
+ *                          kernel (and, with fp32 activations, one device-to-device copy).
+ *   eqat_qlinear_fwd_prepared / _bwd_prepared
+ *                          Y, and dX / ds / dz, exactly (bitwise) as eqat_qlinear_fwd / eqat_qlinear_bwd, or, with a
+ *                          float array z [O,G] given, as eqat_qlinear_fwd_z / eqat_qlinear_bwd_z.  z NULL: the zero
+ *                          points the layer was prepared with.  dz = -s * group-sum (dY^T X) may be asked for either way.
+ *                          Workspace of EQAT_OP_QP_FWD / EQAT_OP_QP_BWD size (the pairs; no room for codes).
+ *                          The tiled GEMM always runs (no few-token kernel).  The prepared layer is only read, except for
+ *                          a few counters inside it that a launch uses and leaves at zero: calls on the same prepared
+ *                          layer must not overlap in time (different streams need their own copy).
+ */
+size_t eqat_prepared_bytes(const eqat_desc *d);
+eqat_status eqat_qlinear_prepare(const eqat_desc *d, const uint8_t *Wpacked, const uint8_t *zpacked, void *prepared,
+                                 size_t prepared_bytes, void *stream);
+eqat_status eqat_qlinear_fwd_prepared(const eqat_desc *d, const void *X, const void *prepared, const float *s,
+                                      const float *z, void *Y, void *ws, size_t ws_bytes, void *stream);
+eqat_status eqat_qlinear_bwd_prepared(const eqat_desc *d, const void *X, const void *prepared, const float *s,
+                                      const float *z, const void *dY, void *dX, float *ds, float *dz,
+                                      void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Test aid: the integer state the GEMM kernels work from, in plain arrays.  `kind` (eqat_state_kind) says what `state` is.
+ *   codes   int32 [O,I]   W_int of Eq.(1) (Block-AP) or the frozen w_q (E2E-QP), or NULL
+ *   clamped uint8 [O,I]   1 where Eq.(1) clamped the weight, i.e. where Eq.(5) zeroes dW; EQAT_STATE_FQ_KEPT only
+ *                         (EQAT_ERR_NULL if asked of another kind), or NULL
+ *   zbar    float [O,G]   the zero point Eq.(2) uses: clamp(round(z), 0, 2^N-1), or the unpacked N-bit zero point; or NULL
+ * bf16 activations only (the fp32 path keeps no such state): EQAT_ERR_DTYPE otherwise.  d->tokens is ignored.
+ */
+eqat_status eqat_unpack_state(const eqat_desc *d, int kind, const void *state, int32_t *codes, uint8_t *clamped,
+                              float *zbar, void *stream);
 
 /*
  * E2E-QP with trained zero points (Sec. 3.3 and the ablation on the trainable parameters of E2E-QP: training z

@@ -17,7 +17,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("EQAT_LIB", os.path.join(_HERE, "libeqat.so"))   # EQAT_LIB: a build under test
 
 F32, BF16 = 0, 1
-OP_FQ_FWD, OP_FQ_BWD, OP_Q_FWD, OP_Q_BWD = 0, 1, 2, 3
+OP_FQ_FWD, OP_FQ_BWD, OP_Q_FWD, OP_Q_BWD, OP_QP_FWD, OP_QP_BWD = 0, 1, 2, 3, 4, 5
+STATE_FQ_KEPT, STATE_Q_KEPT, STATE_PREPARED = 0, 1, 2
 
 STATUS_NAMES = ["EQAT_OK", "EQAT_ERR_NULL", "EQAT_ERR_SHAPE", "EQAT_ERR_BITS", "EQAT_ERR_GROUP", "EQAT_ERR_DTYPE",
                 "EQAT_ERR_ALIGN", "EQAT_ERR_WORKSPACE", "EQAT_ERR_DEVICE", "EQAT_ERR_HYPER"]
@@ -26,7 +27,8 @@ EXPORTS = ["eqat_status_string", "eqat_validate_desc", "eqat_packed_w_bytes", "e
            "eqat_workspace_bytes", "eqat_init_minmax", "eqat_fq_linear_fwd", "eqat_fq_linear_bwd",
            "eqat_fq_linear_fwd_keep", "eqat_fq_linear_bwd_kept", "eqat_pack",
            "eqat_unpack", "eqat_qlinear_fwd", "eqat_qlinear_bwd", "eqat_qlinear_fwd_keep", "eqat_qlinear_bwd_kept",
-           "eqat_qlinear_fwd_z", "eqat_qlinear_bwd_z",
+           "eqat_qlinear_fwd_z", "eqat_qlinear_bwd_z", "eqat_prepared_bytes", "eqat_qlinear_prepare",
+           "eqat_qlinear_fwd_prepared", "eqat_qlinear_bwd_prepared", "eqat_unpack_state",
            "eqat_recon_loss_workspace_bytes", "eqat_recon_loss", "eqat_recon_loss_static", "eqat_block_ap_update",
            "eqat_profile_kernels", "eqat_profile_kernel_name",
            "eqat_profile_start", "eqat_profile_stop"]
@@ -82,6 +84,11 @@ def lib():
         L.eqat_qlinear_bwd_kept.argtypes = L.eqat_qlinear_bwd.argtypes
         L.eqat_qlinear_fwd_z.argtypes = [dp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.eqat_qlinear_bwd_z.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.eqat_prepared_bytes.restype, L.eqat_prepared_bytes.argtypes = sz, [dp]
+        L.eqat_qlinear_prepare.argtypes = [dp, vp, vp, vp, sz, vp]
+        L.eqat_qlinear_fwd_prepared.argtypes = [dp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.eqat_qlinear_bwd_prepared.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.eqat_unpack_state.argtypes = [dp, ctypes.c_int, vp, vp, vp, vp, vp]
         L.eqat_recon_loss_workspace_bytes.restype, L.eqat_recon_loss_workspace_bytes.argtypes = sz, []
         L.eqat_recon_loss.argtypes = [ctypes.c_int64, ctypes.c_int32, vp, vp, vp, vp, vp, sz, vp]
         L.eqat_recon_loss_static.argtypes = [ctypes.c_int64, ctypes.c_int32, vp, vp, vp, vp, vp]
@@ -259,6 +266,58 @@ def eqat_qlinear_bwd_z(X, Wpacked, s, z, dY, in_features, bits, group, want=("dX
                                                           _p(out.get("dX")), _p(out.get("ds")), _p(out.get("dz")),
                                                           _p(ws), ws.numel(), _stream()))
     return out
+
+
+def eqat_qlinear_prepare(Wpacked, zpacked, in_features, bits, group, act_dtype=BF16, prepared=None):
+    """One-time preparation of a packed layer for E2E-QP steps (codes frozen): returns the prepared buffer."""
+    O, I = Wpacked.shape[0], int(in_features)
+    d = make_desc(0, I, O, bits, group, act_dtype, BF16)
+    n = lib().eqat_prepared_bytes(ctypes.byref(d))
+    if n == 0:
+        _check("eqat_qlinear_prepare", lib().eqat_validate_desc(ctypes.byref(d)) or 2)
+    prepared = torch.empty(n, dtype=torch.uint8, device=Wpacked.device) if prepared is None else prepared
+    _check("eqat_qlinear_prepare", lib().eqat_qlinear_prepare(ctypes.byref(d), _p(Wpacked), _p(zpacked), _p(prepared),
+                                                               prepared.numel(), _stream()))
+    return prepared
+
+
+def eqat_qlinear_fwd_prepared(X, prepared, s, out_features, bits, group, z=None, Y=None, ws=None):
+    T, I = X.shape
+    O = int(out_features)
+    d = make_desc(T, I, O, bits, group, _dt(X), BF16)
+    Y = torch.empty((T, O), dtype=X.dtype, device=X.device) if Y is None else Y
+    ws = workspace(d, OP_QP_FWD, X.device) if ws is None else ws
+    _check("eqat_qlinear_fwd_prepared", lib().eqat_qlinear_fwd_prepared(
+        ctypes.byref(d), _p(X), _p(prepared), _p(s), _p(z), _p(Y), _p(ws), ws.numel(), _stream()))
+    return Y
+
+
+def eqat_qlinear_bwd_prepared(X, prepared, s, dY, in_features, bits, group, z=None, want=("dX", "ds"), out=None, ws=None):
+    T, O = dY.shape
+    I = int(in_features)
+    d = make_desc(T, I, O, bits, group, _dt(dY), BF16)
+    out = {} if out is None else out
+    G = _groups(I, group)
+    if "dX" in want and "dX" not in out: out["dX"] = torch.empty((T, I), dtype=dY.dtype, device=dY.device)
+    if "ds" in want and "ds" not in out: out["ds"] = torch.empty((O, G), dtype=torch.float32, device=dY.device)
+    if "dz" in want and "dz" not in out: out["dz"] = torch.empty((O, G), dtype=torch.float32, device=dY.device)
+    ws = workspace(d, OP_QP_BWD, dY.device) if ws is None else ws
+    _check("eqat_qlinear_bwd_prepared", lib().eqat_qlinear_bwd_prepared(
+        ctypes.byref(d), _p(X), _p(prepared), _p(s), _p(z), _p(dY), _p(out.get("dX")), _p(out.get("ds")), _p(out.get("dz")),
+        _p(ws), ws.numel(), _stream()))
+    return out
+
+
+def eqat_unpack_state(kind, state, out_features, in_features, bits, group, want_clamped=False):
+    """Test aid: (codes int32 [O,I], clamped uint8 [O,I] or None, zbar float32 [O,G]) of a kept workspace / prepared layer."""
+    O, I = int(out_features), int(in_features)
+    d = make_desc(0, I, O, bits, group, BF16, BF16)
+    codes = torch.empty((O, I), dtype=torch.int32, device=state.device)
+    clamped = torch.empty((O, I), dtype=torch.uint8, device=state.device) if want_clamped else None
+    zbar = torch.empty((O, _groups(I, group)), dtype=torch.float32, device=state.device)
+    _check("eqat_unpack_state", lib().eqat_unpack_state(ctypes.byref(d), int(kind), _p(state), _p(codes), _p(clamped),
+                                                        _p(zbar), _stream()))
+    return codes, clamped, zbar
 
 
 def eqat_recon_loss(Y, Yref, want_dY=True, loss=None, dY=None, ws=None):

@@ -73,6 +73,28 @@ eqat_status check_desc(const eqat_desc *d, bool with_tokens, Problem *p)
 
 struct WsLayout { size_t codes, clamp, sz, part, dwhat, sk_ctr, sk_ctr_bytes, sk_part, sk_part_bytes, total; };
 
+inline bool op_is_bwd(int op) { return op == EQAT_OP_FQ_BWD || op == EQAT_OP_Q_BWD || op == EQAT_OP_QP_BWD; }
+inline bool op_is_prepared(int op) { return op == EQAT_OP_QP_FWD || op == EQAT_OP_QP_BWD; }
+
+// Prepared E2E-QP layer (eqat_qlinear_prepare): codes as the kernels read them, the packed zero points as floats, and
+// the arrival counters of the GEMM launches that cut tiles along K (zero, and left zero by every launch).
+struct PreparedLayout { size_t codes, zb, sk_ctr, sk_ctr_bytes, total; };
+
+PreparedLayout prepared_layout(const Problem &p)
+{
+    PreparedLayout l{};
+    size_t off = 0;
+    auto take = [&](size_t bytes) { const size_t at = off; off += align256(bytes); return at; };
+    // bf16 activations: working layout; fp32 activations: the dense stream as it is (that path reads it directly)
+    l.codes = take(p.act_bf16 ? eqat::work_code_bytes(p) : (size_t)p.O * p.I * p.bits / 8);
+    l.zb = take((size_t)p.O * p.G * 4);
+    size_t unused = 0;
+    eqat::sk_scratch_bytes(p, true, &unused, &l.sk_ctr_bytes);
+    l.sk_ctr = take(l.sk_ctr_bytes);
+    l.total = off;
+    return l;
+}
+
 WsLayout ws_layout(const Problem &p, int op)
 {
     WsLayout l{};
@@ -80,16 +102,17 @@ WsLayout ws_layout(const Problem &p, int op)
     auto take = [&](size_t bytes) { const size_t at = off; off += align256(bytes); return at; };
     const size_t codes_b = eqat::work_code_bytes(p), clamp_b = (size_t)p.O * p.I / 8, sz_b = (size_t)p.O * p.G * 8;
     const size_t part_b = (size_t)p.O * (p.I / 32) * 4, dwhat_b = (size_t)p.O * p.I * 4;
-    const bool bwd = (op == EQAT_OP_FQ_BWD || op == EQAT_OP_Q_BWD), fq = (op == EQAT_OP_FQ_FWD || op == EQAT_OP_FQ_BWD);
+    const bool bwd = op_is_bwd(op), fq = (op == EQAT_OP_FQ_FWD || op == EQAT_OP_FQ_BWD), prepared = op_is_prepared(op);
     if (p.act_bf16) {
-        l.codes = take(codes_b);          // codes in the working layout (from W, or repacked from the dense stream)
+        if (!prepared) l.codes = take(codes_b);       // codes in the working layout (from W, or repacked from the dense stream)
         if (fq && bwd) l.clamp = take(clamp_b);
-        l.sz = take(sz_b);
+        l.sz = take(sz_b);                            // (step size, zero point of Eq.(2)) of every group, as the GEMMs read them
         if (bwd && eqat::dw_needs_partials(p)) l.part = take(2 * part_b);
         // GEMM launches that cut tiles along K: arrival counters (cleared by the first kernel of every call; their
-        // size and place do not depend on the token count) and, last, the accumulator parts (large, sparsely touched,
-        // never initialised; present only for shapes whose tiles are cut).
+        // size and place do not depend on the token count; a prepared layer carries its own) and, last, the
+        // accumulator parts (large, sparsely touched, never initialised; present only for shapes whose tiles are cut).
         eqat::sk_scratch_bytes(p, bwd, &l.sk_part_bytes, &l.sk_ctr_bytes);
+        if (prepared) l.sk_ctr_bytes = 0;
         l.sk_ctr = take(l.sk_ctr_bytes);
         l.sk_part = take(l.sk_part_bytes);
     } else {
@@ -114,6 +137,7 @@ inline eqat::SkScratch sk_of(const WsLayout &l, char *w8)
     return eqat::SkScratch{l.sk_part_bytes != 0 ? reinterpret_cast<float *>(w8 + l.sk_part) : nullptr,
                            reinterpret_cast<uint32_t *>(w8 + l.sk_ctr)};
 }
+
 
 inline eqat_status launch_status() { return hipGetLastError() == hipSuccess ? EQAT_OK : EQAT_ERR_DEVICE; }
 
@@ -193,7 +217,7 @@ size_t eqat_packed_z_bytes(const eqat_desc *d)
 size_t eqat_workspace_bytes(const eqat_desc *d, int op)
 {
     Problem p;
-    if (op < EQAT_OP_FQ_FWD || op > EQAT_OP_Q_BWD || check_desc(d, true, &p) != EQAT_OK) return 0;
+    if (op < EQAT_OP_FQ_FWD || op > EQAT_OP_QP_BWD || check_desc(d, true, &p) != EQAT_OK) return 0;
     return ws_layout(p, op).total;
 }
 
@@ -323,6 +347,45 @@ static eqat_status fq_bwd_any(const eqat_desc *d, const void *X, const void *W, 
     return launch_status();
 }
 
+// What the E2E-QP GEMMs read: codes (working layout; fp32 activations: the dense stream), the (s, z) pairs, the
+// scratch of launches that cut tiles, the array of per-32-column partials of dW, the fp32 dWhat of the fp32 path.
+struct QOperands { const void *codes; const void *sz; eqat::SkScratch sk; float *part; float *dwhat; };
+
+static eqat_status qlinear_fwd_run(const Problem &p, const void *X, const float *s, const QOperands &q, void *Y, hipStream_t st)
+{
+    if (p.T == 0) return launch_status();
+    if (p.act_bf16) { ProfScope ps(eqat::PK_GEMM_FWD, st); eqat::launch_mfma_fwd(p, X, q.codes, q.sz, Y, q.sk, st); }
+    else { ProfScope ps(eqat::PK_F32, st); eqat::launch_f32_fwd(p, true, X, q.codes, s, q.sz, Y, st); }
+    return launch_status();
+}
+
+static eqat_status qlinear_bwd_run(const Problem &p, const void *X, const float *s, const QOperands &q, const void *dY,
+                                   void *dX, float *ds, float *dz, hipStream_t st)
+{
+    const bool want_g = (ds != nullptr || dz != nullptr);
+    if (p.act_bf16) {
+        if (dX != nullptr) { ProfScope ps(eqat::PK_GEMM_DX, st); eqat::launch_mfma_dx(p, dY, q.codes, q.sz, dX, q.sk, st); }
+        if (want_g) eqat::launch_mfma_dw(p, false, X, dY, nullptr, q.codes, nullptr, q.sz, s, nullptr, ds, dz, q.part, st);
+    } else {
+        ProfScope ps(eqat::PK_F32, st);
+        if (dX != nullptr && p.T > 0) eqat::launch_f32_dx(p, true, dY, q.codes, s, q.sz, dX, st);
+        if (want_g) eqat::launch_f32_dw(p, false, X, dY, q.codes, s, q.sz, q.dwhat, nullptr, ds, dz, st);
+    }
+    return launch_status();
+}
+
+// The launch that every E2E-QP call starts with: the (s, z) pairs of the groups (s changes from step to step), z from
+// the packed zero points or from floats; with `Wpacked` also the codes into the working layout (bf16 activations; a
+// prepared layer has them already); arrival counters cleared (`counters` NULL: a prepared layer's stay at zero).
+static void qlinear_prepare_into(const Problem &p, const uint8_t *Wpacked, const float *s, const uint8_t *zpacked,
+                                 const float *zfloat, void *codes, void *sz, uint32_t *counters, size_t counter_bytes,
+                                 hipStream_t st)
+{
+    ProfScope ps(eqat::PK_PREPARE, st);
+    eqat::launch_e2e_prepare(p, p.act_bf16 ? Wpacked : nullptr, codes, s, zpacked, zfloat, sz, nullptr, counters,
+                             (uint32_t)(counter_bytes / 4), st);
+}
+
 extern "C" {
 
 // E2E-QP forward / backward; the zero points come packed at N bits (zpacked) or as floats (zfloat), one of the two.
@@ -336,7 +399,7 @@ static eqat_status qlinear_fwd_any(const eqat_desc *d, const void *X, const uint
     EQAT_REQUIRE(Wpacked); EQAT_REQUIRE(s); EQAT_REQUIRE(zany);
     if (p.T > 0) { EQAT_REQUIRE(X); EQAT_REQUIRE(Y); }
     EQAT_ALIGNED(X); EQAT_ALIGNED(Wpacked); EQAT_ALIGNED(s); EQAT_ALIGNED(zany); EQAT_ALIGNED(Y);
-    // keep: backward-sized workspace, left holding the codes in the working layout and the (s, z) pairs
+    // keep: backward-sized workspace, left holding the codes in the working layout and the zero points as floats
     const WsLayout l = ws_layout(p, keep ? EQAT_OP_Q_BWD : EQAT_OP_Q_FWD);
     if (eqat_status e = check_ws(l, ws, ws_bytes)) return e;
     if (p.T == 0 && !keep) return EQAT_OK;
@@ -348,15 +411,9 @@ static eqat_status qlinear_fwd_any(const eqat_desc *d, const void *X, const uint
         return launch_status();
     }
     const eqat::SkScratch sk = sk_of(l, w8);
-    {
-        ProfScope ps(eqat::PK_PREPARE, st);
-        eqat::launch_e2e_prepare(p, p.act_bf16 ? Wpacked : nullptr, w8 + l.codes, s, zpacked, zfloat, w8 + l.sz,
-                                 sk.counters, (uint32_t)(l.sk_ctr_bytes / 4), st);
-    }
-    if (p.T == 0) return launch_status();
-    if (p.act_bf16) { ProfScope ps(eqat::PK_GEMM_FWD, st); eqat::launch_mfma_fwd(p, X, w8 + l.codes, w8 + l.sz, Y, sk, st); }
-    else { ProfScope ps(eqat::PK_F32, st); eqat::launch_f32_fwd(p, true, X, Wpacked, s, w8 + l.sz, Y, st); }
-    return launch_status();
+    qlinear_prepare_into(p, Wpacked, s, zpacked, zfloat, w8 + l.codes, w8 + l.sz, sk.counters, l.sk_ctr_bytes, st);
+    const QOperands q{p.act_bf16 ? (const void *)(w8 + l.codes) : (const void *)Wpacked, w8 + l.sz, sk, nullptr, nullptr};
+    return qlinear_fwd_run(p, X, s, q, Y, st);
 }
 
 static eqat_status qlinear_bwd_any(const eqat_desc *d, const void *X, const uint8_t *Wpacked, const float *s,
@@ -377,20 +434,114 @@ static eqat_status qlinear_bwd_any(const eqat_desc *d, const void *X, const uint
     hipStream_t st = (hipStream_t)stream;
     char *w8 = (char *)ws;
     const eqat::SkScratch sk = sk_of(l, w8);
-    if (!kept) {
-        ProfScope ps(eqat::PK_PREPARE, st);
-        eqat::launch_e2e_prepare(p, p.act_bf16 ? Wpacked : nullptr, w8 + l.codes, s, zpacked, zfloat, w8 + l.sz,
-                                 sk.counters, (uint32_t)(l.sk_ctr_bytes / 4), st);
-    }
-    if (p.act_bf16) {
-        if (dX != nullptr) { ProfScope ps(eqat::PK_GEMM_DX, st); eqat::launch_mfma_dx(p, dY, w8 + l.codes, w8 + l.sz, dX, sk, st); }
-        if (want_g)
-            eqat::launch_mfma_dw(p, false, X, dY, nullptr, w8 + l.codes, nullptr, w8 + l.sz, s, nullptr, ds, dz,
-                                 (float *)(w8 + l.part), st);
+    if (!kept) qlinear_prepare_into(p, Wpacked, s, zpacked, zfloat, w8 + l.codes, w8 + l.sz, sk.counters, l.sk_ctr_bytes, st);
+    const QOperands q{p.act_bf16 ? (const void *)(w8 + l.codes) : (const void *)Wpacked, w8 + l.sz, sk,
+                      (float *)(w8 + l.part), (float *)(w8 + l.dwhat)};
+    return qlinear_bwd_run(p, X, s, q, dY, dX, ds, dz, st);
+}
+
+size_t eqat_prepared_bytes(const eqat_desc *d)
+{
+    Problem p;
+    if (check_desc(d, false, &p) != EQAT_OK) return 0;
+    p.act_bf16 = d->act_dtype == EQAT_BF16;
+    return prepared_layout(p).total;
+}
+
+eqat_status eqat_qlinear_prepare(const eqat_desc *d, const uint8_t *Wpacked, const uint8_t *zpacked, void *prepared,
+                                 size_t prepared_bytes, void *stream)
+{
+    Problem p;
+    if (eqat_status e = check_desc(d, false, &p)) return e;
+    EQAT_REQUIRE(Wpacked); EQAT_REQUIRE(zpacked); EQAT_REQUIRE(prepared);
+    EQAT_ALIGNED(Wpacked); EQAT_ALIGNED(zpacked);
+    const PreparedLayout l = prepared_layout(p);
+    if (prepared_bytes < l.total) return EQAT_ERR_WORKSPACE;
+    if (!aligned(prepared, 256)) return EQAT_ERR_ALIGN;
+    hipStream_t st = (hipStream_t)stream;
+    char *p8 = (char *)prepared;
+    if (!p.act_bf16 &&
+        hipMemcpyAsync(p8 + l.codes, Wpacked, (size_t)p.O * p.I * p.bits / 8, hipMemcpyDeviceToDevice, st) != hipSuccess)
+        return EQAT_ERR_DEVICE;
+    // codes into the working layout, zero points into floats, counters to zero: one launch
+    { ProfScope ps(eqat::PK_PREPARE, st);
+      eqat::launch_e2e_prepare(p, p.act_bf16 ? Wpacked : nullptr, p8 + l.codes, nullptr, zpacked, nullptr, nullptr,
+                               (float *)(p8 + l.zb), (uint32_t *)(p8 + l.sk_ctr), (uint32_t)(l.sk_ctr_bytes / 4), st); }
+    return launch_status();
+}
+
+// Operands of a call on a prepared layer; enqueues the small launch that pairs the current step sizes with the zero
+// points (`z` NULL: those the layer was prepared with; else trained zero points, as floats).
+static eqat_status prepared_operands(const Problem &p, const void *prepared, const float *s, const float *z, int op, void *ws,
+                                     size_t ws_bytes, hipStream_t st, QOperands *q)
+{
+    EQAT_REQUIRE(prepared);
+    if (!aligned(prepared, 256)) return EQAT_ERR_ALIGN;
+    const WsLayout l = ws_layout(p, op);
+    if (eqat_status e = check_ws(l, ws, ws_bytes)) return e;
+    const PreparedLayout pl = prepared_layout(p);
+    char *p8 = (char *)const_cast<void *>(prepared), *w8 = (char *)ws;
+    q->codes = p8 + pl.codes;
+    q->sz = w8 + l.sz;
+    q->sk = eqat::SkScratch{l.sk_part_bytes != 0 ? (float *)(w8 + l.sk_part) : nullptr,
+                            pl.sk_ctr_bytes != 0 ? (uint32_t *)(p8 + pl.sk_ctr) : nullptr};
+    q->part = (float *)(w8 + l.part);
+    q->dwhat = (float *)(w8 + l.dwhat);
+    qlinear_prepare_into(p, nullptr, s, nullptr, z != nullptr ? z : (const float *)(p8 + pl.zb), nullptr, w8 + l.sz, nullptr, 0, st);
+    return EQAT_OK;
+}
+
+eqat_status eqat_qlinear_fwd_prepared(const eqat_desc *d, const void *X, const void *prepared, const float *s, const float *z,
+                                      void *Y, void *ws, size_t ws_bytes, void *stream)
+{
+    Problem p;
+    if (eqat_status e = check_desc(d, true, &p)) return e;
+    EQAT_REQUIRE(s);
+    if (p.T > 0) { EQAT_REQUIRE(X); EQAT_REQUIRE(Y); }
+    EQAT_ALIGNED(X); EQAT_ALIGNED(s); EQAT_ALIGNED(z); EQAT_ALIGNED(Y);
+    if (p.T == 0) return prepared == nullptr ? EQAT_ERR_NULL : EQAT_OK;
+    QOperands q{};
+    if (eqat_status e = prepared_operands(p, prepared, s, z, EQAT_OP_QP_FWD, ws, ws_bytes, (hipStream_t)stream, &q)) return e;
+    return qlinear_fwd_run(p, X, s, q, Y, (hipStream_t)stream);
+}
+
+eqat_status eqat_qlinear_bwd_prepared(const eqat_desc *d, const void *X, const void *prepared, const float *s, const float *z,
+                                      const void *dY, void *dX, float *ds, float *dz, void *ws, size_t ws_bytes, void *stream)
+{
+    Problem p;
+    if (eqat_status e = check_desc(d, true, &p)) return e;
+    EQAT_REQUIRE(s);
+    const bool want_g = (ds != nullptr || dz != nullptr);
+    if (p.T > 0) { EQAT_REQUIRE(dY); if (want_g) EQAT_REQUIRE(X); }
+    EQAT_ALIGNED(X); EQAT_ALIGNED(s); EQAT_ALIGNED(z); EQAT_ALIGNED(dY); EQAT_ALIGNED(dX); EQAT_ALIGNED(ds); EQAT_ALIGNED(dz);
+    if (dX == nullptr && !want_g) return prepared == nullptr ? EQAT_ERR_NULL : EQAT_OK;
+    QOperands q{};
+    if (eqat_status e = prepared_operands(p, prepared, s, z, EQAT_OP_QP_BWD, ws, ws_bytes, (hipStream_t)stream, &q)) return e;
+    return qlinear_bwd_run(p, X, s, q, dY, dX, ds, dz, (hipStream_t)stream);
+}
+
+// Test aid: what a forward call that keeps its state, or eqat_qlinear_prepare, left behind, in plain arrays.
+eqat_status eqat_unpack_state(const eqat_desc *d, int kind, const void *state, int32_t *codes, uint8_t *clamped, float *zbar,
+                              void *stream)
+{
+    Problem p;
+    if (eqat_status e = check_desc(d, false, &p)) return e;
+    if (d->act_dtype != EQAT_BF16) return EQAT_ERR_DTYPE;          // the fp32 path keeps no state of this kind
+    if (kind < EQAT_STATE_FQ_KEPT || kind > EQAT_STATE_PREPARED) return EQAT_ERR_SHAPE;
+    EQAT_REQUIRE(state);
+    if (clamped != nullptr && kind != EQAT_STATE_FQ_KEPT) return EQAT_ERR_NULL;    // only Block-AP has a clamp plane
+    const char *s8 = (const char *)state;
+    hipStream_t st = (hipStream_t)stream;
+    if (kind == EQAT_STATE_PREPARED) {
+        const PreparedLayout l = prepared_layout(p);
+        if (codes != nullptr) eqat::launch_unpack_work(p, s8 + l.codes, nullptr, nullptr, codes, nullptr, nullptr, st);
+        if (zbar != nullptr &&
+            hipMemcpyAsync(zbar, s8 + l.zb, (size_t)p.O * p.G * 4, hipMemcpyDeviceToDevice, st) != hipSuccess) return EQAT_ERR_DEVICE;
     } else {
-        ProfScope ps(eqat::PK_F32, st);
-        if (dX != nullptr && p.T > 0) eqat::launch_f32_dx(p, true, dY, Wpacked, s, w8 + l.sz, dX, st);
-        if (want_g) eqat::launch_f32_dw(p, false, X, dY, Wpacked, s, w8 + l.sz, (float *)(w8 + l.dwhat), nullptr, ds, dz, st);
+        p.T = 1;      // the place of these arrays does not depend on the token count
+        const WsLayout l = ws_layout(p, kind == EQAT_STATE_FQ_KEPT ? EQAT_OP_FQ_BWD : EQAT_OP_Q_BWD);
+        if (codes != nullptr || clamped != nullptr || zbar != nullptr)
+            eqat::launch_unpack_work(p, s8 + l.codes, s8 + l.clamp, s8 + l.sz, codes, clamped, zbar, st);
     }
     return launch_status();
 }

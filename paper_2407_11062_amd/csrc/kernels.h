@@ -21,9 +21,14 @@ void launch_quantize(const Problem &p, const void *W, const float *s, const floa
                      void *sz, void *zpacked, bool for_pack, uint32_t *zero_words, uint32_t n_zero, hipStream_t st);
 inline size_t work_code_bytes(const Problem &p) { return (size_t)p.O * p.I / (p.bits == 2 ? 4 : 2); }
 // One launch before the GEMMs of an E2E-QP call: dense stream -> working layout (packed == NULL: skipped) and the
-// (s, z) pairs, z taken from the packed N-bit zero points or from a float array (exactly one of the two not NULL).
+// (s, z) pairs (sz == NULL: skipped), z taken from the packed N-bit zero points or from a float array (exactly one of
+// the two not NULL); zb_out (may be NULL) receives the zero points alone, as floats.
 void launch_e2e_prepare(const Problem &p, const void *packed, void *work, const float *s, const void *zpacked,
-                        const float *zfloat, void *sz, uint32_t *zero_words, uint32_t n_zero, hipStream_t st);
+                        const float *zfloat, void *sz, float *zb_out, uint32_t *zero_words, uint32_t n_zero, hipStream_t st);
+// Test aid: working-layout codes -> int32 [O,I]; clamp bit-plane -> bytes 0/1 [O,I]; (s, zero point) pairs -> the
+// zero points [O,G] (each output may be NULL).
+void launch_unpack_work(const Problem &p, const void *work, const void *clampbits, const void *sz, int32_t *codes,
+                        uint8_t *clamped, float *zbar, hipStream_t st);
 void launch_unpack(const Problem &p, const void *Wpacked, const void *zpacked, int32_t *codes, int32_t *zcodes, hipStream_t st);
 void launch_init_minmax(const Problem &p, const void *W, float *s, float *z, hipStream_t st);
 void launch_reduce_partials(const float *part, float *out, const float *s, size_t n_out, uint32_t n_per, bool scale_by_s,

@@ -204,33 +204,36 @@ __device__ __forceinline__ void repack_segment(const uint32_t *__restrict__ pack
 }
 
 // (s, z) pair of group t for the E2E-QP kernels: z from the packed N-bit zero points, or from a float array.
+// zb_out (may be NULL) also receives the zero point alone; sz may be NULL when only that is wanted.
 template <int BITS>
 __device__ __forceinline__ void pair_sz(const float *__restrict__ s, const uint32_t *__restrict__ zpacked,
-                                        const float *__restrict__ zfloat, floatx2 *__restrict__ sz, uint32_t t, uint32_t G,
-                                        uint32_t row_words)
+                                        const float *__restrict__ zfloat, floatx2 *__restrict__ sz, float *__restrict__ zb_out,
+                                        uint32_t t, uint32_t G, uint32_t row_words)
 {
-    floatx2 o; o[0] = s[t];
+    float zv;
     if (zfloat != nullptr) {
-        o[1] = zfloat[t];
+        zv = zfloat[t];
     } else {
         const uint32_t row = t / G, j = t - row * G;
         const uint32_t bit = j * BITS, wi = bit >> 5, sh = bit & 31u;
         uint64_t two = zpacked[row * row_words + wi];
         if (sh + BITS > 32u) two |= (uint64_t)zpacked[row * row_words + wi + 1] << 32;
-        o[1] = (float)((uint32_t)(two >> sh) & ((1u << BITS) - 1u));
+        zv = (float)((uint32_t)(two >> sh) & ((1u << BITS) - 1u));
     }
-    sz[t] = o;
+    if (zb_out != nullptr) zb_out[t] = zv;
+    if (sz != nullptr) { floatx2 o; o[0] = s[t]; o[1] = zv; sz[t] = o; }
 }
 
-// What every E2E-QP call on the MFMA path needs before its GEMMs, in one launch: the first n_repack_blocks workgroups
-// re-lay the codes (packed == NULL: none), the rest write the (s, z) pairs.
+// What an E2E-QP call needs before its GEMMs, in one launch: the first n_repack_blocks workgroups re-lay the codes from
+// the dense stream into the working layout (packed == NULL: none; a prepared layer has them already), the rest write the
+// (s, z) pairs (and / or the zero points alone: what eqat_qlinear_prepare keeps).
 template <int BITS>
 __global__ __launch_bounds__(256) void k_e2e_prepare(const uint32_t *__restrict__ packed, uint32_t *__restrict__ work,
                                                      uint32_t n_segs, uint32_t n_repack_blocks,
                                                      const float *__restrict__ s, const uint32_t *__restrict__ zpacked,
                                                      const float *__restrict__ zfloat, floatx2 *__restrict__ sz,
-                                                     uint32_t n_groups, uint32_t G, uint32_t row_words,
-                                                     uint32_t *__restrict__ zero_words, uint32_t n_zero)
+                                                     float *__restrict__ zb_out, uint32_t n_groups, uint32_t G,
+                                                     uint32_t row_words, uint32_t *__restrict__ zero_words, uint32_t n_zero)
 {
     if (zero_words != nullptr) clear_words(zero_words, n_zero);
     if (blockIdx.x < n_repack_blocks) {
@@ -238,7 +241,7 @@ __global__ __launch_bounds__(256) void k_e2e_prepare(const uint32_t *__restrict_
         if (t < n_segs) repack_segment<BITS>(packed, work, t);
     } else {
         const uint32_t t = (blockIdx.x - n_repack_blocks) * 256u + threadIdx.x;
-        if (t < n_groups) pair_sz<BITS>(s, zpacked, zfloat, sz, t, G, row_words);
+        if (t < n_groups) pair_sz<BITS>(s, zpacked, zfloat, sz, zb_out, t, G, row_words);
     }
 }
 
@@ -264,6 +267,32 @@ __global__ __launch_bounds__(256) void k_unpack_z(const uint32_t *__restrict__ z
     uint64_t two = zpacked[row * row_words + wi];
     if (sh + BITS > 32u) two |= (uint64_t)zpacked[row * row_words + wi + 1] << 32;
     out[t] = (int32_t)((uint32_t)(two >> sh) & ((1u << BITS) - 1u));
+}
+
+// Test aid: one thread per 32-code segment of the working layout; the first n_groups threads also split the
+// (s, zero point) pairs.
+template <int BITS>
+__global__ __launch_bounds__(256) void k_unpack_work(const uint32_t *__restrict__ work, const uint32_t *__restrict__ clampbits,
+                                                     const floatx2 *__restrict__ sz, int32_t *__restrict__ codes,
+                                                     uint8_t *__restrict__ clamped, float *__restrict__ zbar, uint32_t n_segs,
+                                                     uint32_t n_groups)
+{
+    const uint32_t t = blockIdx.x * 256u + threadIdx.x;
+    if (zbar != nullptr && t < n_groups) zbar[t] = sz[t][1];
+    if (t >= n_segs) return;
+    typedef WorkCodes<BITS> WC;
+    if (codes != nullptr) {
+        uint32_t w[WC::kWords];
+#pragma unroll
+        for (int k = 0; k < WC::kWords; ++k) w[k] = work[(size_t)t * WC::kWords + k];
+#pragma unroll
+        for (int e = 0; e < 32; ++e)
+            codes[(size_t)t * 32 + e] = (int32_t)((w[WC::word_of(e)] >> WC::bit_of(e)) & ((1u << BITS) - 1u));
+    }
+    if (clamped != nullptr) {
+        const uint32_t bits = clampbits[t];                 // bit e of the segment's word: weight e was clamped
+        for (int e = 0; e < 32; ++e) clamped[(size_t)t * 32 + e] = (uint8_t)((bits >> e) & 1u);
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -388,15 +417,15 @@ void launch_quantize(const Problem &p, const void *W, const float *s, const floa
 }
 
 void launch_e2e_prepare(const Problem &p, const void *packed, void *work, const float *s, const void *zpacked,
-                        const float *zfloat, void *sz, uint32_t *zero_words, uint32_t n_zero, hipStream_t st)
+                        const float *zfloat, void *sz, float *zb_out, uint32_t *zero_words, uint32_t n_zero, hipStream_t st)
 {
     const uint32_t n_segs = packed != nullptr ? (uint32_t)((size_t)p.O * p.I / 32) : 0u;
     const uint32_t nb = blocks_for(n_segs), n_groups = (uint32_t)((size_t)p.O * p.G);
     const uint32_t row_words = (uint32_t)((p.G * p.bits + 31) / 32);
     const dim3 grid(nb + blocks_for(n_groups)), block(256);
 #define EQAT_PREP(B) k_e2e_prepare<B><<<grid, block, 0, st>>>((const uint32_t *)packed, (uint32_t *)work, n_segs, nb, s, \
-                                                             (const uint32_t *)zpacked, zfloat, (floatx2 *)sz, n_groups, \
-                                                             (uint32_t)p.G, row_words, zero_words, n_zero)
+                                                             (const uint32_t *)zpacked, zfloat, (floatx2 *)sz, zb_out, \
+                                                             n_groups, (uint32_t)p.G, row_words, zero_words, n_zero)
     if (p.bits == 2) EQAT_PREP(2); else if (p.bits == 3) EQAT_PREP(3); else EQAT_PREP(4);
 #undef EQAT_PREP
 }
@@ -418,6 +447,18 @@ void launch_unpack(const Problem &p, const void *Wpacked, const void *zpacked, i
         else if (p.bits == 3) k_unpack_z<3><<<grid, block, 0, st>>>((const uint32_t *)zpacked, zcodes, (uint32_t)p.O, (uint32_t)p.G, row_words);
         else k_unpack_z<4><<<grid, block, 0, st>>>((const uint32_t *)zpacked, zcodes, (uint32_t)p.O, (uint32_t)p.G, row_words);
     }
+}
+
+void launch_unpack_work(const Problem &p, const void *work, const void *clampbits, const void *sz, int32_t *codes,
+                        uint8_t *clamped, float *zbar, hipStream_t st)
+{
+    const uint32_t n_segs = (uint32_t)((size_t)p.O * p.I / 32), n_groups = (uint32_t)((size_t)p.O * p.G);    // n_groups <= n_segs
+    const dim3 grid(blocks_for(n_segs)), block(256);
+    const uint32_t *w = (const uint32_t *)work, *c = (const uint32_t *)clampbits;
+    const floatx2 *q = (const floatx2 *)sz;
+    if (p.bits == 2) k_unpack_work<2><<<grid, block, 0, st>>>(w, c, q, codes, clamped, zbar, n_segs, n_groups);
+    else if (p.bits == 3) k_unpack_work<3><<<grid, block, 0, st>>>(w, c, q, codes, clamped, zbar, n_segs, n_groups);
+    else k_unpack_work<4><<<grid, block, 0, st>>>(w, c, q, codes, clamped, zbar, n_segs, n_groups);
 }
 
 template <typename WT>

@@ -386,6 +386,122 @@ def check_e2e_trained_z(X, W, s, z, dY, bits, g, tol, seed):
     assert torch.equal(only_ds["ds"], out["ds"])
 
 
+# --------------------------------------------------------------------------- E2E-QP on a layer prepared once
+
+@pytest.mark.parametrize("tag,T,I,O,bits,g,wdt", [c for c in BF16_CASES if c[0] in ("b2g64", "b3g128", "b4g32", "b2perchan", "b3g96", "t1")]
+                         + [("cut_small_p", 4096, 512, 2304, 4, 128, torch.bfloat16)])
+def test_e2e_on_a_prepared_layer_is_bitwise_the_plain_call(tag, T, I, O, bits, g, wdt):
+    """Sec. 3.3: the codes are frozen in this phase, so their re-layout is done once (eqat_qlinear_prepare); a step then
+    runs only its GEMMs.  Same kernels on the same operands: Y, dX, ds (and dz with float zero points) must be bitwise
+    those of eqat_qlinear_fwd / _bwd / _z, which the tests above hold against the oracle.  Two steps in a row on the
+    same prepared layer (its counters must come back to zero)."""
+    X, W, s, z, dY = make_case(tag, T, I, O, bits, g, torch.bfloat16, wdt)
+    Xd, sd, dYd = dev(X), dev(s), dev(dY)
+    Wp, zp = eq.eqat_pack(dev(W), sd, dev(z), bits, g)
+    prep = eq.eqat_qlinear_prepare(Wp, zp, I, bits, g)
+    Y_ref = eq.eqat_qlinear_fwd(Xd, Wp, sd, zp, bits, g) if T > 16 else None      # few tokens: the plain call runs another kernel
+    ref = eq.eqat_qlinear_bwd(Xd, Wp, sd, zp, dYd, I, bits, g)
+    zf = (dev(z).clamp(0, 2 ** bits - 1) + 0.3).contiguous()
+    Yz_ref = eq.eqat_qlinear_fwd_z(Xd, Wp, sd, zf, bits, g) if T > 16 else None
+    refz = eq.eqat_qlinear_bwd_z(Xd, Wp, sd, zf, dYd, I, bits, g)
+    for step in range(2):
+        Y = eq.eqat_qlinear_fwd_prepared(Xd, prep, sd, O, bits, g)
+        out = eq.eqat_qlinear_bwd_prepared(Xd, prep, sd, dYd, I, bits, g)
+        Yz = eq.eqat_qlinear_fwd_prepared(Xd, prep, sd, O, bits, g, z=zf)
+        outz = eq.eqat_qlinear_bwd_prepared(Xd, prep, sd, dYd, I, bits, g, z=zf, want=("dX", "ds", "dz"))
+        torch.cuda.synchronize()
+        if T > 16:
+            assert torch.equal(Y, Y_ref) and torch.equal(Yz, Yz_ref)
+        else:
+            assert relerr(Y, oracle.qlinear_fwd(npf(X), Wp.cpu().numpy(), s.numpy(), zp.cpu().numpy(), bits, g)) <= TOL[torch.bfloat16]
+        for k in ("dX", "ds"):
+            assert torch.equal(out[k], ref[k]), k
+        for k in ("dX", "ds", "dz"):
+            assert torch.equal(outz[k], refz[k]), k
+
+
+def test_e2e_on_a_prepared_layer_fp32_activations():
+    bits, g = 3, 32
+    X, W, s, z, dY = make_case(("prep32", bits, g), 70, 128, 48, bits, g, torch.float32, torch.float32)
+    Xd, sd, dYd = dev(X), dev(s), dev(dY)
+    Wp, zp = eq.eqat_pack(dev(W), sd, dev(z), bits, g)
+    prep = eq.eqat_qlinear_prepare(Wp, zp, 128, bits, g, act_dtype=eq.F32)
+    Y = eq.eqat_qlinear_fwd_prepared(Xd, prep, sd, 48, bits, g)
+    out = eq.eqat_qlinear_bwd_prepared(Xd, prep, sd, dYd, 128, bits, g)
+    ref = eq.eqat_qlinear_bwd(Xd, Wp, sd, zp, dYd, 128, bits, g)
+    assert torch.equal(Y, eq.eqat_qlinear_fwd(Xd, Wp, sd, zp, bits, g))
+    assert torch.equal(out["dX"], ref["dX"]) and torch.equal(out["ds"], ref["ds"])
+
+
+# --------------------------------------------------------------------------- the integer state the GEMMs work from
+
+@pytest.mark.parametrize("wdt", [torch.bfloat16, torch.float32])
+@pytest.mark.parametrize("bits,g", [(2, 64), (3, 128), (4, 32), (2, -1), (3, 96)])
+def test_state_the_gemms_read_is_bit_exact(bits, g, wdt):
+    """Eq.(1)'s integers as the GEMM kernels see them (not the eqat_pack stream, which another instantiation of the
+    quantize kernel writes): codes, clamp plane and zbar left by eqat_fq_linear_fwd_keep, codes and zero points left by
+    eqat_qlinear_fwd_keep and by eqat_qlinear_prepare, each against oracle.quantize / the unpacked oracle stream."""
+    T, I, O = 40, 384, 88
+    qmax = 2 ** bits - 1
+    X, W, s, z, dY = make_case(("state", bits, g), T, I, O, bits, g, torch.bfloat16, wdt)
+    z[::3, 0] = -1.0
+    z[1::3, 0] = qmax + 2.0
+    c_ref, side = oracle.quantize(npf(W), s.numpy(), z.numpy(), bits, g)
+    zb_ref = np.clip(np.rint(z.numpy()), 0, qmax).astype(np.float32)
+    Xd, Wd, sd, zd = dev(X), dev(W), dev(s), dev(z)
+    d = eq.make_desc(T, I, O, bits, g, eq.BF16, eq._dt(Wd))
+    ws = eq.workspace(d, eq.OP_FQ_BWD, Xd.device)
+    ws.fill_(0xA5)
+    eq.eqat_fq_linear_fwd(Xd, Wd, sd, zd, bits, g, ws=ws, keep=True)
+    codes, clamped, zbar = eq.eqat_unpack_state(eq.STATE_FQ_KEPT, ws, O, I, bits, g, want_clamped=True)
+    assert np.array_equal(codes.cpu().numpy(), c_ref)
+    assert np.array_equal(clamped.cpu().numpy(), (side != 0).astype(np.uint8))
+    assert np.array_equal(zbar.cpu().numpy(), zb_ref)
+    Wp, zp = eq.eqat_pack(Wd, sd, zd, bits, g)
+    wsq = eq.workspace(d, eq.OP_Q_BWD, Xd.device)
+    wsq.fill_(0x5A)
+    eq.eqat_qlinear_fwd(Xd, Wp, sd, zp, bits, g, ws=wsq, keep=True)
+    prep = eq.eqat_qlinear_prepare(Wp, zp, I, bits, g)
+    for kind, state in ((eq.STATE_Q_KEPT, wsq), (eq.STATE_PREPARED, prep)):
+        codes, _, zbar = eq.eqat_unpack_state(kind, state, O, I, bits, g)
+        assert np.array_equal(codes.cpu().numpy(), c_ref), kind
+        assert np.array_equal(zbar.cpu().numpy(), zb_ref), kind
+
+
+@pytest.mark.parametrize("wdt", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("bits,g", [(2, 64), (3, 128), (4, 32)])
+def test_working_layout_codes_exact_near_rounding_ties(bits, g, wdt):
+    # as test_codes_exact_near_rounding_ties, for the instantiations of the quantize kernel that the Block-AP calls run
+    # (working layout, with and without the clamp plane); bf16 weights cannot sit a few ulp of binary32 from a tie, so
+    # there the step sizes are chosen such that w/s lands on and around the ties exactly
+    O, I = 64, 1024
+    G = I // g
+    qmax = 2 ** bits - 1
+    rng = np.random.default_rng(7 + bits)
+    z = np.full((O, G), float(qmax // 2), np.float32)
+    k = rng.integers(-(qmax // 2) - 1, qmax - qmax // 2 + 1, (O, I)) + 0.5
+    if wdt == torch.float32:
+        s = rng.uniform(0.001, 0.01, (O, G)).astype(np.float32)
+        W = (k * np.repeat(s, g, 1)).astype(np.float32)
+        W = (W.view(np.int32) + rng.integers(-2, 3, (O, I)).astype(np.int32)).view(np.float32)
+    else:
+        s = (2.0 ** rng.integers(-9, -5, (O, G))).astype(np.float32) * rng.choice(np.array([1.0, 3.0, 5.0], np.float32), (O, G))
+        W = torch.from_numpy((k * np.repeat(s, g, 1)).astype(np.float32)).bfloat16().float().numpy()
+    c_ref, side = oracle.quantize(W, s, z, bits, g)
+    Wd = dev(torch.from_numpy(W).to(wdt)); sd = dev(torch.from_numpy(s)); zd = dev(torch.from_numpy(z))
+    Xd = torch.zeros((8, I), dtype=torch.bfloat16, device="cuda")
+    d = eq.make_desc(8, I, O, bits, g, eq.BF16, eq._dt(Wd))
+    for op, keep in ((eq.OP_FQ_BWD, True), (eq.OP_FQ_FWD, False)):
+        ws = eq.workspace(d, op, Xd.device)
+        eq.eqat_fq_linear_fwd(Xd, Wd, sd, zd, bits, g, ws=ws, keep=keep)
+        if keep:
+            codes, clamped, _ = eq.eqat_unpack_state(eq.STATE_FQ_KEPT, ws, O, I, bits, g, want_clamped=True)
+            assert np.array_equal(clamped.cpu().numpy(), (side != 0).astype(np.uint8))
+        else:       # the forward-only workspace starts with the same code array
+            codes, _, _ = eq.eqat_unpack_state(eq.STATE_Q_KEPT, ws, O, I, bits, g)
+        assert np.array_equal(codes.cpu().numpy(), c_ref), (op, int((codes.cpu().numpy() != c_ref).sum()))
+
+
 @pytest.mark.parametrize("tag,T,I,O,bits,g,wdt", BF16_CASES)
 def test_e2e_qp_trained_z_bf16(tag, T, I, O, bits, g, wdt):
     X, W, s, z, dY = make_case(tag, T, I, O, bits, g, torch.bfloat16, wdt)

@@ -77,6 +77,27 @@ def test_fullsize_layer(case):
     assert np.array_equal(Wp.cpu().numpy(), Wp_ref), "packed codes differ"
     assert np.array_equal(zp.cpu().numpy(), zp_ref), "packed zero points differ"
 
+    # ... and the integer state the GEMM kernels themselves read, in full: Eq.(1)'s codes, which weights it clamped
+    # and the zero point of Eq.(2) as the Block-AP forward leaves them for its backward; the frozen codes and zero
+    # points as eqat_qlinear_prepare lays them out for E2E-QP
+    c_ref, side = oracle.quantize(Wn, s, z, bits, g)
+    d = eq.make_desc(T, I, O, bits, g, eq.BF16, eq._dt(Wd))
+    if "block_ap" in wl.phases:
+        ws = eq.workspace(d, eq.OP_FQ_BWD, Wd.device)
+        eq.eqat_fq_linear_fwd(Xd, Wd, sd, zd, bits, g, ws=ws, keep=True)
+        codes, clamped, zbar = eq.eqat_unpack_state(eq.STATE_FQ_KEPT, ws, O, I, bits, g, want_clamped=True)
+        assert np.array_equal(codes.cpu().numpy(), c_ref), "Block-AP working codes differ"
+        assert np.array_equal(clamped.cpu().numpy(), (side != 0).astype(np.uint8)), "clamp plane differs"
+        assert np.array_equal(zbar.cpu().numpy(), z), "zbar differs"
+        del ws, codes, clamped, zbar
+    if "e2e_qp" in wl.phases:
+        prep = eq.eqat_qlinear_prepare(Wp, zp, I, bits, g)
+        codes, _, zbar = eq.eqat_unpack_state(eq.STATE_PREPARED, prep, O, I, bits, g)
+        assert np.array_equal(codes.cpu().numpy(), c_ref), "prepared codes differ"
+        assert np.array_equal(zbar.cpu().numpy(), z), "prepared zero points differ"
+        del codes, zbar
+    del c_ref, side
+
     errs = {}
     if "block_ap" in wl.phases:
         Y = eq.eqat_fq_linear_fwd(Xd, Wd, sd, zd, bits, g)
@@ -95,7 +116,12 @@ def test_fullsize_layer(case):
     if "e2e_qp" in wl.phases:
         Yq = eq.eqat_qlinear_fwd(Xd, Wp, sd, zp, bits, g)
         outq = eq.eqat_qlinear_bwd(Xd, Wp, sd, zp, dYd, I, bits, g)
+        # the step as bench.py times it: on the prepared layer; bitwise the plain calls
+        Yp = eq.eqat_qlinear_fwd_prepared(Xd, prep, sd, O, bits, g)
+        outp = eq.eqat_qlinear_bwd_prepared(Xd, prep, sd, dYd, I, bits, g)
         torch.cuda.synchronize()
+        assert torch.equal(Yp, Yq) and torch.equal(outp["dX"], outq["dX"]) and torch.equal(outp["ds"], outq["ds"])
+        del Yp, outp
         errs["q.Y"] = relerr(npf(Yq[trows]), oracle.qlinear_fwd(Xs, Wp_ref, s, zp_ref, bits, g))
         errs["q.dX"] = relerr(npf(outq["dX"][trows]), oracle.qlinear_bwd(None, Wp_ref, s, zp_ref, dYs, I, bits, g, want=("dX",))["dX"])
         refq = oracle.qlinear_bwd(Xn_full, Wp_ref[orows], s[orows], zp_ref[orows], dY_cols, I, bits, g, want=("ds",))

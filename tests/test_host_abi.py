@@ -97,11 +97,12 @@ def test_packed_sizes():
 def test_workspace_sizes_are_modest_and_monotone():
     L = eq.lib()
     desc = d(T=4096, I=4096, O=4096)
-    w = [L.eqat_workspace_bytes(ctypes.byref(desc), op) for op in range(4)]
+    w = [L.eqat_workspace_bytes(ctypes.byref(desc), op) for op in range(6)]
     wbytes = 4096 * 4096 * 2
     assert 0 < w[eq.OP_FQ_FWD] < wbytes // 4          # 2-bit codes + (s, z) pairs, a fraction of W itself
     assert w[eq.OP_FQ_FWD] < w[eq.OP_FQ_BWD] < wbytes // 2
-    assert 0 < w[eq.OP_Q_FWD] <= w[eq.OP_Q_BWD] < wbytes // 4         # re-laid-out codes + (s, z) pairs
+    assert 0 < w[eq.OP_Q_FWD] <= w[eq.OP_Q_BWD] < wbytes // 4         # re-laid-out codes + zero points
+    assert w[eq.OP_QP_FWD] == w[eq.OP_QP_BWD] == 4096 * 64 * 8        # a prepared layer: only the (s, z) pairs
     assert L.eqat_workspace_bytes(ctypes.byref(desc), 9) == 0
     f32 = d(T=256, I=512, O=512, bits=4, group=128, act=eq.F32, w=eq.F32)
     assert L.eqat_workspace_bytes(ctypes.byref(f32), eq.OP_FQ_FWD) == 0
@@ -152,6 +153,31 @@ def test_null_alignment_and_workspace_errors_come_back_before_any_launch():
     assert L.eqat_qlinear_bwd_kept(r, P, P, P, P, P, P, P, P, wq_b - 1, None) == WORKSPACE
     assert L.eqat_qlinear_bwd_kept(r, None, P, P, P, P, None, P, P, wq_b, None) == NULL      # ds wanted, X missing
     assert L.eqat_qlinear_bwd_kept(r, P, P, P, P, P, None, None, P, wq_b, None) == OK        # nothing wanted
+    # the prepared-layer entry points
+    pb = L.eqat_prepared_bytes(r)
+    assert pb >= 64 * 128 * 2 // 8 + 64 * 2 * 4
+    assert L.eqat_prepared_bytes(ctypes.byref(d(bits=7))) == 0
+    assert L.eqat_qlinear_prepare(r, None, P, P, pb, None) == NULL
+    assert L.eqat_qlinear_prepare(r, P, P, None, pb, None) == NULL
+    assert L.eqat_qlinear_prepare(r, P, P, P, pb - 1, None) == WORKSPACE
+    assert L.eqat_qlinear_prepare(r, P, P, P + 16, pb, None) == ALIGN
+    wp_f, wp_b = L.eqat_workspace_bytes(r, eq.OP_QP_FWD), L.eqat_workspace_bytes(r, eq.OP_QP_BWD)
+    assert wp_f <= wp_b < wq_b
+    assert L.eqat_qlinear_fwd_prepared(r, P, None, P, None, P, P, 1 << 30, None) == NULL
+    assert L.eqat_qlinear_fwd_prepared(r, P, P, None, None, P, P, 1 << 30, None) == NULL
+    assert L.eqat_qlinear_fwd_prepared(r, P, P + 16, P, None, P, P, 1 << 30, None) == ALIGN
+    assert L.eqat_qlinear_bwd_prepared(r, None, P, P, None, P, None, P, None, P, 1 << 30, None) == NULL      # ds wanted, X missing
+    assert L.eqat_qlinear_bwd_prepared(r, P, P, P, None, P, None, None, None, P, 1 << 30, None) == OK        # nothing wanted
+    per_chan = d(group=-1, I=256)           # one group per row: the backward needs room for per-32-column partial sums
+    rp = ctypes.byref(per_chan)
+    need = L.eqat_workspace_bytes(rp, eq.OP_QP_BWD)
+    assert need > 0
+    assert L.eqat_qlinear_bwd_prepared(rp, P, P, P, None, P, P, P, None, P, need - 1, None) == WORKSPACE
+    # the test aid
+    assert L.eqat_unpack_state(r, 7, P, P, None, P, None) == SHAPE
+    assert L.eqat_unpack_state(r, eq.STATE_PREPARED, None, P, None, P, None) == NULL
+    assert L.eqat_unpack_state(r, eq.STATE_PREPARED, P, P, P, P, None) == NULL          # no clamp plane in a prepared layer
+    assert L.eqat_unpack_state(ctypes.byref(d(act=eq.F32)), eq.STATE_FQ_KEPT, P, P, None, P, None) == DTYPE
     # descriptor errors win over everything else
     bad = d(bits=9)
     assert L.eqat_fq_linear_fwd(ctypes.byref(bad), None, None, None, None, None, None, 0, None) == BITS
