@@ -206,8 +206,9 @@ def main():
     kernels = kernel_table(prof, flop_per_launch, peaks)
     if "quantize" in prof:
         # W and (s, z) in; codes, clamp bit-plane and (s, zbar) pairs out
-        qb = sum_io / len(layers) * (2 + 8.0 / g + bits / 8 + 1.0 / 8 + 8.0 / g)
-        gbs = qb / (prof["quantize"][0] / prof["quantize"][1] * 1e-3) / 1e9
+        # (one launch per step over all linears of the block)
+        qb = sum_io * (2 + 8.0 / g + bits / 8 + 1.0 / 8 + 8.0 / g)
+        gbs = qb / (prof["quantize"][0] / args.steps * 1e-3) / 1e9
         kernels["quantize"].update({"approx_gbs": round(gbs, 1), "frac_of_hbm_peak": round(gbs / PEAK_HBM_GBS, 4),
                                     "frac_of_measured_copy": round(gbs / peaks["copy_kernel_gbs"], 4) if peaks.get("copy_kernel_gbs") else None})
 
@@ -272,11 +273,23 @@ def build_layers(torch, eq, synth, wl, dev, w_dtype=None):
     return layers
 
 
-def run_block_ap_step(eq, layers, bits, g):
-    # as a training step runs them: the forward keeps its Eq.(1) results in the workspace for the backward of the same
-    # (W, s, z), so every linear is quantized once per step
+def block_batch(eq, layers, bits, g, T):
+    """Pointer arrays for the one-launch passes over all linears of the block."""
+    descs = [eq.make_desc(T, L["I"], L["O"], bits, g, eq._dt(L["X"]), eq._dt(L["W"])) for L in layers]
+    return eq.Batch(descs, W=[L["W"] for L in layers], s=[L["s"] for L in layers], z=[L["z"] for L in layers],
+                    ws=[L["ws_b"] for L in layers])
+
+
+def run_block_ap_step(eq, layers, bits, g, batch=None):
+    # as a training step runs them: Eq.(1) of all linears of the block in ONE launch (W, s, z do not change inside a
+    # step), kept in each linear's workspace for its forward and its backward
+    if batch is None:
+        batch = layers[0].get("batch")
+        if batch is None:
+            batch = layers[0]["batch"] = block_batch(eq, layers, bits, g, layers[0]["X"].shape[0])
+    eq.eqat_fq_quantize_batched(batch)
     for L in layers:
-        eq.eqat_fq_linear_fwd(L["X"], L["W"], L["s"], L["z"], bits, g, Y=L["Y"], ws=L["ws_b"], keep=True)
+        eq.eqat_fq_linear_fwd(L["X"], L["W"], L["s"], L["z"], bits, g, Y=L["Y"], ws=L["ws_b"], kept=True)
         eq.eqat_fq_linear_bwd(L["X"], L["W"], L["s"], L["z"], L["dY"], bits, g, out=L["out"], ws=L["ws_b"], kept=True)
 
 
@@ -339,9 +352,12 @@ def config_rows(torch, eq, synth, dev, args, peaks, name, phases=("block_ap", "e
         out["block_ap"] = step_row(torch, eq, lambda: run_block_ap_step(eq, layers, bits, g), 6.0 * T * sum_io, T, fpl, args, peaks)
     packed = pack_block(torch, eq, layers, bits, g, T, dev)
     if "eqat_pack" in phases:
+        pb = eq.Batch(layers[0]["batch"].descs if "batch" in layers[0] else block_batch(eq, layers, bits, g, T).descs,
+                      W=[L["W"] for L in layers], s=[L["s"] for L in layers], z=[L["z"] for L in layers],
+                      Wpacked=[P["Wp"] for P in packed], zpacked=[P["zp"] for P in packed])
+
         def pack_all():
-            for L, P in zip(layers, packed):
-                eq.eqat_pack(L["W"], L["s"], L["z"], bits, g, Wpacked=P["Wp"], zpacked=P["zp"])
+            eq.eqat_pack_batched(pb)
         out["eqat_pack"] = hbm_row(torch, eq, pack_all, sum_io * (2 + 8.0 / g + bits / 8.0 + bits / (8.0 * g)), args, peaks)
     if "e2e_qp" in phases:
         out["e2e_qp"] = step_row(torch, eq, lambda: run_e2e_step(eq, layers, packed, bits, g), 6.0 * T * sum_io, T, fpl, args, peaks)
@@ -369,20 +385,29 @@ def measure_other_rows(torch, eq, layers, bits, g, adt, dev, args, peaks):
                                                   fl, T2, fpl, args, peaks)
     wbytes = 2 if adt == torch.bfloat16 else 4
 
-    def pack_all():
-        for L, P in zip(layers, packed):
-            eq.eqat_pack(L["W"], L["s"], L["z"], bits, g, Wpacked=P["Wp"], zpacked=P["zp"])
+    descs = block_batch(eq, layers, bits, g, T2).descs
+    pb = eq.Batch(descs, W=[L["W"] for L in layers], s=[L["s"] for L in layers], z=[L["z"] for L in layers],
+                  Wpacked=[P["Wp"] for P in packed], zpacked=[P["zp"] for P in packed])
+
+    def pack_all():         # the seven matrices of the block in one launch
+        eq.eqat_pack_batched(pb)
 
     b = sum_io * (wbytes + 8.0 / g + bits / 8.0 + bits / (8.0 * g))
     rows["eqat_pack"] = hbm_row(torch, eq, pack_all, b, args, peaks)
     sz = [(torch.empty_like(L["s"]), torch.empty_like(L["z"])) for L in layers]
+    ib = eq.Batch(descs, W=[L["W"] for L in layers], s=[a for a, _ in sz], z=[c for _, c in sz])
 
     def init_all():
-        for L, (s, z) in zip(layers, sz):
-            eq.eqat_init_minmax(L["W"], bits, g, s=s, z=z)
+        eq.eqat_init_minmax_batched(ib)
 
     b = sum_io * (wbytes + 8.0 / g)
     rows["eqat_init_minmax"] = hbm_row(torch, eq, init_all, b, args, peaks)
+
+    def pack_one_by_one():
+        for L, P in zip(layers, packed):
+            eq.eqat_pack(L["W"], L["s"], L["z"], bits, g, Wpacked=P["Wp"], zpacked=P["zp"])
+
+    rows["eqat_pack_one_launch_per_matrix"] = hbm_row(torch, eq, pack_one_by_one, sum_io * (wbytes + 8.0 / g + bits / 8.0 + bits / (8.0 * g)), args, peaks)
 
     # The 7B matrices are 34-90 MB: each launch lasts 10-25 us, a good part of it ramp-up and the timing events
     # themselves.  The same two passes on the largest matrix of the 70B block (gate/up, 28672 x 8192 = 470 MB, two

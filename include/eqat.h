@@ -136,6 +136,35 @@ eqat_status eqat_fq_linear_bwd_kept(const eqat_desc *d, const void *X, const voi
                                     void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * The forward of the pair above from kept state: `ws` holds what eqat_fq_linear_fwd_keep or eqat_fq_quantize_batched
+ * left for the same descriptor, W, s and z (not checked), and Eq.(1) is not run again.  Bitwise eqat_fq_linear_fwd.
+ */
+eqat_status eqat_fq_linear_fwd_kept(const eqat_desc *d, const void *X, const void *W, const float *s,
+                                    const float *z, void *Y, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Several matrices in ONE launch.  The linears of a decoder block are a few tens of megabytes each; the memory-bound
+ * passes over them (min/max, Eq.(1), packing) last 10-25 microseconds apiece when launched one by one, a good part of it
+ * filling and draining the chip.  n: 1 .. EQAT_MAX_BATCH; descs: n descriptors (host); every other argument: a HOST
+ * array of n device pointers (or sizes), entry i belonging to descs[i].  All descriptors must agree in bits
+ * (EQAT_ERR_BITS) and in the dtypes (EQAT_ERR_DTYPE); shapes and group sizes may differ.  Results are bitwise those of
+ * n single calls.
+ *   eqat_init_minmax_batched   as eqat_init_minmax.
+ *   eqat_pack_batched          as eqat_pack.
+ *   eqat_fq_quantize_batched   Eq.(1) of n linears before their Block-AP forward and backward: leaves every ws[i]
+ *                              (EQAT_OP_FQ_BWD size for descs[i], tokens included) as eqat_fq_linear_fwd_keep would, for
+ *                              eqat_fq_linear_fwd_kept / eqat_fq_linear_bwd_kept.  With fp32 activations nothing is kept
+ *                              and nothing is launched.
+ */
+#define EQAT_MAX_BATCH 8
+eqat_status eqat_init_minmax_batched(int n, const eqat_desc *descs, const void *const *W, float *const *s,
+                                     float *const *z, void *stream);
+eqat_status eqat_pack_batched(int n, const eqat_desc *descs, const void *const *W, const float *const *s,
+                              const float *const *z, uint8_t *const *Wpacked, uint8_t *const *zpacked, void *stream);
+eqat_status eqat_fq_quantize_batched(int n, const eqat_desc *descs, const void *const *W, const float *const *s,
+                                     const float *const *z, void *const *ws, const size_t *ws_bytes, void *stream);
+
+/*
  * Freeze after Block-AP (Sec. 3.2 last paragraph; App. E): W_q and z at N bits.
  * Layout (the paper fixes none): each row is a little-endian bit stream, code i
  * of the row in bits [i*N,(i+1)*N), stored as bytes, least significant first.

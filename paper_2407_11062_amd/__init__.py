@@ -25,7 +25,8 @@ STATUS_NAMES = ["EQAT_OK", "EQAT_ERR_NULL", "EQAT_ERR_SHAPE", "EQAT_ERR_BITS", "
 
 EXPORTS = ["eqat_status_string", "eqat_validate_desc", "eqat_packed_w_bytes", "eqat_packed_z_bytes",
            "eqat_workspace_bytes", "eqat_init_minmax", "eqat_fq_linear_fwd", "eqat_fq_linear_bwd",
-           "eqat_fq_linear_fwd_keep", "eqat_fq_linear_bwd_kept", "eqat_pack",
+           "eqat_fq_linear_fwd_keep", "eqat_fq_linear_bwd_kept", "eqat_fq_linear_fwd_kept", "eqat_pack",
+           "eqat_init_minmax_batched", "eqat_pack_batched", "eqat_fq_quantize_batched",
            "eqat_unpack", "eqat_qlinear_fwd", "eqat_qlinear_bwd", "eqat_qlinear_fwd_keep", "eqat_qlinear_bwd_kept",
            "eqat_qlinear_fwd_z", "eqat_qlinear_bwd_z", "eqat_prepared_bytes", "eqat_qlinear_prepare",
            "eqat_qlinear_fwd_prepared", "eqat_qlinear_bwd_prepared", "eqat_unpack_state",
@@ -76,6 +77,10 @@ def lib():
         L.eqat_fq_linear_bwd.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.eqat_fq_linear_fwd_keep.argtypes = L.eqat_fq_linear_fwd.argtypes
         L.eqat_fq_linear_bwd_kept.argtypes = L.eqat_fq_linear_bwd.argtypes
+        L.eqat_fq_linear_fwd_kept.argtypes = L.eqat_fq_linear_fwd.argtypes
+        L.eqat_init_minmax_batched.argtypes = [ctypes.c_int, dp, vp, vp, vp, vp]
+        L.eqat_pack_batched.argtypes = [ctypes.c_int, dp, vp, vp, vp, vp, vp, vp]
+        L.eqat_fq_quantize_batched.argtypes = [ctypes.c_int, dp, vp, vp, vp, vp, vp, vp]
         L.eqat_pack.argtypes = [dp, vp, vp, vp, vp, vp, vp]
         L.eqat_unpack.argtypes = [dp, vp, vp, vp, vp, vp]
         L.eqat_qlinear_fwd.argtypes = [dp, vp, vp, vp, vp, vp, vp, sz, vp]
@@ -152,16 +157,46 @@ def eqat_init_minmax(W, bits, group, s=None, z=None):
     return s, z
 
 
-def eqat_fq_linear_fwd(X, W, s, z, bits, group, Y=None, ws=None, keep=False):
-    """keep=True: `ws` (EQAT_OP_FQ_BWD size, must then be given) is left holding what eqat_fq_linear_bwd(kept=True) needs."""
+class Batch:
+    """Host arrays of device pointers (and the descriptors) for the *_batched entry points; build once, call often."""
+
+    def __init__(self, descs, **tensor_lists):
+        self.n = len(descs)
+        self.descs = (Desc * self.n)(*descs)
+        self.keep = tensor_lists                     # the tensors must outlive the pointer arrays
+        self.ptr = {k: (ctypes.c_void_p * self.n)(*[t.data_ptr() for t in v]) for k, v in tensor_lists.items()}
+        if "ws" in tensor_lists:
+            self.ws_bytes = (ctypes.c_size_t * self.n)(*[t.numel() for t in tensor_lists["ws"]])
+
+
+def eqat_init_minmax_batched(b: Batch):
+    """b: Batch(descs, W=[...], s=[...], z=[...])"""
+    _check("eqat_init_minmax_batched", lib().eqat_init_minmax_batched(b.n, b.descs, b.ptr["W"], b.ptr["s"], b.ptr["z"], _stream()))
+
+
+def eqat_pack_batched(b: Batch):
+    """b: Batch(descs, W=, s=, z=, Wpacked=, zpacked=)"""
+    _check("eqat_pack_batched", lib().eqat_pack_batched(b.n, b.descs, b.ptr["W"], b.ptr["s"], b.ptr["z"], b.ptr["Wpacked"],
+                                                        b.ptr["zpacked"], _stream()))
+
+
+def eqat_fq_quantize_batched(b: Batch):
+    """b: Batch(descs, W=, s=, z=, ws=): Eq.(1) of every linear in one launch, kept in its workspace (EQAT_OP_FQ_BWD size)."""
+    _check("eqat_fq_quantize_batched", lib().eqat_fq_quantize_batched(b.n, b.descs, b.ptr["W"], b.ptr["s"], b.ptr["z"],
+                                                                      b.ptr["ws"], b.ws_bytes, _stream()))
+
+
+def eqat_fq_linear_fwd(X, W, s, z, bits, group, Y=None, ws=None, keep=False, kept=False):
+    """keep=True: `ws` (EQAT_OP_FQ_BWD size, must then be given) is left holding what eqat_fq_linear_bwd(kept=True) needs.
+    kept=True: `ws` already holds that (from keep=True or eqat_fq_quantize_batched) and Eq.(1) is not run again."""
     T, I = X.shape
     O = W.shape[0]
     d = make_desc(T, I, O, bits, group, _dt(X), _dt(W))
     Y = torch.empty((T, O), dtype=X.dtype, device=X.device) if Y is None else Y
-    if keep and ws is None:
-        raise ValueError("keep=True needs the caller's workspace (it is the thing that is kept)")
+    if (keep or kept) and ws is None:
+        raise ValueError("keep / kept need the caller's workspace (it is the thing that is kept)")
     ws = workspace(d, OP_FQ_FWD, X.device) if ws is None else ws
-    name = "eqat_fq_linear_fwd_keep" if keep else "eqat_fq_linear_fwd"
+    name = "eqat_fq_linear_fwd_kept" if kept else "eqat_fq_linear_fwd_keep" if keep else "eqat_fq_linear_fwd"
     _check(name, getattr(lib(), name)(ctypes.byref(d), _p(X), _p(W), _p(s), _p(z), _p(Y), _p(ws), ws.numel(), _stream()))
     return Y
 

@@ -259,7 +259,7 @@ eqat_status eqat_unpack(const eqat_desc *d, const uint8_t *Wpacked, const uint8_
 // keep: the workspace has the layout of the backward pass and is left holding what Eq.(1) produced (codes, clamp
 // bit-plane, (s, zbar) pairs), so that a backward call on the same (W, s, z) need not run Eq.(1) again.
 static eqat_status fq_fwd_any(const eqat_desc *d, const void *X, const void *W, const float *s, const float *z, void *Y,
-                              void *ws, size_t ws_bytes, void *stream, bool keep)
+                              void *ws, size_t ws_bytes, void *stream, bool keep, bool kept = false)
 {
     Problem p;
     if (eqat_status e = check_desc(d, true, &p)) return e;
@@ -273,7 +273,7 @@ static eqat_status fq_fwd_any(const eqat_desc *d, const void *X, const void *W, 
     char *w8 = (char *)ws;
     if (p.act_bf16) {
         const eqat::SkScratch sk = sk_of(l, w8);
-        { ProfScope ps(eqat::PK_QUANTIZE, st); eqat::launch_quantize(p, W, s, z, w8 + l.codes, keep ? w8 + l.clamp : nullptr, w8 + l.sz, nullptr, false, sk.counters, (uint32_t)(l.sk_ctr_bytes / 4), st); }
+        if (!kept) { ProfScope ps(eqat::PK_QUANTIZE, st); eqat::launch_quantize(p, W, s, z, w8 + l.codes, keep ? w8 + l.clamp : nullptr, w8 + l.sz, nullptr, false, sk.counters, (uint32_t)(l.sk_ctr_bytes / 4), st); }
         if (p.T > 0) { ProfScope ps(eqat::PK_GEMM_FWD, st); eqat::launch_mfma_fwd(p, X, w8 + l.codes, w8 + l.sz, Y, sk, st); }
     } else {
         { ProfScope ps(eqat::PK_F32, st); eqat::launch_f32_fwd(p, false, X, W, s, z, Y, st); }
@@ -298,6 +298,12 @@ eqat_status eqat_fq_linear_fwd_keep(const eqat_desc *d, const void *X, const voi
                                     void *Y, void *ws, size_t ws_bytes, void *stream)
 {
     return fq_fwd_any(d, X, W, s, z, Y, ws, ws_bytes, stream, true);
+}
+
+eqat_status eqat_fq_linear_fwd_kept(const eqat_desc *d, const void *X, const void *W, const float *s, const float *z,
+                                    void *Y, void *ws, size_t ws_bytes, void *stream)
+{
+    return fq_fwd_any(d, X, W, s, z, Y, ws, ws_bytes, stream, true, true);
 }
 
 eqat_status eqat_fq_linear_bwd(const eqat_desc *d, const void *X, const void *W, const float *s, const float *z,
@@ -583,6 +589,76 @@ eqat_status eqat_qlinear_bwd_z(const eqat_desc *d, const void *X, const uint8_t 
                                size_t ws_bytes, void *stream)
 {
     return qlinear_bwd_any(d, X, Wpacked, s, nullptr, z, dY, dX, ds, dz, ws, ws_bytes, stream);
+}
+
+// ---- several matrices in one launch --------------------------------------------------------------------------------
+// All descriptors of a batch must agree in bits and weight dtype (they select the kernel); everything else may differ.
+static eqat_status check_batch(int n, const eqat_desc *descs, Problem *ps)
+{
+    if (descs == nullptr) return EQAT_ERR_NULL;
+    if (n < 1 || n > EQAT_MAX_BATCH) return EQAT_ERR_SHAPE;
+    for (int i = 0; i < n; ++i) {
+        if (eqat_status e = check_desc(&descs[i], false, &ps[i])) return e;
+        if (descs[i].bits != descs[0].bits) return EQAT_ERR_BITS;
+        if (descs[i].w_dtype != descs[0].w_dtype || descs[i].act_dtype != descs[0].act_dtype) return EQAT_ERR_DTYPE;
+    }
+    return EQAT_OK;
+}
+
+eqat_status eqat_init_minmax_batched(int n, const eqat_desc *descs, const void *const *W, float *const *s, float *const *z,
+                                     void *stream)
+{
+    Problem ps[EQAT_MAX_BATCH];
+    if (eqat_status e = check_batch(n, descs, ps)) return e;
+    if (W == nullptr || s == nullptr || z == nullptr) return EQAT_ERR_NULL;
+    eqat::InitJob jobs[EQAT_MAX_BATCH];
+    for (int i = 0; i < n; ++i) {
+        EQAT_REQUIRE(W[i]); EQAT_REQUIRE(s[i]); EQAT_REQUIRE(z[i]);
+        EQAT_ALIGNED(W[i]); EQAT_ALIGNED(s[i]); EQAT_ALIGNED(z[i]);
+        jobs[i] = eqat::InitJob{ps[i], W[i], s[i], z[i]};
+    }
+    { ProfScope pr(eqat::PK_INIT_MINMAX, (hipStream_t)stream); eqat::launch_init_minmax_batch(jobs, n, (hipStream_t)stream); }
+    return launch_status();
+}
+
+eqat_status eqat_pack_batched(int n, const eqat_desc *descs, const void *const *W, const float *const *s,
+                              const float *const *z, uint8_t *const *Wpacked, uint8_t *const *zpacked, void *stream)
+{
+    Problem ps[EQAT_MAX_BATCH];
+    if (eqat_status e = check_batch(n, descs, ps)) return e;
+    if (W == nullptr || s == nullptr || z == nullptr || Wpacked == nullptr || zpacked == nullptr) return EQAT_ERR_NULL;
+    eqat::QuantizeJob jobs[EQAT_MAX_BATCH];
+    for (int i = 0; i < n; ++i) {
+        EQAT_REQUIRE(W[i]); EQAT_REQUIRE(s[i]); EQAT_REQUIRE(z[i]); EQAT_REQUIRE(Wpacked[i]); EQAT_REQUIRE(zpacked[i]);
+        EQAT_ALIGNED(W[i]); EQAT_ALIGNED(s[i]); EQAT_ALIGNED(z[i]); EQAT_ALIGNED(Wpacked[i]); EQAT_ALIGNED(zpacked[i]);
+        jobs[i] = eqat::QuantizeJob{ps[i], W[i], s[i], z[i], Wpacked[i], nullptr, nullptr, zpacked[i], nullptr, 0};
+    }
+    { ProfScope pr(eqat::PK_QUANTIZE, (hipStream_t)stream); eqat::launch_quantize_batch(jobs, n, true, (hipStream_t)stream); }
+    return launch_status();
+}
+
+eqat_status eqat_fq_quantize_batched(int n, const eqat_desc *descs, const void *const *W, const float *const *s,
+                                     const float *const *z, void *const *ws, const size_t *ws_bytes, void *stream)
+{
+    Problem ps[EQAT_MAX_BATCH];
+    if (eqat_status e = check_batch(n, descs, ps)) return e;
+    if (W == nullptr || s == nullptr || z == nullptr || ws == nullptr || ws_bytes == nullptr) return EQAT_ERR_NULL;
+    eqat::QuantizeJob jobs[EQAT_MAX_BATCH];
+    for (int i = 0; i < n; ++i) {
+        Problem p;                                        // with the tokens, which the workspace layout may depend on
+        if (eqat_status e = check_desc(&descs[i], true, &p)) return e;
+        EQAT_REQUIRE(W[i]); EQAT_REQUIRE(s[i]); EQAT_REQUIRE(z[i]);
+        EQAT_ALIGNED(W[i]); EQAT_ALIGNED(s[i]); EQAT_ALIGNED(z[i]);
+        const WsLayout l = ws_layout(p, EQAT_OP_FQ_BWD);
+        if (eqat_status e = check_ws(l, ws[i], ws_bytes[i])) return e;
+        char *w8 = (char *)ws[i];
+        const eqat::SkScratch sk = sk_of(l, w8);
+        jobs[i] = eqat::QuantizeJob{p, W[i], s[i], z[i], w8 + l.codes, w8 + l.clamp, w8 + l.sz, nullptr, sk.counters,
+                                    (uint32_t)(l.sk_ctr_bytes / 4)};
+    }
+    if (!ps[0].act_bf16) return EQAT_OK;                  // the fp32 path keeps nothing
+    { ProfScope pr(eqat::PK_QUANTIZE, (hipStream_t)stream); eqat::launch_quantize_batch(jobs, n, false, (hipStream_t)stream); }
+    return launch_status();
 }
 
 size_t eqat_recon_loss_workspace_bytes(void) { return eqat::recon_loss_ws_bytes(); }

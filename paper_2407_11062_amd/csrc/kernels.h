@@ -4,6 +4,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include "../../include/eqat.h"
+
 namespace eqat {
 
 struct Problem {
@@ -19,6 +21,15 @@ struct Problem {
 // zero_words (may be NULL): n_zero 32-bit words that the launch also clears (the arrival counters of the GEMMs).
 void launch_quantize(const Problem &p, const void *W, const float *s, const float *z, void *codes, void *clampbits,
                      void *sz, void *zpacked, bool for_pack, uint32_t *zero_words, uint32_t n_zero, hipStream_t st);
+// The same for up to kMaxBatch matrices in ONE launch; all jobs share bits, the weight dtype, and whether a clamp plane
+// is written (the first job decides).
+constexpr int kMaxBatch = EQAT_MAX_BATCH;
+struct QuantizeJob {
+    Problem p; const void *W; const float *s, *z; void *codes, *clampbits, *sz, *zpacked; uint32_t *zero_words; uint32_t n_zero;
+};
+void launch_quantize_batch(const QuantizeJob *jobs, int n, bool for_pack, hipStream_t st);
+struct InitJob { Problem p; const void *W; float *s, *z; };
+void launch_init_minmax_batch(const InitJob *jobs, int n, hipStream_t st);       // all jobs share bits and the weight dtype
 inline size_t work_code_bytes(const Problem &p) { return (size_t)p.O * p.I / (p.bits == 2 ? 4 : 2); }
 // One launch before the GEMMs of an E2E-QP call: dense stream -> working layout (packed == NULL: skipped) and the
 // (s, z) pairs (sz == NULL: skipped), z taken from the packed N-bit zero points or from a float array (exactly one of

@@ -83,26 +83,42 @@ struct QuantizeArgs {
     uint32_t *zero_words; uint32_t n_zero;
 };
 
-__device__ __forceinline__ void clear_words(uint32_t *__restrict__ w, uint32_t n)
+// block / nblocks: this workgroup's number among those that share the job
+__device__ __forceinline__ void clear_words(uint32_t *__restrict__ w, uint32_t n, uint32_t block, uint32_t nblocks)
 {
-    for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) w[i] = 0u;
+    for (uint32_t i = block * blockDim.x + threadIdx.x; i < n; i += nblocks * blockDim.x) w[i] = 0u;
+}
+
+// Up to kMaxBatch matrices in one launch (the linears of a decoder block are 34-90 MB each at 7B size: alone, each would
+// be a 10-25 us launch that spends a good part of its time filling and draining the chip).  Workgroups
+// [first[i], first[i + 1]) work on matrix i.
+struct QuantizeBatch { QuantizeArgs a[kMaxBatch]; uint32_t first[kMaxBatch + 1]; };
+__device__ __forceinline__ int batch_slot(const uint32_t (&first)[kMaxBatch + 1], uint32_t block)
+{
+    int i = 0;
+#pragma unroll
+    for (int k = 1; k < kMaxBatch; ++k) i += block >= first[k] ? 1 : 0;      // first[k] of unused slots: the grid size
+    return i;
 }
 
 constexpr int kQuantUnroll = 4;     // chunks per thread: 64 B (bf16) / 128 B (fp32) of W in flight per lane
 
 template <typename WT, int BITS, bool CLAMPBITS, bool WORK>
-__global__ __launch_bounds__(256) void k_quantize(const QuantizeArgs a)
+__global__ __launch_bounds__(256) void k_quantize(const QuantizeBatch batch)
 {
     constexpr int U = kQuantUnroll;
-    if (a.zero_words != nullptr) clear_words(a.zero_words, a.n_zero);
-    if (blockIdx.x >= a.n_quant_blocks) {
-        const uint32_t t = (blockIdx.x - a.n_quant_blocks) * 256u + threadIdx.x;
+    const int slot = batch_slot(batch.first, blockIdx.x);
+    const QuantizeArgs &a = batch.a[slot];
+    const uint32_t block = blockIdx.x - batch.first[slot];
+    if (a.zero_words != nullptr) clear_words(a.zero_words, a.n_zero, block, batch.first[slot + 1] - batch.first[slot]);
+    if (block >= a.n_quant_blocks) {
+        const uint32_t t = (block - a.n_quant_blocks) * 256u + threadIdx.x;
         if (t < a.n_zwords) pack_z_word<BITS>(a.z, a.zpacked, t, a.G, a.row_words);
         return;
     }
     const WT *__restrict__ W = reinterpret_cast<const WT *>(a.W);
     constexpr float qmax = (float)((1 << BITS) - 1);
-    const uint32_t c0 = blockIdx.x * (256u * U) + threadIdx.x;   // chunk index; n_chunks % 4 == 0 so quads stay whole
+    const uint32_t c0 = block * (256u * U) + threadIdx.x;   // chunk index; n_chunks % 4 == 0 so quads stay whole
     // all loads of the thread's U chunks first: the pass lives on bytes in flight
     Chunk8<WT> ch[U];
     uint32_t gi[U];
@@ -235,7 +251,7 @@ __global__ __launch_bounds__(256) void k_e2e_prepare(const uint32_t *__restrict_
                                                      float *__restrict__ zb_out, uint32_t n_groups, uint32_t G,
                                                      uint32_t row_words, uint32_t *__restrict__ zero_words, uint32_t n_zero)
 {
-    if (zero_words != nullptr) clear_words(zero_words, n_zero);
+    if (zero_words != nullptr) clear_words(zero_words, n_zero, blockIdx.x, gridDim.x);
     if (blockIdx.x < n_repack_blocks) {
         const uint32_t t = blockIdx.x * 256u + threadIdx.x;
         if (t < n_segs) repack_segment<BITS>(packed, work, t);
@@ -298,12 +314,22 @@ __global__ __launch_bounds__(256) void k_unpack_work(const uint32_t *__restrict_
 // ---------------------------------------------------------------------------------------------
 // min/max initialisation.  LPG = lanes per group (g/8), a power of two <= 64: one lane reduces its 8
 // weights, an xor butterfly reduces the group.
+struct InitBatch {
+    const void *W[kMaxBatch]; float *s[kMaxBatch], *z[kMaxBatch];
+    uint32_t n[kMaxBatch];                 // chunks of 8 weights (small kernel) / groups (wave kernel)
+    uint32_t g[kMaxBatch];                 // group size (wave kernel)
+    uint32_t first[kMaxBatch + 1];
+};
+
 template <typename WT, int LPG>
-__global__ __launch_bounds__(256) void k_init_minmax_small(const WT *__restrict__ W, float *__restrict__ s,
-                                                           float *__restrict__ z, uint32_t n_chunks, float qmax)
+__global__ __launch_bounds__(256) void k_init_minmax_small(const InitBatch b, float qmax)
 {
     constexpr int U = kQuantUnroll;
-    const uint32_t c0 = blockIdx.x * (256u * U) + threadIdx.x;
+    const int slot = batch_slot(b.first, blockIdx.x);
+    const WT *__restrict__ W = reinterpret_cast<const WT *>(b.W[slot]);
+    float *__restrict__ s = b.s[slot], *__restrict__ z = b.z[slot];
+    const uint32_t n_chunks = b.n[slot];
+    const uint32_t c0 = (blockIdx.x - b.first[slot]) * (256u * U) + threadIdx.x;
     // n_chunks % LPG == 0 and 256 % LPG == 0: a group never straddles the end of the array or of a 256-chunk slice
     Chunk8<WT> ch[U];
 #pragma unroll
@@ -335,10 +361,13 @@ __global__ __launch_bounds__(256) void k_init_minmax_small(const WT *__restrict_
 }
 // Any other group size: one wavefront per group.
 template <typename WT>
-__global__ __launch_bounds__(256) void k_init_minmax_wave(const WT *__restrict__ W, float *__restrict__ s,
-                                                          float *__restrict__ z, uint32_t n_groups, uint32_t g, float qmax)
+__global__ __launch_bounds__(256) void k_init_minmax_wave(const InitBatch b, float qmax)
 {
-    const uint32_t grp = blockIdx.x * 4u + (threadIdx.x >> 6);
+    const int slot = batch_slot(b.first, blockIdx.x);
+    const WT *__restrict__ W = reinterpret_cast<const WT *>(b.W[slot]);
+    float *__restrict__ s = b.s[slot], *__restrict__ z = b.z[slot];
+    const uint32_t n_groups = b.n[slot], g = b.g[slot];
+    const uint32_t grp = (blockIdx.x - b.first[slot]) * 4u + (threadIdx.x >> 6);
     if (grp >= n_groups) return;
     const uint32_t lane = threadIdx.x & 63u;
     const WT *base = W + (size_t)grp * g;
@@ -388,32 +417,52 @@ static inline int pow2_shift(int64_t v)
     return -1;
 }
 
-template <typename WT, int BITS>
-static void quantize_t(const Problem &p, const void *W, const float *s, const float *z, void *codes, void *clampbits,
-                       void *sz, void *zpacked, bool for_pack, uint32_t *zero_words, uint32_t n_zero, hipStream_t st)
+static QuantizeArgs quantize_args(const QuantizeJob &j)
 {
+    const Problem &p = j.p;
     QuantizeArgs a{};
-    a.zero_words = zero_words; a.n_zero = n_zero;
-    a.W = W; a.s = s; a.z = z; a.codes = (uint32_t *)codes; a.clampbits = (uint8_t *)clampbits; a.sz = (floatx2 *)sz;
+    a.zero_words = j.zero_words; a.n_zero = j.n_zero;
+    a.W = j.W; a.s = j.s; a.z = j.z; a.codes = (uint32_t *)j.codes; a.clampbits = (uint8_t *)j.clampbits; a.sz = (floatx2 *)j.sz;
     a.n_chunks = (uint32_t)((size_t)p.O * p.I / 8); a.g = (uint32_t)p.g; a.g_shift = pow2_shift(p.g);
     a.n_quant_blocks = blocks_for(a.n_chunks, 256 * kQuantUnroll);
-    a.zpacked = (uint32_t *)zpacked; a.G = (uint32_t)p.G; a.row_words = (uint32_t)((p.G * p.bits + 31) / 32);
-    a.n_zwords = zpacked != nullptr ? (uint32_t)p.O * a.row_words : 0u;
-    const dim3 grid(a.n_quant_blocks + blocks_for(a.n_zwords)), block(256);
+    a.zpacked = (uint32_t *)j.zpacked; a.G = (uint32_t)p.G; a.row_words = (uint32_t)((p.G * p.bits + 31) / 32);
+    a.n_zwords = j.zpacked != nullptr ? (uint32_t)p.O * a.row_words : 0u;
+    return a;
+}
+
+template <typename WT, int BITS>
+static void quantize_t(const QuantizeJob *jobs, int n, bool for_pack, hipStream_t st)
+{
+    QuantizeBatch b{};
+    uint32_t first = 0;
+    for (int i = 0; i < n; ++i) {
+        b.a[i] = quantize_args(jobs[i]);
+        b.first[i] = first;
+        first += b.a[i].n_quant_blocks + blocks_for(b.a[i].n_zwords);
+    }
+    for (int i = n; i <= kMaxBatch; ++i) b.first[i] = first;
+    const dim3 grid(first), block(256);
     // eqat_pack: dense stream, no clamp plane;
     // the quantize pass of the Block-AP calls: working layout, clamp plane for the backward
-    if (for_pack) k_quantize<WT, BITS, false, false><<<grid, block, 0, st>>>(a);
-    else if (clampbits != nullptr) k_quantize<WT, BITS, true, true><<<grid, block, 0, st>>>(a);
-    else k_quantize<WT, BITS, false, true><<<grid, block, 0, st>>>(a);
+    if (for_pack) k_quantize<WT, BITS, false, false><<<grid, block, 0, st>>>(b);
+    else if (jobs[0].clampbits != nullptr) k_quantize<WT, BITS, true, true><<<grid, block, 0, st>>>(b);
+    else k_quantize<WT, BITS, false, true><<<grid, block, 0, st>>>(b);
+}
+
+void launch_quantize_batch(const QuantizeJob *jobs, int n, bool for_pack, hipStream_t st)
+{
+    const Problem &p = jobs[0].p;        // all jobs share bits, weight dtype and whether a clamp plane is written
+#define EQAT_Q(WT, B) quantize_t<WT, B>(jobs, n, for_pack, st)
+    if (p.w_bf16) { if (p.bits == 2) EQAT_Q(bf16_t, 2); else if (p.bits == 3) EQAT_Q(bf16_t, 3); else EQAT_Q(bf16_t, 4); }
+    else          { if (p.bits == 2) EQAT_Q(float, 2);  else if (p.bits == 3) EQAT_Q(float, 3);  else EQAT_Q(float, 4); }
+#undef EQAT_Q
 }
 
 void launch_quantize(const Problem &p, const void *W, const float *s, const float *z, void *codes, void *clampbits,
                      void *sz, void *zpacked, bool for_pack, uint32_t *zero_words, uint32_t n_zero, hipStream_t st)
 {
-#define EQAT_Q(WT, B) quantize_t<WT, B>(p, W, s, z, codes, clampbits, sz, zpacked, for_pack, zero_words, n_zero, st)
-    if (p.w_bf16) { if (p.bits == 2) EQAT_Q(bf16_t, 2); else if (p.bits == 3) EQAT_Q(bf16_t, 3); else EQAT_Q(bf16_t, 4); }
-    else          { if (p.bits == 2) EQAT_Q(float, 2);  else if (p.bits == 3) EQAT_Q(float, 3);  else EQAT_Q(float, 4); }
-#undef EQAT_Q
+    const QuantizeJob j{p, W, s, z, codes, clampbits, sz, zpacked, zero_words, n_zero};
+    launch_quantize_batch(&j, 1, for_pack, st);
 }
 
 void launch_e2e_prepare(const Problem &p, const void *packed, void *work, const float *s, const void *zpacked,
@@ -462,29 +511,45 @@ void launch_unpack_work(const Problem &p, const void *work, const void *clampbit
 }
 
 template <typename WT>
-static void init_minmax_t(const Problem &p, const void *W, float *s, float *z, hipStream_t st)
+static void init_minmax_t(const InitJob *jobs, int n, hipStream_t st)
 {
-    const float qmax = (float)((1 << p.bits) - 1);
-    const uint32_t n_chunks = (uint32_t)((size_t)p.O * p.I / 8);
-    const dim3 grid(blocks_for(n_chunks, 256 * kQuantUnroll)), block(256);
-    const WT *w = (const WT *)W;
-    switch (p.g) {
-    case 32:  k_init_minmax_small<WT, 4><<<grid, block, 0, st>>>(w, s, z, n_chunks, qmax); break;
-    case 64:  k_init_minmax_small<WT, 8><<<grid, block, 0, st>>>(w, s, z, n_chunks, qmax); break;
-    case 128: k_init_minmax_small<WT, 16><<<grid, block, 0, st>>>(w, s, z, n_chunks, qmax); break;
-    case 256: k_init_minmax_small<WT, 32><<<grid, block, 0, st>>>(w, s, z, n_chunks, qmax); break;
-    case 512: k_init_minmax_small<WT, 64><<<grid, block, 0, st>>>(w, s, z, n_chunks, qmax); break;
-    default: {
-        const uint32_t n_groups = (uint32_t)((size_t)p.O * p.G);
-        k_init_minmax_wave<WT><<<dim3(blocks_for(n_groups, 4)), block, 0, st>>>(w, s, z, n_groups, (uint32_t)p.g, qmax);
+    const float qmax = (float)((1 << jobs[0].p.bits) - 1);
+    // one lane per 8 weights and an xor butterfly over the lanes of a group when every matrix has the same group size
+    // of 32 .. 512; one wavefront per group otherwise
+    int64_t g = jobs[0].p.g;
+    for (int i = 1; i < n; ++i) if (jobs[i].p.g != g) g = 0;
+    const bool small = g == 32 || g == 64 || g == 128 || g == 256 || g == 512;
+    InitBatch b{};
+    uint32_t first = 0;
+    for (int i = 0; i < n; ++i) {
+        const Problem &p = jobs[i].p;
+        b.W[i] = jobs[i].W; b.s[i] = jobs[i].s; b.z[i] = jobs[i].z; b.g[i] = (uint32_t)p.g;
+        b.n[i] = small ? (uint32_t)((size_t)p.O * p.I / 8) : (uint32_t)((size_t)p.O * p.G);
+        b.first[i] = first;
+        first += small ? blocks_for(b.n[i], 256 * kQuantUnroll) : blocks_for(b.n[i], 4);
     }
+    for (int i = n; i <= kMaxBatch; ++i) b.first[i] = first;
+    const dim3 grid(first), block(256);
+    switch (small ? (int)g : 0) {
+    case 32:  k_init_minmax_small<WT, 4><<<grid, block, 0, st>>>(b, qmax); break;
+    case 64:  k_init_minmax_small<WT, 8><<<grid, block, 0, st>>>(b, qmax); break;
+    case 128: k_init_minmax_small<WT, 16><<<grid, block, 0, st>>>(b, qmax); break;
+    case 256: k_init_minmax_small<WT, 32><<<grid, block, 0, st>>>(b, qmax); break;
+    case 512: k_init_minmax_small<WT, 64><<<grid, block, 0, st>>>(b, qmax); break;
+    default:  k_init_minmax_wave<WT><<<grid, block, 0, st>>>(b, qmax);
     }
+}
+
+void launch_init_minmax_batch(const InitJob *jobs, int n, hipStream_t st)
+{
+    if (jobs[0].p.w_bf16) init_minmax_t<bf16_t>(jobs, n, st);
+    else init_minmax_t<float>(jobs, n, st);
 }
 
 void launch_init_minmax(const Problem &p, const void *W, float *s, float *z, hipStream_t st)
 {
-    if (p.w_bf16) init_minmax_t<bf16_t>(p, W, s, z, st);
-    else init_minmax_t<float>(p, W, s, z, st);
+    const InitJob j{p, W, s, z};
+    launch_init_minmax_batch(&j, 1, st);
 }
 
 void launch_reduce_partials(const float *part, float *out, const float *s, size_t n_out, uint32_t n_per, bool scale_by_s,

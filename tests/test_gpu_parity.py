@@ -110,6 +110,47 @@ def test_codes_exact_near_rounding_ties():
     assert np.array_equal(codes.cpu().numpy(), c_ref)
 
 
+@pytest.mark.parametrize("bits,wdt,groups", [(2, torch.bfloat16, (64, 64, 64)), (3, torch.float32, (128, 32, -1)),
+                                             (4, torch.bfloat16, (32, 96, 256))])
+def test_batched_passes_equal_the_single_calls(bits, wdt, groups):
+    """Several matrices in one launch (min/max, pack, Eq.(1) before a Block-AP step): bitwise what one call per matrix
+    gives, which the tests around hold against the oracle.  Shapes and group sizes differ inside a batch."""
+    shapes = [(72, 512), (136, 384), (8, 768)]
+    T = 50
+    Ws = [dev(synth.normal(sh, 0.02, synth.seed_of("batch", bits, k), wdt)) for k, sh in enumerate(shapes)]
+    descs = [eq.make_desc(T, I, O, bits, g, eq.BF16, eq._dt(Ws[0])) for (O, I), g in zip(shapes, groups)]
+    Gs = [1 if g == -1 else I // g for (O, I), g in zip(shapes, groups)]
+    ss = [torch.empty((O, G), dtype=torch.float32, device="cuda") for (O, I), G in zip(shapes, Gs)]
+    zs = [torch.empty_like(t) for t in ss]
+    eq.eqat_init_minmax_batched(eq.Batch(descs, W=Ws, s=ss, z=zs))
+    for W, s, z, g in zip(Ws, ss, zs, groups):
+        s1, z1 = eq.eqat_init_minmax(W, bits, g)
+        assert torch.equal(s, s1) and torch.equal(z, z1)
+    for k, (s, z) in enumerate(zip(ss, zs)):      # a trained state, some zero points outside the N-bit range
+        u, dlt = synth.trained_state_noise(tuple(s.shape), synth.seed_of("batch", bits, k, "sz"))
+        s.mul_(u.cuda()); z.add_(dlt.cuda())
+    Wps = [torch.empty((O, I * bits // 8), dtype=torch.uint8, device="cuda") for O, I in shapes]
+    zps = [torch.empty((O, 4 * ((G * bits + 31) // 32)), dtype=torch.uint8, device="cuda") for (O, I), G in zip(shapes, Gs)]
+    eq.eqat_pack_batched(eq.Batch(descs, W=Ws, s=ss, z=zs, Wpacked=Wps, zpacked=zps))
+    for W, s, z, g, Wp, zp in zip(Ws, ss, zs, groups, Wps, zps):
+        Wp1, zp1 = eq.eqat_pack(W, s, z, bits, g)
+        assert torch.equal(Wp, Wp1) and torch.equal(zp, zp1)
+    wss = [eq.workspace(d, eq.OP_FQ_BWD, "cuda").fill_(0xEE) for d in descs]
+    eq.eqat_fq_quantize_batched(eq.Batch(descs, W=Ws, s=ss, z=zs, ws=wss))
+    for (O, I), W, s, z, g, ws in zip(shapes, Ws, ss, zs, groups, wss):
+        X = dev(synth.normal((T, I), 1.0, synth.seed_of("batch", O, "X"), torch.bfloat16))
+        dY = dev(synth.normal((T, O), 1.0, synth.seed_of("batch", O, "dY"), torch.bfloat16))
+        Y = eq.eqat_fq_linear_fwd(X, W, s, z, bits, g, ws=ws, kept=True)
+        out = eq.eqat_fq_linear_bwd(X, W, s, z, dY, bits, g, ws=ws, kept=True)
+        assert torch.equal(Y, eq.eqat_fq_linear_fwd(X, W, s, z, bits, g))
+        ref = eq.eqat_fq_linear_bwd(X, W, s, z, dY, bits, g)
+        for k in ref:
+            assert torch.equal(out[k], ref[k]), k
+        c_ref, side = oracle.quantize(npf(W), npf(s), npf(z), bits, g)
+        codes, clamped, _ = eq.eqat_unpack_state(eq.STATE_FQ_KEPT, ws, O, I, bits, g, want_clamped=True)
+        assert np.array_equal(codes.cpu().numpy(), c_ref) and np.array_equal(clamped.cpu().numpy(), (side != 0).astype(np.uint8))
+
+
 # --------------------------------------------------------------------------- Block-AP
 
 def check_block_ap(X, W, s, z, dY, bits, g, tol):

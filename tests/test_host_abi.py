@@ -178,6 +178,24 @@ def test_null_alignment_and_workspace_errors_come_back_before_any_launch():
     assert L.eqat_unpack_state(r, eq.STATE_PREPARED, None, P, None, P, None) == NULL
     assert L.eqat_unpack_state(r, eq.STATE_PREPARED, P, P, P, P, None) == NULL          # no clamp plane in a prepared layer
     assert L.eqat_unpack_state(ctypes.byref(d(act=eq.F32)), eq.STATE_FQ_KEPT, P, P, None, P, None) == DTYPE
+    # several matrices in one launch
+    two = (eq.Desc * 2)(d(), d(I=256, O=8))
+    arr = (ctypes.c_void_p * 2)(P, P)
+    sizes = (ctypes.c_size_t * 2)(1 << 30, 1 << 30)
+    assert L.eqat_init_minmax_batched(0, two, arr, arr, arr, None) == SHAPE
+    assert L.eqat_init_minmax_batched(9, two, arr, arr, arr, None) == SHAPE
+    assert L.eqat_init_minmax_batched(2, None, arr, arr, arr, None) == NULL
+    assert L.eqat_init_minmax_batched(2, two, None, arr, arr, None) == NULL
+    assert L.eqat_init_minmax_batched(2, two, (ctypes.c_void_p * 2)(P, None), arr, arr, None) == NULL
+    assert L.eqat_pack_batched(2, two, arr, arr, arr, (ctypes.c_void_p * 2)(P, P + 4), arr, None) == ALIGN
+    assert L.eqat_pack_batched(2, (eq.Desc * 2)(d(), d(bits=3)), arr, arr, arr, arr, arr, None) == BITS
+    assert L.eqat_pack_batched(2, (eq.Desc * 2)(d(), d(w=eq.F32)), arr, arr, arr, arr, arr, None) == DTYPE
+    assert L.eqat_pack_batched(2, (eq.Desc * 2)(d(), d(group=48)), arr, arr, arr, arr, arr, None) == GROUP
+    assert L.eqat_fq_quantize_batched(2, two, arr, arr, arr, arr, (ctypes.c_size_t * 2)(1 << 30, 16), None) == WORKSPACE
+    assert L.eqat_fq_quantize_batched(2, two, arr, arr, arr, arr, None, None) == NULL
+    assert L.eqat_fq_quantize_batched(2, (eq.Desc * 2)(d(act=eq.F32, w=eq.F32), d(act=eq.F32, w=eq.F32)), arr, arr, arr, arr, sizes, None) == OK
+    assert L.eqat_fq_linear_fwd_kept(r, P, P, P, P, P, P, ws_need - 1, None) == WORKSPACE
+    assert L.eqat_fq_linear_fwd_kept(r, P, P, P, P, None, P, ws_need, None) == NULL
     # descriptor errors win over everything else
     bad = d(bits=9)
     assert L.eqat_fq_linear_fwd(ctypes.byref(bad), None, None, None, None, None, None, 0, None) == BITS
