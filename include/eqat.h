@@ -302,13 +302,14 @@ eqat_status eqat_recon_loss_static(int64_t n, int32_t dtype, const void *Y, cons
  * eqat_block_ap_update: one AdamW step, in place, on the three trained tensors of a linear in ONE launch, taking the
  * gradients as eqat_fq_linear_bwd wrote them (dW in W's dtype, ds and dz fp32).  Per element, in binary32:
  *   p <- p - lr wd p;  m <- b1 m + (1-b1) g;  v <- b2 v + (1-b2) g^2;
- *   p <- p - lr (m / (1 - b1^step)) / (sqrt(v / (1 - b2^step)) + eps)
+ *   p <- p - lr (m / (1 - b1^step)) / (sqrt(v / (1 - b2^step)) + eps)          (then s <- max(s, 1e-10), see below)
  * with lr = lr_w, wd = weight_decay_w for W and lr_q, weight_decay_q for s and z.  Moments are fp32 arrays of the
  * parameter's shape, zero before the first step, owned by the caller.  A NULL parameter pointer (W, s or z) skips that
  * tensor together with its gradient and moments (E2E-QP trains s alone).  d->tokens and d->act_dtype are ignored.
  * A bf16 W is rounded to nearest even after the update; steps smaller than half an ulp are lost, so W should be kept
  * in fp32 while it is trained.  Constants outside 0 <= beta < 1, eps >= 0, step >= 1 give EQAT_ERR_HYPER.
- * Nothing keeps s positive: the caller must (eqat_fq_linear_* require a positive, normal s).
+ * The updated step sizes are held at or above 1e-10, the floor of their min/max initialisation (Eq.(1) divides by s, and
+ * nothing else keeps an optimizer step from crossing zero): s <- max(s, 1e-10).
  */
 typedef struct eqat_adamw {
     float lr_w;             /* learning rate of the weights (Sec. 4.1: 2e-5 at 2 bit, 1e-5 at 3 and 4 bit)   */

@@ -221,8 +221,12 @@ def recon_loss(Y, Yref, want_dY=True):
     return float(loss.value), dY
 
 
-def adamw(p, grad, m, v, lr, beta1, beta2, eps, weight_decay, step):
-    """One AdamW step (decoupled weight decay, bias correction; step counted from 1).  Returns new (p, m, v) as fp64 arrays."""
+S_MIN = float(np.float32(1e-10))      # lower bound of a step size: the floor of its min/max initialisation
+
+
+def adamw(p, grad, m, v, lr, beta1, beta2, eps, weight_decay, step, p_min=-np.inf):
+    """One AdamW step (decoupled weight decay, bias correction; step counted from 1), then p = max(p, p_min) (step sizes:
+    p_min = S_MIN).  Returns new (p, m, v) as fp64 arrays."""
     p = np.array(p, dtype=np.float64, order="C"); m = np.array(m, dtype=np.float64, order="C")
     v = np.array(v, dtype=np.float64, order="C")
     grad, pg = _f32(grad)
@@ -230,5 +234,5 @@ def adamw(p, grad, m, v, lr, beta1, beta2, eps, weight_decay, step):
         raise ValueError("shapes differ")
     d = ctypes.c_double
     _check(_load().eqo_adamw(_ptr(p), pg, _ptr(m), _ptr(v), _ll(p.size), d(lr), d(beta1), d(beta2), d(eps), d(weight_decay),
-                             int(step)), "adamw")
+                             int(step), d(p_min)), "adamw")
     return p, m, v

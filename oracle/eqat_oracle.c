@@ -578,9 +578,12 @@ int eqo_recon_loss(const float *Y, const float *Yref, i64 n, double *loss, doubl
 /* One AdamW step on n parameters, in place (p, m, v), `step` counted from 1:
  *   p <- p - lr * wd * p
  *   m <- b1 m + (1 - b1) g ;  v <- b2 v + (1 - b2) g^2
- *   p <- p - lr * (m / (1 - b1^step)) / (sqrt(v / (1 - b2^step)) + eps)                                              */
+ *   p <- p - lr * (m / (1 - b1^step)) / (sqrt(v / (1 - b2^step)) + eps)
+ *   p <- max(p, p_min)
+ * p_min: the step sizes are held at or above the 1e-10 of their initialisation (Eq.(1) divides by s: the paper's method
+ * needs s > 0 and has nothing that keeps an optimizer step from crossing zero); -inf for parameters without a bound.   */
 int eqo_adamw(double *p, const float *grad, double *m, double *v, i64 n,
-              double lr, double b1, double b2, double eps, double wd, int step)
+              double lr, double b1, double b2, double eps, double wd, int step, double p_min)
 {
     if (n < 0 || step < 1 || (n > 0 && (!p || !grad || !m || !v))) return -1;
     const double c1 = 1.0 - pow(b1, (double)step), c2 = 1.0 - pow(b2, (double)step);
@@ -590,6 +593,7 @@ int eqo_adamw(double *p, const float *grad, double *m, double *v, i64 n,
         m[k] = b1 * m[k] + (1.0 - b1) * gk;
         v[k] = b2 * v[k] + (1.0 - b2) * gk * gk;
         p[k] -= lr * (m[k] / c1) / (sqrt(v[k] / c2) + eps);
+        if (p[k] < p_min) p[k] = p_min;
     }
     return 0;
 }

@@ -735,9 +735,9 @@ eqat_status eqat_block_ap_update(const eqat_desc *d, const eqat_adamw *h, void *
     if (z != nullptr) { EQAT_REQUIRE(dz); EQAT_REQUIRE(mz); EQAT_REQUIRE(vz); EQAT_ALIGNED(z); EQAT_ALIGNED(dz); EQAT_ALIGNED(mz); EQAT_ALIGNED(vz); }
     if (W == nullptr && s == nullptr && z == nullptr) return EQAT_OK;
     const eqat::AdamGroup groups[3] = {
-        {W, dW, mW, vW, p.O * p.I, h->lr_w, h->weight_decay_w, p.w_bf16},
-        {s, ds, ms, vs, p.O * p.G, h->lr_q, h->weight_decay_q, false},
-        {z, dz, mz, vz, p.O * p.G, h->lr_q, h->weight_decay_q, false},
+        {W, dW, mW, vW, p.O * p.I, h->lr_w, h->weight_decay_w, p.w_bf16, -__builtin_inff()},
+        {s, ds, ms, vs, p.O * p.G, h->lr_q, h->weight_decay_q, false, 1e-10f},      // s > 0 is what Eq.(1) needs
+        {z, dz, mz, vz, p.O * p.G, h->lr_q, h->weight_decay_q, false, -__builtin_inff()},
     };
     hipStream_t st = (hipStream_t)stream;
     { ProfScope ps(eqat::PK_UPDATE, st); eqat::launch_adamw(groups, h->beta1, h->beta2, h->eps, h->step, st); }

@@ -124,6 +124,55 @@ __device__ __forceinline__ float zbar_of(float z, float qmax)
     return __builtin_amdgcn_fmed3f(__builtin_rintf(z), 0.0f, qmax);
 }
 
+// ---- codes -> bf16 What ----------------------------------------------------------------------------------
+// A group has only 2^N distinct What values, (q - zbar) * s.  For 2 and 3 bits they are computed once per 32-code
+// segment and kept as two byte tables (low and high bytes of the bf16 values); four codes sitting in the four bytes
+// of a register then become four bf16 with four byte permutes, instead of four converts, four FMAs and two packs.
+// 4 bits (16 values) exceed what one permute can index and keep the arithmetic form.
+template <int BITS> struct WhatTable {
+    uint32_t lo[2], hi[2];      // byte q of lo / hi = low / high byte of bf16(What(q)); [1] only for 3 bits
+    float s, b;                 // What(q) = q * s + b
+    __device__ __forceinline__ void build(float s_, float zbar)
+    {
+        s = s_; b = -zbar * s_;
+        if constexpr (BITS <= 3) {
+#pragma unroll
+            for (int half = 0; half < (BITS == 3 ? 2 : 1); ++half) {
+                bf16x2 p01, p23;
+                p01[0] = (bf16_t)__builtin_fmaf((float)(4 * half + 0), s, b); p01[1] = (bf16_t)__builtin_fmaf((float)(4 * half + 1), s, b);
+                p23[0] = (bf16_t)__builtin_fmaf((float)(4 * half + 2), s, b); p23[1] = (bf16_t)__builtin_fmaf((float)(4 * half + 3), s, b);
+                const uint32_t v0 = __builtin_bit_cast(uint32_t, p01), v1 = __builtin_bit_cast(uint32_t, p23);
+                lo[half] = __builtin_amdgcn_perm(v1, v0, 0x06040200u);      // bytes 0 and 2 of v0, then of v1
+                hi[half] = __builtin_amdgcn_perm(v1, v0, 0x07050301u);      // bytes 1 and 3
+            }
+            if constexpr (BITS == 2) { lo[1] = lo[0]; hi[1] = hi[0]; }
+        }
+    }
+    // t: four codes in the four bytes -> two registers holding four bf16
+    __device__ __forceinline__ void four(uint32_t t, uint32_t &d0, uint32_t &d1) const
+    {
+        if constexpr (BITS <= 3) {
+            const uint32_t x = __builtin_amdgcn_perm(lo[1], lo[0], t), y = __builtin_amdgcn_perm(hi[1], hi[0], t);
+            d0 = __builtin_amdgcn_perm(y, x, 0x05010400u);     // x0 y0 x1 y1
+            d1 = __builtin_amdgcn_perm(y, x, 0x07030602u);     // x2 y2 x3 y3
+        } else {
+            bf16x2 p01, p23;
+            p01[0] = (bf16_t)__builtin_fmaf(byte_to_float(t, 0), s, b); p01[1] = (bf16_t)__builtin_fmaf(byte_to_float(t, 1), s, b);
+            p23[0] = (bf16_t)__builtin_fmaf(byte_to_float(t, 2), s, b); p23[1] = (bf16_t)__builtin_fmaf(byte_to_float(t, 3), s, b);
+            d0 = __builtin_bit_cast(uint32_t, p01); d1 = __builtin_bit_cast(uint32_t, p23);
+        }
+    }
+    // codes [8*q8, 8*q8 + 8) of a segment -> eight bf16
+    template <int Q8> __device__ __forceinline__ bf16x8 eight(const WorkCodes<BITS> &c) const
+    {
+        uintx4 u;
+        uint32_t d0, d1;
+        four(c.four(8 * Q8), d0, d1); u[0] = d0; u[1] = d1;
+        four(c.four(8 * Q8 + 4), d0, d1); u[2] = d0; u[3] = d1;
+        return __builtin_bit_cast(bf16x8, u);
+    }
+};
+
 __device__ __forceinline__ float to_float(float v) { return v; }
 __device__ __forceinline__ float to_float(bf16_t v) { return (float)v; }
 

@@ -5,7 +5,7 @@
 // pass, which would triple the traffic).  One workgroup owns 16 output rows; its 4 waves split the input dimension
 // and meet in LDS at the end (fixed order: deterministic).  The contraction runs on v_mfma_f32_16x16x32_bf16 with
 // the WEIGHTS as the A operand (16 rows x 32 k) and the tokens as the 16 columns of B, so that one byte-permute table
-// per 32-code segment (see WhatTable in gemm_mfma.hip: the same trick) turns codes into bf16 at about one VALU
+// per 32-code segment (WhatTable, shared with the GEMM producer) turns codes into bf16 at about one VALU
 // instruction per weight and the multiply-adds cost nothing.
 //
 // Order of the contraction index.  A lane holds one 32-code segment of one row and feeds 8 of its codes to each of 4
@@ -46,45 +46,9 @@ template <int BITS> constexpr bool slot_maps_are_inverse()
 }
 static_assert(slot_maps_are_inverse<2>() && slot_maps_are_inverse<3>() && slot_maps_are_inverse<4>(), "slot order");
 
-// byte tables of the group's possible values bf16((q - z) * s), as in the GEMM producer
-template <int BITS> struct ValueTable {
-    uint32_t lo[2], hi[2];
-    float s, b;
-    __device__ __forceinline__ void build(float s_, float z)
-    {
-        s = s_; b = -z * s_;
-        if constexpr (BITS <= 3) {
-#pragma unroll
-            for (int half = 0; half < (BITS == 3 ? 2 : 1); ++half) {
-                bf16x2 p01, p23;
-                p01[0] = (bf16_t)__builtin_fmaf((float)(4 * half + 0), s, b); p01[1] = (bf16_t)__builtin_fmaf((float)(4 * half + 1), s, b);
-                p23[0] = (bf16_t)__builtin_fmaf((float)(4 * half + 2), s, b); p23[1] = (bf16_t)__builtin_fmaf((float)(4 * half + 3), s, b);
-                const uint32_t v0 = __builtin_bit_cast(uint32_t, p01), v1 = __builtin_bit_cast(uint32_t, p23);
-                lo[half] = __builtin_amdgcn_perm(v1, v0, 0x06040200u);
-                hi[half] = __builtin_amdgcn_perm(v1, v0, 0x07050301u);
-            }
-            if constexpr (BITS == 2) { lo[1] = lo[0]; hi[1] = hi[0]; }
-        }
-    }
-    // four codes in the four bytes of t -> four bf16 in two registers
-    __device__ __forceinline__ void four(uint32_t t, uint32_t &d0, uint32_t &d1) const
-    {
-        if constexpr (BITS <= 3) {
-            const uint32_t x = __builtin_amdgcn_perm(lo[1], lo[0], t), y = __builtin_amdgcn_perm(hi[1], hi[0], t);
-            d0 = __builtin_amdgcn_perm(y, x, 0x05010400u);
-            d1 = __builtin_amdgcn_perm(y, x, 0x07030602u);
-        } else {
-            bf16x2 p01, p23;
-            p01[0] = (bf16_t)__builtin_fmaf(byte_to_float(t, 0), s, b); p01[1] = (bf16_t)__builtin_fmaf(byte_to_float(t, 1), s, b);
-            p23[0] = (bf16_t)__builtin_fmaf(byte_to_float(t, 2), s, b); p23[1] = (bf16_t)__builtin_fmaf(byte_to_float(t, 3), s, b);
-            d0 = __builtin_bit_cast(uint32_t, p01); d1 = __builtin_bit_cast(uint32_t, p23);
-        }
-    }
-};
-
 // the 8 weights of MFMA t of a segment, in slot order
 template <int BITS, int T4>
-__device__ __forceinline__ bf16x8 eight_of(const ValueTable<BITS> &tab, const CodeWords<BITS> &c)
+__device__ __forceinline__ bf16x8 eight_of(const WhatTable<BITS> &tab, const CodeWords<BITS> &c)
 {
     uint32_t t0, t1;
     if constexpr (BITS == 2) {
@@ -202,7 +166,7 @@ __global__ __launch_bounds__(64 * kGemvWaves) void k_gemv_any(const GemvArgs a)
                     const uint64_t two = (uint64_t)zw0[u][rb] | ((uint64_t)zw1[u][rb] << 32);
                     zv[u][rb] = (float)((uint32_t)(two >> sh) & ((1u << BITS) - 1u));
                 }
-                ValueTable<BITS> tab;
+                WhatTable<BITS> tab;
                 tab.build(sv[u][rb], zv[u][rb]);
                 acc[rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(eight_of<BITS, 0>(tab, cw[u][rb]), b0, acc[rb], 0, 0, 0);
                 acc[rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(eight_of<BITS, 1>(tab, cw[u][rb]), b1, acc[rb], 0, 0, 0);
@@ -315,7 +279,7 @@ __global__ __launch_bounds__(64 * kGemvWaves) void k_gemv_run(const GemvArgs a)
         floatx4 sq[SW], zq[SW];
         uint32_t zw[2] = {0u, 0u};
         load_run(sc, cq, sq, zq, zw);
-        ValueTable<BITS> tab;
+        WhatTable<BITS> tab;
         const uint32_t j0 = NG > 1 ? (uint32_t)(seg0 >> 3) * NG : (a.spg_magic ? __umulhi((uint32_t)seg0, a.spg_magic) : (uint32_t)seg0);
         const uint64_t zbits = ((uint64_t)zw[0] | ((uint64_t)zw[1] << 32)) >> ((j0 * BITS) & 31u);
 #pragma unroll

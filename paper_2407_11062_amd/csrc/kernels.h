@@ -82,6 +82,7 @@ struct AdamGroup {                      // one parameter tensor; p == NULL: abse
     int64_t n;
     float lr, weight_decay;
     bool bf16;                          // dtype of p and g (moments are always fp32)
+    float p_min;                        // lower bound of the updated parameter (-inf: none)
 };
 // One launch over three parameter groups (weights, step sizes, zero points); step counts from 1.
 void launch_adamw(const AdamGroup *groups, float beta1, float beta2, float eps, int step, hipStream_t st);

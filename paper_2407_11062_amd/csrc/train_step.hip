@@ -102,6 +102,7 @@ struct AdamSeg {
     void *p; const void *g; float *m; float *v;
     int64_t n;
     float lr, decay;                    // decay = lr * weight_decay
+    float p_min;                        // the updated parameter is held at or above this (-inf: no bound)
     uint32_t first_block;
     int32_t bf16;                       // dtype of p and g
 };
@@ -110,12 +111,13 @@ struct AdamArgs {
     float b1, b2, omb1, omb2, eps, c1, c2;   // omb = 1 - b;  c1 = 1 / (1 - b1^step), c2 = 1 / (1 - b2^step)
 };
 
-__device__ __forceinline__ void adam_one(float &p, float g, float &m, float &v, float lr, float decay, const AdamArgs &a)
+__device__ __forceinline__ void adam_one(float &p, float g, float &m, float &v, const AdamSeg &sg, const AdamArgs &a)
 {
-    p -= decay * p;
+    p -= sg.decay * p;
     m = a.b1 * m + a.omb1 * g;
     v = a.b2 * v + a.omb2 * g * g;
-    p -= lr * (m * a.c1) / (sqrtf(v * a.c2) + a.eps);
+    p -= sg.lr * (m * a.c1) / (sqrtf(v * a.c2) + a.eps);
+    p = fmaxf(p, sg.p_min);
 }
 
 template <typename T>
@@ -128,12 +130,12 @@ __device__ __forceinline__ void adam_chunk(const AdamSeg &sg, const AdamArgs &a,
         float p[8], g[8], m[8], v[8];
         load8(P + e0, p); load8(G + e0, g); load8(sg.m + e0, m); load8(sg.v + e0, v);
 #pragma unroll
-        for (int k = 0; k < 8; ++k) adam_one(p[k], g[k], m[k], v[k], sg.lr, sg.decay, a);
+        for (int k = 0; k < 8; ++k) adam_one(p[k], g[k], m[k], v[k], sg, a);
         store8(P + e0, p); store8(sg.m + e0, m); store8(sg.v + e0, v);
     } else {
         for (int64_t e = e0; e < sg.n; ++e) {
             float p = to_float(P[e]), m = sg.m[e], v = sg.v[e];
-            adam_one(p, to_float(G[e]), m, v, sg.lr, sg.decay, a);
+            adam_one(p, to_float(G[e]), m, v, sg, a);
             store1(P + e, p); sg.m[e] = m; sg.v[e] = v;
         }
     }
@@ -182,7 +184,7 @@ void launch_adamw(const AdamGroup *groups, float beta1, float beta2, float eps, 
         sg.p = gr.p; sg.g = gr.g; sg.m = gr.m; sg.v = gr.v;
         sg.n = gr.p != nullptr ? gr.n : 0;
         sg.lr = gr.lr; sg.decay = (float)((double)gr.lr * (double)gr.weight_decay);
-        sg.first_block = first; sg.bf16 = gr.bf16 ? 1 : 0;
+        sg.first_block = first; sg.bf16 = gr.bf16 ? 1 : 0; sg.p_min = gr.p_min;
         first += blocks_for(sg.n);
     }
     if (first == 0) return;

@@ -100,7 +100,8 @@ def test_adamw_update_three_steps(O, I, g, wdt):
         torch.cuda.synchronize()
         for k, gr, lr, wd in (("W", gW, lr_w, wd_w), ("s", gs, lr_q, wd_q), ("z", gz, lr_q, wd_q)):
             # the reference continues from ITS OWN state; a bf16 parameter is rounded after every step on both sides
-            ref[k], rm[k], rv[k] = oracle.adamw(ref[k], npf(gr), rm[k], rv[k], lr, b1, b2, eps, wd, step)
+            ref[k], rm[k], rv[k] = oracle.adamw(ref[k], npf(gr), rm[k], rv[k], lr, b1, b2, eps, wd, step,
+                                                p_min=oracle.S_MIN if k == "s" else -np.inf)
             if k == "W" and wdt == torch.bfloat16:
                 ref[k] = npf(torch.from_numpy(ref[k]).to(torch.bfloat16)).astype(np.float64)
         for k in ("W", "s", "z"):
@@ -113,6 +114,30 @@ def test_adamw_update_three_steps(O, I, g, wdt):
         assert relerr(dev["W"], ref["W"]) <= 2.0 ** -7
 
 
+def test_update_holds_step_sizes_at_their_floor():
+    # a step that would carry s through zero (gradient positive, learning rate larger than s) leaves it at 1e-10, the
+    # floor of the min/max initialisation; z and W have no bound.  After it the layer still quantizes: codes in range.
+    O, I, g, bits = 8, 128, 64, 2
+    W = synth.normal((O, I), 0.02, 91, torch.float32).cuda()
+    s = torch.full((O, 2), 1e-3, dtype=torch.float32, device="cuda")
+    z = torch.ones((O, 2), dtype=torch.float32, device="cuda")
+    gs = torch.ones_like(s); gz = torch.ones_like(z); gW = torch.ones_like(W)
+    zeros = lambda t: torch.zeros(t.shape, dtype=torch.float32, device="cuda")
+    h = eq.AdamW(1e-4, 0.5, 0.9, 0.999, 1e-8, 0.0, 0.0, 1)
+    s_ref = oracle.adamw(npf(s), npf(gs), np.zeros(s.shape), np.zeros(s.shape), f32(0.5), f32(0.9), f32(0.999), f32(1e-8), 0.0, 1,
+                         p_min=oracle.S_MIN)[0]
+    z_ref = oracle.adamw(npf(z), npf(gz), np.zeros(z.shape), np.zeros(z.shape), f32(0.5), f32(0.9), f32(0.999), f32(1e-8), 0.0, 1)[0]
+    eq.eqat_block_ap_update(h, bits, g, W=W, dW=gW, mW=zeros(W), vW=zeros(W), s=s, ds=gs, ms=zeros(s), vs=zeros(s),
+                            z=z, dz=gz, mz=zeros(z), vz=zeros(z))
+    torch.cuda.synchronize()
+    assert np.all(s_ref == oracle.S_MIN) and np.array_equal(npf(s).astype(np.float64), s_ref)
+    assert np.all(z_ref < 0.6) and relerr(z, z_ref) <= 1e-5
+    Wp, zp = eq.eqat_pack(W, s, z, bits, g)
+    codes, _ = eq.eqat_unpack(Wp, zp, I, bits, g)
+    c_ref, _ = oracle.quantize(npf(W), npf(s), npf(z), bits, g)
+    assert np.array_equal(codes.cpu().numpy(), c_ref)
+
+
 def test_adamw_update_of_a_subset_leaves_the_rest_alone():
     O, I, g = 40, 128, 64
     W, s, z = _state("subset", O, I, g, torch.float32)
@@ -123,7 +148,7 @@ def test_adamw_update_of_a_subset_leaves_the_rest_alone():
     eq.eqat_block_ap_update(h, 2, g, s=sd, ds=gs.cuda(), ms=ms, vs=vs, shape=(O, I))      # E2E-QP: step sizes only
     torch.cuda.synchronize()
     lr_w, lr_q, b1, b2, eps = f32(2e-5), f32(1e-4), f32(0.9), f32(0.999), f32(1e-8)
-    p, m, v = oracle.adamw(npf(s), npf(gs), np.zeros(s.shape), np.zeros(s.shape), lr_q, b1, b2, eps, 0.0, 1)
+    p, m, v = oracle.adamw(npf(s), npf(gs), np.zeros(s.shape), np.zeros(s.shape), lr_q, b1, b2, eps, 0.0, 1, p_min=oracle.S_MIN)
     assert relerr(sd, p) <= 1e-5 and relerr(ms, m) <= 1e-5 and relerr(vs, v) <= 1e-5
     # W and z alone, in one launch; s untouched
     Wd, zd = W.cuda(), z.cuda()
@@ -175,7 +200,7 @@ def test_block_ap_steps_of_one_linear_against_the_oracle_and_the_loss_goes_down(
             torch.cuda.synchronize()
             for name, got, p0, gk, lr in (("W", Wd, npf(W), "dW", lr_w), ("s", sd, s0, "ds", lr_q), ("z", zd, z0, "dz", lr_q)):
                 p, m, v = oracle.adamw(p0, gr_o[gk].astype(np.float32), np.zeros(p0.shape), np.zeros(p0.shape), f32(lr),
-                                       f32(0.9), f32(0.999), f32(1e-8), 0.0, 1)
+                                       f32(0.9), f32(0.999), f32(1e-8), 0.0, 1, p_min=oracle.S_MIN if name == "s" else -np.inf)
                 # the first Adam step moves every parameter by lr * g / (|g| + eps): exactly lr wherever the two
                 # sides agree on the sign of the gradient, which bf16 gradients may not where g is next to zero
                 diff = np.abs(npf(got).astype(np.float64) - p)
@@ -217,7 +242,8 @@ def test_loss_and_update_at_full_size():
         eq.eqat_block_ap_update(h, 2, g, W=Wd, dW=gW.cuda(), mW=mom[0], vW=mom[1], s=sd, ds=gs.cuda(), ms=mom[2], vs=mom[3],
                                 z=zd, dz=gz.cuda(), mz=mom[4], vz=mom[5])
         for k, gr, lr in (("W", gW, lr_w), ("s", gs, lr_q), ("z", gz, lr_q)):
-            ref[k], rm[k], rv[k] = oracle.adamw(ref[k], npf(gr), rm[k], rv[k], lr, b1, b2, eps, 0.0, step)
+            ref[k], rm[k], rv[k] = oracle.adamw(ref[k], npf(gr), rm[k], rv[k], lr, b1, b2, eps, 0.0, step,
+                                                p_min=oracle.S_MIN if k == "s" else -np.inf)
         ref["W"] = npf(torch.from_numpy(ref["W"]).to(torch.bfloat16)).astype(np.float64)
     torch.cuda.synchronize()
     assert relerr(Wd, ref["W"]) <= 2.0 ** -7

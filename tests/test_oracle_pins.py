@@ -575,6 +575,20 @@ def test_adamw_against_the_library_optimizer_over_several_steps(wd):
     np.testing.assert_allclose(v, st["exp_avg_sq"].numpy(), rtol=1e-12, atol=1e-18)
 
 
+def test_adamw_lower_bound_holds_step_sizes_positive():
+    # p_min acts after the step and only on parameters that fell below it; without it the step is the plain one
+    p0 = np.array([1e-3, 2.0, 5e-11, -1.0]); g = np.array([1.0, 1.0, -1.0, 1.0], np.float32)
+    lr = 0.5
+    free = oracle.adamw(p0, g, np.zeros(4), np.zeros(4), lr, 0.9, 0.999, 0.0, 0.0, 1)[0]
+    np.testing.assert_allclose(free, p0 - lr * np.sign(g), rtol=1e-12)
+    held = oracle.adamw(p0, g, np.zeros(4), np.zeros(4), lr, 0.9, 0.999, 0.0, 0.0, 1, p_min=oracle.S_MIN)[0]
+    assert held[0] == oracle.S_MIN and held[3] == oracle.S_MIN and held[1] == free[1] and held[2] == free[2]
+    assert oracle.S_MIN == float(np.float32(1e-10))
+    # the bound is the floor of the min/max initialisation: a constant group starts exactly there
+    s, _ = oracle.init_minmax(np.full((1, 32), 0.5, np.float32), 2, 32)
+    assert float(s[0, 0]) == oracle.S_MIN
+
+
 def test_adamw_first_step_closed_form_and_invariants():
     # step 1 from zero moments: mhat = g, sqrt(vhat) = |g|  =>  p1 = p0 (1 - lr wd) - lr g / (|g| + eps)
     p0 = np.array([1.0, -2.0, 0.5, 3.0]); g = np.array([0.5, -0.25, 0.0, 4.0], np.float32)
