@@ -14,14 +14,19 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "eqat_oracle.c")
-_LIB = os.path.join(_HERE, "libeqat_oracle.so")
+# EQAT_ORACLE_SANITIZE=1: a build with AddressSanitizer and UndefinedBehaviorSanitizer (the process must then run with
+# gcc's libasan preloaded); tests/test_sanitizers.py runs the oracle's pins that way
+_SANITIZE = os.environ.get("EQAT_ORACLE_SANITIZE", "") == "1"
+_LIB = os.path.join(_HERE, "libeqat_oracle_san.so" if _SANITIZE else "libeqat_oracle.so")
 _lib = None
 
 
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc (fp64, no fast-math, no contraction)."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-ffp-contract=off", "-fno-fast-math",
+        opt = ["-O1", "-g", "-fno-omit-frame-pointer", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined"] \
+            if _SANITIZE else ["-O2"]
+        cmd = ["gcc", *opt, "-std=c11", "-fopenmp", "-ffp-contract=off", "-fno-fast-math",
                "-fPIC", "-shared", "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
         subprocess.run(cmd, check=True)
     return _LIB

@@ -35,7 +35,8 @@ def build(verbose: bool = True) -> str:
     with ThreadPoolExecutor(max_workers=4) as ex:
         objs = list(ex.map(_compile, SOURCES + [PEAKS_SOURCE]))
     for out, parts in ((LIB, objs[:-1]), (PEAKS_LIB, objs[-1:])):
-        r = subprocess.run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", *parts, "-o", out],
+        r = subprocess.run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", *os.environ.get("EQAT_EXTRA_LINK_FLAGS", "").split(),
+                            *parts, "-o", out],
                            capture_output=True, text=True)
         if r.returncode != 0:
             raise RuntimeError("link failed:\n" + r.stderr)
