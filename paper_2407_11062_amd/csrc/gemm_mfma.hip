@@ -291,7 +291,8 @@ __device__ __forceinline__ void wait_all_and_barrier()
 //     wave; fragments of slice kk+1 are read while slice kk multiplies.
 // K tiles past the end of K multiply zeros: the weights there are exactly zero (see load_a below).
 // A workgroup may own several output tiles; the pipeline then runs on through the tile boundaries.
-// CUT: the launch cuts tiles along K (SkPlan::dp_rounds == 0 with walk); the other instantiation carries none of that code.
+// CUT: the instantiation for launches that cut tiles along K (SkPlan::dp_rounds == 0 with walk) or whose contraction
+// length is not a multiple of two K tiles; the other one carries none of that code (the main loop is sensitive to it).
 template <int BITS, bool BT, bool CUT, int BM, int BN, int BK, int WGM, int WGN>
 __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_q(const GemmQArgs a)
 {
@@ -347,12 +348,26 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_q(const GemmQArgs a)
 
     // Activation tiles stream into LDS strictly in order (k0 = 0, BK, 2 BK, ... of one output tile, then of the next):
     // every direct-to-LDS instruction keeps a running byte offset that advances by one tile row segment per call, and
-    // M0 comes from wave-uniform scalars.  No test against K: columns past K of a row read the start of the next row
-    // (or, behind the last row, fail the range check and give zeros); they meet weights that are exactly zero (step
-    // size and zero point of a column past the end load as 0), and inputs are finite by contract.
+    // M0 comes from wave-uniform scalars.  Columns past K of a row would read the start of the next row; they meet weights
+    // that are exactly zero (step size and zero point of a column past the end load as 0), and are not loaded at all when
+    // K is ragged (see k_ragged below).
     const uint32_t ldsA = lds_addr_of(sA);
     uint32_t offA[A_LOADS];
     int a_tile = 0, a_left = 0;                     // loader position: tile ordinal, K tiles left in it
+    // When K is not a multiple of two K tiles, the last K tile of an output tile reaches past the end of its rows (and a
+    // padding K tile lies past it altogether).  The weights there are zero, but 0 * Inf is NaN: a non-finite value in
+    // row t + 1 must not leak into row t, so the chunks past K of those tiles are loaded from out of range (zeros).
+    const bool k_ragged = CUT && a.K % (2 * BK) != 0;      // wave-uniform; the host sends every such K to this instantiation
+    int a_kt = 0;                                   // K tile (within its output tile) that the next load_a fetches
+    uint32_t a_past_k = 0;                          // bit `it`: in K tile nk - 1, this lane's chunk of load `it` lies past K
+    if (k_ragged) {
+        const int tail_cols = a.K - (nk - 1) * BK;  // 8 .. 64 valid columns in K tile nk - 1
+#pragma unroll
+        for (int it = 0; it < A_LOADS; ++it) {
+            const int row = (wave * A_LOADS + it) * 8 + (lane >> 3);
+            if (kc_swz(row, lane & 7) * 8 >= tail_cols) a_past_k |= 1u << it;
+        }
+    }
     auto a_enter_tile = [&]() {
         int m0, n0;
         SkItem si;
@@ -364,15 +379,27 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_q(const GemmQArgs a)
             offA[it] = o < kOobOffset ? (uint32_t)o : kOobOffset;   // rows past the matrix stay out of range for good
         }
         a_left = CUT ? 2 * (si.ke - si.kb) : nk2;
+        a_kt = CUT ? 2 * si.kb : 0;
         ++a_tile;
     };
     auto load_a = [&](int buf) {
         --a_left;
+        if (k_ragged && a_kt >= nk - 1) {            // rare: the last (and the padding) K tile of a ragged K
+            const uint32_t past = a_kt >= nk ? ~0u : a_past_k;
 #pragma unroll
-        for (int it = 0; it < A_LOADS; ++it) {
-            load_to_lds16_at(rA, ldsA + (uint32_t)((buf * A_ELEMS + (wave * A_LOADS + it) * 8 * 64) * 2), offA[it]);
-            offA[it] += BK * 2;
+            for (int it = 0; it < A_LOADS; ++it) {
+                load_to_lds16_at(rA, ldsA + (uint32_t)((buf * A_ELEMS + (wave * A_LOADS + it) * 8 * 64) * 2),
+                                 (past >> it) & 1u ? kOobOffset : offA[it]);
+                offA[it] += BK * 2;
+            }
+        } else {
+#pragma unroll
+            for (int it = 0; it < A_LOADS; ++it) {
+                load_to_lds16_at(rA, ldsA + (uint32_t)((buf * A_ELEMS + (wave * A_LOADS + it) * 8 * 64) * 2), offA[it]);
+                offA[it] += BK * 2;
+            }
         }
+        ++a_kt;
     };
     // Weight codes and (s, zbar) pairs, in the same order.  Forward: a segment's group index wcol / g is carried from
     // call to call (a K tile advances wcol by BK <= 2 g, so two conditional steps replace a division per K tile).
@@ -1031,7 +1058,7 @@ void launch_q(const GemmQArgs &args, hipStream_t st)
     const int ntiles = a.tiles_m * a.tiles_n, resident = resident_workgroups(smem);
     a.sk = plan_tiles(ntiles, ((a.K + TS::BK - 1) / TS::BK + 1) / 2, resident, a.sk.partials, a.sk.counters);
     const dim3 grid(a.sk.walk ? resident : ntiles), block(64 * TS::WGM * TS::WGN);
-    if (a.sk.walk && a.sk.dp_rounds == 0) {
+    if ((a.sk.walk && a.sk.dp_rounds == 0) || a.K % (2 * TS::BK) != 0) {
         auto kern = k_gemm_q<BITS, BT, true, TS::BM, TS::BN, TS::BK, TS::WGM, TS::WGN>;
         static uint64_t attr_done = 0;
         allow_dynamic_lds(kern, smem, attr_done);

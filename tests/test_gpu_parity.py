@@ -252,6 +252,30 @@ def test_cut_tiles_are_deterministic_and_ignore_what_the_workspace_held():
             assert torch.equal(out[k], outs[0][1][k]), k
 
 
+@pytest.mark.parametrize("I,O", [(352, 200), (320, 192), (96, 72)])
+def test_a_non_finite_token_does_not_leak_into_its_neighbour(I, O):
+    """K tiles are 64 wide and two are multiplied per trip: with a contraction length that is not a multiple of 128 the
+    last K tile (and a padding tile) reach past the end of an activation row, i.e. into the next row.  The weights there
+    are zero, but 0 * Inf is NaN: the chunks past K must not be loaded at all.  Row 7 of X and of dY carries Inf and
+    NaN; every other row of Y (fwd, K = I) and of dX (K = O) must come out as without them."""
+    T, bits, g = 40, 2, 32
+    X, W, s, z, dY = make_case(("leak", I, O), T, I, O, bits, g, torch.bfloat16, torch.bfloat16)
+    Xd, Wd, sd, zd, dYd = dev(X), dev(W), dev(s), dev(z), dev(dY)
+    Y0 = eq.eqat_fq_linear_fwd(Xd, Wd, sd, zd, bits, g)
+    dX0 = eq.eqat_fq_linear_bwd(Xd, Wd, sd, zd, dYd, bits, g, want=("dX",))["dX"]
+    Xb, dYb = Xd.clone(), dYd.clone()
+    Xb[7, :] = float("inf"); Xb[7, 1] = float("nan")
+    dYb[7, :] = float("-inf"); dYb[7, 0] = float("nan")
+    Y1 = eq.eqat_fq_linear_fwd(Xb, Wd, sd, zd, bits, g)
+    dX1 = eq.eqat_fq_linear_bwd(Xb, Wd, sd, zd, dYb, bits, g, want=("dX",))["dX"]
+    Wp, zp = eq.eqat_pack(Wd, sd, zd, bits, g)
+    Yq1 = eq.eqat_qlinear_fwd(Xb, Wp, sd, zp, bits, g)
+    torch.cuda.synchronize()
+    keep = [t for t in range(T) if t != 7]
+    assert torch.equal(Y1[keep], Y0[keep]) and torch.equal(dX1[keep], dX0[keep]) and torch.equal(Yq1[keep], Y0[keep])
+    assert not torch.isfinite(Y1[7].float()).any() and not torch.isfinite(dX1[7].float()).any()
+
+
 def test_block_ap_outputs_are_optional_and_deterministic():
     X, W, s, z, dY = make_case("opt", 140, 256, 136, 2, 64, torch.bfloat16, torch.bfloat16)
     Xd, Wd, sd, zd, dYd = dev(X), dev(W), dev(s), dev(z), dev(dY)

@@ -193,6 +193,8 @@ def test_block_ap_steps_of_one_linear_against_the_oracle_and_the_loss_goes_down(
             assert abs(loss.item() - loss_o) <= 2e-2 * loss_o
             assert relerr(out["dW"], gr_o["dW"]) <= 2e-2 and relerr(out["ds"], gr_o["ds"]) <= 2e-2
             assert relerr(out["dz"], gr_o["dz"]) <= 2e-2
+        if step == 1:
+            g_gpu = {k: npf(out[k]) for k in ("dW", "ds", "dz")}          # the gradients the update is about to consume
         h = eq.AdamW(lr_w, lr_q, 0.9, 0.999, 1e-8, 0.0, 0.0, step)
         eq.eqat_block_ap_update(h, bits, g, W=Wd, dW=out["dW"], mW=mom[0], vW=mom[1], s=sd, ds=out["ds"], ms=mom[2],
                                 vs=mom[3], z=zd, dz=out["dz"], mz=mom[4], vz=mom[5])
@@ -201,11 +203,19 @@ def test_block_ap_steps_of_one_linear_against_the_oracle_and_the_loss_goes_down(
             for name, got, p0, gk, lr in (("W", Wd, npf(W), "dW", lr_w), ("s", sd, s0, "ds", lr_q), ("z", zd, z0, "dz", lr_q)):
                 p, m, v = oracle.adamw(p0, gr_o[gk].astype(np.float32), np.zeros(p0.shape), np.zeros(p0.shape), f32(lr),
                                        f32(0.9), f32(0.999), f32(1e-8), 0.0, 1, p_min=oracle.S_MIN if name == "s" else -np.inf)
-                # the first Adam step moves every parameter by lr * g / (|g| + eps): exactly lr wherever the two
-                # sides agree on the sign of the gradient, which bf16 gradients may not where g is next to zero
+                # The first Adam step moves every parameter by lr * g / (|g| + eps), i.e. by lr in the direction of the
+                # gradient's sign.  Against the oracle's own chain the two sides can therefore differ by at most 2 lr
+                # (where bf16 gradients next to zero disagree on the sign), and by nothing else:
                 diff = np.abs(npf(got).astype(np.float64) - p)
                 assert diff.max() <= 2.001 * lr + 2.0 ** -22 * np.abs(p).max(), name
-                assert np.mean(diff > 1e-3 * lr + 2.0 ** -22 * np.abs(p)) < 0.03, name
+                # ... and fed the very gradients the GPU computed, the oracle's update reproduces the GPU's to the
+                # fp32 bar (1e-5 of the step, which is what the update changes; plus the parameter's own rounding)
+                q = oracle.adamw(p0, g_gpu[gk], np.zeros(p0.shape), np.zeros(p0.shape), f32(lr), f32(0.9), f32(0.999), f32(1e-8),
+                                 0.0, 1, p_min=oracle.S_MIN if name == "s" else -np.inf)[0]
+                moved = np.abs(npf(got).astype(np.float64) - q)
+                tiny = np.abs(g_gpu[gk]) < 1e-6          # lr * g / (|g| + eps) is steep where |g| is of eps's size (1e-8)
+                if (~tiny).any():       # (dz is all zeros here: right after min/max initialisation nothing is clamped)
+                    assert moved[~tiny].max() <= 1e-5 * lr + 2.0 ** -23 * np.abs(q).max(), name
         losses.append(loss)
     torch.cuda.synchronize()
     losses = [l.item() for l in losses]
