@@ -142,6 +142,7 @@ def measured_peaks(torch, dev, args):
     out["copy_kernel_gbs"] = round(2.0 * nbytes / (t["median_ms"] * 1e-3) / 1e9, 1)      # bytes read + bytes written
     t = time_steps(torch, lambda: dst.copy_(src), 20, 3)
     out["runtime_copy_gbs"] = round(2.0 * nbytes / (t["median_ms"] * 1e-3) / 1e9, 1)
+    out["copy_gbs"] = max(out["copy_kernel_gbs"], out["runtime_copy_gbs"])      # the reference of every frac_of_measured_copy
     out["note"] = ("median of 20 launches by HIP events; copy rates count bytes read plus bytes written of a 1 GiB buffer; "
                    "published peaks: 2500 TFLOP/s dense bf16, 8000 GB/s")
     return out
@@ -210,7 +211,7 @@ def main():
         qb = sum_io * (2 + 8.0 / g + bits / 8 + 1.0 / 8 + 8.0 / g)
         gbs = qb / (prof["quantize"][0] / args.steps * 1e-3) / 1e9
         kernels["quantize"].update({"approx_gbs": round(gbs, 1), "frac_of_hbm_peak": round(gbs / PEAK_HBM_GBS, 4),
-                                    "frac_of_measured_copy": round(gbs / peaks["copy_kernel_gbs"], 4) if peaks.get("copy_kernel_gbs") else None})
+                                    "frac_of_measured_copy": round(gbs / peaks["copy_gbs"], 4) if peaks.get("copy_gbs") else None})
 
     result = {
         "metric": "quantized-linear fwd+bwd TFLOP/s (% bf16 MFMA peak) and tokens/s per layer",
@@ -335,7 +336,7 @@ def hbm_row(torch, eq, fn, nbytes, args, peaks):
     gbs = nbytes / gpu / 1e9
     return {"kernel_ms": round(gpu * 1e3, 4), "wall_ms": round(wall * 1e3, 4), "gbs": round(gbs, 1),
             "frac_of_hbm_peak": round(gbs / PEAK_HBM_GBS, 4),
-            "frac_of_measured_copy": round(gbs / peaks["copy_kernel_gbs"], 4) if peaks.get("copy_kernel_gbs") else None,
+            "frac_of_measured_copy": round(gbs / peaks["copy_gbs"], 4) if peaks.get("copy_gbs") else None,
             "bytes": nbytes, "kernels_ms": {k: round(v[0] / args.steps, 4) for k, v in prof.items()}}
 
 

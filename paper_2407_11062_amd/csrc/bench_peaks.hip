@@ -73,7 +73,7 @@ int eqat_peak_mfma_loop(const void *data, size_t data_bytes, int groups, int ite
 int eqat_peak_copy(void *dst, const void *src, size_t bytes, void *stream)
 {
     if (dst == nullptr || src == nullptr || bytes % 16 != 0 || bytes == 0) return 1;
-    k_copy<<<dim3(256 * 8), dim3(256), 0, (hipStream_t)stream>>>((const uintx4 *)src, (uintx4 *)dst, bytes / 16);
+    k_copy<<<dim3(256 * 16), dim3(256), 0, (hipStream_t)stream>>>((const uintx4 *)src, (uintx4 *)dst, bytes / 16);
     return hipGetLastError() == hipSuccess ? 0 : 1;
 }
 

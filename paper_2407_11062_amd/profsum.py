@@ -89,6 +89,11 @@ def traffic(out_json, workload, fetch_csv, write_csv, copy_fetch_csv, copy_write
         for lab, v in acc.items():
             per[lab][key] = sum(v) / len(v)
             per[lab]["n"] = len(v)
+    try:                                   # other workloads already in the file stay
+        prior = json.load(open(out_json))
+        out.update({k: v for k, v in prior.items() if k != "_comment"})
+    except (OSError, ValueError):
+        pass
     out[workload] = {lab: int(round(d["fetch"] + d["write"])) for lab, d in per.items()}
     out[workload + "_detail"] = {lab: {"fetch_bytes": int(round(d["fetch"])), "write_bytes": int(round(d["write"])),
                                        "launches_sampled": d["n"]} for lab, d in per.items()}
