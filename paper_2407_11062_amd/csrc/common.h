@@ -19,6 +19,7 @@ typedef int intx4 __attribute__((ext_vector_type(4)));
 typedef int intx3 __attribute__((ext_vector_type(3)));
 typedef int intx2 __attribute__((ext_vector_type(2)));
 typedef unsigned int uintx4 __attribute__((ext_vector_type(4)));
+typedef unsigned int uintx2 __attribute__((ext_vector_type(2)));
 
 // Offset that is out of range for every buffer this library binds (tensors are < 2 GiB):
 // a buffer load from it returns zeros.

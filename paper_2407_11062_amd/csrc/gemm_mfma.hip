@@ -626,40 +626,76 @@ struct GemmDwArgs {
     int direct;           // 1: every group lies inside one tile -> final ds/dz; 0: per-32-column partials
 };
 
-template <typename WT> struct WQuad;     // four consecutive weights of one row
-template <> struct WQuad<bf16_t> {
-    float v[4];
-    __device__ __forceinline__ void load(__amdgpu_buffer_rsrc_t r, uint32_t elem)
+// The epilogue of the Block-AP kernel reads W and writes dW through LDS.  In the accumulator layout a lane holds one
+// weight ROW (out-feature) and four consecutive in-features per quad, so straight from the registers every load or
+// store instruction would touch 32 different rows, 8 or 16 bytes of each.  Instead a wave moves the W rows it needs as
+// whole 128- or 256-byte row pieces (16 bytes per lane, straight into LDS), picks its quads out of LDS, puts the dW
+// quads back in their place and writes the rows out the way they came in.
+// A unit = 32 rows x UB blocks of 32 in-features, RBY bytes per row; a wave owns two unit-sized LDS slots.  The 16-byte
+// chunks of a row are XOR-swizzled with (row >> 1) so that the 32 lanes of a quad read (32 rows, same chunk) spread
+// over all banks (two rows share a chunk position: the 2-way conflict of an 8-byte access by 32 lanes is the minimum).
+template <typename WT, int MI> struct DwStage {
+    static constexpr int kEB = (int)sizeof(WT);
+    static constexpr int UB = (8 / kEB) < MI ? (8 / kEB) : MI;       // blocks per unit: rows of at most 256 bytes
+    static constexpr int RBY = UB * 32 * kEB;                         // 128 or 256
+    static constexpr int CPR = RBY / 16, RPI = 64 / CPR, NIU = 32 / RPI;   // chunks per row, rows per instruction, instructions
+    static constexpr int UNIT_BYTES = 32 * RBY;
+    static constexpr int UPJ = MI / UB;                               // units per 32-row block column of the wave
+    static_assert(MI % UB == 0 && RBY <= 256 && UNIT_BYTES == NIU * 1024, "unit geometry");
+    // byte offset (inside a slot) of chunk 0 of this lane's row, with the row's swizzle and the lane's half folded in:
+    // the 16-byte chunk c (bf16: the 8-byte half h of it) is at  lane_base ^ (c * 16)
+    static __device__ __forceinline__ uint32_t lane_base(int lane)
     {
-        const intx2 u = buf_load8(r, elem * 2u);
-        v[0] = __uint_as_float((uint32_t)u[0] << 16); v[1] = __uint_as_float((uint32_t)u[0] & 0xFFFF0000u);
-        v[2] = __uint_as_float((uint32_t)u[1] << 16); v[3] = __uint_as_float((uint32_t)u[1] & 0xFFFF0000u);
+        const uint32_t ol = (uint32_t)lane & 31u, h = (uint32_t)lane >> 5, xo = ((ol >> 1) & (uint32_t)(CPR - 1)) << 4;
+        return kEB == 2 ? (ol * RBY + 8u * h) | xo : (ol * RBY) | (xo ^ (h << 4));
     }
-    // through a buffer resource: an element index past the buffer (or a resource of zero bytes) drops the store
-    static __device__ __forceinline__ void store(__amdgpu_buffer_rsrc_t r, uint32_t elem, const float (&d)[4])
+    // chunk of quad q of block ii of the unit (for fp32 the lane's half is a chunk of its own, folded into lane_base)
+    static constexpr uint32_t quad_chunk_bytes(int ii, int q) { return (uint32_t)(kEB == 2 ? ii * 4 + q : ii * 8 + 2 * q) * 16u; }
+};
+
+template <typename WT> struct WQuad;     // four consecutive weights of one row, to and from LDS
+template <> struct WQuad<bf16_t> {
+    static __device__ __forceinline__ void read(const unsigned char *p, float (&v)[4])
+    {
+        const uintx2 u = *reinterpret_cast<const uintx2 *>(p);
+        v[0] = __uint_as_float(u[0] << 16); v[1] = __uint_as_float(u[0] & 0xFFFF0000u);
+        v[2] = __uint_as_float(u[1] << 16); v[3] = __uint_as_float(u[1] & 0xFFFF0000u);
+    }
+    static __device__ __forceinline__ void write(unsigned char *p, const float (&d)[4])
     {
         floatx2 lo, hi;
         lo[0] = d[0]; lo[1] = d[1]; hi[0] = d[2]; hi[1] = d[3];
         const bf16x2 a = __builtin_convertvector(lo, bf16x2), b = __builtin_convertvector(hi, bf16x2);   // one packed convert each
-        intx2 o;
-        o[0] = __builtin_bit_cast(int, a); o[1] = __builtin_bit_cast(int, b);
-        __builtin_amdgcn_raw_buffer_store_b64(o, r, (int)(elem * 2u), 0, 0);
+        uintx2 o;
+        o[0] = __builtin_bit_cast(uint32_t, a); o[1] = __builtin_bit_cast(uint32_t, b);
+        *reinterpret_cast<uintx2 *>(p) = o;
     }
 };
 template <> struct WQuad<float> {
-    float v[4];
-    __device__ __forceinline__ void load(__amdgpu_buffer_rsrc_t r, uint32_t elem)
+    static __device__ __forceinline__ void read(const unsigned char *p, float (&v)[4])
     {
-        const intx4 u = buf_load16(r, elem * 4u);
-        v[0] = __int_as_float(u[0]); v[1] = __int_as_float(u[1]); v[2] = __int_as_float(u[2]); v[3] = __int_as_float(u[3]);
+        const floatx4 u = *reinterpret_cast<const floatx4 *>(p);
+        v[0] = u[0]; v[1] = u[1]; v[2] = u[2]; v[3] = u[3];
     }
-    static __device__ __forceinline__ void store(__amdgpu_buffer_rsrc_t r, uint32_t elem, const float (&d)[4])
+    static __device__ __forceinline__ void write(unsigned char *p, const float (&d)[4])
     {
-        intx4 o;
-        o[0] = __float_as_int(d[0]); o[1] = __float_as_int(d[1]); o[2] = __float_as_int(d[2]); o[3] = __float_as_int(d[3]);
-        __builtin_amdgcn_raw_buffer_store_b128(o, r, (int)(elem * 4u), 0, 0);
+        *reinterpret_cast<floatx4 *>(p) = floatx4{d[0], d[1], d[2], d[3]};
     }
 };
+
+// LDS the dW kernel asks for: the K loop's tile ring, or (Block-AP) the epilogue's stage plus the group-sum partials.
+template <typename WT, bool BLOCK_AP, int BM, int BN, int BK, int NS, int WGM, int WGN>
+constexpr size_t dw_stage_bytes()
+{
+    return BLOCK_AP ? (size_t)WGM * WGN * 2 * DwStage<WT, BM / WGM / 32>::UNIT_BYTES : 0;
+}
+template <typename WT, bool BLOCK_AP, int BM, int BN, int BK, int NS, int WGM, int WGN>
+constexpr size_t dw_smem_bytes()
+{
+    const size_t ring = (size_t)NS * BK * (BM + BN) * sizeof(bf16_t);
+    const size_t epi = dw_stage_bytes<WT, BLOCK_AP, BM, BN, BK, NS, WGM, WGN>() + (size_t)2 * (BM / 32) * BN * sizeof(float);
+    return ring > epi ? ring : epi;
+}
 
 // ---- KM tile filled by direct-to-LDS loads ------------------------------------------------------------------
 // Tile [BK][COLS] bf16, rows unpadded.  A transpose read touches four consecutive k rows, 64 bytes of each, so
@@ -845,44 +881,115 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_dw(const GemmDwArgs a)
     wait_all_and_barrier();   // tile buffers become the partial-sum arrays
 
     // ---- epilogue ----------------------------------------------------------------------------------
-    float *p_ds = reinterpret_cast<float *>(smem_raw);            // [BM/32][BN]
+    using SG = DwStage<WT, MI>;
+    constexpr uint32_t kStageBytes = (uint32_t)dw_stage_bytes<WT, BLOCK_AP, BM, BN, BK, NS, WGM, WGN>();
+    float *p_ds = reinterpret_cast<float *>(smem_raw + kStageBytes);      // [BM/32][BN]
     float *p_dz = p_ds + (BM / 32) * BN;
     const __amdgpu_buffer_rsrc_t rC = make_rsrc(a.codes, a.codes_bytes);
     const __amdgpu_buffer_rsrc_t rS = make_rsrc(a.sz, a.sz_bytes);
-    const __amdgpu_buffer_rsrc_t rW = make_rsrc(a.W, a.w_bytes);
     const __amdgpu_buffer_rsrc_t rB = make_rsrc(a.clampbits, a.clamp_bytes);
     const __amdgpu_buffer_rsrc_t rDW = make_rsrc(a.dW, a.dW != nullptr ? a.w_bytes : 0u);    // no dW wanted: stores dropped
+    const RawRsrc rWraw = make_raw_rsrc(a.W, a.w_bytes);
     const uint32_t code_row_bytes = (uint32_t)a.I / 32u * (4u * WorkCodes<BITS>::kWords);
     const int h = lane >> 5;
+    const int ibw = m0 + wm * WTM;                             // first in-feature of this wave
 
-    // Two passes per output row of the wave: first EVERY global load of its MI blocks is issued (codes, (s, zbar), clamp
-    // bits, the 16 weights of this lane per block), then the blocks are worked through as the data arrives.  One block
-    // at a time (load, wait, compute, store, next block) put two memory round trips and the acknowledgement of the
-    // previous block's stores on the critical path of each of the 8 blocks.
-    struct BlockOps { WorkCodes<BITS> cw; intx2 sv; uint32_t ncl; WQuad<WT> wq[4]; };
+    // What a lane needs of its weight row for the MI blocks of one block column j, fetched with few, wide loads: the
+    // codes and the clamp bits of the MI blocks lie side by side in memory.  (Blocks past the end of a row read what
+    // follows, or zeros past the buffer; their accumulators and their W are zero, so whatever the codes are the sums
+    // come out as zero, and nothing of such a block is stored.)
+    constexpr int CODE_WORDS = MI * WorkCodes<BITS>::kWords, CODE_LOADS = (CODE_WORDS + 3) / 4;
+    struct RowOps { uint32_t cw[CODE_LOADS * 4]; intx2 sv[MI]; uint32_t ncl[MI]; };
+    auto load_row_ops = [&](int j, RowOps &r) {
+        const int o = n0 + wn * WTN + j * 32 + (lane & 31);
+        const bool row_ok = o < a.O && ibw < a.I;
+        const uint32_t c0 = (uint32_t)o * code_row_bytes + (uint32_t)(ibw >> 5) * (4u * WorkCodes<BITS>::kWords);
+#pragma unroll
+        for (int q = 0; q < CODE_LOADS; ++q) {
+            if constexpr (CODE_WORDS % 4 == 0) {
+                const intx4 v = buf_load16(rC, row_ok ? c0 + 16u * q : kOobOffset);
+                r.cw[4 * q] = v[0]; r.cw[4 * q + 1] = v[1]; r.cw[4 * q + 2] = v[2]; r.cw[4 * q + 3] = v[3];
+            } else {
+                static_assert(CODE_WORDS % 4 == 0 || CODE_WORDS == 2, "code words per wave row");
+                const intx2 v = buf_load8(rC, row_ok ? c0 : kOobOffset);
+                r.cw[0] = v[0]; r.cw[1] = v[1]; r.cw[2] = 0u; r.cw[3] = 0u;
+            }
+        }
+        if constexpr (BLOCK_AP) {
+            const uint32_t b0 = (uint32_t)o * (uint32_t)(a.I >> 3) + (uint32_t)(ibw >> 3);
+            if constexpr (MI == 4) {
+                const intx4 v = buf_load16(rB, row_ok ? b0 : kOobOffset);
+                r.ncl[0] = v[0]; r.ncl[1] = v[1]; r.ncl[2] = v[2]; r.ncl[3] = v[3];
+            } else if constexpr (MI == 2) {
+                const intx2 v = buf_load8(rB, row_ok ? b0 : kOobOffset);
+                r.ncl[0] = v[0]; r.ncl[1] = v[1];
+            } else {
+#pragma unroll
+                for (int i = 0; i < MI; ++i) r.ncl[i] = (uint32_t)buf_load4(rB, row_ok ? b0 + 4u * i : kOobOffset);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < MI; ++i) {
+            const int ib = ibw + i * 32;
+            r.sv[i] = buf_load8(rS, (o < a.O && ib < a.I) ? ((uint32_t)o * (uint32_t)a.G + (uint32_t)(ib / a.g)) * 8u : kOobOffset);
+        }
+    };
+
+    // W rows of unit u = (j, v): global byte offset of this lane's 16-byte chunk, per instruction
+    auto unit_offsets = [&](int u, uint32_t (&off)[SG::NIU]) {
+        const int j = u / SG::UPJ, v = u % SG::UPJ;
+#pragma unroll
+        for (int k = 0; k < SG::NIU; ++k) {
+            const int r = k * SG::RPI + lane / SG::CPR, c = (lane % SG::CPR) ^ ((r >> 1) & (SG::CPR - 1));
+            const int o = n0 + wn * WTN + j * 32 + r, i0 = ibw + v * SG::UB * 32 + c * (16 / SG::kEB);
+            off[k] = (o < a.O && i0 < a.I) ? ((uint32_t)o * (uint32_t)a.I + (uint32_t)i0) * (uint32_t)SG::kEB : kOobOffset;
+        }
+    };
+    const uint32_t stage_lds = lds_addr_of(smem_raw);
+    auto slot_bytes = [&](int slot) { return (uint32_t)((wave * 2 + slot) * SG::UNIT_BYTES); };
+    auto issue_unit = [&](int slot, const uint32_t (&off)[SG::NIU]) {
+#pragma unroll
+        for (int k = 0; k < SG::NIU; ++k) load_to_lds16_at(rWraw, stage_lds + slot_bytes(slot) + (uint32_t)(k * 1024), off[k]);
+    };
+
+    constexpr int NU = BLOCK_AP ? NI * SG::UPJ : 0;
+    uint32_t goff[2][SG::NIU];
+    if constexpr (BLOCK_AP) {
+        // the first two units start to stream in at once; a later one follows when its slot has been written out
+        unit_offsets(0, goff[0]);
+        issue_unit(0, goff[0]);
+        if constexpr (NU > 1) {
+            unit_offsets(1, goff[1]);
+            issue_unit(1, goff[1]);
+        }
+    }
+    RowOps rops[2];
+    load_row_ops(0, rops[0]);
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_waitcnt(0x0070);            // the compiler does not see the loads into LDS: wait for them here
+    asm volatile("" ::: "memory");
+    const uint32_t lane_base = SG::lane_base(lane);
+
 #pragma unroll
     for (int j = 0; j < NI; ++j) {
         const int ol = wn * WTN + j * 32 + (lane & 31), o = n0 + ol;
-        BlockOps ops[MI];
+        if (j + 1 < NI) load_row_ops(j + 1, rops[(j + 1) & 1]);      // under this column's arithmetic
+        const RowOps &ro = rops[j & 1];
 #pragma unroll
         for (int i = 0; i < MI; ++i) {
-            const int ib = m0 + wm * WTM + i * 32;                 // first of 32 in-features; whole block valid or not
+            const int ib = ibw + i * 32;                           // first of 32 in-features; whole block valid or not
             const bool valid = (o < a.O) && (ib < a.I);
-            ops[i].cw = load_work_codes<BITS>(rC, valid ? (uint32_t)o * code_row_bytes + (uint32_t)(ib >> 5) * (4u * WorkCodes<BITS>::kWords) : kOobOffset);
-            ops[i].sv = buf_load8(rS, valid ? ((uint32_t)o * (uint32_t)a.G + (uint32_t)(ib / a.g)) * 8u : kOobOffset);
+            [[maybe_unused]] const int u = j * SG::UPJ + i / SG::UB, ii = i % SG::UB, slot = u & 1;
             if constexpr (BLOCK_AP) {
-                ops[i].ncl = (uint32_t)buf_load4(rB, valid ? (uint32_t)o * (uint32_t)(a.I >> 3) + (uint32_t)(ib >> 3) : kOobOffset);
-#pragma unroll
-                for (int q = 0; q < 4; ++q)
-                    ops[i].wq[q].load(rW, valid ? (uint32_t)o * (uint32_t)a.I + (uint32_t)(ib + 8 * q + 4 * h) : (kOobOffset / (uint32_t)sizeof(WT)));
+                if (ii == 0 && u >= 2) {       // this unit's rows were requested when its slot became free (below)
+                    asm volatile("" ::: "memory");
+                    __builtin_amdgcn_s_waitcnt(0x0070);
+                    asm volatile("" ::: "memory");
+                }
             }
-        }
-        __builtin_amdgcn_sched_barrier(0);
+            WorkCodes<BITS> cw;
 #pragma unroll
-        for (int i = 0; i < MI; ++i) {
-            const int ib = m0 + wm * WTM + i * 32;
-            const bool valid = (o < a.O) && (ib < a.I);
-            const WorkCodes<BITS> &cw = ops[i].cw;
+            for (int k = 0; k < WorkCodes<BITS>::kWords; ++k) cw.w[k] = ro.cw[i * WorkCodes<BITS>::kWords + k];
             // this lane owns codes 8a + 4h + b (a, b in 0..3): four consecutive codes per a, h fields further along
             const uint32_t pre = (uint32_t)h * WorkCodes<BITS>::kField;
             uint32_t cq[4] = {cw.four(0, pre), cw.four(8, pre), cw.four(16, pre), cw.four(24, pre)};
@@ -890,13 +997,13 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_dw(const GemmDwArgs a)
             // conversions (v_cvt_f32_ubyte0..3, one instruction per code) would each need an extract in front
 #pragma unroll
             for (int q = 0; q < 4; ++q) asm volatile("" : "+v"(cq[q]));
-            const float s = __int_as_float(ops[i].sv[0]), zb = __int_as_float(ops[i].sv[1]);
+            const float s = __int_as_float(ro.sv[i][0]), zb = __int_as_float(ro.sv[i][1]);
             float sum_s = 0.0f, sum_z = 0.0f;
             if constexpr (BLOCK_AP) {
                 // keep-bits: 1 where Eq.(1) did NOT clamp the weight
-                const uint32_t ncl = ~(ops[i].ncl >> (4 * h));
+                const uint32_t ncl = ~(ro.ncl[i] >> (4 * h));
                 const float rinv = valid ? 1.0f / s : 0.0f;
-                const WQuad<WT> (&wq)[4] = ops[i].wq;
+                const uint32_t quads = slot_bytes(slot) + lane_base;       // chunk bits are clear in slot_bytes
                 // Per weight, with keep = all ones where it was not clamped (one bit-field extract) and bitwise ANDs
                 // in place of selects:  du = D & keep (this is dW),  cs = (q - (w & keep) / s) - zbar, which is
                 // r - w/s in range and r = q - zbar where clamped,  sum over clamped D = sum D - sum du.
@@ -906,7 +1013,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_dw(const GemmDwArgs a)
         const float d = acc[i][j][(Q) * 4 + (B)];                                                         \
         const uint32_t keep = (uint32_t)((int32_t)(ncl << (31 - ((Q) * 8 + (B)))) >> 31);                 \
         const float du = __uint_as_float(__float_as_uint(d) & keep);                                      \
-        const float wm = __uint_as_float(__float_as_uint(wq[Q].v[B]) & keep);                             \
+        const float wm = __uint_as_float(__float_as_uint(wv[B]) & keep);                                  \
         const float cs = __builtin_fmaf(-wm, rinv, byte_to_float(cq[Q], B)) - zb;                         \
         sum_s = __builtin_fmaf(d, cs, sum_s);                                                             \
         sum_d += d;                                                                                       \
@@ -915,10 +1022,11 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_dw(const GemmDwArgs a)
     }
 #define EQAT_QUAD(Q)                                                                                      \
     {                                                                                                     \
-        float dwv[4];                                                                                     \
+        unsigned char *const cell = smem_raw + (quads ^ SG::quad_chunk_bytes(ii, (Q)));                   \
+        float wv[4], dwv[4];                                                                              \
+        WQuad<WT>::read(cell, wv);                                                                        \
         EQAT_ELEM(Q, 0) EQAT_ELEM(Q, 1) EQAT_ELEM(Q, 2) EQAT_ELEM(Q, 3)                                   \
-        WQuad<WT>::store(rDW, valid ? (uint32_t)o * (uint32_t)a.I + (uint32_t)(ib + 8 * (Q) + 4 * h)      \
-                                    : (kOobOffset / (uint32_t)sizeof(WT)), dwv);                          \
+        WQuad<WT>::write(cell, dwv);                                                                      \
     }
                 EQAT_QUAD(0) EQAT_QUAD(1) EQAT_QUAD(2) EQAT_QUAD(3)
 #undef EQAT_QUAD
@@ -941,6 +1049,26 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_dw(const GemmDwArgs a)
             if (h == 0) {
                 p_ds[(wm * MI + i) * BN + ol] = sum_s;
                 p_dz[(wm * MI + i) * BN + ol] = sum_z;
+            }
+            if constexpr (BLOCK_AP) {
+                if (ii == SG::UB - 1) {
+                    // The unit is complete: dW sits where W sat.  Rows go out the way they came in.  LDS accesses of a
+                    // wave complete in order, so the reads below see the quads every lane of the wave has written.
+                    asm volatile("" ::: "memory");
+                    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                    for (int k = 0; k < SG::NIU; ++k) {
+                        const intx4 v = *reinterpret_cast<const intx4 *>(smem_raw + slot_bytes(slot) + (uint32_t)(k * 1024 + lane * 16));
+                        __builtin_amdgcn_raw_buffer_store_b128(v, rDW, (int)goff[slot][k], 0, 0);
+                    }
+                    if (u + 2 < NU) {
+                        asm volatile("" ::: "memory");
+                        __builtin_amdgcn_s_waitcnt(0xC07F);          // lgkmcnt(0): the slot has been read out
+                        asm volatile("" ::: "memory");
+                        unit_offsets(u + 2, goff[slot]);
+                        issue_unit(slot, goff[slot]);
+                    }
+                }
             }
             __builtin_amdgcn_sched_barrier(0);     // one 32x32 block at a time
         }
@@ -1083,7 +1211,7 @@ void launch_q_bits(int bits, const GemmQArgs &a, hipStream_t st)
 template <int BITS, typename WT, bool AP, typename TS>
 void launch_dw_t(const GemmDwArgs &args, hipStream_t st)
 {
-    constexpr size_t smem = (size_t)TS::NS * TS::BK * (TS::BM + TS::BN) * sizeof(bf16_t);
+    constexpr size_t smem = dw_smem_bytes<WT, AP, TS::BM, TS::BN, TS::BK, TS::NS, TS::WGM, TS::WGN>();
     static_assert(smem <= 160 * 1024, "LDS of one CU");
     auto kern = k_gemm_dw<BITS, WT, AP, TS::BM, TS::BN, TS::BK, TS::NS, TS::WGM, TS::WGN>;
     static uint64_t attr_done = 0;
