@@ -928,10 +928,14 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_dw(const GemmDwArgs a)
                 for (int i = 0; i < MI; ++i) r.ncl[i] = (uint32_t)buf_load4(rB, row_ok ? b0 + 4u * i : kOobOffset);
             }
         }
+        // (s, zbar) of each block's group: one load per group the wave's blocks touch (wave-uniform branches)
+        int grp_prev = -1;
 #pragma unroll
         for (int i = 0; i < MI; ++i) {
-            const int ib = ibw + i * 32;
-            r.sv[i] = buf_load8(rS, (o < a.O && ib < a.I) ? ((uint32_t)o * (uint32_t)a.G + (uint32_t)(ib / a.g)) * 8u : kOobOffset);
+            const int ib = ibw + i * 32, grp = ib < a.I ? ib / a.g : -1 - i;
+            if (i > 0 && grp == grp_prev) r.sv[i] = r.sv[i - 1];
+            else r.sv[i] = buf_load8(rS, (o < a.O && ib < a.I) ? ((uint32_t)o * (uint32_t)a.G + (uint32_t)grp) * 8u : kOobOffset);
+            grp_prev = grp;
         }
     };
 
