@@ -105,20 +105,31 @@ def kernel_table(prof, flop_per_launch, peaks):
     return out
 
 
-def measured_peaks(torch, dev, args):
-    """What this chip gives, in this run: (a) a loop of nothing but v_mfma_f32_32x32x16_bf16, two waves per SIMD on all
-    compute units, on all-zero and on random bf16 operands (the clock the chip holds depends on the bits it multiplies);
-    (b) a plain copy kernel and the runtime's device copy on a 1 GiB buffer.  Bench-only kernels (libeqat_peaks.so)."""
+def peaks_lib():
+    """The bench-only kernels (MFMA loop, copy, read): a library of their own, not part of libeqat.so."""
     import ctypes
     path = os.path.join(ROOT, "paper_2407_11062_amd", "libeqat_peaks.so")
     if not os.path.exists(path):
-        return {"error": "libeqat_peaks.so not built"}
+        return None
     L = ctypes.CDLL(path)
     vp = ctypes.c_void_p
     L.eqat_peak_mfma_flop.restype = ctypes.c_double
     L.eqat_peak_mfma_flop.argtypes = [ctypes.c_int, ctypes.c_int]
     L.eqat_peak_mfma_loop.argtypes = [vp, ctypes.c_size_t, ctypes.c_int, ctypes.c_int, vp, vp]
     L.eqat_peak_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
+    L.eqat_peak_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
+    return L
+
+
+def measured_peaks(torch, dev, args):
+    """What this chip gives, in this run: (a) a loop of nothing but v_mfma_f32_32x32x16_bf16, two waves per SIMD on all
+    compute units, on all-zero and on random bf16 operands (the clock the chip holds depends on the bits it multiplies);
+    (b) a plain copy kernel and the runtime's device copy on a 1 GiB buffer.  Bench-only kernels (libeqat_peaks.so)."""
+    import ctypes
+    L = peaks_lib()
+    if L is None:
+        return {"error": "libeqat_peaks.so not built"}
+    vp = ctypes.c_void_p
     cus = torch.cuda.get_device_properties(dev).multi_processor_count
     groups, iters = cus, 20000                      # one workgroup of 8 waves per compute unit; about 1 ms per launch
     sink = torch.zeros(1, dtype=torch.float32, device=dev)
@@ -143,6 +154,9 @@ def measured_peaks(torch, dev, args):
     t = time_steps(torch, lambda: dst.copy_(src), 20, 3)
     out["runtime_copy_gbs"] = round(2.0 * nbytes / (t["median_ms"] * 1e-3) / 1e9, 1)
     out["copy_gbs"] = max(out["copy_kernel_gbs"], out["runtime_copy_gbs"])      # the reference of every frac_of_measured_copy
+    rsink = torch.zeros(1, dtype=torch.int32, device=dev)
+    t = time_steps(torch, lambda: L.eqat_peak_read(vp(src.data_ptr()), nbytes, vp(rsink.data_ptr()), stream()), 20, 3)
+    out["read_kernel_gbs"] = round(nbytes / (t["median_ms"] * 1e-3) / 1e9, 1)              # bytes read only
     out["note"] = ("median of 20 launches by HIP events; copy rates count bytes read plus bytes written of a 1 GiB buffer; "
                    "published peaks: 2500 TFLOP/s dense bf16, 8000 GB/s")
     return out
@@ -529,7 +543,10 @@ DECODE_SHAPES = [(4096, 4096, 9), (11008, 4096, 21), (5120, 5120, 11), (13824, 5
 def decode_rows(torch, eq, bits, g, dev, args):
     """eqat_qlinear_fwd on ONE token at the six shapes of the paper's matrix-vector table: HBM-bound, N/8 bytes per weight.
     Enough copies of each packed matrix are cycled through that nothing is served from the 256 MB last-level cache."""
+    import ctypes
     out = {}
+    L, vp = peaks_lib(), ctypes.c_void_p
+    rsink = torch.zeros(1, dtype=torch.int32, device=dev)
     for O, I, a100_us in DECODE_SHAPES:
         G = I // g
         wb = O * I * bits // 8
@@ -548,24 +565,41 @@ def decode_rows(torch, eq, bits, g, dev, args):
 
         # A launch lasts 5-25 us: host launch cost and per-kernel timing events would dominate, so one pass over all the
         # copies is captured in a HIP graph and replayed; the time per launch includes the gap between two kernels.
-        run(); torch.cuda.synchronize()
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph):
-            run()
-        graph.replay(); torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        reps = 5
-        e0.record()
-        for _ in range(reps):
-            graph.replay()
-        e1.record(); torch.cuda.synchronize()
-        k_us = e0.elapsed_time(e1) * 1e3 / (reps * copies)
-        del graph
+        def replay_us(fn):
+            fn(); torch.cuda.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                fn()
+            graph.replay(); torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            reps = 5
+            e0.record()
+            for _ in range(reps):
+                graph.replay()
+            e1.record(); torch.cuda.synchronize()
+            del graph
+            return e0.elapsed_time(e1) * 1e3 / (reps * copies)
+
+        k_us = replay_us(run)
         nbytes = wb + O * G * 4 + O * 4 * ((G * bits + 31) // 32) + I * 2 + O * 2      # codes, s (fp32), z, x, y
-        out[f"{O}x{I}"] = {"us_per_launch": round(k_us, 2), "gbs": round(nbytes / k_us / 1e3, 1),
-                           "frac_of_hbm_peak": round(nbytes / k_us / 1e3 / PEAK_HBM_GBS, 4), "bytes": nbytes,
-                           "paper_a100_int2_us": a100_us}
+        row = {"us_per_launch": round(k_us, 2), "gbs": round(nbytes / k_us / 1e3, 1),
+               "frac_of_hbm_peak": round(nbytes / k_us / 1e3 / PEAK_HBM_GBS, 4), "bytes": nbytes,
+               "paper_a100_int2_us": a100_us}
         del Wps
+        if L is not None:
+            # what a kernel that does nothing but read the same number of bytes once reaches, measured the same way
+            rbytes = (nbytes + 15) // 16 * 16
+            bufs = [torch.randint(0, 256, (rbytes,), dtype=torch.uint8, device=dev, generator=gen) for _ in range(copies)]
+
+            def read_all():
+                for b in bufs:
+                    assert L.eqat_peak_read(vp(b.data_ptr()), rbytes, vp(rsink.data_ptr()), vp(torch.cuda.current_stream().cuda_stream)) == 0
+
+            r_us = replay_us(read_all)
+            row["read_only_kernel_us"] = round(r_us, 2)
+            row["frac_of_read_only_kernel"] = round(r_us / k_us, 4)
+            del bufs
+        out[f"{O}x{I}"] = row
     return out
 
 

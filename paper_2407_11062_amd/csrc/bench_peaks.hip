@@ -1,6 +1,6 @@
 // Measurement aids for bench.py, built into their own library (libeqat_peaks.so), not part of libeqat.so:
 // what this very chip, at the clocks it holds under this very load, gives (a) a loop of nothing but
-// v_mfma_f32_32x32x16_bf16 and (b) a plain device copy.  bench.py quotes every roofline fraction against the
+// v_mfma_f32_32x32x16_bf16, (b) a plain device copy and (c) a kernel that only reads.  bench.py quotes every roofline fraction against the
 // published peaks (2.5 PFLOP/s, 8 TB/s) and against these two.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -53,6 +53,24 @@ __global__ __launch_bounds__(256) void k_copy(const uintx4 *__restrict__ src, ui
     for (; i < n_vec; i += stride) dst[i] = src[i];
 }
 
+// Reads `n_vec` 16-byte vectors once (eight loads in flight per lane) and keeps nothing: what a kernel that only has to
+// fetch that many bytes can reach, launch and ramp-up included.
+__global__ __launch_bounds__(256) void k_read(const uintx4 *__restrict__ src, size_t n_vec, uint32_t *__restrict__ sink)
+{
+    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * 256;
+    uintx4 acc = {0u, 0u, 0u, 0u};
+    for (; i + 7 * stride < n_vec; i += 8 * stride) {
+        uintx4 v[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) v[q] = src[i + q * stride];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) acc ^= v[q];
+    }
+    for (; i < n_vec; i += stride) acc ^= src[i];
+    if ((acc[0] ^ acc[1] ^ acc[2] ^ acc[3]) == 0x9E3779B9u) sink[0] = acc[0];      // keeps the loads alive; practically never true
+}
+
 }  // namespace
 
 extern "C" {
@@ -74,6 +92,17 @@ int eqat_peak_copy(void *dst, const void *src, size_t bytes, void *stream)
 {
     if (dst == nullptr || src == nullptr || bytes % 16 != 0 || bytes == 0) return 1;
     k_copy<<<dim3(256 * 16), dim3(256), 0, (hipStream_t)stream>>>((const uintx4 *)src, (uintx4 *)dst, bytes / 16);
+    return hipGetLastError() == hipSuccess ? 0 : 1;
+}
+
+// src: device, 16-byte aligned, bytes a multiple of 16; sink: one word, device.
+int eqat_peak_read(const void *src, size_t bytes, void *sink, void *stream)
+{
+    if (src == nullptr || sink == nullptr || bytes % 16 != 0 || bytes == 0) return 1;
+    const size_t n_vec = bytes / 16;
+    size_t groups = (n_vec + 256 * 8 - 1) / (256 * 8);         // one trip of eight loads per lane, unless that needs too many workgroups
+    if (groups > 256 * 16) groups = 256 * 16;
+    k_read<<<dim3((unsigned)groups), dim3(256), 0, (hipStream_t)stream>>>((const uintx4 *)src, n_vec, (uint32_t *)sink);
     return hipGetLastError() == hipSuccess ? 0 : 1;
 }
 

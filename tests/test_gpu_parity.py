@@ -602,6 +602,12 @@ GEMV_CASES = [
     ("v6", 1, 96, 8, 3, 96),               # a single, partly filled chunk; one 8-row block
     ("v7", 4, 2048, 264, 4, 32),
     ("v8", 7, 160, 24, 3, 32),
+    # a row gets one wave per 1024 inputs, up to 16: five waves, eleven (the last run ragged), eight with 4-bit codes,
+    # and more runs than waves (two trips for some waves: the down projection of the 70B block)
+    ("v9", 2, 5120, 48, 2, 64),
+    ("v10", 1, 11008, 40, 3, 128),
+    ("v11", 3, 8192, 32, 4, 64),
+    ("v12", 1, 28672, 24, 2, 64),
 ]
 
 
