@@ -21,6 +21,7 @@ namespace eqat {
 
 constexpr int kPadKC = 8;    // bf16 elements
 constexpr int kPadKM = 32;
+constexpr uint32_t kStoreStageBytes = 2048;   // per wave: one 32 x 32 bf16 block of the result on its way out
 
 // ---- fragment reads ---------------------------------------------------------------------------------
 // KC tile: lane l supplies row (l % 32), k = kk*16 + (l / 32) * 8 .. + 8
@@ -217,7 +218,7 @@ struct GemmQArgs {
     const bf16_t *A; const uint32_t *codes; const floatx2 *sz; bf16_t *C;
     int M, N, K;           // problem
     int I, G, g;           // weight matrix geometry: row length, groups per row, group size
-    uint32_t a_bytes, codes_bytes, sz_bytes;
+    uint32_t a_bytes, codes_bytes, sz_bytes, c_bytes;
     int tiles_m, tiles_n;
     int band;              // tile rows walked together by one XCD (see tile_of_xcd_slot)
     SkPlan sk;             // which tiles, or parts of tiles, a workgroup computes
@@ -298,6 +299,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_q(const GemmQArgs a)
 {
     constexpr int NT = 64 * WGM * WGN, NW = WGM * WGN, WTM = BM / WGM, WTN = BN / WGN, MI = WTM / 32, NI = WTN / 32;
     constexpr int LDB = BT ? BN + kPadKM : BK + kPadKC;
+    constexpr uint32_t kRingBytes = 2u * (uint32_t)(BM * BK + (BT ? BK * LDB : BN * LDB)) * 2u;    // the two K-tile buffers
     constexpr int A_ELEMS = BM * BK, B_ELEMS = BT ? BK * LDB : BN * LDB;
     constexpr int A_LOADS = BM / 8 / NW;              // direct-to-LDS instructions per wave (8 rows each)
     constexpr int B_SEGS = BN * BK / 32 / NT;         // 32-code segments per thread
@@ -338,6 +340,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_q(const GemmQArgs a)
     };
 
     const RawRsrc rA = make_raw_rsrc(a.A, a.a_bytes);
+    const __amdgpu_buffer_rsrc_t rCst = make_rsrc(a.C, a.c_bytes);
     const __amdgpu_buffer_rsrc_t rC = make_rsrc(a.codes, a.codes_bytes);
     const __amdgpu_buffer_rsrc_t rS = make_rsrc(a.sz, a.sz_bytes);
     const uint32_t code_row_bytes = (uint32_t)a.I / 32u * (4u * WorkCodes<BITS>::kWords);
@@ -590,20 +593,35 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_q(const GemmQArgs a)
             continue;
         }
 
-        // C[m][n]: lane holds column n = l % 32 and rows 8*(r/4) + 4*(l/32) + r%4 of each 32x32 block
+        // C[m][n]: lane holds column n = l % 32 and rows 8*(r/4) + 4*(l/32) + r%4 of each 32x32 block.  Stored from
+        // the registers that is sixteen 2-byte stores per block, each to two rows; instead the block goes through a
+        // 2 KB patch of LDS of the wave's own (behind the tile ring, which the loads of the next tile are filling) and
+        // leaves as two 16-byte stores per lane, 64 bytes of a row from four neighbouring lanes.
+        {
+            unsigned char *const stg = smem_raw + kRingBytes + wave * kStoreStageBytes;
+            bf16_t *const cell = reinterpret_cast<bf16_t *>(stg) + (lane >> 5) * (4 * 32) + (lane & 31);
 #pragma unroll
-        for (int i = 0; i < MI; ++i)
+            for (int i = 0; i < MI; ++i)
 #pragma unroll
-            for (int j = 0; j < NI; ++j) {
-                const int n = n0 + wn * WTN + j * 32 + (lane & 31);
+                for (int j = 0; j < NI; ++j) {
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int m = m0 + wm * WTM + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-                    if (m < a.M && n < a.N) a.C[(size_t)m * a.N + n] = (bf16_t)acc[i][j][r];
-                    acc[i][j][r] = 0.0f;
+                    for (int r = 0; r < 16; ++r) {
+                        cell[(8 * (r >> 2) + (r & 3)) * 32] = (bf16_t)acc[i][j][r];
+                        acc[i][j][r] = 0.0f;
+                    }
+                    asm volatile("" ::: "memory");
+                    __builtin_amdgcn_wave_barrier();       // LDS accesses of a wave complete in order
+#pragma unroll
+                    for (int k = 0; k < 2; ++k) {
+                        const intx4 v = *reinterpret_cast<const intx4 *>(stg + k * 1024 + lane * 16);
+                        const int m = m0 + wm * WTM + i * 32 + k * 16 + (lane >> 2), n = n0 + wn * WTN + j * 32 + (lane & 3) * 8;
+                        const uint32_t off = (m < a.M && n < a.N) ? ((uint32_t)m * (uint32_t)a.N + (uint32_t)n) * 2u : kOobOffset;
+                        __builtin_amdgcn_raw_buffer_store_b128(v, rCst, (int)off, 0, 0);
+                    }
+                    asm volatile("" ::: "memory");
+                    __builtin_amdgcn_sched_barrier(0);     // one 32x32 block at a time: keeps the accumulator copies few
                 }
-                __builtin_amdgcn_sched_barrier(0);     // one 32x32 block at a time: keeps the accumulator copies few
-            }
+        }
     }
     __builtin_amdgcn_s_waitcnt(0x0070);       // the loads issued past the last tile (all zeros) have landed too
 }
@@ -1180,8 +1198,11 @@ template <int BITS, bool BT, typename TS>
 void launch_q(const GemmQArgs &args, hipStream_t st)
 {
     constexpr int LDB = BT ? TS::BN + kPadKM : TS::BK + kPadKC;
-    constexpr size_t smem = 2 * (size_t)(TS::BM * TS::BK + (BT ? TS::BK * LDB : TS::BN * LDB)) * sizeof(bf16_t);
+    constexpr size_t smem = 2 * (size_t)(TS::BM * TS::BK + (BT ? TS::BK * LDB : TS::BN * LDB)) * sizeof(bf16_t) +
+                            (size_t)TS::WGM * TS::WGN * kStoreStageBytes;
+    static_assert(smem + 64 <= 160 * 1024, "LDS of one CU");
     GemmQArgs a = args;
+    a.c_bytes = (uint32_t)((size_t)a.M * a.N * 2);
     a.tiles_m = (a.M + TS::BM - 1) / TS::BM;
     a.tiles_n = (a.N + TS::BN - 1) / TS::BN;
     a.band = 8;
