@@ -14,7 +14,9 @@
  *              s,z [O,G] with G = I/g, Y,dY [T,O], dX [T,I], dW [O,I],
  *              ds,dz [O,G].  Group j of row o covers columns [j*g,(j+1)*g).
  *   Memory     Every pointer is a DEVICE pointer owned by the caller, 16-byte
- *              aligned.  The library never allocates, frees or keeps a pointer.
+ *              aligned.  The library never allocates or frees device memory and
+ *              keeps no pointer of the caller (the optional timing aid at the end
+ *              of this header creates HIP event objects while it is switched on).
  *              Each tensor must be smaller than 2 GiB.
  *   Dtypes     X,Y,dY,dX have desc.act_dtype; W,dW have desc.w_dtype; s,z,ds,dz
  *              are always fp32.  act bf16 selects the MFMA path (needs O % 8 == 0);
@@ -329,7 +331,8 @@ eqat_status eqat_block_ap_update(const eqat_desc *d, const eqat_adamw *h, void *
  * eqat_profile_stop() waits for those events and writes, per kernel class k in
  * [0, eqat_profile_kernels()), the summed elapsed milliseconds and the number of
  * launches into host arrays of length n; it then switches timing off.  Event
- * objects are created on first use and kept.  Not thread-safe.
+ * objects are created on first use and kept until the process ends.  The calls
+ * may come from several threads; a session is process-wide (one start, one stop).
  */
 int eqat_profile_kernels(void);
 const char *eqat_profile_kernel_name(int k);

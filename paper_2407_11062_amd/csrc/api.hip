@@ -6,32 +6,42 @@
 #include "prof.h"
 
 #include <atomic>
+#include <mutex>
 #include <vector>
 
 using eqat::Problem;
 using eqat::ProfScope;
 
 namespace eqat {
-bool g_prof_on = false;
+std::atomic<bool> g_prof_on{false};
 namespace {
-struct ProfRec { hipEvent_t a, b; int kernel; };
+struct ProfRec { hipEvent_t a, b; int kernel; bool closed; };
+std::mutex g_prof_mutex;         // guards the two below
 std::vector<ProfRec> g_recs;     // event pairs, reused between profiling sessions
 size_t g_used = 0;
 }  // namespace
-void prof_mark(int kernel, hipStream_t st, bool begin)
+int prof_begin(int kernel, hipStream_t st)
 {
-    if (begin) {
-        if (g_used == g_recs.size()) {
-            ProfRec r{};
-            if (hipEventCreate(&r.a) != hipSuccess || hipEventCreate(&r.b) != hipSuccess) { g_prof_on = false; return; }
-            g_recs.push_back(r);
-        }
-        g_recs[g_used].kernel = kernel;
-        (void)hipEventRecord(g_recs[g_used].a, st);
-    } else if (g_used < g_recs.size()) {
-        (void)hipEventRecord(g_recs[g_used].b, st);
-        ++g_used;
+    std::lock_guard<std::mutex> lock(g_prof_mutex);
+    if (!g_prof_on.load(std::memory_order_relaxed)) return -1;
+    if (g_used == g_recs.size()) {
+        ProfRec r{};
+        if (hipEventCreate(&r.a) != hipSuccess) { g_prof_on = false; return -1; }
+        if (hipEventCreate(&r.b) != hipSuccess) { (void)hipEventDestroy(r.a); g_prof_on = false; return -1; }
+        g_recs.push_back(r);
     }
+    const int rec = (int)g_used++;
+    g_recs[rec].kernel = kernel;
+    g_recs[rec].closed = false;
+    (void)hipEventRecord(g_recs[rec].a, st);
+    return rec;
+}
+void prof_end(int rec, hipStream_t st)
+{
+    std::lock_guard<std::mutex> lock(g_prof_mutex);
+    if (rec < 0 || (size_t)rec >= g_used) return;             // the session was stopped in between
+    (void)hipEventRecord(g_recs[rec].b, st);
+    g_recs[rec].closed = true;
 }
 }  // namespace eqat
 
@@ -179,6 +189,7 @@ const char *eqat_profile_kernel_name(int k)
 
 eqat_status eqat_profile_start(void)
 {
+    std::lock_guard<std::mutex> lock(eqat::g_prof_mutex);
     eqat::g_used = 0;
     eqat::g_prof_on = true;
     return EQAT_OK;
@@ -186,17 +197,20 @@ eqat_status eqat_profile_start(void)
 
 eqat_status eqat_profile_stop(double *total_ms, int64_t *launches, int n)
 {
+    std::lock_guard<std::mutex> lock(eqat::g_prof_mutex);
     eqat::g_prof_on = false;
+    const size_t used = eqat::g_used;
+    eqat::g_used = 0;
     if (total_ms == nullptr || launches == nullptr) return EQAT_ERR_NULL;
     for (int k = 0; k < n; ++k) { total_ms[k] = 0.0; launches[k] = 0; }
     eqat_status rc = EQAT_OK;
-    for (size_t i = 0; i < eqat::g_used; ++i) {
+    for (size_t i = 0; i < used; ++i) {
         const eqat::ProfRec &r = eqat::g_recs[i];
+        if (!r.closed) continue;                                  // a launch of another thread still under way
         float ms = 0.0f;
         if (hipEventSynchronize(r.b) != hipSuccess || hipEventElapsedTime(&ms, r.a, r.b) != hipSuccess) { rc = EQAT_ERR_DEVICE; continue; }
-        if (r.kernel < n) { total_ms[r.kernel] += ms; launches[r.kernel] += 1; }
+        if (r.kernel >= 0 && r.kernel < n) { total_ms[r.kernel] += ms; launches[r.kernel] += 1; }
     }
-    eqat::g_used = 0;
     return rc;
 }
 
