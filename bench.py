@@ -324,13 +324,14 @@ def pack_block(torch, eq, layers, bits, g, T2, dev):
 
 
 def run_e2e_step(eq, layers, packed, bits, g, zf=None, outs=None):
-    """fwd + bwd (dX, ds; with float zero points zf also dz) of every linear on its prepared layer."""
+    """fwd + bwd (dX, ds; with float zero points zf also dz) of every linear on its prepared layer; the (s, z) pairs the
+    forward made are kept for the backward (one pairing launch per linear and step)."""
     for k, (L, P) in enumerate(zip(layers, packed)):
         z = None if zf is None else zf[k]
-        eq.eqat_qlinear_fwd_prepared(P["X"], P["prep"], L["s"], L["O"], bits, g, z=z, Y=P["Y"], ws=P["ws_b"])
+        eq.eqat_qlinear_fwd_prepared(P["X"], P["prep"], L["s"], L["O"], bits, g, z=z, Y=P["Y"], ws=P["ws_b"], keep=True)
         eq.eqat_qlinear_bwd_prepared(P["X"], P["prep"], L["s"], P["dY"], L["I"], bits, g, z=z,
                                      want=("dX", "ds") if z is None else ("dX", "ds", "dz"),
-                                     out=P["out"] if outs is None else outs[k], ws=P["ws_b"])
+                                     out=P["out"] if outs is None else outs[k], ws=P["ws_b"], kept=True)
 
 
 def hbm_row(torch, eq, fn, nbytes, args, peaks):

@@ -230,6 +230,11 @@ eqat_status eqat_qlinear_bwd_kept(const eqat_desc *d, const void *X, const uint8
  *                          The tiled GEMM always runs (no few-token kernel).  The prepared layer is only read, except for
  *                          a few counters inside it that a launch uses and leaves at zero: calls on the same prepared
  *                          layer must not overlap in time (different streams need their own copy).
+ *   eqat_qlinear_fwd_prepared_keep / eqat_qlinear_bwd_prepared_kept
+ *                          The same two calls for a training step that runs both on unchanged (s, z): the forward takes
+ *                          a workspace of EQAT_OP_QP_BWD size and leaves the pairs in it; the backward, given the same
+ *                          workspace untouched and the same s and z, skips the pairing launch.  Results are bitwise
+ *                          those of the plain pair.  With tokens = 0 the _keep call still writes the pairs.
  */
 size_t eqat_prepared_bytes(const eqat_desc *d);
 eqat_status eqat_qlinear_prepare(const eqat_desc *d, const uint8_t *Wpacked, const uint8_t *zpacked, void *prepared,
@@ -237,6 +242,11 @@ eqat_status eqat_qlinear_prepare(const eqat_desc *d, const uint8_t *Wpacked, con
 eqat_status eqat_qlinear_fwd_prepared(const eqat_desc *d, const void *X, const void *prepared, const float *s,
                                       const float *z, void *Y, void *ws, size_t ws_bytes, void *stream);
 eqat_status eqat_qlinear_bwd_prepared(const eqat_desc *d, const void *X, const void *prepared, const float *s,
+                                      const float *z, const void *dY, void *dX, float *ds, float *dz,
+                                      void *ws, size_t ws_bytes, void *stream);
+eqat_status eqat_qlinear_fwd_prepared_keep(const eqat_desc *d, const void *X, const void *prepared, const float *s,
+                                      const float *z, void *Y, void *ws, size_t ws_bytes, void *stream);
+eqat_status eqat_qlinear_bwd_prepared_kept(const eqat_desc *d, const void *X, const void *prepared, const float *s,
                                       const float *z, const void *dY, void *dX, float *ds, float *dz,
                                       void *ws, size_t ws_bytes, void *stream);
 

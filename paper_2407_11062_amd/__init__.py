@@ -29,7 +29,8 @@ EXPORTS = ["eqat_status_string", "eqat_validate_desc", "eqat_packed_w_bytes", "e
            "eqat_init_minmax_batched", "eqat_pack_batched", "eqat_fq_quantize_batched",
            "eqat_unpack", "eqat_qlinear_fwd", "eqat_qlinear_bwd", "eqat_qlinear_fwd_keep", "eqat_qlinear_bwd_kept",
            "eqat_qlinear_fwd_z", "eqat_qlinear_bwd_z", "eqat_prepared_bytes", "eqat_qlinear_prepare",
-           "eqat_qlinear_fwd_prepared", "eqat_qlinear_bwd_prepared", "eqat_unpack_state",
+           "eqat_qlinear_fwd_prepared", "eqat_qlinear_bwd_prepared", "eqat_qlinear_fwd_prepared_keep",
+           "eqat_qlinear_bwd_prepared_kept", "eqat_unpack_state",
            "eqat_recon_loss_workspace_bytes", "eqat_recon_loss", "eqat_recon_loss_static", "eqat_block_ap_update",
            "eqat_profile_kernels", "eqat_profile_kernel_name",
            "eqat_profile_start", "eqat_profile_stop"]
@@ -93,6 +94,8 @@ def lib():
         L.eqat_qlinear_prepare.argtypes = [dp, vp, vp, vp, sz, vp]
         L.eqat_qlinear_fwd_prepared.argtypes = [dp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.eqat_qlinear_bwd_prepared.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.eqat_qlinear_fwd_prepared_keep.argtypes = L.eqat_qlinear_fwd_prepared.argtypes
+        L.eqat_qlinear_bwd_prepared_kept.argtypes = L.eqat_qlinear_bwd_prepared.argtypes
         L.eqat_unpack_state.argtypes = [dp, ctypes.c_int, vp, vp, vp, vp, vp]
         L.eqat_recon_loss_workspace_bytes.restype, L.eqat_recon_loss_workspace_bytes.argtypes = sz, []
         L.eqat_recon_loss.argtypes = [ctypes.c_int64, ctypes.c_int32, vp, vp, vp, vp, vp, sz, vp]
@@ -316,18 +319,22 @@ def eqat_qlinear_prepare(Wpacked, zpacked, in_features, bits, group, act_dtype=B
     return prepared
 
 
-def eqat_qlinear_fwd_prepared(X, prepared, s, out_features, bits, group, z=None, Y=None, ws=None):
+def eqat_qlinear_fwd_prepared(X, prepared, s, out_features, bits, group, z=None, Y=None, ws=None, keep=False):
+    """keep=True: eqat_qlinear_fwd_prepared_keep (ws of OP_QP_BWD size, left holding the (s, z) pairs)."""
     T, I = X.shape
     O = int(out_features)
     d = make_desc(T, I, O, bits, group, _dt(X), BF16)
     Y = torch.empty((T, O), dtype=X.dtype, device=X.device) if Y is None else Y
-    ws = workspace(d, OP_QP_FWD, X.device) if ws is None else ws
-    _check("eqat_qlinear_fwd_prepared", lib().eqat_qlinear_fwd_prepared(
+    ws = workspace(d, OP_QP_BWD if keep else OP_QP_FWD, X.device) if ws is None else ws
+    name = "eqat_qlinear_fwd_prepared_keep" if keep else "eqat_qlinear_fwd_prepared"
+    _check(name, getattr(lib(), name)(
         ctypes.byref(d), _p(X), _p(prepared), _p(s), _p(z), _p(Y), _p(ws), ws.numel(), _stream()))
     return Y
 
 
-def eqat_qlinear_bwd_prepared(X, prepared, s, dY, in_features, bits, group, z=None, want=("dX", "ds"), out=None, ws=None):
+def eqat_qlinear_bwd_prepared(X, prepared, s, dY, in_features, bits, group, z=None, want=("dX", "ds"), out=None, ws=None,
+                              kept=False):
+    """kept=True: eqat_qlinear_bwd_prepared_kept (ws as eqat_qlinear_fwd_prepared_keep left it, same s and z)."""
     T, O = dY.shape
     I = int(in_features)
     d = make_desc(T, I, O, bits, group, _dt(dY), BF16)
@@ -337,7 +344,8 @@ def eqat_qlinear_bwd_prepared(X, prepared, s, dY, in_features, bits, group, z=No
     if "ds" in want and "ds" not in out: out["ds"] = torch.empty((O, G), dtype=torch.float32, device=dY.device)
     if "dz" in want and "dz" not in out: out["dz"] = torch.empty((O, G), dtype=torch.float32, device=dY.device)
     ws = workspace(d, OP_QP_BWD, dY.device) if ws is None else ws
-    _check("eqat_qlinear_bwd_prepared", lib().eqat_qlinear_bwd_prepared(
+    name = "eqat_qlinear_bwd_prepared_kept" if kept else "eqat_qlinear_bwd_prepared"
+    _check(name, getattr(lib(), name)(
         ctypes.byref(d), _p(X), _p(prepared), _p(s), _p(z), _p(dY), _p(out.get("dX")), _p(out.get("ds")), _p(out.get("dz")),
         _p(ws), ws.numel(), _stream()))
     return out

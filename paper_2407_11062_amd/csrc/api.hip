@@ -491,9 +491,10 @@ eqat_status eqat_qlinear_prepare(const eqat_desc *d, const uint8_t *Wpacked, con
 }
 
 // Operands of a call on a prepared layer; enqueues the small launch that pairs the current step sizes with the zero
-// points (`z` NULL: those the layer was prepared with; else trained zero points, as floats).
+// points (`z` NULL: those the layer was prepared with; else trained zero points, as floats) unless the workspace still
+// holds the pairs of a forward call that kept them.
 static eqat_status prepared_operands(const Problem &p, const void *prepared, const float *s, const float *z, int op, void *ws,
-                                     size_t ws_bytes, hipStream_t st, QOperands *q)
+                                     size_t ws_bytes, hipStream_t st, QOperands *q, bool make_pairs = true)
 {
     EQAT_REQUIRE(prepared);
     if (!aligned(prepared, 256)) return EQAT_ERR_ALIGN;
@@ -507,26 +508,41 @@ static eqat_status prepared_operands(const Problem &p, const void *prepared, con
                             pl.sk_ctr_bytes != 0 ? (uint32_t *)(p8 + pl.sk_ctr) : nullptr};
     q->part = (float *)(w8 + l.part);
     q->dwhat = (float *)(w8 + l.dwhat);
-    qlinear_prepare_into(p, nullptr, s, nullptr, z != nullptr ? z : (const float *)(p8 + pl.zb), nullptr, w8 + l.sz, nullptr, 0, st);
+    if (make_pairs)
+        qlinear_prepare_into(p, nullptr, s, nullptr, z != nullptr ? z : (const float *)(p8 + pl.zb), nullptr, w8 + l.sz, nullptr, 0, st);
     return EQAT_OK;
 }
 
-eqat_status eqat_qlinear_fwd_prepared(const eqat_desc *d, const void *X, const void *prepared, const float *s, const float *z,
-                                      void *Y, void *ws, size_t ws_bytes, void *stream)
+// keep: the workspace has the backward's size and layout, so that a backward call finds the pairs where it looks for them
+static eqat_status fwd_prepared_any(const eqat_desc *d, const void *X, const void *prepared, const float *s, const float *z,
+                                    void *Y, void *ws, size_t ws_bytes, void *stream, bool keep)
 {
     Problem p;
     if (eqat_status e = check_desc(d, true, &p)) return e;
     EQAT_REQUIRE(s);
     if (p.T > 0) { EQAT_REQUIRE(X); EQAT_REQUIRE(Y); }
     EQAT_ALIGNED(X); EQAT_ALIGNED(s); EQAT_ALIGNED(z); EQAT_ALIGNED(Y);
-    if (p.T == 0) return prepared == nullptr ? EQAT_ERR_NULL : EQAT_OK;
+    if (p.T == 0 && !keep) return prepared == nullptr ? EQAT_ERR_NULL : EQAT_OK;
     QOperands q{};
-    if (eqat_status e = prepared_operands(p, prepared, s, z, EQAT_OP_QP_FWD, ws, ws_bytes, (hipStream_t)stream, &q)) return e;
+    if (eqat_status e = prepared_operands(p, prepared, s, z, keep ? EQAT_OP_QP_BWD : EQAT_OP_QP_FWD, ws, ws_bytes, (hipStream_t)stream, &q)) return e;
     return qlinear_fwd_run(p, X, s, q, Y, (hipStream_t)stream);
 }
 
-eqat_status eqat_qlinear_bwd_prepared(const eqat_desc *d, const void *X, const void *prepared, const float *s, const float *z,
-                                      const void *dY, void *dX, float *ds, float *dz, void *ws, size_t ws_bytes, void *stream)
+eqat_status eqat_qlinear_fwd_prepared(const eqat_desc *d, const void *X, const void *prepared, const float *s, const float *z,
+                                      void *Y, void *ws, size_t ws_bytes, void *stream)
+{
+    return fwd_prepared_any(d, X, prepared, s, z, Y, ws, ws_bytes, stream, false);
+}
+
+eqat_status eqat_qlinear_fwd_prepared_keep(const eqat_desc *d, const void *X, const void *prepared, const float *s, const float *z,
+                                           void *Y, void *ws, size_t ws_bytes, void *stream)
+{
+    return fwd_prepared_any(d, X, prepared, s, z, Y, ws, ws_bytes, stream, true);
+}
+
+static eqat_status bwd_prepared_any(const eqat_desc *d, const void *X, const void *prepared, const float *s, const float *z,
+                                    const void *dY, void *dX, float *ds, float *dz, void *ws, size_t ws_bytes, void *stream,
+                                    bool kept)
 {
     Problem p;
     if (eqat_status e = check_desc(d, true, &p)) return e;
@@ -536,8 +552,20 @@ eqat_status eqat_qlinear_bwd_prepared(const eqat_desc *d, const void *X, const v
     EQAT_ALIGNED(X); EQAT_ALIGNED(s); EQAT_ALIGNED(z); EQAT_ALIGNED(dY); EQAT_ALIGNED(dX); EQAT_ALIGNED(ds); EQAT_ALIGNED(dz);
     if (dX == nullptr && !want_g) return prepared == nullptr ? EQAT_ERR_NULL : EQAT_OK;
     QOperands q{};
-    if (eqat_status e = prepared_operands(p, prepared, s, z, EQAT_OP_QP_BWD, ws, ws_bytes, (hipStream_t)stream, &q)) return e;
+    if (eqat_status e = prepared_operands(p, prepared, s, z, EQAT_OP_QP_BWD, ws, ws_bytes, (hipStream_t)stream, &q, !kept)) return e;
     return qlinear_bwd_run(p, X, s, q, dY, dX, ds, dz, (hipStream_t)stream);
+}
+
+eqat_status eqat_qlinear_bwd_prepared(const eqat_desc *d, const void *X, const void *prepared, const float *s, const float *z,
+                                      const void *dY, void *dX, float *ds, float *dz, void *ws, size_t ws_bytes, void *stream)
+{
+    return bwd_prepared_any(d, X, prepared, s, z, dY, dX, ds, dz, ws, ws_bytes, stream, false);
+}
+
+eqat_status eqat_qlinear_bwd_prepared_kept(const eqat_desc *d, const void *X, const void *prepared, const float *s, const float *z,
+                                           const void *dY, void *dX, float *ds, float *dz, void *ws, size_t ws_bytes, void *stream)
+{
+    return bwd_prepared_any(d, X, prepared, s, z, dY, dX, ds, dz, ws, ws_bytes, stream, true);
 }
 
 // Test aid: what a forward call that keeps its state, or eqat_qlinear_prepare, left behind, in plain arrays.

@@ -110,6 +110,9 @@ def test_nothing_is_written_outside_outputs_and_workspaces(tag, T, I, O, bits, g
     eq.eqat_qlinear_fwd_prepared(X, prep, s, O, bits, g, Y=Y, ws=ws[eq.OP_QP_FWD])
     eq.eqat_qlinear_bwd_prepared(X, prep, s, dY, I, bits, g, z=zf, want=("dX", "ds", "dz"), out=out, ws=ws[eq.OP_QP_BWD])
     gd.check("eqat_qlinear_fwd_prepared / _bwd_prepared")
+    eq.eqat_qlinear_fwd_prepared(X, prep, s, O, bits, g, z=zf, Y=Y, ws=ws[eq.OP_QP_BWD], keep=True)
+    eq.eqat_qlinear_bwd_prepared(X, prep, s, dY, I, bits, g, z=zf, want=("dX", "ds", "dz"), out=out, ws=ws[eq.OP_QP_BWD], kept=True)
+    gd.check("eqat_qlinear_fwd_prepared_keep / _bwd_prepared_kept")
 
     # the step glue on the same tensors
     loss = gd.new((1,), torch.float32)

@@ -483,6 +483,14 @@ def test_e2e_on_a_prepared_layer_is_bitwise_the_plain_call(tag, T, I, O, bits, g
             assert torch.equal(out[k], ref[k]), k
         for k in ("dX", "ds", "dz"):
             assert torch.equal(outz[k], refz[k]), k
+        # the pairs the forward made kept for the backward: one workspace (backward-sized), garbage in it to begin with
+        ws = torch.full_like(eq.workspace(eq.make_desc(T, I, O, bits, g, eq.BF16, eq.BF16), eq.OP_QP_BWD, Xd.device), 0xA5)
+        Yk = eq.eqat_qlinear_fwd_prepared(Xd, prep, sd, O, bits, g, z=zf, ws=ws, keep=True)
+        outk = eq.eqat_qlinear_bwd_prepared(Xd, prep, sd, dYd, I, bits, g, z=zf, want=("dX", "ds", "dz"), ws=ws, kept=True)
+        torch.cuda.synchronize()
+        assert torch.equal(Yk, Yz)
+        for k in ("dX", "ds", "dz"):
+            assert torch.equal(outk[k], refz[k]), k
 
 
 def test_e2e_on_a_prepared_layer_fp32_activations():
@@ -496,6 +504,10 @@ def test_e2e_on_a_prepared_layer_fp32_activations():
     ref = eq.eqat_qlinear_bwd(Xd, Wp, sd, zp, dYd, 128, bits, g)
     assert torch.equal(Y, eq.eqat_qlinear_fwd(Xd, Wp, sd, zp, bits, g))
     assert torch.equal(out["dX"], ref["dX"]) and torch.equal(out["ds"], ref["ds"])
+    ws = eq.workspace(eq.make_desc(70, 128, 48, bits, g, eq.F32, eq.F32), eq.OP_QP_BWD, Xd.device)
+    Yk = eq.eqat_qlinear_fwd_prepared(Xd, prep, sd, 48, bits, g, ws=ws, keep=True)
+    outk = eq.eqat_qlinear_bwd_prepared(Xd, prep, sd, dYd, 128, bits, g, ws=ws, kept=True)
+    assert torch.equal(Yk, Y) and torch.equal(outk["dX"], ref["dX"]) and torch.equal(outk["ds"], ref["ds"])
 
 
 # --------------------------------------------------------------------------- the integer state the GEMMs work from

@@ -173,6 +173,13 @@ def test_null_alignment_and_workspace_errors_come_back_before_any_launch():
     need = L.eqat_workspace_bytes(rp, eq.OP_QP_BWD)
     assert need > 0
     assert L.eqat_qlinear_bwd_prepared(rp, P, P, P, None, P, P, P, None, P, need - 1, None) == WORKSPACE
+    # ... and the pair that keeps the (s, z) pairs between forward and backward: the forward takes the backward's workspace
+    assert L.eqat_qlinear_fwd_prepared_keep(rp, P, P, P, None, P, P, need - 1, None) == WORKSPACE
+    assert L.eqat_qlinear_fwd_prepared_keep(r, P, None, P, None, P, P, 1 << 30, None) == NULL
+    assert L.eqat_qlinear_fwd_prepared_keep(r, P, P, None, None, P, P, 1 << 30, None) == NULL
+    assert L.eqat_qlinear_bwd_prepared_kept(rp, P, P, P, None, P, P, P, None, P, need - 1, None) == WORKSPACE
+    assert L.eqat_qlinear_bwd_prepared_kept(r, None, P, P, None, P, None, P, None, P, 1 << 30, None) == NULL  # ds wanted, X missing
+    assert L.eqat_qlinear_bwd_prepared_kept(r, P, P, P, None, P, None, None, None, P, 1 << 30, None) == OK    # nothing wanted
     # the test aid
     assert L.eqat_unpack_state(r, 7, P, P, None, P, None) == SHAPE
     assert L.eqat_unpack_state(r, eq.STATE_PREPARED, None, P, None, P, None) == NULL
