@@ -1206,10 +1206,11 @@ void launch_q(const GemmQArgs &args, hipStream_t st)
     a.tiles_m = (a.M + TS::BM - 1) / TS::BM;
     a.tiles_n = (a.N + TS::BN - 1) / TS::BN;
     // Tile rows that one XCD walks together.  The activation panel of a tile row is eight times heavier than the code
-    // panel of a tile column, so the 32 tiles an XCD holds at a time should span few rows and many columns: per K step
-    // it fetches (rows x 32 KB + columns x 6 KB).  4 rows x 8 columns: 176 KB; 8 x 4: 280 KB; measured, 4 and 2 are
-    // equal within noise and up to 2-4 % ahead of 8 on the 13B shapes, 16 is 3 % behind.
-    a.band = 4;
+    // panel of a tile column, so the 32 tiles an XCD holds at a time should span few rows and many columns (per K step
+    // it fetches rows x 32 KB + columns x 6 KB: 4 rows x 8 columns 176 KB, 8 x 4 280 KB), and with an eighth of the tile
+    // rows per band every XCD owns its rows outright, so that an activation panel is fetched by one XCD only.  Measured:
+    // 4 (8192 tokens) and 2 (4096 tokens) are up to 2-4 % ahead of 8; 16 is 3 % behind.
+    a.band = std::max(2, std::min(8, a.tiles_m / 8));
     // At most as many workgroups as the chip holds at once; with more tiles than that every workgroup walks several
     // (grid a multiple of 8, one share per XCD).
     const int ntiles = a.tiles_m * a.tiles_n, resident = resident_workgroups(smem);
