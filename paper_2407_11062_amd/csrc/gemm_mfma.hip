@@ -90,9 +90,15 @@ __device__ __forceinline__ void tile_of_block(int tiles_m, int tiles_n, int &tm,
 // and flag of a tile are back at zero when its second contributor is done, so a launch leaves them as it found them.
 // Whether cutting pays is a measured matter (host side, plan_tiles): a partly filled round costs less than its share
 // of a full one on this power-limited chip, and every part costs a trip of 256 KB through memory.
+// When the tiles beyond the first round are few (at most half a round), dealing out runs would cut nearly every tile of
+// the launch (1.25 rounds: 31 of 40 per XCD).  Then (`split`) every workgroup first computes one whole tile, and each
+// of the remaining tiles is shared by c = W / n_sk workgroups (at most kSkMaxSplit), a c-th of its K range each; the
+// one with the first piece waits for the others' parts and adds them in their order (a fixed order: reproducible).
+constexpr int kSkMaxSplit = 8;
 struct SkPlan {
     int walk;              // 0: the grid has one workgroup per tile and none of the below applies
     int dp_rounds;         // whole tiles per workgroup: tiles loc0 + r * (G / 8) of its XCD, r < dp_rounds
+    int split;             // 1: the tiles beyond the whole rounds are split among groups of workgroups (see above)
     int pairs;             // K-tile pairs per output tile
     float *partials;       // [G][2] accumulator tiles (a run has at most a head and a tail piece)
     uint32_t *counters;    // [2][2 G], zero: arrivals, then flags, one each per tile that may be cut (at most 2 G / 8 per XCD)
@@ -102,6 +108,7 @@ struct SkItem {
     int kb, ke;            // K-tile pairs [kb, ke) of the tile
     int parts, first;      // number of contributors (1: the whole tile is mine) and the first one's index in the XCD
     int first_slot;        // which of its two buffers the first contributor used (all others use buffer 0)
+    int fixed;             // 1: the first contributor sums (split); 0: whoever arrives second does (runs, two contributors)
 };
 __device__ __forceinline__ int sk_owner_of_pair(int p, int base, int extra)
 {
@@ -112,12 +119,24 @@ __device__ __forceinline__ int sk_owner_of_pair(int p, int base, int extra)
 __device__ __forceinline__ bool sk_item(const SkPlan &sk, int nb, int tiles_m, int tiles_n, int band, int j, SkItem &it)
 {
     const int xcd = (int)(blockIdx.x & 7), loc0 = (int)(blockIdx.x >> 3);
-    it.kb = 0; it.ke = sk.pairs; it.parts = 1; it.first = 0; it.first_slot = 0; it.ctr = 0;
+    it.kb = 0; it.ke = sk.pairs; it.parts = 1; it.first = 0; it.first_slot = 0; it.ctr = 0; it.fixed = 0;
     if (!sk.walk) return j == 0 && tile_of_xcd_slot((int)gridDim.x, xcd, loc0, tiles_m, tiles_n, it.tm, it.tn, band);
     const int W = (int)(gridDim.x >> 3);
     if (j < sk.dp_rounds) return tile_of_xcd_slot(nb, xcd, loc0 + j * W, tiles_m, tiles_n, it.tm, it.tn, band);
     const int n_sk = (nb >> 3) + (xcd < (nb & 7) ? 1 : 0) - sk.dp_rounds * W;
     if (n_sk <= 0) return false;
+    if (sk.split) {
+        if (j != sk.dp_rounds) return false;                       // one piece per workgroup
+        const int c = min(W / n_sk, kSkMaxSplit);                   // contributors per tile (at least 2: the host's choice)
+        const int t = loc0 / c, me = loc0 - t * c;
+        if (t >= n_sk) return false;
+        const int base = sk.pairs / c, extra = sk.pairs % c;
+        it.kb = me * base + min(me, extra);
+        it.ke = it.kb + base + (me < extra ? 1 : 0);
+        it.parts = c; it.first = t * c; it.fixed = 1;
+        it.ctr = xcd * 2 * W + t;
+        return tile_of_xcd_slot(nb, xcd, sk.dp_rounds * W + t, tiles_m, tiles_n, it.tm, it.tn, band);
+    }
     const int P = sk.pairs, total = n_sk * P, base = total / W, extra = total % W;
     const int start = loc0 * base + min(loc0, extra), end = start + base + (loc0 < extra ? 1 : 0);
     const int t = start / P + (j - sk.dp_rounds);
@@ -134,36 +153,34 @@ __device__ __forceinline__ bool sk_item(const SkPlan &sk, int nb, int tiles_m, i
     return tile_of_xcd_slot(nb, xcd, sk.dp_rounds * W + t, tiles_m, tiles_n, it.tm, it.tn, band);
 }
 
-// One of the two contributors of a tile cut along K is done with its K range.  Returns false in the one that arrived
-// first (its part is in memory, its work on the tile done) and true in the second, with the first one's part added to `acc`.
+// A contributor of a tile cut along K is done with its K range.  Returns true in the one that holds the sum of all
+// parts in `acc` afterwards and runs the tile's epilogue, false in the others (their part is in memory, their work on
+// the tile done).  Who sums: with two contributors of a run, the one that arrives second; in a split tile, the first.
 // Layout of a part: the float4 number q of accumulator block (i, j) of thread t at ((i * NI + j) * 4 + q) * NT + t.
-// The two may sit on different XCDs, each with its own L2, so part and flag are written and read with device-scope
-// accesses (cache policy sc1: written through to memory, read from memory); no cache is flushed or invalidated as a
-// whole (a device-scope fence writes back and invalidates the entire L2 of the XCD, operand panels included: measured,
-// that alone cost more than cutting the tiles gained).  Order on the writing side: every wave waits for its stores to
-// complete, the workgroup meets, then one thread raises the flag.
+// The contributors may sit on different XCDs, each with its own L2, so parts and flag are written and read with
+// device-scope accesses (cache policy sc1: written through to memory, read from memory); no cache is flushed or
+// invalidated as a whole (a device-scope fence writes back and invalidates the entire L2 of the XCD, operand panels
+// included: measured, that alone cost more than cutting the tiles gained).  Order on the writing side: every wave
+// waits for its stores to complete, the workgroup meets, then one thread counts the part in on the tile's flag.
 constexpr int kAuxDeviceScope = 16;      // "sc1" of the raw buffer intrinsics on gfx940 and later
 constexpr int kSkSpinLimit = 1 << 22;    // polls of ~1 us: a bound that is never reached, so that no wave can spin for ever
 __device__ __forceinline__ void wait_all_and_barrier();
 template <int MI, int NI, int NT>
 __device__ __forceinline__ bool sk_hand_in(const SkPlan &sk, const SkItem &it, floatx16 (&acc)[MI][NI], int tid)
 {
-    __shared__ uint32_t s_second;
+    __shared__ uint32_t s_sums;
     constexpr size_t kTile = (size_t)MI * NI * 16 * NT;          // floats per part
     constexpr uint32_t kTileBytes = (uint32_t)(kTile * sizeof(float));
-    const int xcd = (int)(blockIdx.x & 7), me = (int)(blockIdx.x >> 3) - it.first;       // me: 0 or 1
+    const int xcd = (int)(blockIdx.x & 7), me = (int)(blockIdx.x >> 3) - it.first;       // 0 .. parts - 1
     uint32_t *arrivals = sk.counters + it.ctr, *flag = sk.counters + 2 * (int)gridDim.x + it.ctr;
-    if (tid == 0) s_second = atomicInc(arrivals, 1u);            // 0 -> 1 -> 0
+    if (tid == 0) s_sums = it.fixed ? (me == 0 ? 1u : 0u) : atomicInc(arrivals, 1u);     // arrivals: 0 -> 1 -> 0
     __syncthreads();
-    const bool second = s_second != 0u;
+    const bool sums = s_sums != 0u;
     // Straight-line code for both roles (branches around the accumulators make the register allocator spill them):
-    // the second contributor's stores and the first one's loads go to an out-of-range offset, where a buffer store is
-    // dropped and a buffer load returns zeros.
-    const uint32_t st_base = second ? kOobOffset : (uint32_t)tid * 16u, ld_base = second ? (uint32_t)tid * 16u : kOobOffset;
-    const size_t other = (size_t)(it.first + (1 - me)) * 8 + xcd;
+    // the summing contributor's stores go to an out-of-range offset, where a buffer store is dropped.
+    const uint32_t st_base = sums ? kOobOffset : (uint32_t)tid * 16u;
     const __amdgpu_buffer_rsrc_t mine =
-        make_rsrc(sk.partials + ((size_t)blockIdx.x * 2 + (me == 0 ? it.first_slot : 0)) * kTile, kTileBytes);
-    const __amdgpu_buffer_rsrc_t theirs = make_rsrc(sk.partials + (other * 2 + (me == 1 ? it.first_slot : 0)) * kTile, kTileBytes);
+        make_rsrc(sk.partials + ((size_t)blockIdx.x * 2 + (!it.fixed && me == 0 ? it.first_slot : 0)) * kTile, kTileBytes);
 #pragma unroll
     for (int i = 0; i < MI; ++i)
 #pragma unroll
@@ -179,34 +196,42 @@ __device__ __forceinline__ bool sk_hand_in(const SkPlan &sk, const SkItem &it, f
         }
     wait_all_and_barrier();                // every store of the workgroup has completed
     if (tid == 0) {
-        if (!second) {
-            __hip_atomic_store(flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (!sums) {
+            (void)__hip_atomic_fetch_add(flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         } else {
             int polls = 0;
-            while (__hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u && ++polls < kSkSpinLimit)
+            while (__hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != (uint32_t)(it.parts - 1) && ++polls < kSkSpinLimit)
                 __builtin_amdgcn_s_sleep(32);
             __hip_atomic_store(flag, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
     __syncthreads();
-    // two 32 x 32 blocks (32 registers) in flight at a time: all of them at once would not fit beside the accumulators
+    // The others' parts, in the order of the contributors (a trip count of zero for those that do not sum).
+    const int n_take = sums ? it.parts - 1 : 0;
+    for (int k = 1; k <= n_take; ++k) {
+        const int from = it.fixed ? it.first + k : it.first + (1 - me);               // contributor whose part this is
+        const int slot = (!it.fixed && me == 1) ? it.first_slot : 0;
+        const __amdgpu_buffer_rsrc_t theirs = make_rsrc(sk.partials + (((size_t)from * 8 + xcd) * 2 + slot) * kTile, kTileBytes);
+        // Two 32 x 32 blocks (32 registers) in flight at a time.  More (two parts together, 64 registers) did not fit: the
+        // pipeline state of the next tile is alive here, and the kernels spilled or lost their second workgroup per CU.
 #pragma unroll
-    for (int b0 = 0; b0 < MI * NI; b0 += 2) {
-        intx4 v[2][4];
+        for (int b0 = 0; b0 < MI * NI; b0 += 2) {
+            intx4 v[2][4];
 #pragma unroll
-        for (int b = 0; b < 2; ++b)
+            for (int b = 0; b < 2; ++b)
 #pragma unroll
-            for (int q = 0; q < 4; ++q)
-                v[b][q] = __builtin_amdgcn_raw_buffer_load_b128(theirs, ld_base + (uint32_t)(((b0 + b) * 4 + q) * NT * 16), 0, kAuxDeviceScope);
+                for (int q = 0; q < 4; ++q)
+                    v[b][q] = __builtin_amdgcn_raw_buffer_load_b128(theirs, (uint32_t)tid * 16u + (uint32_t)(((b0 + b) * 4 + q) * NT * 16), 0, kAuxDeviceScope);
 #pragma unroll
-        for (int b = 0; b < 2; ++b)
+            for (int b = 0; b < 2; ++b)
 #pragma unroll
-            for (int q = 0; q < 4; ++q)
+                for (int q = 0; q < 4; ++q)
 #pragma unroll
-                for (int e = 0; e < 4; ++e) acc[(b0 + b) / NI][(b0 + b) % NI][4 * q + e] += __int_as_float(v[b][q][e]);
-        __builtin_amdgcn_sched_barrier(0);
+                    for (int e = 0; e < 4; ++e) acc[(b0 + b) / NI][(b0 + b) % NI][4 * q + e] += __int_as_float(v[b][q][e]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
     }
-    return second;
+    return sums;
 }
 
 // ======================================================================================================
@@ -292,7 +317,7 @@ __device__ __forceinline__ void wait_all_and_barrier()
 //     wave; fragments of slice kk+1 are read while slice kk multiplies.
 // K tiles past the end of K multiply zeros: the weights there are exactly zero (see load_a below).
 // A workgroup may own several output tiles; the pipeline then runs on through the tile boundaries.
-// CUT: the instantiation for launches that cut tiles along K (SkPlan::dp_rounds == 0 with walk) or whose contraction
+// CUT: the instantiation for launches that cut tiles along K (SkPlan::dp_rounds == 0, or split, with walk) or whose contraction
 // length is not a multiple of two K tiles; the other one carries none of that code (the main loop is sensitive to it).
 template <int BITS, bool BT, bool CUT, int BM, int BN, int BK, int WGM, int WGN>
 __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_q(const GemmQArgs a)
@@ -1191,6 +1216,9 @@ SkPlan plan_tiles(int ntiles, int pairs, int resident, float *partials, uint32_t
     const bool even = (per % W == 0) && (ntiles % 8 == 0);
     const bool cut = !even && full == 1 && pairs >= 4 && partials != nullptr && counters != nullptr;
     sk.dp_rounds = cut ? 0 : (per + (ntiles % 8 ? 1 : 0) + W - 1) / W;
+    // few tiles beyond the first round (at most half a round on every XCD): a whole tile each, then the rest split
+    const int n_sk_max = per + (ntiles % 8 ? 1 : 0) - W;
+    if (cut && n_sk_max >= 1 && 2 * n_sk_max <= W && pairs >= 2 * kSkMaxSplit) { sk.dp_rounds = 1; sk.split = 1; }
     return sk;
 }
 
@@ -1216,7 +1244,7 @@ void launch_q(const GemmQArgs &args, hipStream_t st)
     const int ntiles = a.tiles_m * a.tiles_n, resident = resident_workgroups(smem);
     a.sk = plan_tiles(ntiles, ((a.K + TS::BK - 1) / TS::BK + 1) / 2, resident, a.sk.partials, a.sk.counters);
     const dim3 grid(a.sk.walk ? resident : ntiles), block(64 * TS::WGM * TS::WGN);
-    if ((a.sk.walk && a.sk.dp_rounds == 0) || a.K % (2 * TS::BK) != 0) {
+    if ((a.sk.walk && (a.sk.dp_rounds == 0 || a.sk.split)) || a.K % (2 * TS::BK) != 0) {
         auto kern = k_gemm_q<BITS, BT, true, TS::BM, TS::BN, TS::BK, TS::WGM, TS::WGN>;
         static uint64_t attr_done = 0;
         allow_dynamic_lds(kern, smem, attr_done);

@@ -220,6 +220,11 @@ SPLIT_CASES = [
     ("cut_dw", 600, 4416, 4104, 2, 64),        # dW: 18 x 17 tiles, K = T = 600
     ("cut_small", 4096, 512, 2304, 4, 128),    # fwd: 576 tiles of 128 x 128 on 512 resident workgroups
     ("cut_dw_perchan", 520, 4352, 4096, 2, -1),  # dW, 17 x 16 tiles, one group per row (partials + reduce kernel)
+    # few tiles beyond the first round and a long K: a whole tile per workgroup, then every remaining tile split among
+    # four (small tiles: eight) workgroups, whose parts the first of them adds up in their order
+    ("split_fwd", 4400, 2048, 4104, 2, 64),    # fwd: 306 tiles, 16 K-tile pairs
+    ("split_dx", 4400, 4128, 2056, 3, 32),     # dX: 306 tiles, K = O = 2056: 17 pairs (uneven pieces, ragged last K tile)
+    ("split_small", 4096, 2048, 2304, 4, 128), # fwd: 576 tiles of 128 x 128, 16 pairs, eight contributors
 ]
 
 
@@ -230,8 +235,9 @@ def test_block_ap_and_e2e_with_tiles_cut_along_k(tag, T, I, O, bits, g):
     check_e2e(X, W, s, z, dY, bits, g, TOL[torch.bfloat16])
 
 
-def test_cut_tiles_are_deterministic_and_ignore_what_the_workspace_held():
-    tag, T, I, O, bits, g = SPLIT_CASES[2]
+@pytest.mark.parametrize("case", [2, 5, 6], ids=lambda c: SPLIT_CASES[c][0])
+def test_cut_tiles_are_deterministic_and_ignore_what_the_workspace_held(case):
+    tag, T, I, O, bits, g = SPLIT_CASES[case]
     X, W, s, z, dY = make_case(tag, T, I, O, bits, g, torch.bfloat16, torch.bfloat16)
     Xd, Wd, sd, zd, dYd = dev(X), dev(W), dev(s), dev(z), dev(dY)
     d = eq.make_desc(T, I, O, bits, g, eq.BF16, eq.BF16)
