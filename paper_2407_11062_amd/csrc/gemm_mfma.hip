@@ -1203,9 +1203,11 @@ int resident_workgroups(size_t smem)
 }
 
 // How `resident` workgroups share `ntiles` tiles of `pairs` K-tile pairs each (see SkPlan).  One workgroup per tile
-// when they all fit; otherwise whole tiles, except that between one and two rounds of tiles, with K long enough, every
-// tile is cut along K.  With more rounds cutting the last 1.x of them measured slower than leaving the last round
-// partly filled (7B gate, 5.4 rounds: -3 %; 13B gate, 3.4 rounds: -4 %; 13B q and down, 1.25 rounds: +3 to +11 %).
+// when they all fit; otherwise whole tiles, except that (K long enough)
+//   - between one and two rounds of tiles, with more than half a round beyond the first, every tile is cut along K into
+//     equal runs (with more rounds, cutting the last 1.x of them into runs measured slower than leaving the last round
+//     partly filled: 7B gate, 5.4 rounds: -3 %; 13B gate, 3.4 rounds: -4 %);
+//   - with at most half a round of tiles beyond the whole rounds, those few tiles are split among groups of workgroups.
 SkPlan plan_tiles(int ntiles, int pairs, int resident, float *partials, uint32_t *counters)
 {
     SkPlan sk{};
@@ -1214,11 +1216,14 @@ SkPlan plan_tiles(int ntiles, int pairs, int resident, float *partials, uint32_t
     sk.walk = 1;
     const int W = resident / 8, per = ntiles / 8, full = per / W;
     const bool even = (per % W == 0) && (ntiles % 8 == 0);
-    const bool cut = !even && full == 1 && pairs >= 4 && partials != nullptr && counters != nullptr;
-    sk.dp_rounds = cut ? 0 : (per + (ntiles % 8 ? 1 : 0) + W - 1) / W;
-    // few tiles beyond the first round (at most half a round on every XCD): a whole tile each, then the rest split
-    const int n_sk_max = per + (ntiles % 8 ? 1 : 0) - W;
-    if (cut && n_sk_max >= 1 && 2 * n_sk_max <= W && pairs >= 2 * kSkMaxSplit) { sk.dp_rounds = 1; sk.split = 1; }
+    const bool may_cut = !even && pairs >= 4 && partials != nullptr && counters != nullptr;
+    sk.dp_rounds = (may_cut && full == 1) ? 0 : (per + (ntiles % 8 ? 1 : 0) + W - 1) / W;
+    // Few tiles beyond the whole rounds (at most half a round on every XCD): whole tiles first, then the rest split.
+    // The tile arithmetic promises (1 - 1/c) of a round; measured, 5.4 rounds (7B gate, up) gain 2.6 %, 3.4 rounds (13B
+    // gate) 1.5-2.3 %: the partly filled round that the split replaces ran at a higher clock, and the instantiation that
+    // can cut is 1-5 % slower in its main loop.  Beyond six whole rounds the promise is smaller than that price.
+    const int n_sk_max = per + (ntiles % 8 ? 1 : 0) - full * W;
+    if (may_cut && full <= 6 && n_sk_max >= 1 && 2 * n_sk_max <= W && pairs >= 2 * kSkMaxSplit) { sk.dp_rounds = full; sk.split = 1; }
     return sk;
 }
 
