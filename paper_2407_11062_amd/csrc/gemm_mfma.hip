@@ -92,8 +92,8 @@ __device__ __forceinline__ void tile_of_block(int tiles_m, int tiles_n, int &tm,
 // of a full one on this power-limited chip, and every part costs a trip of 256 KB through memory.
 // When the tiles beyond the first round are few (at most half a round), dealing out runs would cut nearly every tile of
 // the launch (1.25 rounds: 31 of 40 per XCD).  Then (`split`) every workgroup first computes one whole tile, and each
-// of the remaining tiles is shared by c = W / n_sk workgroups (at most kSkMaxSplit), a c-th of its K range each; the
-// one with the first piece waits for the others' parts and adds them in their order (a fixed order: reproducible).
+// of the remaining tiles is shared by c = W / n_sk workgroups (at most kSkMaxSplit), a c-th of its K range each; all
+// write their parts and the one that arrives last adds them up in their order (a fixed order: reproducible).
 constexpr int kSkMaxSplit = 8;
 struct SkPlan {
     int walk;              // 0: the grid has one workgroup per tile and none of the below applies
@@ -108,7 +108,7 @@ struct SkItem {
     int kb, ke;            // K-tile pairs [kb, ke) of the tile
     int parts, first;      // number of contributors (1: the whole tile is mine) and the first one's index in the XCD
     int first_slot;        // which of its two buffers the first contributor used (all others use buffer 0)
-    int fixed;             // 1: the first contributor sums (split); 0: whoever arrives second does (runs, two contributors)
+    int fixed;             // 1: a split tile (all contributors write, the last one to arrive sums all parts); 0: a run's tile
 };
 __device__ __forceinline__ int sk_owner_of_pair(int p, int base, int extra)
 {
@@ -155,13 +155,19 @@ __device__ __forceinline__ bool sk_item(const SkPlan &sk, int nb, int tiles_m, i
 
 // A contributor of a tile cut along K is done with its K range.  Returns true in the one that holds the sum of all
 // parts in `acc` afterwards and runs the tile's epilogue, false in the others (their part is in memory, their work on
-// the tile done).  Who sums: with two contributors of a run, the one that arrives second; in a split tile, the first.
+// the tile done).
+//   Two contributors of a run: the one that arrives first writes its part and raises the tile's flag, the one that
+//   arrives second waits for the flag (for a workgroup that is already running and itself waits for nobody) and adds
+//   that part to its own accumulators (a + b = b + a).
+//   A split tile (it.fixed): every contributor writes its part and counts itself in; the one that finds itself last
+//   adds up ALL parts from memory, its own included, in the order of the contributors.  Nobody waits for anybody, and
+//   the sum does not depend on who came last.
 // Layout of a part: the float4 number q of accumulator block (i, j) of thread t at ((i * NI + j) * 4 + q) * NT + t.
 // The contributors may sit on different XCDs, each with its own L2, so parts and flag are written and read with
 // device-scope accesses (cache policy sc1: written through to memory, read from memory); no cache is flushed or
 // invalidated as a whole (a device-scope fence writes back and invalidates the entire L2 of the XCD, operand panels
 // included: measured, that alone cost more than cutting the tiles gained).  Order on the writing side: every wave
-// waits for its stores to complete, the workgroup meets, then one thread counts the part in on the tile's flag.
+// waits for its stores to complete, the workgroup meets, then one thread signals.
 constexpr int kAuxDeviceScope = 16;      // "sc1" of the raw buffer intrinsics on gfx940 and later
 constexpr int kSkSpinLimit = 1 << 22;    // polls of ~1 us: a bound that is never reached, so that no wave can spin for ever
 __device__ __forceinline__ void wait_all_and_barrier();
@@ -172,15 +178,16 @@ __device__ __forceinline__ bool sk_hand_in(const SkPlan &sk, const SkItem &it, f
     constexpr size_t kTile = (size_t)MI * NI * 16 * NT;          // floats per part
     constexpr uint32_t kTileBytes = (uint32_t)(kTile * sizeof(float));
     const int xcd = (int)(blockIdx.x & 7), me = (int)(blockIdx.x >> 3) - it.first;       // 0 .. parts - 1
+    const bool split = it.fixed != 0;
     uint32_t *arrivals = sk.counters + it.ctr, *flag = sk.counters + 2 * (int)gridDim.x + it.ctr;
-    if (tid == 0) s_sums = it.fixed ? (me == 0 ? 1u : 0u) : atomicInc(arrivals, 1u);     // arrivals: 0 -> 1 -> 0
+    if (tid == 0) s_sums = split ? 0u : atomicInc(arrivals, 1u);                          // run: 0 -> 1 -> 0
     __syncthreads();
-    const bool sums = s_sums != 0u;
-    // Straight-line code for both roles (branches around the accumulators make the register allocator spill them):
-    // the summing contributor's stores go to an out-of-range offset, where a buffer store is dropped.
-    const uint32_t st_base = sums ? kOobOffset : (uint32_t)tid * 16u;
+    const bool second = s_sums != 0u;              // of a run
+    // Straight-line code for all roles (branches around the accumulators make the register allocator spill them): the
+    // stores of the contributor that keeps its part in registers go to an out-of-range offset, where they are dropped.
+    const uint32_t st_base = second ? kOobOffset : (uint32_t)tid * 16u;
     const __amdgpu_buffer_rsrc_t mine =
-        make_rsrc(sk.partials + ((size_t)blockIdx.x * 2 + (!it.fixed && me == 0 ? it.first_slot : 0)) * kTile, kTileBytes);
+        make_rsrc(sk.partials + ((size_t)blockIdx.x * 2 + (!split && me == 0 ? it.first_slot : 0)) * kTile, kTileBytes);
 #pragma unroll
     for (int i = 0; i < MI; ++i)
 #pragma unroll
@@ -196,21 +203,36 @@ __device__ __forceinline__ bool sk_hand_in(const SkPlan &sk, const SkItem &it, f
         }
     wait_all_and_barrier();                // every store of the workgroup has completed
     if (tid == 0) {
-        if (!sums) {
-            (void)__hip_atomic_fetch_add(flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (split) {
+            const uint32_t before = __hip_atomic_fetch_add(arrivals, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const bool last = before == (uint32_t)(it.parts - 1);
+            if (last) __hip_atomic_store(arrivals, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            s_sums = last ? 1u : 0u;
+        } else if (!second) {
+            __hip_atomic_store(flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         } else {
             int polls = 0;
-            while (__hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != (uint32_t)(it.parts - 1) && ++polls < kSkSpinLimit)
+            while (__hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u && ++polls < kSkSpinLimit)
                 __builtin_amdgcn_s_sleep(32);
             __hip_atomic_store(flag, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
     __syncthreads();
-    // The others' parts, in the order of the contributors (a trip count of zero for those that do not sum).
-    const int n_take = sums ? it.parts - 1 : 0;
-    for (int k = 1; k <= n_take; ++k) {
-        const int from = it.fixed ? it.first + k : it.first + (1 - me);               // contributor whose part this is
-        const int slot = (!it.fixed && me == 1) ? it.first_slot : 0;
+    const bool sums = s_sums != 0u;
+    // the last contributor of a split tile starts from zero and takes every part, its own too, from memory (bitwise AND
+    // instead of a branch, see above)
+    const uint32_t keep = (split && sums) ? 0u : ~0u;
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NI; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = __uint_as_float(__float_as_uint(acc[i][j][r]) & keep);
+    // parts to add, in the order of the contributors (a trip count of zero for those that do not sum)
+    const int n_take = !sums ? 0 : split ? it.parts : 1;
+    for (int k = 0; k < n_take; ++k) {
+        const int from = split ? it.first + k : it.first + (1 - me);                  // contributor whose part this is
+        const int slot = (!split && me == 1) ? it.first_slot : 0;
         const __amdgpu_buffer_rsrc_t theirs = make_rsrc(sk.partials + (((size_t)from * 8 + xcd) * 2 + slot) * kTile, kTileBytes);
         // Two 32 x 32 blocks (32 registers) in flight at a time.  More (two parts together, 64 registers) did not fit: the
         // pipeline state of the next tile is alive here, and the kernels spilled or lost their second workgroup per CU.
