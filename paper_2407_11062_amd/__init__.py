@@ -30,7 +30,7 @@ EXPORTS = ["eqat_status_string", "eqat_validate_desc", "eqat_packed_w_bytes", "e
            "eqat_unpack", "eqat_qlinear_fwd", "eqat_qlinear_bwd", "eqat_qlinear_fwd_keep", "eqat_qlinear_bwd_kept",
            "eqat_qlinear_fwd_z", "eqat_qlinear_bwd_z", "eqat_prepared_bytes", "eqat_qlinear_prepare",
            "eqat_qlinear_fwd_prepared", "eqat_qlinear_bwd_prepared", "eqat_qlinear_fwd_prepared_keep",
-           "eqat_qlinear_bwd_prepared_kept", "eqat_unpack_state",
+           "eqat_qlinear_bwd_prepared_kept", "eqat_unpack_state", "eqat_plan_item",
            "eqat_recon_loss_workspace_bytes", "eqat_recon_loss", "eqat_recon_loss_static", "eqat_block_ap_update",
            "eqat_profile_kernels", "eqat_profile_kernel_name",
            "eqat_profile_start", "eqat_profile_stop"]
@@ -95,6 +95,7 @@ def lib():
         L.eqat_qlinear_fwd_prepared.argtypes = [dp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.eqat_qlinear_bwd_prepared.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.eqat_qlinear_fwd_prepared_keep.argtypes = L.eqat_qlinear_fwd_prepared.argtypes
+        L.eqat_plan_item.argtypes = [dp, ctypes.c_int, ctypes.c_int, ctypes.c_int, vp, vp]
         L.eqat_qlinear_bwd_prepared_kept.argtypes = L.eqat_qlinear_bwd_prepared.argtypes
         L.eqat_unpack_state.argtypes = [dp, ctypes.c_int, vp, vp, vp, vp, vp]
         L.eqat_recon_loss_workspace_bytes.restype, L.eqat_recon_loss_workspace_bytes.argtypes = sz, []

@@ -568,6 +568,19 @@ eqat_status eqat_qlinear_bwd_prepared_kept(const eqat_desc *d, const void *X, co
     return bwd_prepared_any(d, X, prepared, s, z, dY, dX, ds, dz, ws, ws_bytes, stream, true);
 }
 
+// Test aid (host only): how a fwd / dX launch divides its work.
+eqat_status eqat_plan_item(const eqat_desc *d, int gemm, int block, int j, int32_t *item, int32_t *exists)
+{
+    Problem p;
+    if (eqat_status e = check_desc(d, true, &p)) return e;
+    if (item == nullptr || exists == nullptr) return EQAT_ERR_NULL;
+    if (d->act_dtype != EQAT_BF16) return EQAT_ERR_DTYPE;            // the fp32 path has one workgroup per tile
+    const int rc = eqat::plan_item_for_test(p, gemm, block, j, item);
+    if (rc < 0) return EQAT_ERR_SHAPE;
+    *exists = rc;
+    return EQAT_OK;
+}
+
 // Test aid: what a forward call that keeps its state, or eqat_qlinear_prepare, left behind, in plain arrays.
 eqat_status eqat_unpack_state(const eqat_desc *d, int kind, const void *state, int32_t *codes, uint8_t *clamped, float *zbar,
                               void *stream)

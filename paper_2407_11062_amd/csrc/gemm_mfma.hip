@@ -61,13 +61,13 @@ __device__ __forceinline__ bf16x8 frag_km(const bf16_t *tile, int col0, int kk, 
 // contiguous range of tile ids, then walk the tiles in bands of kBand tile-rows so that the tiles resident on
 // one XCD at a time share their operand panels.
 // nb = number of tiles; (xcd, loc) = the loc-th tile of XCD xcd.  Returns false past the end of that XCD's range.
-__device__ __forceinline__ bool tile_of_xcd_slot(int nb, int xcd, int loc, int tiles_m, int tiles_n, int &tm, int &tn, int kBand)
+__host__ __device__ __forceinline__ bool tile_of_xcd_slot(int nb, int xcd, int loc, int tiles_m, int tiles_n, int &tm, int &tn, int kBand)
 {
     const int per = nb >> 3, rem = nb & 7;
     if (loc >= per + (xcd < rem ? 1 : 0)) return false;
     const int pid = (xcd < rem ? xcd * (per + 1) : rem * (per + 1) + (xcd - rem) * per) + loc;
     const int width = kBand * tiles_n, band = pid / width, first = band * kBand;
-    const int rows = min(tiles_m - first, kBand), in = pid - band * width;
+    const int rows = tiles_m - first < kBand ? tiles_m - first : kBand, in = pid - band * width;
     tm = first + in % rows;
     tn = in / rows;
     return true;
@@ -110,47 +110,52 @@ struct SkItem {
     int first_slot;        // which of its two buffers the first contributor used (all others use buffer 0)
     int fixed;             // 1: a split tile (all contributors write, the last one to arrive sums all parts); 0: a run's tile
 };
-__device__ __forceinline__ int sk_owner_of_pair(int p, int base, int extra)
+__host__ __device__ __forceinline__ int sk_owner_of_pair(int p, int base, int extra)
 {
     const int cut = extra * (base + 1);
     return p < cut ? p / (base + 1) : extra + (p - cut) / (base > 0 ? base : 1);
 }
-// item number j of this workgroup; false past its last one
-__device__ __forceinline__ bool sk_item(const SkPlan &sk, int nb, int tiles_m, int tiles_n, int band, int j, SkItem &it)
+// item number j of workgroup `bid` of a grid of `grid`; false past its last one
+__host__ __device__ __forceinline__ bool sk_item_of(const SkPlan &sk, int nb, int tiles_m, int tiles_n, int band, int bid, int grid,
+                                                   int j, SkItem &it)
 {
-    const int xcd = (int)(blockIdx.x & 7), loc0 = (int)(blockIdx.x >> 3);
+    const int xcd = bid & 7, loc0 = bid >> 3;
     it.kb = 0; it.ke = sk.pairs; it.parts = 1; it.first = 0; it.first_slot = 0; it.ctr = 0; it.fixed = 0;
-    if (!sk.walk) return j == 0 && tile_of_xcd_slot((int)gridDim.x, xcd, loc0, tiles_m, tiles_n, it.tm, it.tn, band);
-    const int W = (int)(gridDim.x >> 3);
+    if (!sk.walk) return j == 0 && tile_of_xcd_slot(grid, xcd, loc0, tiles_m, tiles_n, it.tm, it.tn, band);
+    const int W = grid >> 3;
     if (j < sk.dp_rounds) return tile_of_xcd_slot(nb, xcd, loc0 + j * W, tiles_m, tiles_n, it.tm, it.tn, band);
     const int n_sk = (nb >> 3) + (xcd < (nb & 7) ? 1 : 0) - sk.dp_rounds * W;
     if (n_sk <= 0) return false;
     if (sk.split) {
         if (j != sk.dp_rounds) return false;                       // one piece per workgroup
-        const int c = min(W / n_sk, kSkMaxSplit);                   // contributors per tile (at least 2: the host's choice)
+        const int c = W / n_sk < kSkMaxSplit ? W / n_sk : kSkMaxSplit;                   // contributors per tile (at least 2: the host's choice)
         const int t = loc0 / c, me = loc0 - t * c;
         if (t >= n_sk) return false;
         const int base = sk.pairs / c, extra = sk.pairs % c;
-        it.kb = me * base + min(me, extra);
+        it.kb = me * base + (me < extra ? me : extra);
         it.ke = it.kb + base + (me < extra ? 1 : 0);
         it.parts = c; it.first = t * c; it.fixed = 1;
         it.ctr = xcd * 2 * W + t;
         return tile_of_xcd_slot(nb, xcd, sk.dp_rounds * W + t, tiles_m, tiles_n, it.tm, it.tn, band);
     }
     const int P = sk.pairs, total = n_sk * P, base = total / W, extra = total % W;
-    const int start = loc0 * base + min(loc0, extra), end = start + base + (loc0 < extra ? 1 : 0);
+    const int start = loc0 * base + (loc0 < extra ? loc0 : extra), end = start + base + (loc0 < extra ? 1 : 0);
     const int t = start / P + (j - sk.dp_rounds);
     if (start >= end || t * P >= end) return false;
-    it.kb = max(start, t * P) - t * P;
-    it.ke = min(end, (t + 1) * P) - t * P;
+    it.kb = (start > t * P ? start : t * P) - t * P;
+    it.ke = (end < (t + 1) * P ? end : (t + 1) * P) - t * P;
     if (it.kb > 0 || it.ke < P) {
         it.first = sk_owner_of_pair(t * P, base, extra);
         it.parts = sk_owner_of_pair((t + 1) * P - 1, base, extra) - it.first + 1;
-        const int fstart = it.first * base + min(it.first, extra);
+        const int fstart = it.first * base + (it.first < extra ? it.first : extra);
         it.first_slot = fstart / P == t ? 0 : 1;
         it.ctr = xcd * 2 * W + t;          // t < n_sk <= 2 W: the plan never cuts more than two rounds
     }
     return tile_of_xcd_slot(nb, xcd, sk.dp_rounds * W + t, tiles_m, tiles_n, it.tm, it.tn, band);
+}
+__device__ __forceinline__ bool sk_item(const SkPlan &sk, int nb, int tiles_m, int tiles_n, int band, int j, SkItem &it)
+{
+    return sk_item_of(sk, nb, tiles_m, tiles_n, band, (int)blockIdx.x, (int)gridDim.x, j, it);
 }
 
 // A contributor of a tile cut along K is done with its K range.  Returns true in the one that holds the sum of all
@@ -1249,29 +1254,46 @@ SkPlan plan_tiles(int ntiles, int pairs, int resident, float *partials, uint32_t
     return sk;
 }
 
-template <int BITS, bool BT, typename TS>
-void launch_q(const GemmQArgs &args, hipStream_t st)
+// Geometry of a fwd / dX launch: tiles, the XCD band, who computes what (SkPlan), the grid, and which instantiation runs.
+struct QLaunchPlan { int tiles_m, tiles_n, band, ntiles, grid; SkPlan sk; bool cut_inst; };
+template <bool BT, typename TS> constexpr size_t q_smem_bytes()
 {
     constexpr int LDB = BT ? TS::BN + kPadKM : TS::BK + kPadKC;
-    constexpr size_t smem = 2 * (size_t)(TS::BM * TS::BK + (BT ? TS::BK * LDB : TS::BN * LDB)) * sizeof(bf16_t) +
-                            (size_t)TS::WGM * TS::WGN * kStoreStageBytes;
-    static_assert(smem + 64 <= 160 * 1024, "LDS of one CU");
-    GemmQArgs a = args;
-    a.c_bytes = (uint32_t)((size_t)a.M * a.N * 2);
-    a.tiles_m = (a.M + TS::BM - 1) / TS::BM;
-    a.tiles_n = (a.N + TS::BN - 1) / TS::BN;
+    return 2 * (size_t)(TS::BM * TS::BK + (BT ? TS::BK * LDB : TS::BN * LDB)) * sizeof(bf16_t) + (size_t)TS::WGM * TS::WGN * kStoreStageBytes;
+}
+template <bool BT, typename TS>
+QLaunchPlan plan_q(int M, int N, int K, float *partials, uint32_t *counters)
+{
+    QLaunchPlan q{};
+    q.tiles_m = (M + TS::BM - 1) / TS::BM;
+    q.tiles_n = (N + TS::BN - 1) / TS::BN;
     // Tile rows that one XCD walks together.  The activation panel of a tile row is eight times heavier than the code
     // panel of a tile column, so the 32 tiles an XCD holds at a time should span few rows and many columns (per K step
     // it fetches rows x 32 KB + columns x 6 KB: 4 rows x 8 columns 176 KB, 8 x 4 280 KB), and with an eighth of the tile
     // rows per band every XCD owns its rows outright, so that an activation panel is fetched by one XCD only.  Measured:
     // 4 (8192 tokens) and 2 (4096 tokens) are up to 2-4 % ahead of 8; 16 is 3 % behind.
-    a.band = std::max(2, std::min(8, a.tiles_m / 8));
+    q.band = std::max(2, std::min(8, q.tiles_m / 8));
     // At most as many workgroups as the chip holds at once; with more tiles than that every workgroup walks several
     // (grid a multiple of 8, one share per XCD).
-    const int ntiles = a.tiles_m * a.tiles_n, resident = resident_workgroups(smem);
-    a.sk = plan_tiles(ntiles, ((a.K + TS::BK - 1) / TS::BK + 1) / 2, resident, a.sk.partials, a.sk.counters);
-    const dim3 grid(a.sk.walk ? resident : ntiles), block(64 * TS::WGM * TS::WGN);
-    if ((a.sk.walk && (a.sk.dp_rounds == 0 || a.sk.split)) || a.K % (2 * TS::BK) != 0) {
+    q.ntiles = q.tiles_m * q.tiles_n;
+    const int resident = resident_workgroups(q_smem_bytes<BT, TS>());
+    q.sk = plan_tiles(q.ntiles, ((K + TS::BK - 1) / TS::BK + 1) / 2, resident, partials, counters);
+    q.grid = q.sk.walk ? resident : q.ntiles;
+    q.cut_inst = (q.sk.walk && (q.sk.dp_rounds == 0 || q.sk.split)) || K % (2 * TS::BK) != 0;
+    return q;
+}
+
+template <int BITS, bool BT, typename TS>
+void launch_q(const GemmQArgs &args, hipStream_t st)
+{
+    constexpr size_t smem = q_smem_bytes<BT, TS>();
+    static_assert(smem + 64 <= 160 * 1024, "LDS of one CU");
+    GemmQArgs a = args;
+    a.c_bytes = (uint32_t)((size_t)a.M * a.N * 2);
+    const QLaunchPlan q = plan_q<BT, TS>(a.M, a.N, a.K, a.sk.partials, a.sk.counters);
+    a.tiles_m = q.tiles_m; a.tiles_n = q.tiles_n; a.band = q.band; a.sk = q.sk;
+    const dim3 grid(q.grid), block(64 * TS::WGM * TS::WGN);
+    if (q.cut_inst) {
         auto kern = k_gemm_q<BITS, BT, true, TS::BM, TS::BN, TS::BK, TS::WGM, TS::WGN>;
         static uint64_t attr_done = 0;
         allow_dynamic_lds(kern, smem, attr_done);
@@ -1343,6 +1365,33 @@ void sk_scratch_bytes(const Problem &p, bool bwd, size_t *partial_bytes, size_t 
     };
     one(p.T, p.O, p.I);
     if (bwd) one(p.T, p.I, p.O);
+}
+
+// Test aid: work item number j of workgroup `block` in the launch that the forward (gemm = 0) or the dX (gemm = 1) GEMM of
+// this problem makes, as the kernel itself works it out.  item = {tile row, tile column, first and past-the-last K-tile
+// pair, contributors of the tile, the first contributor's index in its XCD, 1 for a split tile, counter index, grid,
+// K-tile pairs per tile, tile rows, tile columns}.  Returns 1, 0 past the workgroup's last item, -1 for a bad argument.
+int plan_item_for_test(const Problem &p, int gemm, int block, int j, int32_t item[12])
+{
+    if (!p.act_bf16 || p.T < 1 || gemm < 0 || gemm > 1 || block < 0 || j < 0) return -1;
+    const int M = (int)p.T, N = (int)(gemm == 0 ? p.O : p.I), K = (int)(gemm == 0 ? p.I : p.O);
+    float *const some_p = reinterpret_cast<float *>(16); uint32_t *const some_c = reinterpret_cast<uint32_t *>(16);
+    const bool small = use_small_tile(M, N);
+    const QLaunchPlan q = gemm == 0 ? (small ? plan_q<false, TileSmall>(M, N, K, some_p, some_c) : plan_q<false, TileBig>(M, N, K, some_p, some_c))
+                                    : (small ? plan_q<true, TileSmall>(M, N, K, some_p, some_c) : plan_q<true, TileBig>(M, N, K, some_p, some_c));
+    if (block >= q.grid) return -1;
+    SkItem it{};
+    bool ok;
+    if (q.cut_inst) {
+        ok = sk_item_of(q.sk, q.ntiles, q.tiles_m, q.tiles_n, q.band, block, q.grid, j, it);
+    } else {        // whole tiles only, as in the kernel's other instantiation
+        const int loc_step = q.sk.walk ? q.grid >> 3 : q.ntiles;
+        ok = tile_of_xcd_slot(q.sk.walk ? q.ntiles : q.grid, block & 7, (block >> 3) + j * loc_step, q.tiles_m, q.tiles_n, it.tm, it.tn, q.band);
+        it.kb = 0; it.ke = q.sk.pairs; it.parts = 1;
+    }
+    const int32_t v[12] = {it.tm, it.tn, it.kb, it.ke, it.parts, it.first, it.fixed, it.ctr, q.grid, q.sk.pairs, q.tiles_m, q.tiles_n};
+    for (int k = 0; k < 12; ++k) item[k] = v[k];
+    return ok ? 1 : 0;
 }
 
 void launch_mfma_fwd(const Problem &p, const void *X, const void *codes, const void *sz, void *Y, const SkScratch &sk,

@@ -50,6 +50,7 @@ void launch_reduce_partials(const float *part, float *out, const float *s, size_
 // tiles and one arrival counter per tile.  The counters must be zero when a launch starts; every launch leaves them zero.
 // Either pointer NULL: tiles are never cut.
 struct SkScratch { float *partials; uint32_t *counters; };
+int plan_item_for_test(const Problem &p, int gemm, int block, int j, int32_t item[12]);      // test aid, see gemm_mfma.hip
 void sk_scratch_bytes(const Problem &p, bool bwd, size_t *partial_bytes, size_t *counter_bytes);
 // Y[T,O] = X[T,I] * What[O,I]^T with What = (code - zbar) * s rebuilt per tile from packed codes.
 void launch_mfma_fwd(const Problem &p, const void *X, const void *codes, const void *sz, void *Y, const SkScratch &sk,
