@@ -32,7 +32,7 @@ def test_oracle_pins_pass_under_asan_and_ubsan():
     assert "passed" in r.stdout and "ERROR: AddressSanitizer" not in tail and "runtime error" not in tail, tail
 
 
-def test_host_side_of_the_library_passes_its_abi_tests_under_asan_and_ubsan(tmp_path):
+def test_host_side_of_the_library_passes_its_abi_and_work_plan_tests_under_asan_and_ubsan(tmp_path):
     import glob
     rts = glob.glob("/opt/rocm/lib/llvm/lib/clang/*/lib/linux/libclang_rt.asan-x86_64.so")
     if not rts:
@@ -45,7 +45,7 @@ def test_host_side_of_the_library_passes_its_abi_tests_under_asan_and_ubsan(tmp_
     assert b.returncode == 0, (b.stdout + b.stderr)[-3000:]
     # (all of them but the one that links a plain gcc program against the library: that program has no sanitizer runtime)
     r = subprocess.run([sys.executable, "-m", "pytest", "-x", "-q", "-p", "no:cacheprovider", "-k", "not plain_c",
-                        os.path.join(ROOT, "tests", "test_host_abi.py")],
+                        os.path.join(ROOT, "tests", "test_host_abi.py"), os.path.join(ROOT, "tests", "test_work_plan.py")],
                        cwd=ROOT, env=_env(rts[0], EQAT_LIB=str(lib)), capture_output=True, text=True, timeout=900)
     tail = (r.stdout + r.stderr)[-3000:]
     assert r.returncode == 0, tail
