@@ -102,11 +102,14 @@ __device__ __forceinline__ int batch_slot(const uint32_t (&first)[kMaxBatch + 1]
 }
 
 constexpr int kQuantUnroll = 4;     // chunks per thread: 64 B (bf16) / 128 B (fp32) of W in flight per lane
+// eqat_pack of one large bf16 matrix (the 70B-sized ones, 235 M weights): twice the loads in flight measured +5 %; on
+// smaller matrices, with several matrices per launch and in the working-layout instantiations it measured 2-10 % slower.
+constexpr int kPackUnrollLarge = 8;
+constexpr size_t kPackLargeChunks = (size_t)1 << 24;     // 8-weight chunks: 134 M weights
 
-template <typename WT, int BITS, bool CLAMPBITS, bool WORK>
+template <typename WT, int BITS, bool CLAMPBITS, bool WORK, int U = kQuantUnroll>
 __global__ __launch_bounds__(256) void k_quantize(const QuantizeBatch batch)
 {
-    constexpr int U = kQuantUnroll;
     const int slot = batch_slot(batch.first, blockIdx.x);
     const QuantizeArgs &a = batch.a[slot];
     const uint32_t block = blockIdx.x - batch.first[slot];
@@ -417,14 +420,14 @@ static inline int pow2_shift(int64_t v)
     return -1;
 }
 
-static QuantizeArgs quantize_args(const QuantizeJob &j)
+static QuantizeArgs quantize_args(const QuantizeJob &j, int unroll)
 {
     const Problem &p = j.p;
     QuantizeArgs a{};
     a.zero_words = j.zero_words; a.n_zero = j.n_zero;
     a.W = j.W; a.s = j.s; a.z = j.z; a.codes = (uint32_t *)j.codes; a.clampbits = (uint8_t *)j.clampbits; a.sz = (floatx2 *)j.sz;
     a.n_chunks = (uint32_t)((size_t)p.O * p.I / 8); a.g = (uint32_t)p.g; a.g_shift = pow2_shift(p.g);
-    a.n_quant_blocks = blocks_for(a.n_chunks, 256 * kQuantUnroll);
+    a.n_quant_blocks = blocks_for(a.n_chunks, 256 * unroll);
     a.zpacked = (uint32_t *)j.zpacked; a.G = (uint32_t)p.G; a.row_words = (uint32_t)((p.G * p.bits + 31) / 32);
     a.n_zwords = j.zpacked != nullptr ? (uint32_t)p.O * a.row_words : 0u;
     return a;
@@ -435,8 +438,9 @@ static void quantize_t(const QuantizeJob *jobs, int n, bool for_pack, hipStream_
 {
     QuantizeBatch b{};
     uint32_t first = 0;
+    const bool large_pack = for_pack && n == 1 && sizeof(WT) == 2 && (size_t)jobs[0].p.O * jobs[0].p.I / 8 >= kPackLargeChunks;
     for (int i = 0; i < n; ++i) {
-        b.a[i] = quantize_args(jobs[i]);
+        b.a[i] = quantize_args(jobs[i], large_pack ? kPackUnrollLarge : kQuantUnroll);
         b.first[i] = first;
         first += b.a[i].n_quant_blocks + blocks_for(b.a[i].n_zwords);
     }
@@ -444,6 +448,9 @@ static void quantize_t(const QuantizeJob *jobs, int n, bool for_pack, hipStream_
     const dim3 grid(first), block(256);
     // eqat_pack: dense stream, no clamp plane;
     // the quantize pass of the Block-AP calls: working layout, clamp plane for the backward
+    if constexpr (sizeof(WT) == 2) {
+        if (large_pack) { k_quantize<WT, BITS, false, false, kPackUnrollLarge><<<grid, block, 0, st>>>(b); return; }
+    }
     if (for_pack) k_quantize<WT, BITS, false, false><<<grid, block, 0, st>>>(b);
     else if (jobs[0].clampbits != nullptr) k_quantize<WT, BITS, true, true><<<grid, block, 0, st>>>(b);
     else k_quantize<WT, BITS, false, true><<<grid, block, 0, st>>>(b);
