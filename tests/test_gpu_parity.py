@@ -225,6 +225,7 @@ SPLIT_CASES = [
     ("split_fwd", 4400, 2048, 4104, 2, 64),    # fwd: 306 tiles, 16 K-tile pairs
     ("split_dx", 4400, 4128, 2056, 3, 32),     # dX: 306 tiles, K = O = 2056: 17 pairs (uneven pieces, ragged last K tile)
     ("split_small", 4096, 2048, 2304, 4, 128), # fwd: 576 tiles of 128 x 128, 16 pairs, eight contributors
+    ("split_3r", 4400, 2048, 8440, 2, 64),     # fwd: 18 x 33 = 594 tiles (not a multiple of 8): two whole rounds, then 10 or 11 tiles per XCD split two ways
 ]
 
 
