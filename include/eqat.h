@@ -335,13 +335,13 @@ eqat_status eqat_block_ap_update(const eqat_desc *d, const eqat_adamw *h, void *
                                  float *ms, float *vs, float *mz, float *vz, void *stream);
 
 /*
- * Test aid (host only, nothing is launched): how the forward (gemm = 0) or dX (gemm = 1) GEMM of this descriptor
- * (bf16 activations, tokens >= 1) divides its output tiles and their K range among its workgroups, as the kernel
- * itself works it out.  item[12] = { tile row, tile column, first and past-the-last K-tile pair of this piece,
+ * Test aid (host only, nothing is launched): how the forward (gemm = 0), dX (gemm = 1) or dW (gemm = 2: tile rows are
+ * in-features, tile columns out-features, K runs over the tokens) GEMM of this descriptor (bf16 activations, tokens >= 1)
+ * divides its output tiles and their K range among its workgroups, as the kernel itself works it out.  item[12] = { tile row, tile column, first and past-the-last K-tile pair of this piece,
  * number of workgroups that contribute to the tile, index of the first of them within its XCD (workgroup = index * 8 +
  * XCD, XCD = block % 8), 1 if the tile is split among a group of workgroups (else pieces come from runs), index of the
  * tile's counter, workgroups in the launch, K-tile pairs per tile, tile rows, tile columns }; *exists = 0 past the last
- * item j of workgroup `block`.  EQAT_ERR_SHAPE for block outside the launch, gemm not 0 or 1, j < 0.  Lets a test check,
+ * item j of workgroup `block`.  EQAT_ERR_SHAPE for block outside the launch, gemm not 0, 1 or 2, j < 0.  Lets a test check,
  * without a GPU, that every K-tile pair of every tile is computed exactly once for any shape.
  */
 eqat_status eqat_plan_item(const eqat_desc *d, int gemm, int block, int j, int32_t *item, int32_t *exists);

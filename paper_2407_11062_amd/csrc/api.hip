@@ -358,7 +358,7 @@ static eqat_status fq_bwd_any(const eqat_desc *d, const void *X, const void *W, 
         if (dX != nullptr) { ProfScope ps(eqat::PK_GEMM_DX, st); eqat::launch_mfma_dx(p, dY, w8 + l.codes, w8 + l.sz, dX, sk, st); }
         if (want_w)
             eqat::launch_mfma_dw(p, true, X, dY, W, w8 + l.codes, w8 + l.clamp, w8 + l.sz, s, dW, ds, dz,
-                                 (float *)(w8 + l.part), st);
+                                 (float *)(w8 + l.part), sk, st);
     } else {
         ProfScope ps(eqat::PK_F32, st);
         if (dX != nullptr && p.T > 0) eqat::launch_f32_dx(p, false, dY, W, s, z, dX, st);
@@ -385,7 +385,7 @@ static eqat_status qlinear_bwd_run(const Problem &p, const void *X, const float 
     const bool want_g = (ds != nullptr || dz != nullptr);
     if (p.act_bf16) {
         if (dX != nullptr) { ProfScope ps(eqat::PK_GEMM_DX, st); eqat::launch_mfma_dx(p, dY, q.codes, q.sz, dX, q.sk, st); }
-        if (want_g) eqat::launch_mfma_dw(p, false, X, dY, nullptr, q.codes, nullptr, q.sz, s, nullptr, ds, dz, q.part, st);
+        if (want_g) eqat::launch_mfma_dw(p, false, X, dY, nullptr, q.codes, nullptr, q.sz, s, nullptr, ds, dz, q.part, q.sk, st);
     } else {
         ProfScope ps(eqat::PK_F32, st);
         if (dX != nullptr && p.T > 0) eqat::launch_f32_dx(p, true, dY, q.codes, s, q.sz, dX, st);
@@ -568,7 +568,7 @@ eqat_status eqat_qlinear_bwd_prepared_kept(const eqat_desc *d, const void *X, co
     return bwd_prepared_any(d, X, prepared, s, z, dY, dX, ds, dz, ws, ws_bytes, stream, true);
 }
 
-// Test aid (host only): how a fwd / dX launch divides its work.
+// Test aid (host only): how a fwd / dX / dW launch divides its work.
 eqat_status eqat_plan_item(const eqat_desc *d, int gemm, int block, int j, int32_t *item, int32_t *exists)
 {
     Problem p;

@@ -176,9 +176,11 @@ __device__ __forceinline__ bool sk_item(const SkPlan &sk, int nb, int tiles_m, i
 constexpr int kAuxDeviceScope = 16;      // "sc1" of the raw buffer intrinsics on gfx940 and later
 constexpr int kSkSpinLimit = 1 << 22;    // polls of ~1 us: a bound that is never reached, so that no wave can spin for ever
 __device__ __forceinline__ void wait_all_and_barrier();
-template <int MI, int NI, int NT>
+// NB = 32 x 32 blocks of a part that are fetched together (16 registers each)
+template <int MI, int NI, int NT, int NB = 2>
 __device__ __forceinline__ bool sk_hand_in(const SkPlan &sk, const SkItem &it, floatx16 (&acc)[MI][NI], int tid)
 {
+    static_assert((MI * NI) % NB == 0, "whole batches");
     __shared__ uint32_t s_sums;
     constexpr size_t kTile = (size_t)MI * NI * 16 * NT;          // floats per part
     constexpr uint32_t kTileBytes = (uint32_t)(kTile * sizeof(float));
@@ -239,18 +241,19 @@ __device__ __forceinline__ bool sk_hand_in(const SkPlan &sk, const SkItem &it, f
         const int from = split ? it.first + k : it.first + (1 - me);                  // contributor whose part this is
         const int slot = (!split && me == 1) ? it.first_slot : 0;
         const __amdgpu_buffer_rsrc_t theirs = make_rsrc(sk.partials + (((size_t)from * 8 + xcd) * 2 + slot) * kTile, kTileBytes);
-        // Two 32 x 32 blocks (32 registers) in flight at a time.  More (two parts together, 64 registers) did not fit: the
-        // pipeline state of the next tile is alive here, and the kernels spilled or lost their second workgroup per CU.
+        // NB blocks in flight at a time.  In the fwd / dX kernels two (32 registers): with more (two parts together, 64
+        // registers) they spilled or lost their second workgroup per CU, because the pipeline state of the next tile is
+        // alive here.
 #pragma unroll
-        for (int b0 = 0; b0 < MI * NI; b0 += 2) {
-            intx4 v[2][4];
+        for (int b0 = 0; b0 < MI * NI; b0 += NB) {
+            intx4 v[NB][4];
 #pragma unroll
-            for (int b = 0; b < 2; ++b)
+            for (int b = 0; b < NB; ++b)
 #pragma unroll
                 for (int q = 0; q < 4; ++q)
                     v[b][q] = __builtin_amdgcn_raw_buffer_load_b128(theirs, (uint32_t)tid * 16u + (uint32_t)(((b0 + b) * 4 + q) * NT * 16), 0, kAuxDeviceScope);
 #pragma unroll
-            for (int b = 0; b < 2; ++b)
+            for (int b = 0; b < NB; ++b)
 #pragma unroll
                 for (int q = 0; q < 4; ++q)
 #pragma unroll
@@ -694,6 +697,7 @@ struct GemmDwArgs {
     uint32_t x_bytes, dy_bytes, w_bytes, codes_bytes, clamp_bytes, sz_bytes;
     int tiles_m, tiles_n;
     int direct;           // 1: every group lies inside one tile -> final ds/dz; 0: per-32-column partials
+    SkPlan sk;            // which tiles, or parts of tiles, a workgroup computes (kernels that cut tiles along T)
 };
 
 // The epilogue of the Block-AP kernel reads W and writes dW through LDS.  In the accumulator layout a lane holds one
@@ -808,6 +812,12 @@ struct KmLoader {
             adv[it] = ok ? (uint32_t)BK * (uint32_t)ld * 2u : 0u;
         }
     }
+    // start n tiles further along K
+    __device__ __forceinline__ void skip_tiles(int n)
+    {
+#pragma unroll
+        for (int it = 0; it < LOADS; ++it) off[it] += (uint32_t)n * adv[it];
+    }
     // instruction `it` of the next tile for this instruction slot; tile_lds = LDS address of the destination tile
     __device__ __forceinline__ void issue(const RawRsrc &r, int it, uint32_t tile_lds, int wave)
     {
@@ -819,7 +829,10 @@ struct KmLoader {
 // s_waitcnt operand: "at most N vector-memory operations still outstanding, all LDS operations complete".
 constexpr int waitcnt_vm_lgkm0(int n) { return (n & 15) | 0x70 | ((n >> 4) << 14); }
 
-template <int BITS, typename WT, bool BLOCK_AP, int BM, int BN, int BK, int NS, int WGM, int WGN>
+// CUT: the grid is as large as the chip holds at once and a workgroup works through the items that a.sk deals it: whole
+// tiles, and parts (along T) of tiles that it shares with others (see SkPlan; the accumulators of the parts meet in
+// sk_hand_in, and the contributor that ends up with their sum runs the tile's epilogue).  Otherwise one tile per workgroup.
+template <int BITS, typename WT, bool BLOCK_AP, int BM, int BN, int BK, int NS, int WGM, int WGN, bool CUT>
 __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_dw(const GemmDwArgs a)
 {
     constexpr int NT = 64 * WGM * WGN, NW = WGM * WGN, WTM = BM / WGM, WTN = BN / WGN, MI = WTM / 32, NI = WTN / 32;
@@ -832,19 +845,38 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_dw(const GemmDwArgs a)
     bf16_t *sA = reinterpret_cast<bf16_t *>(smem_raw);            // [NS][A_ELEMS]
     bf16_t *sB = sA + NS * A_ELEMS;                               // [NS][B_ELEMS]
 
-    int tm, tn;
-    tile_of_block(a.tiles_m, a.tiles_n, tm, tn);
-    const int m0 = tm * BM, n0 = tn * BN;      // m0: first in-feature i, n0: first out-feature o
-    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave / WGN, wn = wave % WGN;
-
+    int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), wm = wave / WGN, wn = wave % WGN;
     const RawRsrc rX = make_raw_rsrc(a.X, a.x_bytes);
     const RawRsrc rY = make_raw_rsrc(a.dY, a.dy_bytes);
     const uint32_t ldsA = lds_addr_of(sA), ldsB = lds_addr_of(sB);
+
+  for ([[maybe_unused]] int item = 0;; ++item) {
+    // What depends on the lane alone would otherwise be worked out once, in front of this loop, and kept in registers
+    // through every phase of every item; the main loop has none to spare.
+    if constexpr (CUT) asm volatile("" : "+v"(tid));
+    int lane = tid & 63;
+    int tm, tn;
+    [[maybe_unused]] SkItem si;
+    if constexpr (CUT) {
+        if (!sk_item(a.sk, a.tiles_m * a.tiles_n, a.tiles_m, a.tiles_n, 8, item, si)) break;
+        tm = si.tm; tn = si.tn;
+    } else {
+        tile_of_block(a.tiles_m, a.tiles_n, tm, tn);
+    }
+    const int m0 = tm * BM, n0 = tn * BN;      // m0: first in-feature i, n0: first out-feature o
+    // K tiles (of BK tokens) of this item: all of them, or the pairs [kb, ke) of a part (an even number of tiles, except
+    // that the last pair of all may lack its second tile)
+    int kt0 = 0, nk = (a.T + BK - 1) / BK;
+    if constexpr (CUT) {
+        kt0 = 2 * si.kb;
+        nk = (2 * si.ke < nk ? 2 * si.ke : nk) - kt0;
+    }
     KmLoader<BK, BM, NW> ldX;
     KmLoader<BK, BN, NW> ldY;
     ldX.init((int)a.I, m0, wave, lane);
     ldY.init((int)a.O, n0, wave, lane);
+    if constexpr (CUT) { ldX.skip_tiles(kt0); ldY.skip_tiles(kt0); }
     constexpr int LA = KmLoader<BK, BM, NW>::LOADS, LB = KmLoader<BK, BN, NW>::LOADS, ND = LA + LB;
     // load number d (0 .. ND-1) of the NEXT K tile (tiles are fetched strictly in order) into LDS buffer `buf`
     auto issue_load = [&](int d, int buf) {
@@ -928,7 +960,6 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_dw(const GemmDwArgs a)
         }
     };
 
-    const int nk = (a.T + BK - 1) / BK;
     if (nk > 0) {
 #pragma unroll
         for (int st = 0; st < NS; ++st) load_tiles(st);            // tiles 0 .. NS-1 (past T: zeros)
@@ -949,6 +980,13 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_dw(const GemmDwArgs a)
         }
     }
     wait_all_and_barrier();   // tile buffers become the partial-sum arrays
+    if constexpr (CUT) {
+        // a tile cut along T: only the contributor that ends up with the sum of all parts goes on to the epilogue
+        asm volatile("" : "+v"(tid));
+        if (si.parts > 1 && !sk_hand_in<MI, NI, NT, 4>(a.sk, si, acc, tid)) continue;      // nothing else is alive here: four blocks at a time
+        asm volatile("" : "+v"(tid));
+        lane = tid & 63;
+    }
 
     // ---- epilogue ----------------------------------------------------------------------------------
     using SG = DwStage<WT, MI>;
@@ -1172,6 +1210,9 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_dw(const GemmDwArgs a)
             if (a.dz != nullptr) a.part_dz[(size_t)o * nb32 + (i0 >> 5)] = p_dz[blk * BN + ol];
         }
     }
+    if constexpr (!CUT) break;
+    __syncthreads();          // the next item's tiles go where the sums were
+  }
 }
 
 // ======================================================================================================
@@ -1235,7 +1276,7 @@ int resident_workgroups(size_t smem)
 //     equal runs (with more rounds, cutting the last 1.x of them into runs measured slower than leaving the last round
 //     partly filled: 7B gate, 5.4 rounds: -3 %; 13B gate, 3.4 rounds: -4 %);
 //   - with at most half a round of tiles beyond the whole rounds, those few tiles are split among groups of workgroups.
-SkPlan plan_tiles(int ntiles, int pairs, int resident, float *partials, uint32_t *counters)
+SkPlan plan_tiles(int ntiles, int pairs, int resident, float *partials, uint32_t *counters, bool runs = true)
 {
     SkPlan sk{};
     sk.pairs = pairs; sk.partials = partials; sk.counters = counters;
@@ -1244,7 +1285,7 @@ SkPlan plan_tiles(int ntiles, int pairs, int resident, float *partials, uint32_t
     const int W = resident / 8, per = ntiles / 8, full = per / W;
     const bool even = (per % W == 0) && (ntiles % 8 == 0);
     const bool may_cut = !even && pairs >= 4 && partials != nullptr && counters != nullptr;
-    sk.dp_rounds = (may_cut && full == 1) ? 0 : (per + (ntiles % 8 ? 1 : 0) + W - 1) / W;
+    sk.dp_rounds = (may_cut && runs && full == 1) ? 0 : (per + (ntiles % 8 ? 1 : 0) + W - 1) / W;
     // Few tiles beyond the whole rounds (at most half a round on every XCD): whole tiles first, then the rest split.
     // The tile arithmetic promises (1 - 1/c) of a round; measured, 5.4 rounds (7B gate, up) gain 2.6 %, 3.4 rounds (13B
     // gate) 1.5-2.3 %: the partly filled round that the split replaces ran at a higher clock, and the instantiation that
@@ -1315,26 +1356,54 @@ void launch_q_bits(int bits, const GemmQArgs &a, hipStream_t st)
 #undef EQAT_GO
 }
 
+// Geometry of a dW launch: tiles (rows: in-features, columns: out-features), and whether tiles are cut along T (then the
+// grid is what the chip holds at once and sk says who computes what), or every tile has a workgroup of its own.
+struct DwLaunchPlan { int tiles_m, tiles_n, ntiles, grid; SkPlan sk; bool cut; };
+template <typename WT, bool AP, typename TS>
+DwLaunchPlan plan_dw(int I, int O, int T, float *partials, uint32_t *counters)
+{
+    DwLaunchPlan d{};
+    d.tiles_m = (I + TS::BM - 1) / TS::BM;
+    d.tiles_n = (O + TS::BN - 1) / TS::BN;
+    d.ntiles = d.tiles_m * d.tiles_n;
+    const int resident = resident_workgroups(dw_smem_bytes<WT, AP, TS::BM, TS::BN, TS::BK, TS::NS, TS::WGM, TS::WGN>());
+    d.sk = plan_tiles(d.ntiles, ((T + TS::BK - 1) / TS::BK + 1) / 2, resident, partials, counters, false);
+    d.cut = d.sk.walk && (d.sk.dp_rounds == 0 || d.sk.split);
+    if (!d.cut) d.sk = SkPlan{};
+    d.grid = d.cut ? resident : d.ntiles;
+    return d;
+}
+
 template <int BITS, typename WT, bool AP, typename TS>
-void launch_dw_t(const GemmDwArgs &args, hipStream_t st)
+void launch_dw_t(const GemmDwArgs &args, const SkScratch &scratch, hipStream_t st)
 {
     constexpr size_t smem = dw_smem_bytes<WT, AP, TS::BM, TS::BN, TS::BK, TS::NS, TS::WGM, TS::WGN>();
-    static_assert(smem <= 160 * 1024, "LDS of one CU");
-    auto kern = k_gemm_dw<BITS, WT, AP, TS::BM, TS::BN, TS::BK, TS::NS, TS::WGM, TS::WGN>;
-    static uint64_t attr_done = 0;
-    allow_dynamic_lds(kern, smem, attr_done);
+    static_assert(smem + 64 <= 160 * 1024, "LDS of one CU");
     GemmDwArgs a = args;
-    a.tiles_m = (a.I + TS::BM - 1) / TS::BM;
-    a.tiles_n = (a.O + TS::BN - 1) / TS::BN;
+    const DwLaunchPlan d = plan_dw<WT, AP, TS>(a.I, a.O, a.T, scratch.partials, scratch.counters);
+    a.tiles_m = d.tiles_m;
+    a.tiles_n = d.tiles_n;
     a.direct = (TS::BM % a.g == 0) ? 1 : 0;
-    kern<<<dim3(a.tiles_m * a.tiles_n), dim3(64 * TS::WGM * TS::WGN), smem, st>>>(a);
+    a.sk = d.sk;
+    const dim3 grid(d.grid), block(64 * TS::WGM * TS::WGN);
+    if (d.cut) {
+        auto kern = k_gemm_dw<BITS, WT, AP, TS::BM, TS::BN, TS::BK, TS::NS, TS::WGM, TS::WGN, true>;
+        static uint64_t attr_done = 0;
+        allow_dynamic_lds(kern, smem, attr_done);
+        kern<<<grid, block, smem, st>>>(a);
+    } else {
+        auto kern = k_gemm_dw<BITS, WT, AP, TS::BM, TS::BN, TS::BK, TS::NS, TS::WGM, TS::WGN, false>;
+        static uint64_t attr_done = 0;
+        allow_dynamic_lds(kern, smem, attr_done);
+        kern<<<grid, block, smem, st>>>(a);
+    }
 }
 
 template <typename WT, bool AP>
-bool launch_dw_bits(int bits, const GemmDwArgs &a, hipStream_t st)      // returns whether per-segment partials were written
+bool launch_dw_bits(int bits, const GemmDwArgs &a, const SkScratch &sk, hipStream_t st)   // returns whether per-segment partials were written
 {
     const bool small = use_small_tile(a.I, a.O);
-#define EQAT_GO(B) do { if (small) launch_dw_t<B, WT, AP, DwTileSmall>(a, st); else launch_dw_t<B, WT, AP, DwTileBig>(a, st); } while (0)
+#define EQAT_GO(B) do { if (small) launch_dw_t<B, WT, AP, DwTileSmall>(a, sk, st); else launch_dw_t<B, WT, AP, DwTileBig>(a, sk, st); } while (0)
     if (bits == 2) EQAT_GO(2); else if (bits == 3) EQAT_GO(3); else EQAT_GO(4);
 #undef EQAT_GO
     return ((small ? TileSmall::BM : TileBig::BM) % a.g) != 0;
@@ -1345,35 +1414,54 @@ bool launch_dw_bits(int bits, const GemmDwArgs &a, hipStream_t st)      // retur
 // workspace reservation: either tile shape may be picked at launch
 bool dw_needs_partials(const Problem &p) { return (TileSmall::BM % p.g) != 0; }
 
-// Scratch that cutting tiles along K needs, for whichever of the fwd / dX GEMMs of a problem may do so (bwd: both,
-// else the forward alone): the larger of the two tile shapes' needs, with the full complement of compute units.
+// Scratch that cutting tiles along K needs, for whichever of the GEMMs of a problem may do so (bwd: fwd, dX and dW,
+// else the forward alone): the largest of their needs, with the full complement of compute units.
 void sk_scratch_bytes(const Problem &p, bool bwd, size_t *partial_bytes, size_t *counter_bytes)
 {
     *partial_bytes = 0;
     *counter_bytes = p.act_bf16 ? (size_t)kSkCounterWords * sizeof(uint32_t) : 0;     // whatever the token count
     if (!p.act_bf16 || p.T == 0) return;
     float *const some_p = reinterpret_cast<float *>(16); uint32_t *const some_c = reinterpret_cast<uint32_t *>(16);
-    auto one = [&](int64_t m, int64_t n, int64_t k) {
+    auto one = [&](int64_t m, int64_t n, int64_t k, bool runs) {
         const bool small = use_small_tile(m, n);
         const int b = small ? TileSmall::BM : TileBig::BM, resident = kMaxCus * (small ? 2 : 1);
         const int ntiles = (int)(((m + b - 1) / b) * ((n + b - 1) / b));
-        const SkPlan sk = plan_tiles(ntiles, (int)(((k + 63) / 64 + 1) / 2), resident, some_p, some_c);
+        const SkPlan sk = plan_tiles(ntiles, (int)(((k + 63) / 64 + 1) / 2), resident, some_p, some_c, runs);
         if (!sk.walk) return;
         const int W = resident / 8, n_sk = (ntiles + 7) / 8 - sk.dp_rounds * W;
         if (n_sk <= 0) return;
         *partial_bytes = std::max(*partial_bytes, (size_t)resident * 2 * b * b * sizeof(float));
     };
-    one(p.T, p.O, p.I);
-    if (bwd) one(p.T, p.I, p.O);
+    one(p.T, p.O, p.I, true);
+    if (bwd) { one(p.T, p.I, p.O, true); one(p.I, p.O, p.T, false); }
 }
 
-// Test aid: work item number j of workgroup `block` in the launch that the forward (gemm = 0) or the dX (gemm = 1) GEMM of
-// this problem makes, as the kernel itself works it out.  item = {tile row, tile column, first and past-the-last K-tile
-// pair, contributors of the tile, the first contributor's index in its XCD, 1 for a split tile, counter index, grid,
-// K-tile pairs per tile, tile rows, tile columns}.  Returns 1, 0 past the workgroup's last item, -1 for a bad argument.
+// Test aid: work item number j of workgroup `block` in the launch that the forward (gemm = 0), the dX (gemm = 1) or the dW
+// (gemm = 2; tile rows: in-features, tile columns: out-features, K: tokens) GEMM of this problem makes, as the kernel
+// itself works it out.  item = {tile row, tile column, first and past-the-last K-tile pair, contributors of the tile, the
+// first contributor's index in its XCD, 1 for a split tile, counter index, grid, K-tile pairs per tile, tile rows, tile
+// columns}.  Returns 1, 0 past the workgroup's last item, -1 for a bad argument.
 int plan_item_for_test(const Problem &p, int gemm, int block, int j, int32_t item[12])
 {
-    if (!p.act_bf16 || p.T < 1 || gemm < 0 || gemm > 1 || block < 0 || j < 0) return -1;
+    if (!p.act_bf16 || p.T < 1 || gemm < 0 || gemm > 2 || block < 0 || j < 0) return -1;
+    if (gemm == 2) {
+        float *const some_p = reinterpret_cast<float *>(16); uint32_t *const some_c = reinterpret_cast<uint32_t *>(16);
+        const bool small = use_small_tile(p.I, p.O);
+        const DwLaunchPlan d = small ? plan_dw<bf16_t, true, DwTileSmall>((int)p.I, (int)p.O, (int)p.T, some_p, some_c)
+                                     : plan_dw<bf16_t, true, DwTileBig>((int)p.I, (int)p.O, (int)p.T, some_p, some_c);
+        if (block >= d.grid) return -1;
+        SkItem it{};
+        bool ok;
+        if (d.cut) {
+            ok = sk_item_of(d.sk, d.ntiles, d.tiles_m, d.tiles_n, 8, block, d.grid, j, it);
+        } else {        // one workgroup per tile
+            ok = j == 0 && tile_of_xcd_slot(d.grid, block & 7, block >> 3, d.tiles_m, d.tiles_n, it.tm, it.tn, 8);
+            it.kb = 0; it.ke = (((int)p.T + 63) / 64 + 1) / 2; it.parts = 1;
+        }
+        const int32_t v[12] = {it.tm, it.tn, it.kb, it.ke, it.parts, it.first, it.fixed, it.ctr, d.grid, (((int)p.T + 63) / 64 + 1) / 2, d.tiles_m, d.tiles_n};
+        for (int k = 0; k < 12; ++k) item[k] = v[k];
+        return ok ? 1 : 0;
+    }
     const int M = (int)p.T, N = (int)(gemm == 0 ? p.O : p.I), K = (int)(gemm == 0 ? p.I : p.O);
     float *const some_p = reinterpret_cast<float *>(16); uint32_t *const some_c = reinterpret_cast<uint32_t *>(16);
     const bool small = use_small_tile(M, N);
@@ -1420,7 +1508,7 @@ void launch_mfma_dx(const Problem &p, const void *dY, const void *codes, const v
 
 void launch_mfma_dw(const Problem &p, bool block_ap, const void *X, const void *dY, const void *W, const void *codes,
                     const void *clampbits, const void *sz, const float *s, void *dW, float *ds, float *dz, float *part,
-                    hipStream_t st)
+                    const SkScratch &sk, hipStream_t st)
 {
     GemmDwArgs a{};
     a.X = (const bf16_t *)X; a.dY = (const bf16_t *)dY; a.W = W; a.codes = (const uint32_t *)codes;
@@ -1436,10 +1524,10 @@ void launch_mfma_dw(const Problem &p, bool block_ap, const void *X, const void *
     {
         ProfScope ps(PK_GEMM_DW, st);
         if (block_ap) {
-            if (p.w_bf16) partials = launch_dw_bits<bf16_t, true>(p.bits, a, st);
-            else partials = launch_dw_bits<float, true>(p.bits, a, st);
+            if (p.w_bf16) partials = launch_dw_bits<bf16_t, true>(p.bits, a, sk, st);
+            else partials = launch_dw_bits<float, true>(p.bits, a, sk, st);
         } else {
-            partials = launch_dw_bits<bf16_t, false>(p.bits, a, st);
+            partials = launch_dw_bits<bf16_t, false>(p.bits, a, sk, st);
         }
     }
     if (partials) {

@@ -61,10 +61,11 @@ void launch_mfma_dx(const Problem &p, const void *dY, const void *codes, const v
 // dWhat = dY^T X fused with the per-element / per-group epilogue.
 //   block_ap: needs W, clampbits; writes dW (W's dtype, may be NULL), ds, dz (may be NULL).
 //   e2e_qp  : W = clampbits = dW = NULL; writes ds and, if not NULL, dz = -s * group-sum dWhat.
-// `part` is scratch for [2][O, I/32] floats, used only when a group is wider than one tile (see dw_needs_partials).
+// `part` is scratch for [2][O, I/32] floats, used only when a group is wider than one tile (see dw_needs_partials);
+// `sk` is the scratch of launches that cut tiles along T.
 void launch_mfma_dw(const Problem &p, bool block_ap, const void *X, const void *dY, const void *W, const void *codes,
                     const void *clampbits, const void *sz, const float *s, void *dW, float *ds, float *dz, float *part,
-                    hipStream_t st);
+                    const SkScratch &sk, hipStream_t st);
 bool dw_needs_partials(const Problem &p);
 
 // ---- gemv.hip (E2E-QP forward for a few tokens, straight from the dense packed stream) -----------

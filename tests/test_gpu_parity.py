@@ -226,6 +226,9 @@ SPLIT_CASES = [
     ("split_dx", 4400, 4128, 2056, 3, 32),     # dX: 306 tiles, K = O = 2056: 17 pairs (uneven pieces, ragged last K tile)
     ("split_small", 4096, 2048, 2304, 4, 128), # fwd: 576 tiles of 128 x 128, 16 pairs, eight contributors
     ("split_3r", 4400, 2048, 8440, 2, 64),     # fwd: 18 x 33 = 594 tiles (not a multiple of 8): two whole rounds, then 10 or 11 tiles per XCD split two ways
+    ("split_dw", 2100, 4352, 4104, 3, 64),     # dW: 17 x 17 = 289 tiles, K = T = 2100: 17 pairs, six contributors per split tile
+    ("split_dw_small", 2100, 2304, 4096, 4, 128), # dW: 18 x 32 = 576 tiles of 128 x 128 on 512 resident workgroups, eight contributors
+    ("split_dw_perchan", 2100, 4352, 4096, 2, -1),  # dW: 17 x 16 tiles, one group per row (per-block partials + reduce kernel), eight contributors
 ]
 
 
@@ -236,7 +239,13 @@ def test_block_ap_and_e2e_with_tiles_cut_along_k(tag, T, I, O, bits, g):
     check_e2e(X, W, s, z, dY, bits, g, TOL[torch.bfloat16])
 
 
-@pytest.mark.parametrize("case", [2, 5, 6], ids=lambda c: SPLIT_CASES[c][0])
+def test_block_ap_with_fp32_master_weights_and_dw_tiles_split_along_the_tokens():
+    # 17 x 16 tiles of dW; W and dW in fp32 (the epilogue moves four units of W rows per wave instead of two)
+    X, W, s, z, dY = make_case("split_dw_f32w", 2100, 4352, 4096, 3, 128, torch.bfloat16, torch.float32)
+    check_block_ap(X, W, s, z, dY, 3, 128, TOL[torch.bfloat16])
+
+
+@pytest.mark.parametrize("case", [2, 5, 6, 9], ids=lambda c: SPLIT_CASES[c][0])
 def test_cut_tiles_are_deterministic_and_ignore_what_the_workspace_held(case):
     tag, T, I, O, bits, g = SPLIT_CASES[case]
     X, W, s, z, dY = make_case(tag, T, I, O, bits, g, torch.bfloat16, torch.bfloat16)

@@ -1,4 +1,4 @@
-"""How the forward and dX GEMMs divide their work among workgroups, checked on the host for many shapes.
+"""How the forward, dX and dW GEMMs divide their work among workgroups, checked on the host for many shapes.
 
 The kernels compute an output tile either whole, in one workgroup, or in pieces along K: as the head and tail of
 "runs" (two contributors at most), or split among a group of workgroups.  The function that tells a workgroup its
@@ -46,7 +46,7 @@ def items_of_launch(T, I, O, gemm):
 
 def check_launch(T, I, O, gemm):
     items, grid, pairs, tiles_m, tiles_n = items_of_launch(T, I, O, gemm)
-    M, N, K = T, (O if gemm == 0 else I), (I if gemm == 0 else O)
+    M, N, K = (T, O, I) if gemm == 0 else (T, I, O) if gemm == 1 else (I, O, T)
     assert pairs == ((K + 63) // 64 + 1) // 2
     assert grid % 8 == 0 or grid == tiles_m * tiles_n
     cover = np.zeros((tiles_m, tiles_n, pairs), dtype=np.int32)
@@ -87,7 +87,7 @@ BENCH_SHAPES = [      # (tokens, in, out) of the benchmark's linears
 
 
 @pytest.mark.parametrize("T,I,O", BENCH_SHAPES)
-@pytest.mark.parametrize("gemm", [0, 1], ids=["fwd", "dx"])
+@pytest.mark.parametrize("gemm", [0, 1, 2], ids=["fwd", "dx", "dw"])
 def test_every_k_tile_pair_of_every_tile_is_computed_once_at_the_benchmark_shapes(T, I, O, gemm):
     check_launch(T, I, O, gemm)
 
@@ -116,7 +116,7 @@ def test_many_ragged_shapes():
         T = int(rng.integers(1, 40)) * int(rng.choice([64, 100, 256, 300]))
         I = 32 * int(rng.integers(1, 300))
         O = 8 * int(rng.integers(1, 1200))
-        for gemm in (0, 1):
+        for gemm in (0, 1, 2):
             check_launch(T, I, O, gemm)
 
 
@@ -126,7 +126,7 @@ def test_bad_arguments():
     ex = ctypes.c_int32(0)
     d = eq.make_desc(512, 512, 512, 2, 32, eq.BF16, eq.BF16)
     r = ctypes.byref(d)
-    assert L.eqat_plan_item(r, 2, 0, 0, item, ctypes.byref(ex)) != 0
+    assert L.eqat_plan_item(r, 3, 0, 0, item, ctypes.byref(ex)) != 0
     assert L.eqat_plan_item(r, 0, -1, 0, item, ctypes.byref(ex)) != 0
     assert L.eqat_plan_item(r, 0, 0, -1, item, ctypes.byref(ex)) != 0
     assert L.eqat_plan_item(r, 0, 0, 0, None, ctypes.byref(ex)) != 0
