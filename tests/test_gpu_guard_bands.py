@@ -55,6 +55,7 @@ CASES = [
     ("fp32_path", 70, 160, 56, 4, 32, torch.float32, torch.float32),
     ("cut_tiles", 4400, 512, 4104, 2, 64, torch.bfloat16, torch.bfloat16),
     ("walk_odd_k", 4400, 320, 4104, 2, 64, torch.bfloat16, torch.bfloat16),
+    ("split_dw_tiles", 2100, 4352, 4104, 3, 64, torch.bfloat16, torch.bfloat16),     # 289 dW tiles, 33 K tiles: split along the tokens
 ]
 
 
