@@ -280,6 +280,11 @@ struct GemmQArgs {
 };
 
 template <int V> struct IC { static constexpr int value = V; };
+// f(IC<0>{}), f(IC<1>{}), ..., f(IC<N - 1>{}): a loop whose index is a compile-time constant inside the body
+template <int N, int I = 0, typename F> __device__ __forceinline__ void static_for(F &&f)
+{
+    if constexpr (I < N) { f(IC<I>{}); static_for<N, I + 1>(f); }
+}
 
 // With more than 128 accumulator registers per lane the accumulators must live in AGPRs (the MFMA "acd" form);
 // the compiler only picks that form when it believes the kernel needs AGPRs, which this empty statement asserts.
@@ -791,6 +796,22 @@ __device__ __forceinline__ bf16x8 frag_km_swz(const bf16_t *tile, int col0, int 
     return __builtin_bit_cast(bf16x8, r);
 }
 
+// The same tile as an operand of v_mfma_f32_16x16x32_bf16: the lane holds column col0 + lane % 16 and the eight k values
+// 32 ks + 8 (lane / 16) + 0 .. 7.  Every group of 16 lanes reads a patch of 4 k rows x 16 columns per instruction.
+template <int COLS>
+__device__ __forceinline__ bf16x8 frag_km16_swz(const bf16_t *tile, int col0, int ks, int lane)
+{
+    const int i = lane & 15, b = lane >> 4;
+    const int k = ks * 32 + b * 8 + (i >> 2), col = col0 + (i & 3) * 4;
+    const bf16_t *p = tile + k * COLS + km_swz_col<COLS>(k, col);
+    typedef short4v __attribute__((address_space(3))) * lds_p;
+    const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_p)(p));
+    const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_p)(p + 4 * COLS));     // (k + 4) & 3 == k & 3
+    typedef short short8v __attribute__((ext_vector_type(8)));
+    short8v r = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, r);
+}
+
 // Streams consecutive [BK][COLS] row blocks of a row-major [rows][ld] bf16 matrix into LDS tiles, one direct-to-LDS
 // instruction at a time (LOADS per wave and tile, RPI rows each).  Every instruction keeps its own running byte offset,
 // so issuing one costs a scalar move to M0, the load and one add.  Columns past `ld` start at an out-of-range offset and
@@ -836,8 +857,8 @@ template <int BITS, typename WT, bool BLOCK_AP, int BM, int BN, int BK, int NS, 
 __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_dw(const GemmDwArgs a)
 {
     constexpr int NT = 64 * WGM * WGN, NW = WGM * WGN, WTM = BM / WGM, WTN = BN / WGN, MI = WTM / 32, NI = WTN / 32;
-    constexpr int A_ELEMS = BK * BM, B_ELEMS = BK * BN, KK = BK / 16;
-    static_assert(BK % 16 == 0 && KK >= 2 && NS >= 2, "16-wide slices, at least two per tile; at least two LDS stages");
+    constexpr int A_ELEMS = BK * BM, B_ELEMS = BK * BN;
+    static_assert(NS >= 2, "at least two LDS stages");
     static_assert(NS * (A_ELEMS + B_ELEMS) * 2 >= 2 * (BM / 32) * BN * 4, "partials must fit in the tile buffers");
 
     want_agpr_accumulators<MI * NI * 16>();
@@ -896,68 +917,63 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_dw(const GemmDwArgs a)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
-    bf16x8 fa[2][MI], fb[2][NI];
-    auto read_frags = [&](int slot, int buf, int kk) {      // B first: see the forward kernel
+    // The contraction runs on v_mfma_f32_16x16x32_bf16 (measured 4-7 % ahead of the 32x32x16 form in this loop, which
+    // moves twice the accumulator registers per flop): the 32 x 32 block (i, j) of the wave is four 16 x 16 products, and
+    // product (ii, jj) lives in registers 4 (2 ii + jj) .. + 3 of acc[i][j] until the end of the K loop, where the blocks
+    // are brought into the lane order of the 32 x 32 form that the epilogue is written for (to_block_layout below).
+    // A K tile is KS slices of 32.  Per slice a wave needs MA = 2 MI fragments of X and NB = 2 NI of dY (4 registers
+    // each).  The dY fragments are double-buffered; an X fragment is used by NB consecutive MFMAs only, so the fragment
+    // of the next slice takes its registers as soon as those have been issued.
+    constexpr int KS = BK / 32, MA = 2 * MI, NB = 2 * NI;
+    static_assert(BK % 32 == 0 && KS >= 2 && MA >= NB, "slices of 32, at least two per tile; B fragments ride along with the first A fragments");
+    bf16x8 fa[MA], fb[2][NB];
+    auto frag_a = [&](int buf, int ks, int ia) { return frag_km16_swz<BM>(sA + buf * A_ELEMS, wm * WTM + ia * 16, ks, lane); };
+    auto frag_b = [&](int buf, int ks, int jb) { return frag_km16_swz<BN>(sB + buf * B_ELEMS, wn * WTN + jb * 16, ks, lane); };
+    auto mfma16 = [&](auto ia_, auto jb_, int pb) __attribute__((always_inline)) {
+        constexpr int ia = decltype(ia_)::value, jb = decltype(jb_)::value, r0 = 4 * ((ia & 1) * 2 + (jb & 1));
+        floatx4 c;
 #pragma unroll
-        for (int j = 0; j < NI; ++j) fb[slot][j] = frag_km_swz<BN>(sB + buf * B_ELEMS, wn * WTN + j * 32, kk, lane);
+        for (int e = 0; e < 4; ++e) c[e] = acc[ia >> 1][jb >> 1][r0 + e];
+        c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[ia], fb[pb][jb], c, 0, 0, 0);
 #pragma unroll
-        for (int i = 0; i < MI; ++i) fa[slot][i] = frag_km_swz<BM>(sA + buf * A_ELEMS, wm * WTM + i * 32, kk, lane);
+        for (int e = 0; e < 4; ++e) acc[ia >> 1][jb >> 1][r0 + e] = c[e];
     };
-    auto mfma_slice = [&](int slot) {
-#pragma unroll
-        for (int i = 0; i < MI; ++i)
-#pragma unroll
-            for (int j = 0; j < NI; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[slot][i], fb[slot][j], acc[i][j], 0, 0, 0);
-    };
-    // Same pipeline as the forward kernel: the barrier sits before the last slice, whose MFMAs then cover the first
-    // fragment reads of the next tile and the issue of the loads for a later tile.  The K tiles go round a ring of NS
-    // LDS stages: behind the barrier of tile kt the stage of tile kt itself is free (its last fragments are in
+    // One K tile.  Same pipeline as the forward kernel: the barrier sits before the last slice, whose MFMAs then cover
+    // the first fragment reads of the next tile and the issue of the loads for a later tile.  The K tiles go round a ring
+    // of NS LDS stages: behind the barrier of tile kt the stage of tile kt itself is free (its last fragments are in
     // registers) and takes tile kt + NS, so a load has NS - 1 tile times to land; the barrier waits only for the loads
     // of tile kt + 1 (vector-memory operations complete in order: "all but the newest (NS - 2) batches").
-    // P = fragment slot that holds slice 0 of this tile; slices alternate slots, so the next tile starts in slot
-    // (P + KK) & 1.
-    auto step = [&](auto par, int buf, int nxt) {
+    // P = dY fragment buffer that holds slice 0 of this tile; slices alternate, so the next tile starts in (P + KS) & 1.
+    auto step = [&](auto par, int buf, int nxt) __attribute__((always_inline)) {
         constexpr int P = decltype(par)::value;
-        // fragment reads of the next slice spread between the MFMAs of this one (see the forward kernel)
-        auto weave = [&]() {
+        // MFMAs of X fragment ia, then, in their shadow, the fragments that replace it (and one dY fragment of the next
+        // slice), from slice `ks_next` of stage `src`; in the last slice also one or two loads for tile kt + NS.
+        auto run_slice = [&](auto pb_, auto last_, int src, int ks_next) __attribute__((always_inline)) {
+            constexpr int pb = decltype(pb_)::value;
+            constexpr bool last = decltype(last_)::value;
+            static_for<MA>([&](auto ia_) __attribute__((always_inline)) {
+                constexpr int ia = decltype(ia_)::value;
+                static_for<NB>([&](auto jb_) __attribute__((always_inline)) { mfma16(ia_, jb_, pb); });
+                __builtin_amdgcn_sched_barrier(0);
+                if constexpr (last) {
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
-                __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);
-            }
+                    for (int d = 0; d < ND; ++d)
+                        if (d * MA / ND == ia) issue_load(d, buf);
+                }
+                fa[ia] = frag_a(src, ks_next, ia);
+                if constexpr (ia < NB) fb[pb ^ 1][ia] = frag_b(src, ks_next, ia);
+                __builtin_amdgcn_sched_barrier(0);
+            });
         };
-#pragma unroll
-        for (int kk = 0; kk + 1 < KK; ++kk) {
-            read_frags((P + kk + 1) & 1, buf, kk + 1);
-            mfma_slice((P + kk) & 1);
-            weave();
-            __builtin_amdgcn_sched_barrier(0);
-        }
+        static_for<KS - 1>([&](auto ks_) __attribute__((always_inline)) {
+            constexpr int ks = decltype(ks_)::value;
+            run_slice(IC<((P + ks) & 1)>{}, IC<0>{}, buf, ks + 1);
+        });
         asm volatile("" ::: "memory");
         __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0((NS - 2) * ND));
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
-        // Last slice, in a fixed order: an MFMA first, then in its shadow one or two of the loads for tile kt + NS and
-        // a fragment of the next tile's first slice.  (Issued as a block in front of the MFMAs, the loads kept the MFMA
-        // pipe of both waves of a SIMD empty for their whole issue sequence right after every barrier.)
-        constexpr int NQ = MI * NI, NF = NI + MI, SL = (P + KK - 1) & 1, SN = SL ^ 1;
-#pragma unroll
-        for (int q = 0; q < NQ; ++q) {
-            const int i = q / NI, j = q % NI;
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[SL][i], fb[SL][j], acc[i][j], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int d = 0; d < ND; ++d)
-                if (d * NQ / ND == q) issue_load(d, buf);
-#pragma unroll
-            for (int f = 0; f < NF; ++f) {
-                if (f * NQ / NF != q) continue;
-                if (f < NI) fb[SN][f] = frag_km_swz<BN>(sB + nxt * B_ELEMS, wn * WTN + f * 32, 0, lane);
-                else fa[SN][f - NI] = frag_km_swz<BM>(sA + nxt * A_ELEMS, wm * WTM + (f - NI) * 32, 0, lane);
-            }
-            __builtin_amdgcn_sched_barrier(0);
-        }
+        run_slice(IC<((P + KS - 1) & 1)>{}, IC<1>{}, nxt, 0);
     };
 
     if (nk > 0) {
@@ -967,15 +983,18 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_dw(const GemmDwArgs a)
         __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0((NS - 1) * ND));      // tile 0 has landed
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
-        read_frags(0, 0, 0);
-        // Two tiles per trip, so that the fragment slots alternate at compile time when a tile has an odd number of
+#pragma unroll
+        for (int jb = 0; jb < NB; ++jb) fb[0][jb] = frag_b(0, 0, jb);
+#pragma unroll
+        for (int ia = 0; ia < MA; ++ia) fa[ia] = frag_a(0, 0, ia);
+        // Two tiles per trip, so that the fragment buffers alternate at compile time when a tile has an odd number of
         // slices; with an odd tile count the extra tile lies past T and multiplies zeros.
         int buf = 0;
         for (int kt = 0; kt < nk; kt += 2) {
             int nxt = buf + 1 == NS ? 0 : buf + 1;
             step(IC<0>{}, buf, nxt);
             buf = nxt; nxt = buf + 1 == NS ? 0 : buf + 1;
-            step(IC<(KK & 1)>{}, buf, nxt);
+            step(IC<(KS & 1)>{}, buf, nxt);
             buf = nxt;
         }
     }
@@ -1067,18 +1086,68 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_dw(const GemmDwArgs a)
     constexpr int NU = BLOCK_AP ? NI * SG::UPJ : 0;
     uint32_t goff[2][SG::NIU];
     if constexpr (BLOCK_AP) {
-        // the first two units start to stream in at once; a later one follows when its slot has been written out
+        // the first unit starts to stream in at once; the second follows below, a later one when its slot has been written out
         unit_offsets(0, goff[0]);
         issue_unit(0, goff[0]);
-        if constexpr (NU > 1) {
-            unit_offsets(1, goff[1]);
-            issue_unit(1, goff[1]);
-        }
     }
     RowOps rops[2];
     load_row_ops(0, rops[0]);
+
+    // ---- accumulators into the lane order of the 32 x 32 MFMA (while the loads above are under way) ----------------
+    // From the K loop a lane holds, of block (i, j), product (ii, jj) in registers 4 (2 ii + jj) + b: row 16 ii +
+    // 4 (lane / 16) + b, column 16 jj + lane % 16.  What follows wants register 4 q + b to be row 8 q + 4 (lane / 32) + b
+    // of column lane % 32.  Rows 16 ii .. 16 ii + 15 are quads q = 2 ii and 2 ii + 1, so each half of a block is
+    // converted by itself: every lane puts its two quads (16 bytes each) into a 2 KB patch of LDS that belongs to its
+    // wave, [column][row quad] with the quad's place rotated by column / 4 against bank conflicts, and takes the two
+    // quads it owns in the other order.  LDS accesses of a wave complete in order; nothing else touches the patch.
+    {
+        // Block-AP: the wave's second W slot, which is still empty; else the tile ring behind the partial sums
+        const uint32_t patch = BLOCK_AP ? slot_bytes(1) : (uint32_t)(2 * (BM / 32) * BN * sizeof(float)) + (uint32_t)(wave * 2048);
+        static_assert(BLOCK_AP ? SG::UNIT_BYTES >= 2048 : NS * (A_ELEMS + B_ELEMS) * 2 >= 2 * (BM / 32) * BN * 4 + NW * 2048, "room for the patch");
+        const int c16 = lane & 15, rq_in = lane >> 4, c32 = lane & 31, h32 = lane >> 5;
+        uint32_t at_in[2], at_out[2];
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            const int col = 16 * t + c16, rq = 2 * t + h32;
+            at_in[t] = patch + (uint32_t)(col * 64 + ((rq_in + (col >> 2)) & 3) * 16);
+            at_out[t] = patch + (uint32_t)(c32 * 64 + ((rq + (c32 >> 2)) & 3) * 16);
+        }
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int j = 0; j < NI; ++j)
+#pragma unroll
+                for (int hh = 0; hh < 2; ++hh) {
+#pragma unroll
+                    for (int t = 0; t < 2; ++t) {
+                        floatx4 v;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) v[e] = acc[i][j][4 * (2 * hh + t) + e];
+                        *reinterpret_cast<floatx4 *>(smem_raw + at_in[t]) = v;
+                    }
+                    asm volatile("" ::: "memory");
+                    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                    for (int t = 0; t < 2; ++t) {
+                        const floatx4 v = *reinterpret_cast<const floatx4 *>(smem_raw + at_out[t]);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) acc[i][j][4 * (2 * hh + t) + e] = v[e];
+                    }
+                    asm volatile("" ::: "memory");
+                    __builtin_amdgcn_wave_barrier();
+                }
+    }
     asm volatile("" ::: "memory");
-    __builtin_amdgcn_s_waitcnt(0x0070);            // the compiler does not see the loads into LDS: wait for them here
+    __builtin_amdgcn_s_waitcnt(0xC07F);            // lgkmcnt(0): the patch has been read out, its place may take W rows
+    asm volatile("" ::: "memory");
+    if constexpr (NU > 1) {
+        unit_offsets(1, goff[1]);
+        issue_unit(1, goff[1]);
+    }
+    // The compiler does not see the loads into LDS: wait for them here.  The second unit was requested last and may
+    // still be under way; its block column waits for it below.
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(NU > 1 ? SG::NIU : 0));
     asm volatile("" ::: "memory");
     const uint32_t lane_base = SG::lane_base(lane);
 
@@ -1093,7 +1162,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_dw(const GemmDwArgs a)
             const bool valid = (o < a.O) && (ib < a.I);
             [[maybe_unused]] const int u = j * SG::UPJ + i / SG::UB, ii = i % SG::UB, slot = u & 1;
             if constexpr (BLOCK_AP) {
-                if (ii == 0 && u >= 2) {       // this unit's rows were requested when its slot became free (below)
+                if (ii == 0 && u >= 1) {       // requested after the first unit, or when its slot became free (below)
                     asm volatile("" ::: "memory");
                     __builtin_amdgcn_s_waitcnt(0x0070);
                     asm volatile("" ::: "memory");
