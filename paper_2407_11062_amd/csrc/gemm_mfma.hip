@@ -176,9 +176,14 @@ __device__ __forceinline__ bool sk_item(const SkPlan &sk, int nb, int tiles_m, i
 constexpr int kAuxDeviceScope = 16;      // "sc1" of the raw buffer intrinsics on gfx940 and later
 constexpr int kSkSpinLimit = 1 << 22;    // polls of ~1 us: a bound that is never reached, so that no wave can spin for ever
 __device__ __forceinline__ void wait_all_and_barrier();
+// register r of block (i, j), whichever way a kernel keeps its accumulators
+template <int MI, int NI> __device__ __forceinline__ float acc_get(const floatx16 (&acc)[MI][NI], int i, int j, int r) { return acc[i][j][r]; }
+template <int MI, int NI> __device__ __forceinline__ float acc_get(const floatx4 (&acc)[MI][NI][4], int i, int j, int r) { return acc[i][j][r >> 2][r & 3]; }
+template <int MI, int NI> __device__ __forceinline__ void acc_set(floatx16 (&acc)[MI][NI], int i, int j, int r, float v) { acc[i][j][r] = v; }
+template <int MI, int NI> __device__ __forceinline__ void acc_set(floatx4 (&acc)[MI][NI][4], int i, int j, int r, float v) { acc[i][j][r >> 2][r & 3] = v; }
 // NB = 32 x 32 blocks of a part that are fetched together (16 registers each)
-template <int MI, int NI, int NT, int NB = 2>
-__device__ __forceinline__ bool sk_hand_in(const SkPlan &sk, const SkItem &it, floatx16 (&acc)[MI][NI], int tid)
+template <int MI, int NI, int NT, int NB = 2, typename ACC>
+__device__ __forceinline__ bool sk_hand_in(const SkPlan &sk, const SkItem &it, ACC &acc, int tid)
 {
     static_assert((MI * NI) % NB == 0, "whole batches");
     __shared__ uint32_t s_sums;
@@ -203,7 +208,7 @@ __device__ __forceinline__ bool sk_hand_in(const SkPlan &sk, const SkItem &it, f
             for (int q = 0; q < 4; ++q) {
                 intx4 v;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) v[e] = __float_as_int(acc[i][j][4 * q + e]);
+                for (int e = 0; e < 4; ++e) v[e] = __float_as_int(acc_get<MI, NI>(acc, i, j, 4 * q + e));
                 __builtin_amdgcn_raw_buffer_store_b128(v, mine, st_base + (uint32_t)(((i * NI + j) * 4 + q) * NT * 16), 0, kAuxDeviceScope);
             }
             __builtin_amdgcn_sched_barrier(0);      // one 32 x 32 block at a time: few register copies
@@ -234,7 +239,7 @@ __device__ __forceinline__ bool sk_hand_in(const SkPlan &sk, const SkItem &it, f
 #pragma unroll
         for (int j = 0; j < NI; ++j)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = __uint_as_float(__float_as_uint(acc[i][j][r]) & keep);
+            for (int r = 0; r < 16; ++r) acc_set<MI, NI>(acc, i, j, r, __uint_as_float(__float_as_uint(acc_get<MI, NI>(acc, i, j, r)) & keep));
     // parts to add, in the order of the contributors (a trip count of zero for those that do not sum)
     const int n_take = !sums ? 0 : split ? it.parts : 1;
     for (int k = 0; k < n_take; ++k) {
@@ -257,7 +262,9 @@ __device__ __forceinline__ bool sk_hand_in(const SkPlan &sk, const SkItem &it, f
 #pragma unroll
                 for (int q = 0; q < 4; ++q)
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) acc[(b0 + b) / NI][(b0 + b) % NI][4 * q + e] += __int_as_float(v[b][q][e]);
+                    for (int e = 0; e < 4; ++e)
+                        acc_set<MI, NI>(acc, (b0 + b) / NI, (b0 + b) % NI, 4 * q + e,
+                                        acc_get<MI, NI>(acc, (b0 + b) / NI, (b0 + b) % NI, 4 * q + e) + __int_as_float(v[b][q][e]));
             __builtin_amdgcn_sched_barrier(0);
         }
     }
@@ -762,6 +769,19 @@ template <> struct WQuad<float> {
     }
 };
 
+// K-major tiles ([k][COLS] bf16, filled by direct-to-LDS loads of 1 KB = kmRowsPerLoad rows each): in the operand layout
+// of the 16x16x32 MFMA the two groups of sixteen lanes that the LDS serves together read the same 32 bytes of columns
+// eight rows apart, and rows of 256 or 512 bytes all start on the same bank, so the two groups collided on every read
+// (SQ_LDS_BANK_CONFLICT: 45 M cycles per launch at the 7B shapes).  Every eight rows are therefore followed by a gap of 32
+// bytes: the second group's pieces land in the other half of each 64-byte unit (counter back to what the epilogue
+// leaves, 1.6 M).  Gaps of 128 or 256 bytes do not help (the banks repeat every 256 bytes and the swizzle of the 64-byte
+// units already uses all four positions), and swapping the halves by a swizzle of the columns reorders the 16-byte
+// chunks that four neighbouring lanes fetch from memory, which costs far more than the conflicts did (-19 %).
+template <int COLS> constexpr int kmRowsPerLoad = 64 / (COLS / 8);
+constexpr int kmGapElems = 16;
+template <int COLS> __host__ __device__ constexpr int km_row_elems(int k) { return k * COLS + (k >> 3) * kmGapElems; }
+template <int COLS> constexpr int kmTileElems(int rows) { return rows * COLS + (rows / 8) * kmGapElems; }
+
 // LDS the dW kernel asks for: the K loop's tile ring, or (Block-AP) the epilogue's stage plus the group-sum partials.
 template <typename WT, bool BLOCK_AP, int BM, int BN, int BK, int NS, int WGM, int WGN>
 constexpr size_t dw_stage_bytes()
@@ -771,7 +791,7 @@ constexpr size_t dw_stage_bytes()
 template <typename WT, bool BLOCK_AP, int BM, int BN, int BK, int NS, int WGM, int WGN>
 constexpr size_t dw_smem_bytes()
 {
-    const size_t ring = (size_t)NS * BK * (BM + BN) * sizeof(bf16_t);
+    const size_t ring = (size_t)NS * (kmTileElems<BM>(BK) + kmTileElems<BN>(BK)) * sizeof(bf16_t);
     const size_t epi = dw_stage_bytes<WT, BLOCK_AP, BM, BN, BK, NS, WGM, WGN>() + (size_t)2 * (BM / 32) * BN * sizeof(float);
     return ring > epi ? ring : epi;
 }
@@ -782,31 +802,18 @@ constexpr size_t dw_smem_bytes()
 template <int COLS>
 __device__ __forceinline__ int km_swz_col(int k, int col) { return (((col >> 5) ^ (k & 3)) << 5) | (col & 31); }
 
-template <int COLS>
-__device__ __forceinline__ bf16x8 frag_km_swz(const bf16_t *tile, int col0, int kk, int lane)
-{
-    const int i = lane & 15, b = lane >> 4;
-    const int k = kk * 16 + (b >> 1) * 8 + (i >> 2), col = col0 + (b & 1) * 16 + (i & 3) * 4;
-    const bf16_t *p = tile + k * COLS + km_swz_col<COLS>(k, col);
-    typedef short4v __attribute__((address_space(3))) * lds_p;
-    const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_p)(p));
-    const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_p)(p + 4 * COLS));     // (k + 4) & 3 == k & 3
-    typedef short short8v __attribute__((ext_vector_type(8)));
-    short8v r = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-    return __builtin_bit_cast(bf16x8, r);
-}
-
-// The same tile as an operand of v_mfma_f32_16x16x32_bf16: the lane holds column col0 + lane % 16 and the eight k values
-// 32 ks + 8 (lane / 16) + 0 .. 7.  Every group of 16 lanes reads a patch of 4 k rows x 16 columns per instruction.
+// A fragment of the tile as an operand of v_mfma_f32_16x16x32_bf16: the lane holds column col0 + lane % 16 and the eight
+// k values 32 ks + 8 (lane / 16) + 0 .. 7.  Every group of 16 lanes reads a patch of 4 k rows x 16 columns per instruction
+// (the transpose read hands lane i of the group four k-consecutive values of column i).
 template <int COLS>
 __device__ __forceinline__ bf16x8 frag_km16_swz(const bf16_t *tile, int col0, int ks, int lane)
 {
     const int i = lane & 15, b = lane >> 4;
     const int k = ks * 32 + b * 8 + (i >> 2), col = col0 + (i & 3) * 4;
-    const bf16_t *p = tile + k * COLS + km_swz_col<COLS>(k, col);
+    const int c = km_swz_col<COLS>(k, col);                                               // (k + 4) & 3 == k & 3
     typedef short4v __attribute__((address_space(3))) * lds_p;
-    const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_p)(p));
-    const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_p)(p + 4 * COLS));     // (k + 4) & 3 == k & 3
+    const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_p)(tile + km_row_elems<COLS>(k) + c));
+    const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_p)(tile + km_row_elems<COLS>(k + 4) + c));
     typedef short short8v __attribute__((ext_vector_type(8)));
     short8v r = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     return __builtin_bit_cast(bf16x8, r);
@@ -815,12 +822,13 @@ __device__ __forceinline__ bf16x8 frag_km16_swz(const bf16_t *tile, int col0, in
 // Streams consecutive [BK][COLS] row blocks of a row-major [rows][ld] bf16 matrix into LDS tiles, one direct-to-LDS
 // instruction at a time (LOADS per wave and tile, RPI rows each).  Every instruction keeps its own running byte offset,
 // so issuing one costs a scalar move to M0, the load and one add.  Columns past `ld` start at an out-of-range offset and
-// never advance (no wrap-around into range); rows past the end of the matrix fail the buffer's range check.
+// advance like the others: tensors are smaller than 2 GiB, so 2 GiB plus any offset into one stays out of range (no
+// wrap-around); rows past the end of the matrix fail the buffer's range check.
 template <int BK, int COLS, int NW>
 struct KmLoader {
-    static constexpr int CPR = COLS / 8, RPI = 64 / CPR, LOADS = BK / RPI / NW;   // chunks per row, rows per instruction
+    static constexpr int CPR = COLS / 8, RPI = kmRowsPerLoad<COLS>, LOADS = BK / RPI / NW;   // chunks per row, rows per instruction
     static_assert(BK % (RPI * NW) == 0 && CPR <= 64, "tile / wave mismatch");
-    uint32_t off[LOADS], adv[LOADS];
+    uint32_t off[LOADS], adv;                 // adv: bytes from one K tile to the next, the same for every lane
     __device__ __forceinline__ void init(int ld, int col0, int wave, int lane)
     {
 #pragma unroll
@@ -828,22 +836,21 @@ struct KmLoader {
             const int rb = (wave * LOADS + it) * RPI;                 // wave-uniform first row
             const int k = rb + lane / CPR, p = lane % CPR;
             const int col = col0 + (((p >> 2) ^ (k & 3)) << 5) + (p & 3) * 8;
-            const bool ok = col < ld;
-            off[it] = ok ? ((uint32_t)k * (uint32_t)ld + (uint32_t)col) * 2u : kOobOffset;
-            adv[it] = ok ? (uint32_t)BK * (uint32_t)ld * 2u : 0u;
+            off[it] = col < ld ? ((uint32_t)k * (uint32_t)ld + (uint32_t)col) * 2u : kOobOffset;
         }
+        adv = (uint32_t)BK * (uint32_t)ld * 2u;
     }
     // start n tiles further along K
     __device__ __forceinline__ void skip_tiles(int n)
     {
 #pragma unroll
-        for (int it = 0; it < LOADS; ++it) off[it] += (uint32_t)n * adv[it];
+        for (int it = 0; it < LOADS; ++it) off[it] += (uint32_t)n * adv;
     }
     // instruction `it` of the next tile for this instruction slot; tile_lds = LDS address of the destination tile
     __device__ __forceinline__ void issue(const RawRsrc &r, int it, uint32_t tile_lds, int wave)
     {
-        load_to_lds16_at(r, tile_lds + (uint32_t)((wave * LOADS + it) * RPI * COLS * 2), off[it]);
-        off[it] += adv[it];
+        load_to_lds16_at(r, tile_lds + (uint32_t)(km_row_elems<COLS>((wave * LOADS + it) * RPI) * 2), off[it]);
+        off[it] += adv;
     }
 };
 
@@ -857,7 +864,7 @@ template <int BITS, typename WT, bool BLOCK_AP, int BM, int BN, int BK, int NS, 
 __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_dw(const GemmDwArgs a)
 {
     constexpr int NT = 64 * WGM * WGN, NW = WGM * WGN, WTM = BM / WGM, WTN = BN / WGN, MI = WTM / 32, NI = WTN / 32;
-    constexpr int A_ELEMS = BK * BM, B_ELEMS = BK * BN;
+    constexpr int A_ELEMS = kmTileElems<BM>(BK), B_ELEMS = kmTileElems<BN>(BK);      // with the gaps between the 1 KB pieces
     static_assert(NS >= 2, "at least two LDS stages");
     static_assert(NS * (A_ELEMS + B_ELEMS) * 2 >= 2 * (BM / 32) * BN * 4, "partials must fit in the tile buffers");
 
@@ -909,17 +916,17 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_dw(const GemmDwArgs a)
         for (int d = 0; d < ND; ++d) issue_load(d, buf);
     };
 
-    floatx16 acc[MI][NI];
+    floatx4 acc[MI][NI][4];      // [q] = registers 4 q .. 4 q + 3 of the block
 #pragma unroll
     for (int i = 0; i < MI; ++i)
 #pragma unroll
         for (int j = 0; j < NI; ++j)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+            for (int r = 0; r < 16; ++r) acc[i][j][r >> 2][r & 3] = 0.0f;
 
     // The contraction runs on v_mfma_f32_16x16x32_bf16 (measured 4-7 % ahead of the 32x32x16 form in this loop, which
     // moves twice the accumulator registers per flop): the 32 x 32 block (i, j) of the wave is four 16 x 16 products, and
-    // product (ii, jj) lives in registers 4 (2 ii + jj) .. + 3 of acc[i][j] until the end of the K loop, where the blocks
+    // product (ii, jj) lives in acc[i][j][2 ii + jj] until the end of the K loop, where the blocks
     // are brought into the lane order of the 32 x 32 form that the epilogue is written for (to_block_layout below).
     // A K tile is KS slices of 32.  Per slice a wave needs MA = 2 MI fragments of X and NB = 2 NI of dY (4 registers
     // each).  The dY fragments are double-buffered; an X fragment is used by NB consecutive MFMAs only, so the fragment
@@ -930,13 +937,9 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_dw(const GemmDwArgs a)
     auto frag_a = [&](int buf, int ks, int ia) { return frag_km16_swz<BM>(sA + buf * A_ELEMS, wm * WTM + ia * 16, ks, lane); };
     auto frag_b = [&](int buf, int ks, int jb) { return frag_km16_swz<BN>(sB + buf * B_ELEMS, wn * WTN + jb * 16, ks, lane); };
     auto mfma16 = [&](auto ia_, auto jb_, int pb) __attribute__((always_inline)) {
-        constexpr int ia = decltype(ia_)::value, jb = decltype(jb_)::value, r0 = 4 * ((ia & 1) * 2 + (jb & 1));
-        floatx4 c;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) c[e] = acc[ia >> 1][jb >> 1][r0 + e];
+        constexpr int ia = decltype(ia_)::value, jb = decltype(jb_)::value;
+        floatx4 &c = acc[ia >> 1][jb >> 1][(ia & 1) * 2 + (jb & 1)];
         c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[ia], fb[pb][jb], c, 0, 0, 0);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) acc[ia >> 1][jb >> 1][r0 + e] = c[e];
     };
     // One K tile.  Same pipeline as the forward kernel: the barrier sits before the last slice, whose MFMAs then cover
     // the first fragment reads of the next tile and the issue of the loads for a later tile.  The K tiles go round a ring
@@ -1003,9 +1006,10 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_dw(const GemmDwArgs a)
         // a tile cut along T: only the contributor that ends up with the sum of all parts goes on to the epilogue
         asm volatile("" : "+v"(tid));
         if (si.parts > 1 && !sk_hand_in<MI, NI, NT, 4>(a.sk, si, acc, tid)) continue;      // nothing else is alive here: four blocks at a time
-        asm volatile("" : "+v"(tid));
-        lane = tid & 63;
     }
+    // what the epilogue derives from the lane is worked out here, not in front of the K loop (see the top of the loop)
+    asm volatile("" : "+v"(tid));
+    lane = tid & 63;
 
     // ---- epilogue ----------------------------------------------------------------------------------
     using SG = DwStage<WT, MI>;
@@ -1120,18 +1124,13 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_dw(const GemmDwArgs a)
                 for (int hh = 0; hh < 2; ++hh) {
 #pragma unroll
                     for (int t = 0; t < 2; ++t) {
-                        floatx4 v;
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) v[e] = acc[i][j][4 * (2 * hh + t) + e];
-                        *reinterpret_cast<floatx4 *>(smem_raw + at_in[t]) = v;
+                        *reinterpret_cast<floatx4 *>(smem_raw + at_in[t]) = acc[i][j][2 * hh + t];
                     }
                     asm volatile("" ::: "memory");
                     __builtin_amdgcn_wave_barrier();
 #pragma unroll
                     for (int t = 0; t < 2; ++t) {
-                        const floatx4 v = *reinterpret_cast<const floatx4 *>(smem_raw + at_out[t]);
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) acc[i][j][4 * (2 * hh + t) + e] = v[e];
+                        acc[i][j][2 * hh + t] = *reinterpret_cast<const floatx4 *>(smem_raw + at_out[t]);
                     }
                     asm volatile("" ::: "memory");
                     __builtin_amdgcn_wave_barrier();
@@ -1191,7 +1190,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_dw(const GemmDwArgs a)
                 float sum_d = 0.0f, sum_u = 0.0f;
 #define EQAT_ELEM(Q, B)                                                                                   \
     {                                                                                                     \
-        const float d = acc[i][j][(Q) * 4 + (B)];                                                         \
+        const float d = acc[i][j][Q][B];                                                         \
         const uint32_t keep = (uint32_t)((int32_t)(ncl << (31 - ((Q) * 8 + (B)))) >> 31);                 \
         const float du = __uint_as_float(__float_as_uint(d) & keep);                                      \
         const float wm = __uint_as_float(__float_as_uint(wv[B]) & keep);                                  \
@@ -1216,7 +1215,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_dw(const GemmDwArgs a)
             } else {
 #define EQAT_ELEM(Q, B)                                                                                   \
     {                                                                                                     \
-        const float d = acc[i][j][(Q) * 4 + (B)];                                                         \
+        const float d = acc[i][j][Q][B];                                                         \
         sum_s = __builtin_fmaf(d, byte_to_float(cq[Q], B) - zb, sum_s);                                   \
         sum_z += d;                                                                                       \
     }
