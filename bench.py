@@ -116,14 +116,19 @@ def peaks_lib():
     L.eqat_peak_mfma_flop.restype = ctypes.c_double
     L.eqat_peak_mfma_flop.argtypes = [ctypes.c_int, ctypes.c_int]
     L.eqat_peak_mfma_loop.argtypes = [vp, ctypes.c_size_t, ctypes.c_int, ctypes.c_int, vp, vp]
+    L.eqat_peak_mfma16_flop.restype = ctypes.c_double
+    L.eqat_peak_mfma16_flop.argtypes = [ctypes.c_int, ctypes.c_int]
+    L.eqat_peak_mfma16_loop.argtypes = [vp, ctypes.c_size_t, ctypes.c_int, ctypes.c_int, vp, vp]
     L.eqat_peak_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
     L.eqat_peak_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
     return L
 
 
 def measured_peaks(torch, dev, args):
-    """What this chip gives, in this run: (a) a loop of nothing but v_mfma_f32_32x32x16_bf16, two waves per SIMD on all
-    compute units, on all-zero and on random bf16 operands (the clock the chip holds depends on the bits it multiplies);
+    """What this chip gives, in this run: (a) a loop of nothing but v_mfma_f32_32x32x16_bf16, and one of nothing but
+    v_mfma_f32_16x16x32_bf16 (the GEMM kernels use both shapes), two waves per SIMD on all compute units, on all-zero and
+    on random bf16 operands (the clock the chip holds depends on the bits it multiplies); the better of the two shapes is
+    the reference of every frac_of_measured_peak;
     (b) a plain copy kernel and the runtime's device copy on a 1 GiB buffer.  Bench-only kernels (libeqat_peaks.so)."""
     import ctypes
     L = peaks_lib()
@@ -140,8 +145,17 @@ def measured_peaks(torch, dev, args):
         def run():
             rc = L.eqat_peak_mfma_loop(vp(data.data_ptr()), data.numel() * 2, groups, iters, vp(sink.data_ptr()), stream())
             assert rc == 0
+
+        def run16():
+            rc = L.eqat_peak_mfma16_loop(vp(data.data_ptr()), data.numel() * 2, groups, iters, vp(sink.data_ptr()), stream())
+            assert rc == 0
         t = time_steps(torch, run, 20, 3)
-        out[f"mfma_bf16_{name}_operands_tflops"] = round(L.eqat_peak_mfma_flop(groups, iters) / (t["median_ms"] * 1e-3) / 1e12, 1)
+        a32 = round(L.eqat_peak_mfma_flop(groups, iters) / (t["median_ms"] * 1e-3) / 1e12, 1)
+        t = time_steps(torch, run16, 20, 3)
+        a16 = round(L.eqat_peak_mfma16_flop(groups, iters) / (t["median_ms"] * 1e-3) / 1e12, 1)
+        out[f"mfma_32x32x16_bf16_{name}_operands_tflops"] = a32
+        out[f"mfma_16x16x32_bf16_{name}_operands_tflops"] = a16
+        out[f"mfma_bf16_{name}_operands_tflops"] = max(a32, a16)
     nbytes = 1 << 30
     src = torch.empty(nbytes, dtype=torch.uint8, device=dev).random_(0, 256)
     dst = torch.empty_like(src)

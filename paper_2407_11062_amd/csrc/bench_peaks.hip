@@ -1,6 +1,6 @@
 // Measurement aids for bench.py, built into their own library (libeqat_peaks.so), not part of libeqat.so:
 // what this very chip, at the clocks it holds under this very load, gives (a) a loop of nothing but
-// v_mfma_f32_32x32x16_bf16, (b) a plain device copy and (c) a kernel that only reads.  bench.py quotes every roofline fraction against the
+// v_mfma_f32_32x32x16_bf16 or v_mfma_f32_16x16x32_bf16 (the GEMM kernels use both), (b) a plain device copy and (c) a kernel that only reads.  bench.py quotes every roofline fraction against the
 // published peaks (2.5 PFLOP/s, 8 TB/s) and against these two.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -9,6 +9,7 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef unsigned int uintx4 __attribute__((ext_vector_type(4)));
 
 constexpr int kWavesPerGroup = 8;      // two per SIMD, like the GEMM kernels
@@ -38,6 +39,33 @@ __global__ __launch_bounds__(64 * kWavesPerGroup) void k_mfma_loop(const uintx4 
     for (int c = 0; c < kChains; ++c)
 #pragma unroll
         for (int r = 0; r < 16; ++r) s += acc[c][r];
+    if (s == 12345.678f) sink[0] = s;          // keeps the loop alive; practically never true
+}
+
+// The same with v_mfma_f32_16x16x32_bf16: half the flops per instruction, twice the instructions and chains.
+constexpr int kChains16 = 8;
+__global__ __launch_bounds__(64 * kWavesPerGroup) void k_mfma16_loop(const uintx4 *__restrict__ data, uint32_t n_vec, int iters,
+                                                                     float *__restrict__ sink)
+{
+    const uint32_t t = blockIdx.x * blockDim.x + threadIdx.x;
+    bf16x8 a[kChains16], b[kChains16];
+    floatx4 acc[kChains16];
+#pragma unroll
+    for (int c = 0; c < kChains16; ++c) {
+        a[c] = __builtin_bit_cast(bf16x8, data[(t * 2 * kChains16 + 2 * c) % n_vec]);
+        b[c] = __builtin_bit_cast(bf16x8, data[(t * 2 * kChains16 + 2 * c + 1) % n_vec]);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) acc[c][r] = 0.0f;
+    }
+    for (int i = 0; i < iters; ++i) {
+#pragma unroll
+        for (int c = 0; c < kChains16; ++c) acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[c], b[c], acc[c], 0, 0, 0);
+    }
+    float s = 0.0f;
+#pragma unroll
+    for (int c = 0; c < kChains16; ++c)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) s += acc[c][r];
     if (s == 12345.678f) sink[0] = s;          // keeps the loop alive; practically never true
 }
 
@@ -84,6 +112,16 @@ int eqat_peak_mfma_loop(const void *data, size_t data_bytes, int groups, int ite
     if (data == nullptr || sink == nullptr || data_bytes < 16 || data_bytes % 16 != 0 || groups < 1 || iters < 1) return 1;
     k_mfma_loop<<<dim3(groups), dim3(64 * kWavesPerGroup), 0, (hipStream_t)stream>>>((const uintx4 *)data, (uint32_t)(data_bytes / 16),
                                                                                       iters, sink);
+    return hipGetLastError() == hipSuccess ? 0 : 1;
+}
+
+// The 16x16x32 form: flop of one launch = groups * 8 waves * iters * 8 MFMAs * 2 * 16 * 16 * 32; arguments as above.
+double eqat_peak_mfma16_flop(int groups, int iters) { return (double)groups * kWavesPerGroup * (double)iters * kChains16 * 16384.0; }
+int eqat_peak_mfma16_loop(const void *data, size_t data_bytes, int groups, int iters, float *sink, void *stream)
+{
+    if (data == nullptr || sink == nullptr || data_bytes < 16 || data_bytes % 16 != 0 || groups < 1 || iters < 1) return 1;
+    k_mfma16_loop<<<dim3(groups), dim3(64 * kWavesPerGroup), 0, (hipStream_t)stream>>>((const uintx4 *)data, (uint32_t)(data_bytes / 16),
+                                                                                        iters, sink);
     return hipGetLastError() == hipSuccess ? 0 : 1;
 }
 
