@@ -1,4 +1,5 @@
-// bf16 MFMA GEMMs of the quantized linear layer (gfx950, v_mfma_f32_32x32x16_bf16).
+// bf16 MFMA GEMMs of the quantized linear layer (gfx950; fwd and dX on v_mfma_f32_32x32x16_bf16, dW on
+// v_mfma_f32_16x16x32_bf16).
 //
 //   fwd :  Y [T,O]  = X [T,I]  * What[O,I]^T        (K = I)
 //   dX  :  dX[T,I]  = dY[T,O]  * What[O,I]          (K = O)
@@ -927,7 +928,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm_dw(const GemmDwArgs a)
     // The contraction runs on v_mfma_f32_16x16x32_bf16 (measured 4-7 % ahead of the 32x32x16 form in this loop, which
     // moves twice the accumulator registers per flop): the 32 x 32 block (i, j) of the wave is four 16 x 16 products, and
     // product (ii, jj) lives in acc[i][j][2 ii + jj] until the end of the K loop, where the blocks
-    // are brought into the lane order of the 32 x 32 form that the epilogue is written for (to_block_layout below).
+    // are brought into the lane order of the 32 x 32 form that the epilogue is written for (see the start of the epilogue).
     // A K tile is KS slices of 32.  Per slice a wave needs MA = 2 MI fragments of X and NB = 2 NI of dY (4 registers
     // each).  The dY fragments are double-buffered; an X fragment is used by NB consecutive MFMAs only, so the fragment
     // of the next slice takes its registers as soon as those have been issued.
